@@ -1,0 +1,225 @@
+/*
+ * memosight.h -- C ABI of the MI355X (gfx950) library for MemoSight's per-step decode hot path:
+ * fused Predict+Verify attention over a paged KV cache that context compression keeps compacting,
+ * the accepted-KV append, the segment -> memory-token compaction and greedy prefix acceptance.
+ *
+ * Conventions
+ *   - Every function returns an int status: MS_OK (0) or a negative MS_ERR_* code.  Nothing throws
+ *     or aborts across this boundary; ms_last_error() gives a thread-local message for the last
+ *     failing call on the calling thread.
+ *   - "host" pointers are ordinary CPU memory read (or written) before the call returns.
+ *     "device" pointers are HIP device memory on the cache's GPU; they are only touched by work
+ *     queued on `stream` (a hipStream_t passed as void*, NULL = the default stream).
+ *   - Small control arrays (sequence ids, counts, ranges) are host pointers; tensors (Q, K, V,
+ *     position ids, outputs, token ids) are device pointers.
+ *   - The caller allocates and owns the KV pool, all tensors and workspaces; the library never
+ *     frees them.  The library owns the opaque ms_cache handle, its host-side page tables and a
+ *     small device mirror of them which it allocates in ms_cache_create and frees in
+ *     ms_cache_destroy.  No other call allocates device memory.
+ *   - Calls that take a cache are asynchronous on `stream` unless stated; all calls on one cache
+ *     must be issued from one thread at a time and on one stream (or be ordered by the caller).
+ *   - Tensor element type follows the cache dtype: float (MS_F32) or bfloat16 bit patterns
+ *     (MS_BF16, 2 bytes, upper half of an IEEE float).  Position ids and token ids are int32.
+ *
+ * KV pool layout (row-major, innermost last), element = cache dtype:
+ *     pool[n_layers][n_pages][n_kv_heads][2 (0 = K, 1 = V)][16 slots][head_dim]
+ * Logical token t of a sequence lives in page page_table[t / 16], slot t % 16; one page table per
+ * sequence serves every layer.  Cached K is stored already rotated (RoPE at its position id).
+ *
+ * RoPE convention (the paper names RoPE, Section 2.1.2 "Uniform Position Layout", without fixing a
+ * variant; this is the rotate-half form of the model families it evaluates): element i < D/2 pairs
+ * with i + D/2; inv_freq_i = float(rope_base^(-2i/D)); angle = float(pos) * inv_freq_i in fp32;
+ * x'_i = x_i cos - x_{i+D/2} sin,  x'_{i+D/2} = x_{i+D/2} cos + x_i sin.
+ */
+#ifndef MEMOSIGHT_H
+#define MEMOSIGHT_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MS_PAGE_SIZE 16
+#define MS_MAX_BATCH 256        /* sequences per call */
+#define MS_MAX_QUERIES 16       /* n_verify + n_foresight per sequence */
+
+enum { MS_F32 = 0, MS_BF16 = 1 };
+
+enum {
+    MS_OK = 0,
+    MS_ERR_INVALID = -1,        /* null pointer, bad size, bad flag, unknown sequence id */
+    MS_ERR_OOM_PAGES = -2,      /* the pool (or a sequence's page table) cannot hold the request;
+                                   the cache is left unchanged */
+    MS_ERR_RANGE = -3,          /* a segment or length lies outside the sequence */
+    MS_ERR_HIP = -4,            /* a HIP runtime call failed */
+    MS_ERR_UNSUPPORTED = -5,    /* shape outside what the kernels are built for */
+    MS_ERR_WORKSPACE = -6       /* workspace missing or too small */
+};
+
+enum {
+    MS_PRE_ROTATED = 0,         /* K rows are already rotated; pos_ids is ignored (may be NULL) */
+    MS_ROPE_APPLY = 1           /* rotate K rows by pos_ids before storing */
+};
+
+typedef struct ms_cache ms_cache;
+
+typedef struct ms_cache_desc {
+    int n_layers;
+    int n_q_heads;              /* multiple of n_kv_heads; query head h reads KV head h / (Hq/Hkv) */
+    int n_kv_heads;
+    int head_dim;               /* 64 or 128 */
+    int page_size;              /* must be MS_PAGE_SIZE */
+    int n_pages;                /* pages per layer in the pool */
+    int max_seqs;               /* sequence ids are 0 .. max_seqs-1 */
+    int max_pages_per_seq;
+    int dtype;                  /* MS_F32 or MS_BF16 */
+    float rope_base;
+    void* pool;                 /* device; ms_pool_bytes(desc) bytes; owned by the caller */
+    size_t pool_bytes;
+} ms_cache_desc;
+
+/* ---- library ---------------------------------------------------------------------------- */
+
+/* Thread-local text of the last error returned on this thread ("" if none). Never NULL. */
+const char* ms_last_error(void);
+
+/* ---- cache life cycle (Algorithm 1's KV cache S) ------------------------------------------ */
+
+/* Bytes the pool must have for this descriptor (ignores desc->pool / pool_bytes). 0 if invalid. */
+size_t ms_pool_bytes(const ms_cache_desc* desc);
+
+/* Creates an empty cache over the caller's pool on the current HIP device: all pages free, no
+ * sequences.  Allocates the device mirror of the page tables (max_seqs * (max_pages_per_seq + 1)
+ * ints) and a small pinned staging ring.  Synchronous. */
+int ms_cache_create(const ms_cache_desc* desc, ms_cache** out);
+
+/* Frees the handle and what ms_cache_create allocated (not the pool).  Synchronous. */
+int ms_cache_destroy(ms_cache* cache);
+
+/* New empty sequence; *seq_id receives the lowest unused id. */
+int ms_seq_create(ms_cache* cache, int* seq_id);
+
+/* Adopts `n_pages` pages (host array, logical order) that the caller has already filled in the
+ * pool as a new sequence of `length` tokens (n_pages must equal ceil(length / 16)).  Every page
+ * must currently be free and appear once.  Used to hand over a prefilled or restored cache. */
+int ms_seq_import(ms_cache* cache, int length, const int* pages, int n_pages, int* seq_id,
+                  void* stream);
+
+/* Releases the sequence and returns all its pages to the free set. */
+int ms_seq_free(ms_cache* cache, int seq_id);
+
+/* ---- S <- S (+) A : append KV rows (Algorithm 1, "Append to cache") ----------------------- */
+
+/* Appends n_tok[b] rows to sequence seq_ids[b], for b = 0..B-1 in that order, in every layer.
+ *   seq_ids, n_tok : host [B]
+ *   k, v           : device [n_layers][sum n_tok][n_kv_heads][head_dim]
+ *   pos_ids        : device [sum n_tok] int32 (ignored with MS_PRE_ROTATED)
+ * A page is taken exactly when a sequence's length before a row is a multiple of 16, always the
+ * lowest free page index.  If the pool cannot hold the whole call: MS_ERR_OOM_PAGES, nothing
+ * changes. */
+int ms_append_kv(ms_cache* cache, int B, const int* seq_ids, const int* n_tok, const void* k,
+                 const void* v, const int* pos_ids, int flags, void* stream);
+
+/* Appends the first accept_len[b] in-flight rows of each sequence (the accepted verify tokens of
+ * the step; foresight rows are never stored -- Section 2.3 "MTP Attention").
+ *   accept_len : host [B], 0 <= accept_len[b] <= n_q
+ *   k_new,v_new: device [n_layers][B][n_q][n_kv_heads][head_dim] (K not rotated)
+ *   pos_ids    : device [B][n_q]
+ * Same page policy and error behaviour as ms_append_kv. */
+int ms_commit_accepted(ms_cache* cache, int B, const int* seq_ids, const int* accept_len, int n_q,
+                       const void* k_new, const void* v_new, const int* pos_ids, void* stream);
+
+/* ---- UpdateCache : evict a finished step, keep its memory tokens -------------------------- */
+
+/* For b = 0..B-1 in order: logical rows [seg_begin[b], seg_begin[b] + seg_len[b]) of sequence
+ * seq_ids[b] are dropped and n_mem[b] memory-token rows take their place; rows after the segment
+ * (none when the segment is the cache suffix, as in Algorithm 1) keep their stored values and
+ * follow.  All layers at once.  (Section 2.1.2; Algorithm 1 "Evict verbose and insert memory".)
+ *   seq_ids, seg_begin, seg_len, n_mem : host [B]
+ *   mem_k, mem_v : device [n_layers][sum n_mem][n_kv_heads][head_dim]
+ *   mem_pos      : device [sum n_mem] (the memory tokens' UPL position ids; see ms_upl_positions)
+ *   workspace    : device scratch, only needed when some sequence has rows after its segment:
+ *                  ms_compact_workspace_bytes() bytes; may be NULL otherwise.
+ * A sequence id may appear at most once per call.
+ * Page policy per sequence: pages holding any row below seg_begin are kept, all later pages of
+ * the sequence are released first, then rows are re-appended (memory rows, then tail rows), each
+ * new page being the lowest free index.  Errors (MS_ERR_RANGE, MS_ERR_OOM_PAGES,
+ * MS_ERR_WORKSPACE) leave the cache unchanged. */
+int ms_compact_segment(ms_cache* cache, int B, const int* seq_ids, const int* seg_begin,
+                       const int* seg_len, const int* n_mem, const void* mem_k, const void* mem_v,
+                       const int* mem_pos, int flags, void* workspace, size_t ws_bytes,
+                       void* stream);
+
+/* Scratch bytes ms_compact_segment needs for the given call (0 if every segment is a suffix). */
+size_t ms_compact_workspace_bytes(ms_cache* cache, int B, const int* seq_ids, const int* seg_begin,
+                                  const int* seg_len);
+
+/* ---- fused Predict+Verify attention -------------------------------------------------------- */
+
+/* One attention layer of one decode step (Section 2.1.1 Predict and Verify, fused in one pass;
+ * visibility from Section 2.3 "Compression Attention" / "MTP Attention").  For sequence
+ * b = seq_ids[.], query i in [0, n_q), n_q = n_verify + n_foresight, query head h:
+ *     out[b][i][h] = softmax_t(scale * rope(q[b][i][h], pos[b][i]) . k_t) . v_t
+ * over t in: every cached token of the sequence (layer `layer`), the in-flight tokens
+ * j < ctx_new[b][i], and the in-flight token i itself; in-flight keys are
+ * rope(k_new[b][j][g], pos[b][j]).  With ctx_new == NULL the default layout is used: verify token i
+ * sees the i verify tokens before it; each foresight token sees the whole verify block and no
+ * other foresight token.  The cache is only read.
+ *   seq_ids : host [B], B <= MS_MAX_BATCH;  n_q <= MS_MAX_QUERIES, n_verify >= 0, n_q >= 1
+ *   q       : device [B][n_q][n_q_heads][head_dim]
+ *   k_new, v_new : device [B][n_q][n_kv_heads][head_dim]
+ *   pos_ids : device [B][n_q];  ctx_new : device [B][n_q] or NULL
+ *   scale   : 0 means 1/sqrt(head_dim)
+ *   out     : device [B][n_q][n_q_heads][head_dim], cache dtype
+ *   workspace : device, at least ms_attention_workspace_bytes(cache, B, n_q) bytes, 256-byte
+ *               aligned; holds rotated queries and split-KV partial results. */
+int ms_predict_verify_attention(ms_cache* cache, int layer, int B, const int* seq_ids, int n_verify,
+                                int n_foresight, const void* q, const void* k_new,
+                                const void* v_new, const int* pos_ids, const int* ctx_new,
+                                float scale, void* out, void* workspace, size_t ws_bytes,
+                                void* stream);
+
+size_t ms_attention_workspace_bytes(ms_cache* cache, int B, int n_q);
+
+/* ---- greedy longest-prefix acceptance (footnote of Section 2.1.1) -------------------------- */
+
+/* accept_len[b] = number of leading j with draft[b][j] == target[b][j] (target[b][j] being the
+ * model's argmax token for the slot draft[b][j] fills); if stop ids are given the count ends just
+ * after the first accepted stop id (so a finished step is always the cache suffix, Algorithm 1).
+ * next_token[b] = target[b][accept_len[b]] if accept_len[b] < n, else -1.
+ *   draft, target : device [B][n] int32;  stop_ids : device [n_stop] or NULL
+ *   accept_len, next_token : device [B] int32 */
+int ms_accept(int B, int n, const int* draft, const int* target, const int* stop_ids, int n_stop,
+              int* accept_len, int* next_token, void* stream);
+
+/* ---- introspection (host side; synchronous where noted) ------------------------------------ */
+
+int ms_seq_len(ms_cache* cache, int seq_id, int* len);
+/* Copies up to `cap` page ids to `out` (host) and stores the page count in *n. */
+int ms_seq_page_table(ms_cache* cache, int seq_id, int* out, int cap, int* n);
+int ms_free_page_count(ms_cache* cache, int* n);
+int ms_peak_pages(ms_cache* cache, int* n);
+/* Checks: every page is free or owned exactly once, page counts match lengths, and (after
+ * synchronising `stream`) the device mirror equals the host tables.  MS_OK or MS_ERR_INVALID. */
+int ms_check_integrity(ms_cache* cache, void* stream);
+
+/* ---- position layout helpers (pure host integer functions) --------------------------------- */
+
+/* Adaptive Memory Allocation: ceil(n_tokens / c).  Negative on bad input. */
+int ms_ama_count(int n_tokens, int c);
+/* Uniform Position Layout: the step's tokens hold PIDs first_pid .. first_pid + n_tokens - 1 and
+ * are cut into groups of c (the last may be shorter); out[g] = centre PID of group g (lower middle
+ * for even-sized groups).  Writes at most cap entries, returns the group count. */
+int ms_upl_positions(int first_pid, int n_tokens, int c, int* out, int cap);
+/* PID of <o> after a step whose last token has PID last_pid (Section 2.2): last_pid + 1. */
+int ms_output_token_pid(int last_pid);
+/* PIDs of d foresight tokens after a prefix ending at last_prefix_pid: last + 1 .. last + d. */
+int ms_foresight_pids(int last_prefix_pid, int d, int* out, int cap);
+/* Default ctx_new row for n_verify + n_foresight queries. */
+int ms_default_ctx_new(int n_verify, int n_foresight, int* out, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MEMOSIGHT_H */

@@ -1,0 +1,256 @@
+"""ctypes binding for libmemosight.so: argument marshalling only, same names as the C ABI.
+
+Device tensors are passed as torch tensors (their data_ptr() is handed over), host control arrays
+as sequences of ints.  There is no fallback: if the HIP library cannot be loaded, importing this
+module fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+# torch ships its own HIP runtime (same SONAME as the system one).  It is imported first so that
+# the library below binds to that already-loaded copy: two HIP runtimes in one process do not share
+# devices, streams or allocations.
+import torch  # noqa: F401
+
+from . import build as _build
+
+MS_PAGE_SIZE = 16
+MS_MAX_BATCH = 256
+MS_MAX_QUERIES = 16
+MS_F32, MS_BF16 = 0, 1
+MS_OK, MS_ERR_INVALID, MS_ERR_OOM_PAGES, MS_ERR_RANGE = 0, -1, -2, -3
+MS_ERR_HIP, MS_ERR_UNSUPPORTED, MS_ERR_WORKSPACE = -4, -5, -6
+MS_PRE_ROTATED, MS_ROPE_APPLY = 0, 1
+
+
+class MsError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"memosight error {code}: {msg}")
+        self.code = code
+
+
+class ms_cache_desc(C.Structure):
+    _fields_ = [("n_layers", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int),
+                ("head_dim", C.c_int), ("page_size", C.c_int), ("n_pages", C.c_int),
+                ("max_seqs", C.c_int), ("max_pages_per_seq", C.c_int), ("dtype", C.c_int),
+                ("rope_base", C.c_float), ("pool", C.c_void_p), ("pool_bytes", C.c_size_t)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    return C.CDLL(_build.LIB)
+
+
+lib = _load()
+
+_P, _I, _IP, _SZ, _F = C.c_void_p, C.c_int, C.POINTER(C.c_int), C.c_size_t, C.c_float
+_SIGS = {
+    "ms_last_error": (C.c_char_p, []),
+    "ms_pool_bytes": (_SZ, [C.POINTER(ms_cache_desc)]),
+    "ms_cache_create": (_I, [C.POINTER(ms_cache_desc), C.POINTER(_P)]),
+    "ms_cache_destroy": (_I, [_P]),
+    "ms_seq_create": (_I, [_P, _IP]),
+    "ms_seq_import": (_I, [_P, _I, _IP, _I, _IP, _P]),
+    "ms_seq_free": (_I, [_P, _I]),
+    "ms_append_kv": (_I, [_P, _I, _IP, _IP, _P, _P, _P, _I, _P]),
+    "ms_commit_accepted": (_I, [_P, _I, _IP, _IP, _I, _P, _P, _P, _P]),
+    "ms_compact_segment": (_I, [_P, _I, _IP, _IP, _IP, _IP, _P, _P, _P, _I, _P, _SZ, _P]),
+    "ms_compact_workspace_bytes": (_SZ, [_P, _I, _IP, _IP, _IP]),
+    "ms_predict_verify_attention": (_I, [_P, _I, _I, _IP, _I, _I, _P, _P, _P, _P, _P, _F, _P, _P, _SZ, _P]),
+    "ms_attention_workspace_bytes": (_SZ, [_P, _I, _I]),
+    "ms_accept": (_I, [_I, _I, _P, _P, _P, _I, _P, _P, _P]),
+    "ms_seq_len": (_I, [_P, _I, _IP]),
+    "ms_seq_page_table": (_I, [_P, _I, _IP, _I, _IP]),
+    "ms_free_page_count": (_I, [_P, _IP]),
+    "ms_peak_pages": (_I, [_P, _IP]),
+    "ms_check_integrity": (_I, [_P, _P]),
+    "ms_ama_count": (_I, [_I, _I]),
+    "ms_upl_positions": (_I, [_I, _I, _I, _IP, _I]),
+    "ms_output_token_pid": (_I, [_I]),
+    "ms_foresight_pids": (_I, [_I, _I, _IP, _I]),
+    "ms_default_ctx_new": (_I, [_I, _I, _IP, _I]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _fn = getattr(lib, _name)
+    _fn.restype, _fn.argtypes = _res, _args
+
+EXPORTED = tuple(_SIGS)
+
+
+def _check(rc: int) -> None:
+    if rc != MS_OK:
+        raise MsError(rc, lib.ms_last_error().decode())
+
+
+def _ints(xs: Sequence[int]):
+    xs = [int(x) for x in xs]
+    return (C.c_int * max(1, len(xs)))(*xs)
+
+
+def _dev(t) -> Optional[int]:
+    """Device address of a torch tensor (None stays NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        if not torch.cuda.is_available():
+            return None
+        return torch.cuda.current_stream().cuda_stream or None
+    return getattr(stream, "cuda_stream", stream) or None
+
+
+def ms_last_error() -> str:
+    return lib.ms_last_error().decode()
+
+
+def make_desc(n_layers, n_q_heads, n_kv_heads, head_dim, n_pages, max_seqs, max_pages_per_seq, dtype,
+              rope_base, pool=None) -> ms_cache_desc:
+    d = ms_cache_desc(n_layers, n_q_heads, n_kv_heads, head_dim, MS_PAGE_SIZE, n_pages, max_seqs,
+                      max_pages_per_seq, dtype, rope_base, None, 0)
+    if pool is not None:
+        d.pool = _dev(pool)
+        d.pool_bytes = pool.numel() * pool.element_size()
+    return d
+
+
+def ms_pool_bytes(desc: ms_cache_desc) -> int:
+    return lib.ms_pool_bytes(C.byref(desc))
+
+
+def ms_cache_create(desc: ms_cache_desc) -> int:
+    h = _P()
+    _check(lib.ms_cache_create(C.byref(desc), C.byref(h)))
+    return h.value
+
+
+def ms_cache_destroy(cache: int) -> None:
+    _check(lib.ms_cache_destroy(cache))
+
+
+def ms_seq_create(cache: int) -> int:
+    s = C.c_int(-1)
+    _check(lib.ms_seq_create(cache, C.byref(s)))
+    return s.value
+
+
+def ms_seq_import(cache: int, length: int, pages: Sequence[int], stream=None) -> int:
+    s = C.c_int(-1)
+    _check(lib.ms_seq_import(cache, length, _ints(pages), len(pages), C.byref(s), _stream(stream)))
+    return s.value
+
+
+def ms_seq_free(cache: int, seq_id: int) -> None:
+    _check(lib.ms_seq_free(cache, seq_id))
+
+
+def ms_append_kv(cache, seq_ids, n_tok, k, v, pos_ids, flags=MS_ROPE_APPLY, stream=None) -> None:
+    _check(lib.ms_append_kv(cache, len(seq_ids), _ints(seq_ids), _ints(n_tok), _dev(k), _dev(v),
+                            _dev(pos_ids), flags, _stream(stream)))
+
+
+def ms_commit_accepted(cache, seq_ids, accept_len, n_q, k_new, v_new, pos_ids, stream=None) -> None:
+    _check(lib.ms_commit_accepted(cache, len(seq_ids), _ints(seq_ids), _ints(accept_len), n_q,
+                                  _dev(k_new), _dev(v_new), _dev(pos_ids), _stream(stream)))
+
+
+def ms_compact_workspace_bytes(cache, seq_ids, seg_begin, seg_len) -> int:
+    return lib.ms_compact_workspace_bytes(cache, len(seq_ids), _ints(seq_ids), _ints(seg_begin), _ints(seg_len))
+
+
+def ms_compact_segment(cache, seq_ids, seg_begin, seg_len, n_mem, mem_k, mem_v, mem_pos,
+                       flags=MS_ROPE_APPLY, workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.ms_compact_segment(cache, len(seq_ids), _ints(seq_ids), _ints(seg_begin), _ints(seg_len),
+                                  _ints(n_mem), _dev(mem_k), _dev(mem_v), _dev(mem_pos), flags,
+                                  _dev(workspace), ws_bytes, _stream(stream)))
+
+
+def ms_attention_workspace_bytes(cache, B: int, n_q: int) -> int:
+    return lib.ms_attention_workspace_bytes(cache, B, n_q)
+
+
+def ms_predict_verify_attention(cache, layer, seq_ids, n_verify, n_foresight, q, k_new, v_new, pos_ids,
+                                ctx_new, scale, out, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.ms_predict_verify_attention(cache, layer, len(seq_ids), _ints(seq_ids), n_verify, n_foresight,
+                                           _dev(q), _dev(k_new), _dev(v_new), _dev(pos_ids), _dev(ctx_new),
+                                           float(scale), _dev(out), _dev(workspace), ws_bytes, _stream(stream)))
+
+
+def ms_accept(B, n, draft, target, stop_ids, accept_len, next_token, stream=None) -> None:
+    n_stop = 0 if stop_ids is None else stop_ids.numel()
+    _check(lib.ms_accept(B, n, _dev(draft), _dev(target), _dev(stop_ids), n_stop, _dev(accept_len),
+                         _dev(next_token), _stream(stream)))
+
+
+def ms_seq_len(cache, seq_id: int) -> int:
+    n = C.c_int(0)
+    _check(lib.ms_seq_len(cache, seq_id, C.byref(n)))
+    return n.value
+
+
+def ms_seq_page_table(cache, seq_id: int):
+    n = C.c_int(0)
+    _check(lib.ms_seq_page_table(cache, seq_id, None, 0, C.byref(n)))
+    buf = (C.c_int * max(1, n.value))()
+    _check(lib.ms_seq_page_table(cache, seq_id, buf, n.value, C.byref(n)))
+    return list(buf[:n.value])
+
+
+def ms_free_page_count(cache) -> int:
+    n = C.c_int(0)
+    _check(lib.ms_free_page_count(cache, C.byref(n)))
+    return n.value
+
+
+def ms_peak_pages(cache) -> int:
+    n = C.c_int(0)
+    _check(lib.ms_peak_pages(cache, C.byref(n)))
+    return n.value
+
+
+def ms_check_integrity(cache, stream=None) -> None:
+    _check(lib.ms_check_integrity(cache, _stream(stream)))
+
+
+def ms_ama_count(n_tokens: int, c: int) -> int:
+    return lib.ms_ama_count(n_tokens, c)
+
+
+def ms_upl_positions(first_pid: int, n_tokens: int, c: int):
+    n = lib.ms_upl_positions(first_pid, n_tokens, c, None, 0)
+    if n < 0:
+        raise MsError(n, "bad arguments")
+    buf = (C.c_int * max(1, n))()
+    lib.ms_upl_positions(first_pid, n_tokens, c, buf, n)
+    return list(buf[:n])
+
+
+def ms_output_token_pid(last_pid: int) -> int:
+    return lib.ms_output_token_pid(last_pid)
+
+
+def ms_foresight_pids(last_prefix_pid: int, d: int):
+    buf = (C.c_int * max(1, d))()
+    n = lib.ms_foresight_pids(last_prefix_pid, d, buf, d)
+    if n < 0:
+        raise MsError(n, "bad arguments")
+    return list(buf[:n])
+
+
+def ms_default_ctx_new(n_verify: int, n_foresight: int):
+    n = n_verify + n_foresight
+    buf = (C.c_int * max(1, n))()
+    r = lib.ms_default_ctx_new(n_verify, n_foresight, buf, n)
+    if r < 0:
+        raise MsError(r, "bad arguments")
+    return list(buf[:n])

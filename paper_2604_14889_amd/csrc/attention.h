@@ -1,0 +1,34 @@
+// Argument blocks shared by the attention kernels (internal).
+#pragma once
+
+#include "memosight.h"
+
+namespace ms {
+
+constexpr int kMaxRowwaveSplits = 16;
+
+// Per-call sequence ids and cache lengths, passed by value in the kernel argument block so that a
+// launch sees exactly the host state of the moment it was issued.
+struct BatchMeta {
+    int seq[MS_MAX_BATCH];
+    int len[MS_MAX_BATCH];
+};
+
+struct AttnArgs {
+    const void* pool_layer;  // first element of this layer's pages
+    const int* d_pt;         // device page tables [max_seqs][max_pages]
+    const float* inv_freq;   // [head_dim / 2]
+    const void* q;
+    const void* k_new;
+    const void* v_new;
+    const int* pos;
+    const int* ctx_new;      // may be null: default layout
+    void* out;
+    float* ws;
+    int n_q, n_verify, n_q_heads, n_kv_heads, group, max_pages;
+    long page_elems;
+    int n_splits, chunk;
+    float scale;
+};
+
+}  // namespace ms

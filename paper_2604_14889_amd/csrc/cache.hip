@@ -1,0 +1,636 @@
+// Paged KV cache: host-side page tables and allocator, device mirror, and the row scatter /
+// gather kernels behind append, commit and segment compaction (Algorithm 1: "S <- S (+) A" and
+// "UpdateCache"; Section 2.1.2 of the MemoSight paper).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "ms_device.h"
+#include "ms_internal.h"
+
+// ---------------------------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------------------------
+namespace ms {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+void clear_error() { g_err[0] = 0; }
+
+// ---------------------------------------------------------------------------------------------
+// staging ring
+// ---------------------------------------------------------------------------------------------
+int StageRing::init() {
+    MS_HIP_TRY(hipHostMalloc((void**)&h, kSlots * kSlotBytes, hipHostMallocDefault));
+    MS_HIP_TRY(hipMalloc((void**)&d, kSlots * kSlotBytes));
+    for (int i = 0; i < kSlots; ++i) {
+        MS_HIP_TRY(hipEventCreateWithFlags(&ev[i], hipEventDisableTiming));
+        used[i] = false;
+    }
+    next = 0;
+    return MS_OK;
+}
+
+void StageRing::destroy() {
+    for (int i = 0; i < kSlots; ++i)
+        if (ev[i]) (void)hipEventDestroy(ev[i]);
+    if (h) (void)hipHostFree(h);
+    if (d) (void)hipFree(d);
+    h = d = nullptr;
+}
+
+int StageRing::upload(const void* src, size_t bytes, hipStream_t stream, void** dev) {
+    if (bytes > kSlotBytes) MS_FAIL(MS_ERR_INVALID, "internal: staging upload of %zu bytes", bytes);
+    int s = next;
+    next = (next + 1) % kSlots;
+    if (used[s]) MS_HIP_TRY(hipEventSynchronize(ev[s]));
+    memcpy(h + s * kSlotBytes, src, bytes);
+    MS_HIP_TRY(hipMemcpyAsync(d + s * kSlotBytes, h + s * kSlotBytes, bytes, hipMemcpyHostToDevice,
+                              stream));
+    MS_HIP_TRY(hipEventRecord(ev[s], stream));
+    used[s] = true;
+    *dev = d + s * kSlotBytes;
+    return MS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// kernels
+// ---------------------------------------------------------------------------------------------
+
+// Writes (seq, index, page) triples into the device page-table mirror.
+__global__ void patch_page_table(int* __restrict__ d_pt, const int* __restrict__ triples, int n,
+                                 int max_pages) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) d_pt[(size_t)triples[3 * i] * max_pages + triples[3 * i + 1]] = triples[3 * i + 2];
+}
+
+struct ScatterArgs {
+    void* pool;
+    const int* d_pt;
+    const float* inv_freq;
+    const RowDesc* desc;
+    int n_seq;
+    int total_rows;
+    const void* k;
+    const void* v;
+    const int* pos;        // indexed by buffer row; may be null when !rope
+    long buf_layer_rows;   // rows per layer in the packed buffers
+    int n_kv_heads;
+    int max_pages;
+    long page_elems;
+    long layer_elems;
+    int rope;
+};
+
+__device__ __forceinline__ int find_seq(const RowDesc* desc, int n_seq, int r) {
+    int lo = 0, hi = n_seq - 1;  // last b with prefix <= r
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (desc[mid].prefix <= r) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// One workgroup per (row, layer): stores one token's K (rotated on request) and V for every KV
+// head into its page slot.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void kv_scatter(ScatterArgs a) {
+    const int r = blockIdx.x, layer = blockIdx.y;
+    const int b = find_seq(a.desc, a.n_seq, r);
+    const RowDesc de = a.desc[b];
+    const int j = r - de.prefix;
+    const long src_row = (long)layer * a.buf_layer_rows + de.buf_first + j;
+    const int t = de.cache_begin + j;
+    const int page = a.d_pt[(size_t)de.seq * a.max_pages + t / MS_PAGE_SIZE];
+    const int slot = t % MS_PAGE_SIZE;
+    T* pool = (T*)a.pool + (size_t)layer * a.layer_elems + (size_t)page * a.page_elems;
+    const T* ks = (const T*)a.k + src_row * a.n_kv_heads * D;
+    const T* vs = (const T*)a.v + src_row * a.n_kv_heads * D;
+    const float posf = a.rope ? (float)a.pos[de.buf_first + j] : 0.f;
+    constexpr int H2 = D / 2;
+    for (int e = threadIdx.x; e < a.n_kv_heads * H2; e += blockDim.x) {
+        const int g = e / H2, i = e % H2;
+        float x0 = to_float(ks[g * D + i]), x1 = to_float(ks[g * D + i + H2]);
+        if (a.rope) {
+            float sn, cs;
+            sincosf(posf * a.inv_freq[i], &sn, &cs);
+            const float y0 = x0 * cs - x1 * sn, y1 = x1 * cs + x0 * sn;
+            x0 = y0;
+            x1 = y1;
+        }
+        T* kd = pool + ((size_t)g * 2 + 0) * MS_PAGE_SIZE * D + slot * D;
+        T* vd = pool + ((size_t)g * 2 + 1) * MS_PAGE_SIZE * D + slot * D;
+        kd[i] = from_float<T>(x0);
+        kd[i + H2] = from_float<T>(x1);
+        vd[i] = vs[g * D + i];
+        vd[i + H2] = vs[g * D + i + H2];
+    }
+}
+
+// Inverse of kv_scatter without rotation: copies cache rows into packed buffers.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void kv_gather(ScatterArgs a) {
+    const int r = blockIdx.x, layer = blockIdx.y;
+    const int b = find_seq(a.desc, a.n_seq, r);
+    const RowDesc de = a.desc[b];
+    const int j = r - de.prefix;
+    const long dst_row = (long)layer * a.buf_layer_rows + de.buf_first + j;
+    const int t = de.cache_begin + j;
+    const int page = a.d_pt[(size_t)de.seq * a.max_pages + t / MS_PAGE_SIZE];
+    const int slot = t % MS_PAGE_SIZE;
+    const T* pool = (const T*)a.pool + (size_t)layer * a.layer_elems + (size_t)page * a.page_elems;
+    T* kd = (T*)a.k + dst_row * a.n_kv_heads * D;
+    T* vd = (T*)a.v + dst_row * a.n_kv_heads * D;
+    for (int e = threadIdx.x; e < a.n_kv_heads * D; e += blockDim.x) {
+        const int g = e / D, i = e % D;
+        kd[e] = pool[((size_t)g * 2 + 0) * MS_PAGE_SIZE * D + slot * D + i];
+        vd[e] = pool[((size_t)g * 2 + 1) * MS_PAGE_SIZE * D + slot * D + i];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host helpers
+// ---------------------------------------------------------------------------------------------
+
+int check_seq(const ms_cache* c, int seq, const char* what) {
+    if (seq < 0 || seq >= c->d.max_seqs || !c->live[seq])
+        MS_FAIL(MS_ERR_INVALID, "%s: unknown sequence id %d", what, seq);
+    return MS_OK;
+}
+
+int flush_page_table_patches(ms_cache* c, hipStream_t stream) {
+    const size_t per = StageRing::kSlotBytes / (3 * sizeof(int));
+    size_t n = c->pending_pt.size() / 3, done = 0;
+    while (done < n) {
+        size_t cnt = std::min(per, n - done);
+        void* dev = nullptr;
+        int rc = c->stage.upload(c->pending_pt.data() + 3 * done, cnt * 3 * sizeof(int), stream, &dev);
+        if (rc != MS_OK) return rc;
+        hipLaunchKernelGGL(patch_page_table, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, stream,
+                           c->d_pt, (const int*)dev, (int)cnt, c->d.max_pages_per_seq);
+        MS_HIP_TRY(hipGetLastError());
+        done += cnt;
+    }
+    c->pending_pt.clear();
+    return MS_OK;
+}
+
+static int take_page(ms_cache* c, int seq) {
+    int page = *c->free_pages.begin();
+    c->free_pages.erase(c->free_pages.begin());
+    c->pending_pt.push_back(seq);
+    c->pending_pt.push_back((int)c->pt[seq].size());
+    c->pending_pt.push_back(page);
+    c->pt[seq].push_back(page);
+    int in_use = c->d.n_pages - (int)c->free_pages.size();
+    if (in_use > c->peak_pages) c->peak_pages = in_use;
+    return page;
+}
+
+// Grows `seq` by n rows (pages first-fit lowest); the caller has verified capacity.
+static void grow(ms_cache* c, int seq, int n) {
+    for (int j = 0; j < n; ++j) {
+        if (c->len[seq] % MS_PAGE_SIZE == 0) take_page(c, seq);
+        c->len[seq]++;
+    }
+}
+
+static inline int pages_for(long n) { return (int)((n + MS_PAGE_SIZE - 1) / MS_PAGE_SIZE); }
+
+template <typename F>
+static int dispatch(const ms_cache* c, F&& f) {
+    const int D = c->d.head_dim;
+    if (c->d.dtype == MS_F32) return D == 64 ? f((float*)0, std::integral_constant<int, 64>()) : f((float*)0, std::integral_constant<int, 128>());
+    return D == 64 ? f((bf16_t*)0, std::integral_constant<int, 64>()) : f((bf16_t*)0, std::integral_constant<int, 128>());
+}
+
+static int launch_rows(ms_cache* c, bool gather, const std::vector<RowDesc>& desc, int total_rows,
+                       const void* k, const void* v, const int* pos, long buf_layer_rows, int rope,
+                       hipStream_t stream) {
+    if (total_rows == 0) return MS_OK;
+    void* dev = nullptr;
+    int rc = c->stage.upload(desc.data(), desc.size() * sizeof(RowDesc), stream, &dev);
+    if (rc != MS_OK) return rc;
+    ScatterArgs a;
+    a.pool = c->d.pool;
+    a.d_pt = c->d_pt;
+    a.inv_freq = c->d_inv_freq;
+    a.desc = (const RowDesc*)dev;
+    a.n_seq = (int)desc.size();
+    a.total_rows = total_rows;
+    a.k = k;
+    a.v = v;
+    a.pos = pos;
+    a.buf_layer_rows = buf_layer_rows;
+    a.n_kv_heads = c->d.n_kv_heads;
+    a.max_pages = c->d.max_pages_per_seq;
+    a.page_elems = (long)c->page_elems;
+    a.layer_elems = (long)c->layer_elems;
+    a.rope = rope;
+    dim3 grid((unsigned)total_rows, (unsigned)c->d.n_layers);
+    return dispatch(c, [&](auto* tp, auto dc) -> int {
+        using T = std::remove_pointer_t<decltype(tp)>;
+        constexpr int D = decltype(dc)::value;
+        if (gather)
+            hipLaunchKernelGGL((kv_gather<T, D>), grid, dim3(256), 0, stream, a);
+        else
+            hipLaunchKernelGGL((kv_scatter<T, D>), grid, dim3(256), 0, stream, a);
+        MS_HIP_TRY(hipGetLastError());
+        return (int)MS_OK;
+    });
+}
+
+static int validate_desc(const ms_cache_desc* d) {
+    if (!d) MS_FAIL(MS_ERR_INVALID, "descriptor is null");
+    if (d->n_layers < 1 || d->n_kv_heads < 1 || d->n_q_heads < 1 || d->n_pages < 1 || d->max_seqs < 1 ||
+        d->max_pages_per_seq < 1)
+        MS_FAIL(MS_ERR_INVALID, "descriptor: counts must be positive");
+    if (d->n_q_heads % d->n_kv_heads) MS_FAIL(MS_ERR_INVALID, "n_q_heads must be a multiple of n_kv_heads");
+    if (d->head_dim != 64 && d->head_dim != 128) MS_FAIL(MS_ERR_UNSUPPORTED, "head_dim must be 64 or 128");
+    if (d->page_size != MS_PAGE_SIZE) MS_FAIL(MS_ERR_UNSUPPORTED, "page_size must be %d", MS_PAGE_SIZE);
+    if (d->dtype != MS_F32 && d->dtype != MS_BF16) MS_FAIL(MS_ERR_INVALID, "unknown dtype %d", d->dtype);
+    if (!(d->rope_base > 1.0f)) MS_FAIL(MS_ERR_INVALID, "rope_base must be > 1");
+    return MS_OK;
+}
+
+}  // namespace ms
+
+using namespace ms;
+
+// ---------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------
+extern "C" {
+
+const char* ms_last_error(void) { return g_err; }
+
+size_t ms_pool_bytes(const ms_cache_desc* d) {
+    if (validate_desc(d) != MS_OK) return 0;
+    size_t es = d->dtype == MS_F32 ? 4 : 2;
+    return (size_t)d->n_layers * d->n_pages * d->n_kv_heads * 2 * MS_PAGE_SIZE * d->head_dim * es;
+}
+
+int ms_cache_create(const ms_cache_desc* desc, ms_cache** out) {
+    if (!out) MS_FAIL(MS_ERR_INVALID, "out is null");
+    *out = nullptr;
+    int rc = validate_desc(desc);
+    if (rc != MS_OK) return rc;
+    if (!desc->pool) MS_FAIL(MS_ERR_INVALID, "pool is null");
+    if (desc->pool_bytes < ms_pool_bytes(desc))
+        MS_FAIL(MS_ERR_INVALID, "pool has %zu bytes, needs %zu", desc->pool_bytes, ms_pool_bytes(desc));
+    ms_cache* c = new (std::nothrow) ms_cache();
+    if (!c) MS_FAIL(MS_ERR_INVALID, "out of host memory");
+    c->d = *desc;
+    c->group = desc->n_q_heads / desc->n_kv_heads;
+    c->esize = desc->dtype == MS_F32 ? 4 : 2;
+    c->page_elems = (size_t)desc->n_kv_heads * 2 * MS_PAGE_SIZE * desc->head_dim;
+    c->layer_elems = c->page_elems * desc->n_pages;
+    for (int p = 0; p < desc->n_pages; ++p) c->free_pages.insert(c->free_pages.end(), p);
+    c->pt.assign(desc->max_seqs, {});
+    c->len.assign(desc->max_seqs, 0);
+    c->live.assign(desc->max_seqs, 0);
+    auto fail = [&](int code) {
+        ms_cache_destroy(c);
+        return code;
+    };
+    if (hipGetDevice(&c->device) != hipSuccess) {
+        set_error("hipGetDevice failed");
+        return fail(MS_ERR_HIP);
+    }
+    size_t pt_bytes = (size_t)desc->max_seqs * desc->max_pages_per_seq * sizeof(int);
+    if (hipMalloc((void**)&c->d_pt, pt_bytes) != hipSuccess || hipMemset(c->d_pt, 0, pt_bytes) != hipSuccess) {
+        set_error("allocating the page-table mirror (%zu bytes) failed", pt_bytes);
+        return fail(MS_ERR_HIP);
+    }
+    // inv_freq_i = float(base^(-2i/D)), evaluated in double and rounded once
+    std::vector<float> inv(desc->head_dim / 2);
+    for (int i = 0; i < desc->head_dim / 2; ++i)
+        inv[i] = (float)pow((double)desc->rope_base, -2.0 * i / desc->head_dim);
+    if (hipMalloc((void**)&c->d_inv_freq, inv.size() * sizeof(float)) != hipSuccess ||
+        hipMemcpy(c->d_inv_freq, inv.data(), inv.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) {
+        set_error("allocating the inv_freq table failed");
+        return fail(MS_ERR_HIP);
+    }
+    rc = c->stage.init();
+    if (rc != MS_OK) return fail(rc);
+    *out = c;
+    return MS_OK;
+}
+
+int ms_cache_destroy(ms_cache* c) {
+    if (!c) return MS_OK;
+    (void)hipDeviceSynchronize();
+    c->stage.destroy();
+    if (c->d_pt) (void)hipFree(c->d_pt);
+    if (c->d_inv_freq) (void)hipFree(c->d_inv_freq);
+    delete c;
+    return MS_OK;
+}
+
+int ms_seq_create(ms_cache* c, int* seq_id) {
+    if (!c || !seq_id) MS_FAIL(MS_ERR_INVALID, "ms_seq_create: null argument");
+    for (int s = 0; s < c->d.max_seqs; ++s)
+        if (!c->live[s]) {
+            c->live[s] = 1;
+            c->len[s] = 0;
+            c->pt[s].clear();
+            *seq_id = s;
+            return MS_OK;
+        }
+    MS_FAIL(MS_ERR_INVALID, "ms_seq_create: all %d sequence ids are in use", c->d.max_seqs);
+}
+
+int ms_seq_import(ms_cache* c, int length, const int* pages, int n_pages, int* seq_id, void* stream) {
+    if (!c || !seq_id || (n_pages > 0 && !pages)) MS_FAIL(MS_ERR_INVALID, "ms_seq_import: null argument");
+    if (length < 0 || n_pages != pages_for(length))
+        MS_FAIL(MS_ERR_INVALID, "ms_seq_import: %d pages do not match length %d", n_pages, length);
+    if (n_pages > c->d.max_pages_per_seq)
+        MS_FAIL(MS_ERR_OOM_PAGES, "ms_seq_import: %d pages exceed max_pages_per_seq %d", n_pages, c->d.max_pages_per_seq);
+    std::set<int> seen;
+    for (int i = 0; i < n_pages; ++i) {
+        if (pages[i] < 0 || pages[i] >= c->d.n_pages || !c->free_pages.count(pages[i]) || !seen.insert(pages[i]).second)
+            MS_FAIL(MS_ERR_INVALID, "ms_seq_import: page %d is not free or is listed twice", pages[i]);
+    }
+    int s = -1;
+    int rc = ms_seq_create(c, &s);
+    if (rc != MS_OK) return rc;
+    for (int i = 0; i < n_pages; ++i) {
+        c->free_pages.erase(pages[i]);
+        c->pending_pt.push_back(s);
+        c->pending_pt.push_back(i);
+        c->pending_pt.push_back(pages[i]);
+        c->pt[s].push_back(pages[i]);
+    }
+    c->len[s] = length;
+    int in_use = c->d.n_pages - (int)c->free_pages.size();
+    if (in_use > c->peak_pages) c->peak_pages = in_use;
+    *seq_id = s;
+    return flush_page_table_patches(c, (hipStream_t)stream);
+}
+
+int ms_seq_free(ms_cache* c, int seq_id) {
+    if (!c) MS_FAIL(MS_ERR_INVALID, "ms_seq_free: null cache");
+    int rc = check_seq(c, seq_id, "ms_seq_free");
+    if (rc != MS_OK) return rc;
+    for (int p : c->pt[seq_id]) c->free_pages.insert(p);
+    c->pt[seq_id].clear();
+    c->len[seq_id] = 0;
+    c->live[seq_id] = 0;
+    return MS_OK;
+}
+
+// Shared by ms_append_kv and ms_commit_accepted: counts[b] rows per sequence, taken from buffer
+// rows src_first[b] .. of a packed buffer with `buf_layer_rows` rows per layer.
+static int append_rows(ms_cache* c, const char* what, int B, const int* seq_ids, const int* counts,
+                       const std::vector<int>& src_first, long buf_layer_rows, const void* k,
+                       const void* v, const int* pos, int rope, hipStream_t stream) {
+    long need = 0;
+    std::vector<int> extra(c->d.max_seqs, 0);  // a sequence may appear more than once in a call
+    for (int b = 0; b < B; ++b) {
+        int rc = check_seq(c, seq_ids[b], what);
+        if (rc != MS_OK) return rc;
+        if (counts[b] < 0) MS_FAIL(MS_ERR_INVALID, "%s: negative row count", what);
+        extra[seq_ids[b]] += counts[b];
+    }
+    for (int s = 0; s < c->d.max_seqs; ++s) {
+        if (!extra[s]) continue;
+        int np = pages_for((long)c->len[s] + extra[s]);
+        if (np > c->d.max_pages_per_seq)
+            MS_FAIL(MS_ERR_OOM_PAGES, "%s: sequence %d would need %d pages (max_pages_per_seq %d)", what, s, np,
+                    c->d.max_pages_per_seq);
+        need += np - (int)c->pt[s].size();
+    }
+    if (need > (long)c->free_pages.size())
+        MS_FAIL(MS_ERR_OOM_PAGES, "%s: needs %ld pages, %zu free", what, need, c->free_pages.size());
+    std::vector<RowDesc> desc;
+    int total = 0;
+    for (int b = 0; b < B; ++b) {
+        if (counts[b] == 0) continue;
+        RowDesc de{seq_ids[b], c->len[seq_ids[b]], src_first[b], total};
+        desc.push_back(de);
+        grow(c, seq_ids[b], counts[b]);
+        total += counts[b];
+    }
+    int rc = flush_page_table_patches(c, stream);
+    if (rc != MS_OK) return rc;
+    return launch_rows(c, false, desc, total, k, v, pos, buf_layer_rows, rope, stream);
+}
+
+int ms_append_kv(ms_cache* c, int B, const int* seq_ids, const int* n_tok, const void* k, const void* v,
+                 const int* pos_ids, int flags, void* stream) {
+    if (!c || B < 0 || (B > 0 && (!seq_ids || !n_tok))) MS_FAIL(MS_ERR_INVALID, "ms_append_kv: null argument");
+    if (B > MS_MAX_BATCH) MS_FAIL(MS_ERR_INVALID, "ms_append_kv: B %d exceeds %d", B, MS_MAX_BATCH);
+    if (flags != MS_PRE_ROTATED && flags != MS_ROPE_APPLY) MS_FAIL(MS_ERR_INVALID, "ms_append_kv: bad flags %d", flags);
+    long total = 0;
+    std::vector<int> first(B);
+    for (int b = 0; b < B; ++b) {
+        first[b] = (int)total;
+        total += n_tok[b] > 0 ? n_tok[b] : 0;
+    }
+    if (total > 0 && (!k || !v)) MS_FAIL(MS_ERR_INVALID, "ms_append_kv: k or v is null");
+    if (total > 0 && flags == MS_ROPE_APPLY && !pos_ids) MS_FAIL(MS_ERR_INVALID, "ms_append_kv: pos_ids is null");
+    return append_rows(c, "ms_append_kv", B, seq_ids, n_tok, first, total, k, v, pos_ids, flags == MS_ROPE_APPLY,
+                       (hipStream_t)stream);
+}
+
+int ms_commit_accepted(ms_cache* c, int B, const int* seq_ids, const int* accept_len, int n_q, const void* k_new,
+                       const void* v_new, const int* pos_ids, void* stream) {
+    if (!c || B < 0 || (B > 0 && (!seq_ids || !accept_len))) MS_FAIL(MS_ERR_INVALID, "ms_commit_accepted: null argument");
+    if (B > MS_MAX_BATCH) MS_FAIL(MS_ERR_INVALID, "ms_commit_accepted: B %d exceeds %d", B, MS_MAX_BATCH);
+    if (n_q < 1 || n_q > MS_MAX_QUERIES) MS_FAIL(MS_ERR_INVALID, "ms_commit_accepted: n_q %d out of range", n_q);
+    std::vector<int> first(B);
+    bool any = false;
+    for (int b = 0; b < B; ++b) {
+        if (accept_len[b] < 0 || accept_len[b] > n_q)
+            MS_FAIL(MS_ERR_RANGE, "ms_commit_accepted: accept_len[%d] = %d outside [0, %d]", b, accept_len[b], n_q);
+        first[b] = b * n_q;
+        any |= accept_len[b] > 0;
+    }
+    if (any && (!k_new || !v_new || !pos_ids)) MS_FAIL(MS_ERR_INVALID, "ms_commit_accepted: null tensor");
+    return append_rows(c, "ms_commit_accepted", B, seq_ids, accept_len, first, (long)B * n_q, k_new, v_new, pos_ids, 1,
+                       (hipStream_t)stream);
+}
+
+size_t ms_compact_workspace_bytes(ms_cache* c, int B, const int* seq_ids, const int* seg_begin, const int* seg_len) {
+    if (!c || B < 0 || (B > 0 && (!seq_ids || !seg_begin || !seg_len))) return 0;
+    std::vector<int> cur(c->len);
+    long tail = 0;
+    for (int b = 0; b < B; ++b) {
+        int s = seq_ids[b];
+        if (s < 0 || s >= c->d.max_seqs || !c->live[s]) return 0;
+        long t = (long)cur[s] - seg_begin[b] - seg_len[b];
+        if (t > 0) tail += t;
+    }
+    return (size_t)tail * 2 * c->d.n_layers * c->d.n_kv_heads * c->d.head_dim * c->esize;
+}
+
+int ms_compact_segment(ms_cache* c, int B, const int* seq_ids, const int* seg_begin, const int* seg_len,
+                       const int* n_mem, const void* mem_k, const void* mem_v, const int* mem_pos, int flags,
+                       void* workspace, size_t ws_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!c || B < 0 || (B > 0 && (!seq_ids || !seg_begin || !seg_len || !n_mem)))
+        MS_FAIL(MS_ERR_INVALID, "ms_compact_segment: null argument");
+    if (B > MS_MAX_BATCH) MS_FAIL(MS_ERR_INVALID, "ms_compact_segment: B %d exceeds %d", B, MS_MAX_BATCH);
+    if (flags != MS_PRE_ROTATED && flags != MS_ROPE_APPLY) MS_FAIL(MS_ERR_INVALID, "ms_compact_segment: bad flags %d", flags);
+    // ---- validate everything on a simulated copy of the lengths / page counts ----
+    std::vector<int> sim_len(c->len);
+    std::vector<int> sim_pages(c->d.max_seqs);
+    for (int s = 0; s < c->d.max_seqs; ++s) sim_pages[s] = (int)c->pt[s].size();
+    long sim_free = (long)c->free_pages.size();
+    long total_mem = 0, total_tail = 0;
+    for (int b = 0; b < B; ++b) {
+        int rc = check_seq(c, seq_ids[b], "ms_compact_segment");
+        if (rc != MS_OK) return rc;
+        const int s = seq_ids[b], L = sim_len[s];
+        if (seg_begin[b] < 0 || seg_len[b] < 0 || n_mem[b] < 0 || (long)seg_begin[b] + seg_len[b] > L)
+            MS_FAIL(MS_ERR_RANGE, "ms_compact_segment: segment [%d, %d+%d) outside sequence %d of length %d", seg_begin[b],
+                    seg_begin[b], seg_len[b], s, L);
+        const int keep = pages_for(seg_begin[b]);
+        const int new_len = L - seg_len[b] + n_mem[b];
+        const int np = pages_for(new_len);
+        if (np > c->d.max_pages_per_seq)
+            MS_FAIL(MS_ERR_OOM_PAGES, "ms_compact_segment: sequence %d would need %d pages", s, np);
+        sim_free += sim_pages[s] - keep;
+        sim_free -= np - keep;
+        if (sim_free < 0) MS_FAIL(MS_ERR_OOM_PAGES, "ms_compact_segment: pool exhausted");
+        sim_pages[s] = np;
+        sim_len[s] = new_len;
+        total_mem += n_mem[b];
+        total_tail += L - seg_begin[b] - seg_len[b];
+    }
+    if (total_mem > 0 && (!mem_k || !mem_v)) MS_FAIL(MS_ERR_INVALID, "ms_compact_segment: mem_k or mem_v is null");
+    if (total_mem > 0 && flags == MS_ROPE_APPLY && !mem_pos) MS_FAIL(MS_ERR_INVALID, "ms_compact_segment: mem_pos is null");
+    const size_t row_bytes = (size_t)c->d.n_kv_heads * c->d.head_dim * c->esize;
+    const size_t need_ws = (size_t)total_tail * 2 * c->d.n_layers * row_bytes;
+    if (total_tail > 0 && (!workspace || ws_bytes < need_ws))
+        MS_FAIL(MS_ERR_WORKSPACE, "ms_compact_segment: rows follow a segment; workspace needs %zu bytes, has %zu", need_ws,
+                workspace ? ws_bytes : (size_t)0);
+    char* tail_k = (char*)workspace;
+    char* tail_v = tail_k + (size_t)total_tail * c->d.n_layers * row_bytes;
+
+    // ---- 1. save rows that follow each segment (old page tables still in the mirror) ----
+    // A sequence listed twice would need its first splice applied before its second gather.
+    std::vector<char> seen(c->d.max_seqs, 0);
+    for (int b = 0; b < B; ++b) {
+        if (seen[seq_ids[b]]) MS_FAIL(MS_ERR_INVALID, "ms_compact_segment: sequence %d is listed twice", seq_ids[b]);
+        seen[seq_ids[b]] = 1;
+    }
+    std::vector<RowDesc> tails;
+    int tprefix = 0;
+    for (int b = 0; b < B; ++b) {
+        const int s = seq_ids[b];
+        const int t = c->len[s] - seg_begin[b] - seg_len[b];
+        if (t > 0) {
+            tails.push_back(RowDesc{s, seg_begin[b] + seg_len[b], tprefix, tprefix});
+            tprefix += t;
+        }
+    }
+    int rc = launch_rows(c, true, tails, (int)total_tail, tail_k, tail_v, nullptr, total_tail, 0, stream);
+    if (rc != MS_OK) return rc;
+
+    // ---- 2. host page tables: release, then re-grow (memory rows, then tail rows) ----
+    std::vector<RowDesc> mems;
+    std::vector<RowDesc> tails_dst;
+    int mprefix = 0, moff = 0, tp2 = 0;
+    for (int b = 0; b < B; ++b) {
+        const int s = seq_ids[b];
+        const int L = c->len[s];
+        const int t = L - seg_begin[b] - seg_len[b];
+        const int keep = pages_for(seg_begin[b]);
+        for (size_t i = keep; i < c->pt[s].size(); ++i) c->free_pages.insert(c->pt[s][i]);
+        c->pt[s].resize(keep);
+        c->len[s] = seg_begin[b];
+        if (n_mem[b] > 0) {
+            mems.push_back(RowDesc{s, c->len[s], moff, mprefix});
+            mprefix += n_mem[b];
+        }
+        grow(c, s, n_mem[b]);
+        moff += n_mem[b];
+        if (t > 0) {
+            tails_dst.push_back(RowDesc{s, c->len[s], tp2, tp2});
+            tp2 += t;
+        }
+        grow(c, s, t);
+    }
+    rc = flush_page_table_patches(c, stream);
+    if (rc != MS_OK) return rc;
+    // ---- 3. scatter memory rows (rotated at their UPL position ids), then the saved tails ----
+    rc = launch_rows(c, false, mems, (int)total_mem, mem_k, mem_v, mem_pos, total_mem, flags == MS_ROPE_APPLY, stream);
+    if (rc != MS_OK) return rc;
+    return launch_rows(c, false, tails_dst, (int)total_tail, tail_k, tail_v, nullptr, total_tail, 0, stream);
+}
+
+int ms_seq_len(ms_cache* c, int seq_id, int* len) {
+    if (!c || !len) MS_FAIL(MS_ERR_INVALID, "ms_seq_len: null argument");
+    int rc = check_seq(c, seq_id, "ms_seq_len");
+    if (rc != MS_OK) return rc;
+    *len = c->len[seq_id];
+    return MS_OK;
+}
+
+int ms_seq_page_table(ms_cache* c, int seq_id, int* out, int cap, int* n) {
+    if (!c || !n || (cap > 0 && !out)) MS_FAIL(MS_ERR_INVALID, "ms_seq_page_table: null argument");
+    int rc = check_seq(c, seq_id, "ms_seq_page_table");
+    if (rc != MS_OK) return rc;
+    *n = (int)c->pt[seq_id].size();
+    for (int i = 0; i < *n && i < cap; ++i) out[i] = c->pt[seq_id][i];
+    return MS_OK;
+}
+
+int ms_free_page_count(ms_cache* c, int* n) {
+    if (!c || !n) MS_FAIL(MS_ERR_INVALID, "ms_free_page_count: null argument");
+    *n = (int)c->free_pages.size();
+    return MS_OK;
+}
+
+int ms_peak_pages(ms_cache* c, int* n) {
+    if (!c || !n) MS_FAIL(MS_ERR_INVALID, "ms_peak_pages: null argument");
+    *n = c->peak_pages;
+    return MS_OK;
+}
+
+int ms_check_integrity(ms_cache* c, void* stream) {
+    if (!c) MS_FAIL(MS_ERR_INVALID, "ms_check_integrity: null cache");
+    std::vector<char> owner(c->d.n_pages, 0);
+    for (int s = 0; s < c->d.max_seqs; ++s) {
+        if (!c->live[s]) {
+            if (!c->pt[s].empty()) MS_FAIL(MS_ERR_INVALID, "integrity: dead sequence %d owns pages", s);
+            continue;
+        }
+        if ((int)c->pt[s].size() != pages_for(c->len[s]))
+            MS_FAIL(MS_ERR_INVALID, "integrity: sequence %d has %zu pages for %d rows", s, c->pt[s].size(), c->len[s]);
+        for (int p : c->pt[s]) {
+            if (p < 0 || p >= c->d.n_pages) MS_FAIL(MS_ERR_INVALID, "integrity: page id %d out of range", p);
+            if (owner[p]++) MS_FAIL(MS_ERR_INVALID, "integrity: page %d owned twice", p);
+        }
+    }
+    for (int p : c->free_pages)
+        if (owner[p]++) MS_FAIL(MS_ERR_INVALID, "integrity: page %d both free and owned", p);
+    for (int p = 0; p < c->d.n_pages; ++p)
+        if (!owner[p]) MS_FAIL(MS_ERR_INVALID, "integrity: page %d leaked", p);
+    if (!c->pending_pt.empty()) MS_FAIL(MS_ERR_INVALID, "integrity: page-table patches not flushed");
+    MS_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    std::vector<int> row(c->d.max_pages_per_seq);
+    for (int s = 0; s < c->d.max_seqs; ++s) {
+        if (!c->live[s] || c->pt[s].empty()) continue;
+        MS_HIP_TRY(hipMemcpy(row.data(), c->d_pt + (size_t)s * c->d.max_pages_per_seq, c->pt[s].size() * sizeof(int),
+                             hipMemcpyDeviceToHost));
+        for (size_t i = 0; i < c->pt[s].size(); ++i)
+            if (row[i] != c->pt[s][i])
+                MS_FAIL(MS_ERR_INVALID, "integrity: device mirror of sequence %d differs at page %zu (%d vs %d)", s, i, row[i],
+                        c->pt[s][i]);
+    }
+    return MS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,83 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <set>
+#include <vector>
+
+#include "memosight.h"
+
+namespace ms {
+
+void set_error(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
+void clear_error();
+
+#define MS_FAIL(code, ...)          \
+    do {                            \
+        ::ms::set_error(__VA_ARGS__); \
+        return (code);              \
+    } while (0)
+
+#define MS_HIP_TRY(expr)                                                               \
+    do {                                                                               \
+        hipError_t e_ = (expr);                                                        \
+        if (e_ != hipSuccess) {                                                        \
+            ::ms::set_error("%s failed: %s", #expr, hipGetErrorString(e_));            \
+            return MS_ERR_HIP;                                                         \
+        }                                                                              \
+    } while (0)
+
+// Pinned-host + device staging ring for small control uploads.  A slot's pinned half may be
+// rewritten once the event recorded after its copy has completed; the device half is only
+// rewritten by a later copy on the same stream, i.e. after every kernel that read it.
+struct StageRing {
+    static constexpr int kSlots = 16;
+    static constexpr size_t kSlotBytes = 256 * 1024;
+    char* h = nullptr;
+    char* d = nullptr;
+    hipEvent_t ev[kSlots] = {};
+    bool used[kSlots] = {};
+    int next = 0;
+    int init();
+    void destroy();
+    // Copies `bytes` (<= kSlotBytes) to a device slot on `stream`; *dev receives the slot address.
+    int upload(const void* src, size_t bytes, hipStream_t stream, void** dev);
+};
+
+// Which rows of a packed [rows][Hkv][D] buffer go to / come from which logical cache rows.
+struct RowDesc {
+    int seq;          // sequence id
+    int cache_begin;  // logical cache row of this sequence's first row in the call
+    int buf_first;    // row index of that first row in the packed buffer (per layer)
+    int prefix;       // number of rows of earlier sequences in this call
+};
+
+}  // namespace ms
+
+struct ms_cache {
+    ms_cache_desc d;
+    int device = 0;
+    int group = 1;               // query heads per KV head
+    size_t esize = 2;            // bytes per element
+    size_t page_elems = 0;       // elements per page (all heads, K and V)
+    size_t layer_elems = 0;      // elements per layer
+    std::set<int> free_pages;    // ordered: *begin() is the lowest free page
+    std::vector<std::vector<int>> pt;
+    std::vector<int> len;
+    std::vector<char> live;
+    int peak_pages = 0;
+    int* d_pt = nullptr;         // device mirror [max_seqs][max_pages_per_seq]
+    float* d_inv_freq = nullptr; // device [head_dim / 2]
+    ms::StageRing stage;
+    std::vector<int> pending_pt; // (seq, index, page) triples not yet sent to the mirror
+};
+
+namespace ms {
+
+// cache.hip
+int flush_page_table_patches(ms_cache* c, hipStream_t stream);
+int check_seq(const ms_cache* c, int seq, const char* what);
+
+}  // namespace ms

@@ -1,0 +1,70 @@
+"""CPU-side checks of the C-ABI library: it loads, exports everything the header declares, and its
+pure host helpers agree with the paper's printed values.  No GPU compute is called here."""
+import os
+import re
+
+import pytest
+
+from paper_2604_14889_amd import binding as M
+from tests.test_oracle_layout import G
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "memosight.h")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ms_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    syms = declared_symbols()
+    assert len(syms) >= 20
+    for s in syms:
+        assert hasattr(M.lib, s), f"{s} declared in memosight.h but not exported"
+    assert sorted(M.EXPORTED) == syms
+
+
+def test_helpers_match_paper_values():
+    inp, exp = G["upl"]
+    assert M.ms_upl_positions(inp["first_pid"], inp["n"], inp["c"]) == [exp]
+    inp, exp = G["ama"]
+    assert M.ms_ama_count(inp["n"], inp["c"]) == exp
+    inp, exp = G["ama_long"]
+    assert M.ms_ama_count(inp["n"], inp["c"]) == exp
+    inp, exp = G["output_pid"]
+    assert M.ms_output_token_pid(inp["last_pid"]) == exp
+    inp, exp = G["foresight_pid"]
+    assert M.ms_foresight_pids(exp - 1, 1) == [exp]
+    inp, exp = G["drafts_per_pass"]
+    assert 1 + len(M.ms_foresight_pids(7, inp["d"])) == exp
+
+
+def test_helpers_match_oracle_exhaustively():
+    from oracle import memosight_oracle as O
+    for c in range(1, 10):
+        for n in range(0, 70):
+            assert M.ms_ama_count(n, c) == O.ama_count(n, c)
+            for first in (0, 1, 257):
+                assert M.ms_upl_positions(first, n, c) == O.upl_positions(first, n, c)
+    for nv in range(0, 7):
+        for d in range(0, 6):
+            if nv + d == 0:
+                continue
+            assert M.ms_default_ctx_new(nv, d) == O.default_ctx_new(nv, d)
+            assert M.ms_foresight_pids(100 + nv, d) == O.foresight_pids(100 + nv, d)
+
+
+def test_bad_arguments_return_errors_not_crashes():
+    assert M.ms_ama_count(3, 0) < 0
+    d = M.make_desc(1, 8, 8, 64, 8, 2, 8, M.MS_F32, 10000.0)
+    assert M.ms_pool_bytes(d) == 1 * 8 * 8 * 2 * 16 * 64 * 4
+    bad = M.make_desc(1, 7, 4, 64, 8, 2, 8, M.MS_F32, 10000.0)        # 7 not a multiple of 4
+    assert M.ms_pool_bytes(bad) == 0
+    bad = M.make_desc(1, 8, 8, 96, 8, 2, 8, M.MS_F32, 10000.0)        # unsupported head_dim
+    assert M.ms_pool_bytes(bad) == 0
+    with pytest.raises(M.MsError) as e:
+        M.ms_cache_create(d)                                           # pool is NULL
+    assert e.value.code == M.MS_ERR_INVALID and "pool" in str(e.value)
+    with pytest.raises(M.MsError):
+        M.ms_accept(-1, 4, None, None, None, None, None)

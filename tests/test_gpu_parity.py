@@ -1,0 +1,597 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Tolerances (from the build target): page tables, lengths, accept lengths and tokens bit-exact;
+attention outputs max-abs <= 1e-5 for float32 caches, and max-abs <= 2e-2 with mean-rel <= 1e-2
+(mean |a-b| / mean |b| over the tensor) for bfloat16 caches against the fp64 oracle on the same
+bf16-valued inputs.  Stored K rows of bfloat16 caches may differ from the oracle by one bf16 ulp
+(fp32 vs fp64 rotation before the rounding); stored V rows are exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import memosight_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+F32_MAX_ABS = 1e-5
+BF16_MAX_ABS = 2e-2
+BF16_MEAN_REL = 1e-2
+
+
+def _mods():
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import session as S
+    return M, S
+
+
+def check_out(got: np.ndarray, want: np.ndarray, dtype: str, what: str = ""):
+    mask = ~np.isnan(want)
+    g, w = got[mask].astype(np.float64), want[mask]
+    max_abs = float(np.abs(g - w).max())
+    mean_rel = float(np.abs(g - w).mean() / max(np.abs(w).mean(), 1e-30))
+    if dtype == "f32":
+        assert max_abs <= F32_MAX_ABS, f"{what}: max-abs {max_abs:.3e}"
+    else:
+        assert max_abs <= BF16_MAX_ABS and mean_rel <= BF16_MEAN_REL, \
+            f"{what}: max-abs {max_abs:.3e} mean-rel {mean_rel:.3e}"
+    return max_abs, mean_rel
+
+
+
+def assert_k_rows_close(a: np.ndarray, b: np.ndarray):
+    """Stored bf16 K rows: at most one bf16 ulp from the oracle (fp32 vs fp64 rotation ahead of the
+    rounding), plus the fp32 rotation error itself where cancellation leaves a tiny result."""
+    bad = np.abs(a - b) > np.abs(b) * 2.0 ** -7 + 1e-6
+    assert not bad.any(), f"{int(bad.sum())} elements off, worst {float(np.abs(a - b).max()):.3e}"
+
+
+def as_f32(x: np.ndarray, dtype: str) -> np.ndarray:
+    return O.bf16_bits_to_f32(x) if dtype == "bf16" else x
+
+
+def pids_for(inp: W.AttnInputs, M):
+    """Position ids [B, n_q]: verify block consecutive from first_pid, foresight after it; from the
+    library's helper on the GPU side and the oracle's on the other, asserted equal."""
+    sh = inp.shape
+    rows_lib, rows_ora = [], []
+    for b in range(sh.batch):
+        ver = list(range(inp.first_pid[b], inp.first_pid[b] + sh.n_verify))
+        last = ver[-1] if ver else inp.first_pid[b] - 1
+        rows_lib.append(ver + M.ms_foresight_pids(last, sh.n_foresight))
+        rows_ora.append(ver + O.foresight_pids(last, sh.n_foresight))
+    assert rows_lib == rows_ora
+    return np.asarray(rows_ora, dtype=np.int32)
+
+
+def setup_pair(inp: W.AttnInputs, with_oracle_pool: bool = True):
+    """Session (GPU) and oracle cache holding the same imported sequences."""
+    M, S = _mods()
+    sh = inp.shape
+    dt = M.MS_BF16 if sh.dtype == "bf16" else M.MS_F32
+    max_pp = max(4, max(len(p) for p in inp.page_tables) + 2)
+    ses = S.Session(sh.n_layers, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.n_pages, dt, sh.rope_base,
+                    max_seqs=max(4, sh.batch), max_pages_per_seq=max_pp, pool=inp.pool)
+    ora = None
+    if with_oracle_pool:
+        ora = O.PagedCache(sh.n_layers, sh.n_kv_heads, sh.head_dim, sh.n_pages,
+                           dtype=O.BF16 if sh.dtype == "bf16" else O.F32, rope_base=sh.rope_base,
+                           max_seqs=max(4, sh.batch), pool=as_f32(inp.pool, sh.dtype).copy())
+    gids, oids = [], []
+    for n, pt in zip(sh.lengths, inp.page_tables):
+        gids.append(M.ms_seq_import(ses.cache, n, pt))
+        if ora is not None:
+            oids.append(ora.seq_import(n, pt))
+    if ora is not None:
+        assert gids == oids
+    return ses, ora, gids
+
+
+def run_gpu_attention(ses, inp, gids, pos, layer=0, ctx_new=None):
+    M, S = _mods()
+    sh = inp.shape
+    dt = M.MS_BF16 if sh.dtype == "bf16" else M.MS_F32
+    q, kn, vn = S.to_device(inp.q, dt), S.to_device(inp.k_new, dt), S.to_device(inp.v_new, dt)
+    cn = None if ctx_new is None else S.ints_dev(ctx_new).view(sh.batch, sh.n_q)
+    out = ses.attention(layer, gids, sh.n_verify, sh.n_foresight, q, kn, vn,
+                        S.ints_dev(pos).view(sh.batch, sh.n_q), cn)
+    torch.cuda.synchronize()
+    return S.to_host_f32(out)
+
+
+def oracle_attention(ora, inp, oids, pos, layer=0, ctx_new=None):
+    sh = inp.shape
+    return O.attention(ora, layer, oids, sh.n_verify, sh.n_foresight, as_f32(inp.q, sh.dtype),
+                       as_f32(inp.k_new, sh.dtype), as_f32(inp.v_new, sh.dtype), pos, ctx_new)
+
+
+# ------------------------------------------------------------------ attention, small shapes ---
+
+SMALL = [
+    # dtype, Hq, Hkv, D, n_verify, n_foresight, lengths
+    ("f32", 8, 8, 64, 4, 3, [80]),
+    ("f32", 4, 2, 128, 1, 0, [0, 1, 17, 200]),
+    ("f32", 6, 2, 64, 3, 2, [333, 64, 15]),
+    ("bf16", 28, 4, 128, 4, 3, [300, 1, 0, 129]),
+    ("bf16", 28, 4, 128, 5, 4, [1000, 2047, 16, 700]),
+    ("bf16", 8, 2, 64, 2, 5, [77, 500]),
+    ("bf16", 28, 4, 128, 0, 3, [260]),
+    ("bf16", 28, 4, 128, 9, 0, [515, 31]),
+    ("bf16", 4, 4, 128, 12, 4, [100, 1500]),
+]
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d,nv,nf,lengths", SMALL)
+def test_attention_small_shapes_match_oracle(dtype, hq, hkv, d, nv, nf, lengths):
+    M, S = _mods()
+    sh = W.AttnShape("small", dtype, len(lengths), hq, hkv, d, nv, nf, lengths,
+                     1.0 if dtype == "f32" else 0.5, 10000.0 if dtype == "f32" else 1000000.0, n_layers=2)
+    inp = W.attention_inputs(sh, 400, hq, d, nv, len(lengths))
+    ses, ora, ids = setup_pair(inp)
+    with ses:
+        pos = pids_for(inp, M)
+        for layer in (0, 1):
+            got = run_gpu_attention(ses, inp, ids, pos, layer)
+            want = oracle_attention(ora, inp, ids, pos, layer)
+            check_out(got, want, dtype, f"layer {layer}")
+        M.ms_check_integrity(ses.cache)
+
+
+def test_attention_custom_ctx_new_and_peaked_scores():
+    M, S = _mods()
+    sh = W.AttnShape("ctx", "bf16", 2, 28, 4, 128, 4, 3, [450, 130], 0.5, 1000000.0)
+    inp = W.attention_inputs(sh, 401, peaked=0.05)
+    ses, ora, ids = setup_pair(inp)
+    with ses:
+        pos = pids_for(inp, M)
+        # per-position foresight layout: foresight j hangs off verify token j (sees j+1 verify tokens)
+        ctx = np.asarray([[0, 1, 2, 3, 1, 2, 3], [0, 1, 2, 3, 4, 4, 4]], dtype=np.int32)
+        got = run_gpu_attention(ses, inp, ids, pos, ctx_new=ctx)
+        want = oracle_attention(ora, inp, ids, pos, ctx_new=ctx)
+        check_out(got, want, "bf16", "custom ctx_new, peaked")
+
+
+def test_gpu_foresight_rows_independent_and_page_permutation_invariant():
+    M, S = _mods()
+    sh = W.AttnShape("inv", "bf16", 1, 28, 4, 128, 4, 3, [700], 0.5, 1000000.0)
+    inp = W.attention_inputs(sh, 402)
+    ses, _, ids = setup_pair(inp, with_oracle_pool=False)
+    with ses:
+        pos = pids_for(inp, M)
+        base = run_gpu_attention(ses, inp, ids, pos)
+        inp2 = W.attention_inputs(sh, 402)
+        inp2.q[0, 5] ^= 0x0100          # perturb foresight query 5 and its key / value
+        inp2.k_new[0, 5] ^= 0x0080
+        inp2.v_new[0, 5] ^= 0x0040
+        got = run_gpu_attention(ses, inp2, ids, pos)
+        others = [0, 1, 2, 3, 4, 6]
+        assert np.array_equal(got[0, others], base[0, others])
+        assert not np.array_equal(got[0, 5], base[0, 5])
+    # same logical content under a different physical page placement: bit-identical output
+    rng = W.make_rng(4020)
+    perm = rng.permutation(sh.n_pages)
+    pool2 = np.zeros_like(inp.pool)
+    pool2[:, perm] = inp.pool
+    inp3 = W.AttnInputs(sh, [[int(perm[p]) for p in inp.page_tables[0]]], pool2, inp.q, inp.k_new, inp.v_new,
+                        inp.first_pid)
+    ses3, _, ids3 = setup_pair(inp3, with_oracle_pool=False)
+    with ses3:
+        got3 = run_gpu_attention(ses3, inp3, ids3, pos)
+    assert np.array_equal(got3, base)
+
+
+# ------------------------------------------------------------------ the named configurations ---
+
+def test_config1_fp32_built_through_append_and_compact():
+    """One layer, fp32, 8 heads x 64: four 64-token segments each compacted to 4 memory tokens
+    (c = 16), a 64-token live tail, then 4 verify + 3 foresight queries; acceptance on vocab 1000."""
+    M, S = _mods()
+    rng = W.make_rng(1)
+    H, D = 8, 64
+    ses = S.Session(1, H, H, D, 12, M.MS_F32, 10000.0, max_seqs=2, max_pages_per_seq=8)
+    ora = O.PagedCache(1, H, D, 12, dtype=O.F32, rope_base=10000.0, max_seqs=2)
+    with ses:
+        g, o = M.ms_seq_create(ses.cache), ora.seq_create()
+        assert g == o
+        pid = 1
+        for seg in range(4):
+            k, v = W.normal_f32(rng, (1, 64, H, D)), W.normal_f32(rng, (1, 64, H, D))
+            pos = list(range(pid, pid + 64))
+            begin = M.ms_seq_len(ses.cache, g)
+            M.ms_append_kv(ses.cache, [g], [64], S.to_device(k, M.MS_F32), S.to_device(v, M.MS_F32), S.ints_dev(pos))
+            ora.append([o], [64], k, v, pos)
+            l = M.ms_ama_count(64, 16)
+            assert l == O.ama_count(64, 16) == 4
+            mpos = M.ms_upl_positions(pid, 64, 16)
+            assert mpos == O.upl_positions(pid, 64, 16)
+            mk, mv = W.normal_f32(rng, (1, l, H, D)), W.normal_f32(rng, (1, l, H, D))
+            M.ms_compact_segment(ses.cache, [g], [begin], [64], [l], S.to_device(mk, M.MS_F32),
+                                 S.to_device(mv, M.MS_F32), S.ints_dev(mpos))
+            ora.compact([o], [begin], [64], [l], mk, mv, mpos)
+            assert M.ms_seq_len(ses.cache, g) == ora.seq_len[o] == 4 * (seg + 1)
+            assert M.ms_seq_page_table(ses.cache, g) == ora.page_table[o]
+            M.ms_check_integrity(ses.cache)
+            pid += 64
+        k, v = W.normal_f32(rng, (1, 64, H, D)), W.normal_f32(rng, (1, 64, H, D))
+        pos = list(range(257, 321))
+        M.ms_append_kv(ses.cache, [g], [64], S.to_device(k, M.MS_F32), S.to_device(v, M.MS_F32), S.ints_dev(pos))
+        ora.append([o], [64], k, v, pos)
+        assert M.ms_seq_len(ses.cache, g) == 80
+        assert M.ms_seq_page_table(ses.cache, g) == ora.page_table[o] == [0, 1, 2, 3, 4]
+        assert M.ms_free_page_count(ses.cache) == ora.free_page_count() == 7
+        assert M.ms_peak_pages(ses.cache) == ora.peak_pages
+        M.ms_check_integrity(ses.cache)
+        # stored rows
+        torch.cuda.synchronize()
+        gp = ses.pool_host_f32()
+        for p in ora.page_table[o]:
+            assert np.abs(gp[0, p] - ora.pool[0, p]).max() < 3e-6
+        # attention: PIDs 321..324 verify, 325..327 foresight
+        ver = list(range(321, 325))
+        fpos = M.ms_foresight_pids(ver[-1], 3)
+        assert fpos == O.foresight_pids(ver[-1], 3) == [325, 326, 327]
+        pos_q = np.asarray([ver + fpos], dtype=np.int32)
+        q = W.normal_f32(rng, (1, 7, H, D))
+        kn, vn = W.normal_f32(rng, (1, 7, H, D)), W.normal_f32(rng, (1, 7, H, D))
+        out = ses.attention(0, [g], 4, 3, S.to_device(q, M.MS_F32), S.to_device(kn, M.MS_F32),
+                            S.to_device(vn, M.MS_F32), S.ints_dev(pos_q).view(1, 7))
+        want = O.attention(ora, 0, [o], 4, 3, q, kn, vn, pos_q)
+        check_out(S.to_host_f32(out), want, "f32", "config 1")
+        # acceptance, every accepted length 0..4 forced plus free draws
+        forced = [0, 1, 2, 3, 4]
+        draft, target = W.draft_and_target(rng, 5, 4, 1000, forced)
+        d2, t2 = W.draft_and_target(rng, 27, 4, 1000)
+        draft, target = np.concatenate([draft, d2]), np.concatenate([target, t2])
+        acc, nxt = torch.empty(32, dtype=torch.int32, device="cuda"), torch.empty(32, dtype=torch.int32, device="cuda")
+        M.ms_accept(32, 4, S.ints_dev(draft), S.ints_dev(target), None, acc, nxt)
+        wa, wn = O.accept(draft, target)
+        assert np.array_equal(acc.cpu().numpy(), wa) and np.array_equal(nxt.cpu().numpy(), wn)
+        assert wa[:5].tolist() == forced
+
+
+def test_config2_bf16_batch1_4k_all_rows():
+    M, S = _mods()
+    sh = W.config2()
+    inp = W.attention_inputs(sh, 2)
+    assert inp.first_pid == [12289]
+    ses, ora, ids = setup_pair(inp)
+    with ses:
+        pos = pids_for(inp, M)
+        assert pos[0].tolist() == [12289, 12290, 12291, 12292, 12293, 12294, 12295]
+        got = run_gpu_attention(ses, inp, ids, pos)
+        want = oracle_attention(ora, inp, ids, pos)
+        print("config2 max-abs %.3e mean-rel %.3e" % check_out(got, want, "bf16", "config 2"))
+        inp_p = W.attention_inputs(sh, 2, peaked=0.01)
+    ses, ora, ids = setup_pair(inp_p)
+    with ses:
+        got = run_gpu_attention(ses, inp_p, ids, pos)
+        want = oracle_attention(ora, inp_p, ids, pos)
+        check_out(got, want, "bf16", "config 2 peaked")
+
+
+def sampled_rows_check(sh: W.AttnShape, stream: int, seqs_to_check, rows_per_seq: int):
+    """Full-size run on the GPU in the benchmark's launch configuration; the oracle computes sampled
+    (query, head) rows one by one, each over that sequence's whole cache."""
+    M, S = _mods()
+    inp = W.attention_inputs(sh, stream)
+    ses, ora, ids = setup_pair(inp)
+    with ses:
+        pos = pids_for(inp, M)
+        got = run_gpu_attention(ses, inp, ids, pos)
+        assert np.isfinite(got).all()
+        rng = W.make_rng(stream, 77)
+        worst = (0.0, 0.0)
+        for b in seqs_to_check:
+            rows = [(int(rng.integers(sh.n_q)), int(rng.integers(sh.n_q_heads))) for _ in range(rows_per_seq)]
+            rows += [(sh.n_q - 1, sh.n_q_heads - 1), (0, 0)]
+            want = O.attention_rows(ora, 0, ids[b], as_f32(inp.q[b], "bf16"), as_f32(inp.k_new[b], "bf16"),
+                                    as_f32(inp.v_new[b], "bf16"), pos[b],
+                                    O.default_ctx_new(sh.n_verify, sh.n_foresight), rows=rows)
+            r = check_out(got[b], want, "bf16", f"{sh.name} seq {b} len {sh.lengths[b]}")
+            worst = (max(worst[0], r[0]), max(worst[1], r[1]))
+        print(f"{sh.name}: sampled max-abs {worst[0]:.3e} mean-rel {worst[1]:.3e}")
+        M.ms_check_integrity(ses.cache)
+
+
+def test_config3_ragged_batch32_sampled():
+    sh = W.config3()
+    order = np.argsort(sh.lengths)
+    picks = [int(order[0]), int(order[-1]), int(order[len(order) // 2]), 0, 31]
+    sampled_rows_check(sh, 3, picks, 4)
+
+
+def test_metric_point_batch32_kv8192_sampled():
+    sampled_rows_check(W.metric_point(), 5, [0, 13, 31], 4)
+
+
+# ------------------------------------------------------------------ append / commit ----------
+
+def test_append_bf16_rows_and_page_tables():
+    M, S = _mods()
+    rng = W.make_rng(410)
+    L, Hkv, D, NP = 3, 4, 128, 40
+    ses = S.Session(L, 28, Hkv, D, NP, M.MS_BF16, 1000000.0, max_seqs=4, max_pages_per_seq=16)
+    ora = O.PagedCache(L, Hkv, D, NP, dtype=O.BF16, rope_base=1000000.0, max_seqs=4)
+    with ses:
+        gs = [M.ms_seq_create(ses.cache) for _ in range(3)]
+        os_ = [ora.seq_create() for _ in range(3)]
+        assert gs == os_
+        for step, counts in enumerate([[5, 40, 16], [30, 1, 0], [13, 7, 100]]):
+            n = sum(counts)
+            k, v = W.normal_bf16_bits(rng, (L, n, Hkv, D)), W.normal_bf16_bits(rng, (L, n, Hkv, D))
+            pos = rng.integers(0, 50000, size=n).astype(np.int32)
+            order = [2, 0, 1] if step == 1 else [0, 1, 2]
+            sid = [gs[i] for i in order]
+            cnt = [counts[i] for i in order]
+            M.ms_append_kv(ses.cache, sid, cnt, S.to_device(k, M.MS_BF16), S.to_device(v, M.MS_BF16), S.ints_dev(pos))
+            ora.append(sid, cnt, O.bf16_bits_to_f32(k), O.bf16_bits_to_f32(v), pos)
+            for s in gs:
+                assert M.ms_seq_page_table(ses.cache, s) == ora.page_table[s]
+                assert M.ms_seq_len(ses.cache, s) == ora.seq_len[s]
+            M.ms_check_integrity(ses.cache)
+        torch.cuda.synchronize()
+        gp = ses.pool_host_f32()
+        n_diff = n_tot = 0
+        for s in gs:
+            for li in range(L):
+                for t in range(ora.seq_len[s]):
+                    p, sl = ora.page_table[s][t // 16], t % 16
+                    assert np.array_equal(gp[li, p, :, 1, sl], ora.pool[li, p, :, 1, sl])          # V exact
+                    a, b = gp[li, p, :, 0, sl], ora.pool[li, p, :, 0, sl]
+                    assert_k_rows_close(a, b)
+                    n_diff += int((a != b).sum())
+                    n_tot += a.size
+        assert n_diff <= 0.01 * n_tot, (n_diff, n_tot)
+
+
+def test_commit_accepted_appends_only_accepted_verify_rows():
+    M, S = _mods()
+    rng = W.make_rng(411)
+    L, Hq, Hkv, D, NP, B, nq = 2, 28, 4, 128, 24, 4, 7
+    ses = S.Session(L, Hq, Hkv, D, NP, M.MS_BF16, 1000000.0, max_seqs=4, max_pages_per_seq=8)
+    ora = O.PagedCache(L, Hkv, D, NP, dtype=O.BF16, rope_base=1000000.0, max_seqs=4)
+    with ses:
+        gs = [M.ms_seq_create(ses.cache) for _ in range(B)]
+        for _ in range(B):
+            ora.seq_create()
+        start = [14, 15, 16, 30]
+        n = sum(start)
+        k, v = W.normal_bf16_bits(rng, (L, n, Hkv, D)), W.normal_bf16_bits(rng, (L, n, Hkv, D))
+        pos = np.arange(n, dtype=np.int32)
+        M.ms_append_kv(ses.cache, gs, start, S.to_device(k, M.MS_BF16), S.to_device(v, M.MS_BF16), S.ints_dev(pos))
+        ora.append(gs, start, O.bf16_bits_to_f32(k), O.bf16_bits_to_f32(v), pos)
+        kn, vn = W.normal_bf16_bits(rng, (L, B, nq, Hkv, D)), W.normal_bf16_bits(rng, (L, B, nq, Hkv, D))
+        pq = (np.arange(nq)[None] + np.asarray([100, 200, 300, 400])[:, None]).astype(np.int32)
+        acc = [4, 0, 1, 3]
+        M.ms_commit_accepted(ses.cache, gs, acc, nq, S.to_device(kn, M.MS_BF16), S.to_device(vn, M.MS_BF16),
+                             S.ints_dev(pq).view(B, nq))
+        knf, vnf = O.bf16_bits_to_f32(kn), O.bf16_bits_to_f32(vn)
+        for b in range(B):          # oracle: plain append of the accepted rows, sequence by sequence
+            ora.append([gs[b]], [acc[b]], knf[:, b, :acc[b]], vnf[:, b, :acc[b]], pq[b, :acc[b]])
+        torch.cuda.synchronize()
+        gp = ses.pool_host_f32()
+        for s in gs:
+            assert M.ms_seq_page_table(ses.cache, s) == ora.page_table[s]
+            assert M.ms_seq_len(ses.cache, s) == ora.seq_len[s]
+            for li in range(L):
+                for t in range(ora.seq_len[s]):
+                    p, sl = ora.page_table[s][t // 16], t % 16
+                    assert np.array_equal(gp[li, p, :, 1, sl], ora.pool[li, p, :, 1, sl])
+                    a, b_ = gp[li, p, :, 0, sl], ora.pool[li, p, :, 0, sl]
+                    assert_k_rows_close(a, b_)
+        M.ms_check_integrity(ses.cache)
+
+
+# ------------------------------------------------------------------ compaction ---------------
+
+def test_config4_page_tables_batch16_28_layers():
+    """Batch 16, 28 layers: each sequence closes a 256-token segment (16 whole pages released) and
+    keeps 8 memory tokens in fresh pages.  Page tables, lengths and free counts must equal the
+    oracle's; memory-token rows are checked in sampled layers."""
+    M, S = _mods()
+    rng = W.make_rng(4)
+    B, L, Hq, Hkv, D = 16, 28, 28, 4, 128
+    lens = [int(16 * x) for x in rng.integers(2304 // 16, 8448 // 16 + 1, size=B)]
+    shape = W.AttnShape("c4", "bf16", B, Hq, Hkv, D, 4, 3, lens, 0.5, 1000000.0, n_layers=L, slack_pages=0.02)
+    pts = W.shuffled_page_tables(rng, shape.n_pages, lens)
+    ses = S.Session(L, Hq, Hkv, D, shape.n_pages, M.MS_BF16, 1000000.0, max_seqs=B, max_pages_per_seq=600)
+    ora = O.PagedCache(1, 1, 8, shape.n_pages, dtype=O.BF16, max_seqs=B)     # tables only
+    with ses:
+        gs = [M.ms_seq_import(ses.cache, n, pt) for n, pt in zip(lens, pts)]
+        os_ = [ora.seq_import(n, pt) for n, pt in zip(lens, pts)]
+        assert gs == os_
+        c = 32
+        n_mem = [M.ms_ama_count(256, c)] * B
+        assert n_mem[0] == 8
+        begin = [n - 256 for n in lens]
+        first_pid = [3 * n for n in lens]
+        mpos = sum((M.ms_upl_positions(fp, 256, c) for fp in first_pid), [])
+        assert mpos == sum((O.upl_positions(fp, 256, c) for fp in first_pid), [])
+        mk = W.normal_bf16_bits(rng, (L, 8 * B, Hkv, D))
+        mv = W.normal_bf16_bits(rng, (L, 8 * B, Hkv, D))
+        free_before = M.ms_free_page_count(ses.cache)
+        M.ms_compact_segment(ses.cache, gs, begin, [256] * B, n_mem, S.to_device(mk, M.MS_BF16),
+                             S.to_device(mv, M.MS_BF16), S.ints_dev(mpos))
+        ora.compact(os_, begin, [256] * B, n_mem, np.zeros((1, 8 * B, 1, 8)), np.zeros((1, 8 * B, 1, 8)), mpos)
+        assert M.ms_free_page_count(ses.cache) == ora.free_page_count() == free_before + 15 * B
+        for s in gs:
+            assert M.ms_seq_page_table(ses.cache, s) == ora.page_table[s]
+            assert M.ms_seq_len(ses.cache, s) == ora.seq_len[s]
+        M.ms_check_integrity(ses.cache)
+        torch.cuda.synchronize()
+        inv = O.rope_inv_freq(D, 1000000.0)
+        for li in (0, 13, 27):
+            want_k = O.round_bf16(O.rope(O.bf16_bits_to_f32(mk[li]), np.asarray(mpos)[:, None], inv).astype(np.float32))
+            for b in (0, 7, 15):
+                s = gs[b]
+                for j in range(8):
+                    t = begin[b] + j
+                    p, sl = ora.page_table[s][t // 16], t % 16
+                    row = S.to_host_f32(ses.pool[li, p, :, :, sl])          # [Hkv, 2, D]
+                    assert np.array_equal(row[:, 1], O.bf16_bits_to_f32(mv[li, 8 * b + j]))
+                    wk = want_k[8 * b + j]
+                    assert_k_rows_close(row[:, 0], wk)
+
+
+def test_compaction_content_attention_and_recompute_equivalence():
+    """Reduced config 4 (2 layers, batch 4) with real data: after compaction the cache rows and the
+    attention over them match the oracle, and match a GPU cache rebuilt from the kept rows only."""
+    M, S = _mods()
+    rng = W.make_rng(41)
+    B, L, Hq, Hkv, D = 4, 2, 28, 4, 128
+    lens = [1024 + 256, 2048 + 256, 640 + 256, 1296 + 256]
+    sh = W.AttnShape("c4small", "bf16", B, Hq, Hkv, D, 4, 3, lens, 0.5, 1000000.0, n_layers=L)
+    inp = W.attention_inputs(sh, 41)
+    ses, ora, ids = setup_pair(inp)
+    with ses:
+        n_mem = [8] * B
+        begin = [n - 256 for n in lens]
+        mpos = sum((M.ms_upl_positions(3 * n, 256, 32) for n in lens), [])
+        mk = W.normal_bf16_bits(rng, (L, 8 * B, Hkv, D))
+        mv = W.normal_bf16_bits(rng, (L, 8 * B, Hkv, D))
+        M.ms_compact_segment(ses.cache, ids, begin, [256] * B, n_mem, S.to_device(mk, M.MS_BF16),
+                             S.to_device(mv, M.MS_BF16), S.ints_dev(mpos))
+        ora.compact(ids, begin, [256] * B, n_mem, O.bf16_bits_to_f32(mk), O.bf16_bits_to_f32(mv), mpos)
+        for s in ids:
+            assert M.ms_seq_page_table(ses.cache, s) == ora.page_table[s]
+            assert M.ms_seq_len(ses.cache, s) == ora.seq_len[s] == lens[s] - 256 + 8
+        M.ms_check_integrity(ses.cache)
+        sh2 = W.AttnShape("c4small", "bf16", B, Hq, Hkv, D, 4, 3, [n - 248 for n in lens], 0.5, 1000000.0, n_layers=L)
+        inp2 = W.AttnInputs(sh2, inp.page_tables, inp.pool, inp.q, inp.k_new, inp.v_new,
+                            [3 * n + 1 for n in lens])
+        pos = pids_for(inp2, M)
+        outs = []
+        for layer in range(L):
+            got = run_gpu_attention(ses, inp2, ids, pos, layer)
+            want = oracle_attention(ora, inp2, ids, pos, layer)
+            check_out(got, want, "bf16", f"after compaction, layer {layer}")
+            outs.append(got)
+        # rebuild on the GPU from the kept rows only (download, re-append pre-rotated)
+        torch.cuda.synchronize()
+        gp = ses.pool.view(torch.int16).cpu().numpy().view(np.uint16)
+        tables = ses.page_tables(ids)
+        new_lens = ses.lengths(ids)
+    ses2 = S.Session(L, Hq, Hkv, D, sh.n_pages, M.MS_BF16, 1000000.0, max_seqs=B, max_pages_per_seq=200)
+    with ses2:
+        ids2 = [M.ms_seq_create(ses2.cache) for _ in range(B)]
+        for b in range(B):
+            pt = np.asarray(tables[b])
+            rows = gp[:, pt].transpose(0, 1, 4, 2, 3, 5).reshape(L, -1, Hkv, 2, D)[:, :new_lens[b]]
+            k = np.ascontiguousarray(rows[:, :, :, 0])
+            v = np.ascontiguousarray(rows[:, :, :, 1])
+            M.ms_append_kv(ses2.cache, [ids2[b]], [new_lens[b]], S.to_device(k, M.MS_BF16), S.to_device(v, M.MS_BF16),
+                           None, flags=M.MS_PRE_ROTATED)
+        for layer in range(L):
+            again = run_gpu_attention(ses2, inp2, ids2, pos, layer)
+            assert np.array_equal(again, outs[layer]), "compaction must equal recomputation over the kept KV"
+
+
+def test_compaction_in_the_middle_moves_the_tail():
+    M, S = _mods()
+    rng = W.make_rng(412)
+    L, Hkv, D, NP = 2, 2, 64, 16
+    ses = S.Session(L, 4, Hkv, D, NP, M.MS_F32, 10000.0, max_seqs=2, max_pages_per_seq=8)
+    ora = O.PagedCache(L, Hkv, D, NP, dtype=O.F32, rope_base=10000.0, max_seqs=2)
+    with ses:
+        gs = [M.ms_seq_create(ses.cache), M.ms_seq_create(ses.cache)]
+        ora.seq_create(), ora.seq_create()
+        counts = [50, 37]
+        k, v = W.normal_f32(rng, (L, 87, Hkv, D)), W.normal_f32(rng, (L, 87, Hkv, D))
+        pos = np.arange(87, dtype=np.int32)
+        M.ms_append_kv(ses.cache, gs, counts, S.to_device(k, M.MS_F32), S.to_device(v, M.MS_F32), S.ints_dev(pos))
+        ora.append(gs, counts, k, v, pos)
+        mk, mv = W.normal_f32(rng, (L, 5, Hkv, D)), W.normal_f32(rng, (L, 5, Hkv, D))
+        mpos = [12, 17, 22, 3, 9]
+        args = (gs, [10, 2], [25, 20], [3, 2])
+        need = M.ms_compact_workspace_bytes(ses.cache, *args[:3])
+        assert need == (15 + 15) * 2 * L * Hkv * D * 4
+        with pytest.raises(M.MsError) as e:
+            M.ms_compact_segment(ses.cache, *args, S.to_device(mk, M.MS_F32), S.to_device(mv, M.MS_F32), S.ints_dev(mpos))
+        assert e.value.code == M.MS_ERR_WORKSPACE
+        assert M.ms_seq_len(ses.cache, gs[0]) == 50                      # unchanged by the failed call
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        M.ms_compact_segment(ses.cache, *args, S.to_device(mk, M.MS_F32), S.to_device(mv, M.MS_F32), S.ints_dev(mpos),
+                             workspace=ws)
+        ora.compact(*args, mk, mv, mpos)
+        torch.cuda.synchronize()
+        gp = ses.pool_host_f32()
+        for s in gs:
+            assert M.ms_seq_page_table(ses.cache, s) == ora.page_table[s]
+            assert M.ms_seq_len(ses.cache, s) == ora.seq_len[s]
+            for li in range(L):
+                for t in range(ora.seq_len[s]):
+                    p, sl = ora.page_table[s][t // 16], t % 16
+                    assert np.abs(gp[li, p, :, :, sl] - ora.pool[li, p, :, :, sl]).max() < 3e-6
+        M.ms_check_integrity(ses.cache)
+
+
+# ------------------------------------------------------------------ acceptance ---------------
+
+def test_accept_matches_oracle_including_stop_ids():
+    M, S = _mods()
+    rng = W.make_rng(413)
+    for n in (1, 4, 5, 9):
+        B = 200
+        forced = [int(x) for x in rng.integers(0, n + 1, size=B)]
+        draft, target = W.draft_and_target(rng, B, n, 50, forced)
+        for stops in (None, [7, 11, 13]):
+            acc = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+            nxt = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+            M.ms_accept(B, n, S.ints_dev(draft), S.ints_dev(target), None if stops is None else S.ints_dev(stops), acc, nxt)
+            wa, wn = O.accept(draft, target, stops or ())
+            assert np.array_equal(acc.cpu().numpy(), wa)
+            assert np.array_equal(nxt.cpu().numpy(), wn)
+            if stops is None:
+                assert wa.tolist() == forced
+            a = acc.cpu().numpy()
+            for b in range(B):      # accepted tokens form a prefix of the drafts
+                assert np.array_equal(draft[b, :a[b]], target[b, :a[b]])
+
+
+# ------------------------------------------------------------------ error paths --------------
+
+def test_errors_are_reported_and_leave_state_unchanged():
+    M, S = _mods()
+    ses = S.Session(1, 4, 2, 64, 3, M.MS_F32, 10000.0, max_seqs=2, max_pages_per_seq=2)
+    with ses:
+        s = M.ms_seq_create(ses.cache)
+        k = torch.zeros(1, 40, 2, 64, device="cuda")
+        pos = torch.zeros(40, dtype=torch.int32, device="cuda")
+        M.ms_append_kv(ses.cache, [s], [20], k, k, pos)
+        with pytest.raises(M.MsError) as e:
+            M.ms_append_kv(ses.cache, [s], [20], k, k, pos)              # 40 rows -> 3 pages > max_pages_per_seq
+        assert e.value.code == M.MS_ERR_OOM_PAGES
+        s2 = M.ms_seq_create(ses.cache)
+        with pytest.raises(M.MsError) as e:
+            M.ms_append_kv(ses.cache, [s2, s], [17, 12], k, k, pos)      # needs 2 pages, 1 free
+        assert e.value.code == M.MS_ERR_OOM_PAGES
+        assert M.ms_seq_len(ses.cache, s) == 20 and M.ms_seq_len(ses.cache, s2) == 0
+        assert M.ms_free_page_count(ses.cache) == 1
+        with pytest.raises(M.MsError) as e:
+            M.ms_append_kv(ses.cache, [5], [1], k, k, pos)
+        assert e.value.code == M.MS_ERR_INVALID
+        with pytest.raises(M.MsError) as e:
+            M.ms_compact_segment(ses.cache, [s], [10], [11], [1], k, k, pos)
+        assert e.value.code == M.MS_ERR_RANGE
+        with pytest.raises(M.MsError) as e:
+            M.ms_seq_import(ses.cache, 16, [0])                           # page 0 is owned
+        assert e.value.code == M.MS_ERR_INVALID
+        q = torch.zeros(1, 3, 4, 64, device="cuda")
+        kn = torch.zeros(1, 3, 2, 64, device="cuda")
+        pq = torch.zeros(1, 3, dtype=torch.int32, device="cuda")
+        with pytest.raises(M.MsError) as e:
+            M.ms_predict_verify_attention(ses.cache, 0, [s], 2, 1, q, kn, kn, pq, None, 0.0, q.clone(),
+                                          torch.empty(256, dtype=torch.uint8, device="cuda"))
+        assert e.value.code == M.MS_ERR_WORKSPACE
+        with pytest.raises(M.MsError) as e:
+            M.ms_predict_verify_attention(ses.cache, 1, [s], 2, 1, q, kn, kn, pq, None, 0.0, q.clone(), None)
+        assert e.value.code == M.MS_ERR_INVALID
+        with pytest.raises(M.MsError) as e:
+            ses.attention(0, [s], 12, 5, q, kn, kn, pq)
+        assert e.value.code == M.MS_ERR_INVALID
+        M.ms_check_integrity(ses.cache)
+        M.ms_seq_free(ses.cache, s)
+        with pytest.raises(M.MsError):
+            M.ms_seq_len(ses.cache, s)
+        assert M.ms_free_page_count(ses.cache) == 3
