@@ -1,11 +1,14 @@
 // Argument blocks shared by the attention kernels (internal).
 #pragma once
 
+#include <hip/hip_runtime.h>
+
 #include "memosight.h"
 
 namespace ms {
 
 constexpr int kMaxRowwaveSplits = 16;
+constexpr int kMaxMfmaItems = 256;   // stream-kernel workgroups per KV head
 
 // Per-call sequence ids and cache lengths, passed by value in the kernel argument block so that a
 // launch sees exactly the host state of the moment it was issued.
@@ -30,5 +33,17 @@ struct AttnArgs {
     int n_splits, chunk;
     float scale;
 };
+
+}  // namespace ms
+
+struct ms_cache;
+
+namespace ms {
+
+// attention_mfma.hip
+bool mfma_eligible(const ms_cache* c, int n_q);
+size_t mfma_workspace_bytes(const ms_cache* c, int B);
+int mfma_plan_ints(int B);
+int launch_mfma(ms_cache* c, const AttnArgs& a, const BatchMeta& bm, int B, hipStream_t stream);
 
 }  // namespace ms

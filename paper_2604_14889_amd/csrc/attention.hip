@@ -225,7 +225,7 @@ using namespace ms;
 
 extern "C" size_t ms_attention_workspace_bytes(ms_cache* c, int B, int n_q) {
     if (!c || B < 1 || B > MS_MAX_BATCH || n_q < 1 || n_q > MS_MAX_QUERIES) return 0;
-    size_t need = rowwave_workspace_bytes(c, B, n_q);
+    size_t need = mfma_eligible(c, n_q) ? mfma_workspace_bytes(c, B) : rowwave_workspace_bytes(c, B, n_q);
     return (need + 255) & ~(size_t)255;
 }
 
@@ -279,6 +279,7 @@ extern "C" int ms_predict_verify_attention(ms_cache* c, int layer, int B, const 
     a.n_splits = 1;
     a.chunk = 0;
     a.scale = scale != 0.f ? scale : 1.0f / sqrtf((float)c->d.head_dim);
+    if (mfma_eligible(c, n_q)) return launch_mfma(c, a, bm, B, stream);
     const int D = c->d.head_dim;
     if (c->d.dtype == MS_F32)
         return D == 64 ? launch_rowwave<float, 64>(a, bm, B, max_len, stream) : launch_rowwave<float, 128>(a, bm, B, max_len, stream);

@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <new>
 
+#include "attention.h"
 #include "ms_device.h"
 #include "ms_internal.h"
 
@@ -323,6 +324,12 @@ int ms_cache_create(const ms_cache_desc* desc, ms_cache** out) {
     }
     rc = c->stage.init();
     if (rc != MS_OK) return fail(rc);
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0) c->n_cus = cus;
+    if (hipMalloc((void**)&c->d_plan, (size_t)mfma_plan_ints(MS_MAX_BATCH) * sizeof(int)) != hipSuccess) {
+        set_error("allocating the attention plan buffer failed");
+        return fail(MS_ERR_HIP);
+    }
     *out = c;
     return MS_OK;
 }
@@ -333,6 +340,7 @@ int ms_cache_destroy(ms_cache* c) {
     c->stage.destroy();
     if (c->d_pt) (void)hipFree(c->d_pt);
     if (c->d_inv_freq) (void)hipFree(c->d_inv_freq);
+    if (c->d_plan) (void)hipFree(c->d_plan);
     delete c;
     return MS_OK;
 }
