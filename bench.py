@@ -1,0 +1,273 @@
+#!/usr/bin/env python3
+"""Benchmark of the MemoSight decode hot path on one MI355X.
+
+One step = one pass of the whole hot path over the batch, shaped like a decode step of a
+Qwen2.5-7B-sized model (28 attention layers, 28 query / 4 KV heads x 128, bf16):
+  position ids from the layout helpers (host)            -> uploaded
+  28 x fused Predict+Verify attention, one per layer pool -> the HBM-bound part
+  greedy longest-prefix acceptance on the device, accept lengths read back
+  commit of the accepted verify rows into every layer's cache
+  every 14th step: the 56-token segment closed so far is compacted to 8 memory tokens
+    (ratio 7, as in the paper's long-context analysis), in every layer.
+The workload is the metric point: batch 32, 8192 cached tokens per sequence, 5 verify + 4 foresight
+queries, page tables shuffled over a shared pool.  All inputs are seeded and synthetic.
+
+Prints ONE JSON line.  `value` is whole-step algorithmic KV throughput in GB/s with everything
+resident in HBM; `roofline` prices the streaming attention kernel alone against 8 TB/s; the
+`cpu_baseline` leg times the CPU oracle on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+SEG_TOKENS, RATIO = 56, 7
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=28)
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--kv", type=int, default=8192)
+    ap.add_argument("--ragged", action="store_true", help="lengths uniform in [1k, 16k] instead of --kv")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=2, help="sequences the CPU oracle is timed on")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one MI355X per box); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import workloads as W
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import session as S
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    sh = W.config3(n_layers=args.layers, batch=args.batch) if args.ragged else \
+        W.metric_point(args.batch, args.kv, n_layers=args.layers)
+    B, nq, nv, nf = sh.batch, sh.n_q, sh.n_verify, sh.n_foresight
+    Hq, Hkv, D, NL = sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.n_layers
+    growth_pages = 8 * B                      # room for the tokens appended while the bench runs
+    n_pages = sh.n_pages + growth_pages
+    rng = W.make_rng(1000, B, NL)
+    page_tables = W.shuffled_page_tables(rng, n_pages, sh.lengths)
+
+    # ---- pool filled on the device from a seeded generator, N(0, 0.5), already "rotated" keys ----
+    ses = S.Session(NL, Hq, Hkv, D, n_pages, M.MS_BF16, sh.rope_base, max_seqs=B,
+                    max_pages_per_seq=max(len(p) for p in page_tables) + 64)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(W.BASE_SEED)
+    for layer in range(NL):
+        ses.pool[layer].normal_(0.0, sh.sigma, generator=gen)
+    ids = [M.ms_seq_import(ses.cache, n, pt) for n, pt in zip(sh.lengths, page_tables)]
+
+    def dev_normal(*shape):
+        return torch.empty(*shape, dtype=torch.bfloat16, device=dev).normal_(0.0, sh.sigma, generator=gen)
+
+    q = dev_normal(B, nq, Hq, D)
+    k_new = dev_normal(NL, B, nq, Hkv, D)
+    v_new = dev_normal(NL, B, nq, Hkv, D)
+    n_mem = SEG_TOKENS // RATIO
+    mem_k = dev_normal(NL, B * n_mem, Hkv, D)
+    mem_v = dev_normal(NL, B * n_mem, Hkv, D)
+    out = torch.empty_like(q)
+    draft_np, target_np = W.draft_and_target(rng, B, nv, 1000, forced_prefix=[nv - 1] * B)
+    draft, target = S.ints_dev(draft_np).view(B, nv), S.ints_dev(target_np).view(B, nv)
+    acc_d = torch.empty(B, dtype=torch.int32, device=dev)
+    nxt_d = torch.empty(B, dtype=torch.int32, device=dev)
+    acc_h = torch.empty(B, dtype=torch.int32, pin_memory=True)
+    pos_h = torch.empty(B, nq, dtype=torch.int32, pin_memory=True)
+    pos_d = torch.empty(B, nq, dtype=torch.int32, device=dev)
+    mpos_h = torch.empty(B * n_mem, dtype=torch.int32, pin_memory=True)
+    mpos_d = torch.empty(B * n_mem, dtype=torch.int32, device=dev)
+    pos_np, mpos_np = pos_h.numpy(), mpos_h.numpy()     # views of the pinned buffers
+    ses.ensure_workspace(B, nq)
+
+    # raw position of each sequence's next token (about 3x the compressed length) and the open segment
+    next_pid = [sh.first_query_pid(b) for b in range(B)]
+    seg_len = [0] * B
+    state = {"kv_bytes": 0.0, "accepted": 0, "attn_calls": 0}
+
+    def algorithmic_bytes(lengths):
+        es = 2
+        per_call = sum(2 * L * Hkv * D * es + 4 * (-(-L // 16)) for L in lengths)
+        per_call += B * nq * (2 * Hq + 2 * Hkv) * D * es
+        return per_call
+
+    def step():
+        # a1: position layout (verify block, then foresight tokens right after it)
+        for b in range(B):
+            ver = list(range(next_pid[b], next_pid[b] + nv))
+            pos_np[b, :nv] = ver
+            pos_np[b, nv:] = M.ms_foresight_pids(ver[-1], nf)
+        pos_d.copy_(pos_h, non_blocking=True)
+        lengths = ses.lengths(ids)
+        # a2-a5: attention in every layer
+        for layer in range(NL):
+            ses.attention(layer, ids, nv, nf, q, k_new[layer], v_new[layer], pos_d, None, 0.0, out)
+        state["kv_bytes"] += NL * algorithmic_bytes(lengths)
+        state["attn_calls"] += NL
+        # a6: acceptance on the device, lengths back to the host
+        M.ms_accept(B, nv, draft, target, None, acc_d, nxt_d)
+        acc_h.copy_(acc_d, non_blocking=True)
+        torch.cuda.current_stream().synchronize()
+        acc = acc_h.tolist()
+        # a7: commit accepted verify rows in every layer
+        M.ms_commit_accepted(ses.cache, ids, acc, nq, k_new, v_new, pos_d)
+        for b in range(B):
+            next_pid[b] += acc[b]
+            seg_len[b] += acc[b]
+        state["accepted"] += sum(acc)
+        # a8: close and compact the segment once it holds 56 tokens
+        if all(s >= SEG_TOKENS for s in seg_len):
+            begin = [M.ms_seq_len(ses.cache, s) - n for s, n in zip(ids, seg_len)]
+            cnt = [M.ms_ama_count(n, RATIO) for n in seg_len]
+            assert all(c == n_mem for c in cnt)
+            off = 0
+            for b in range(B):
+                first = next_pid[b] - seg_len[b]
+                mp = M.ms_upl_positions(first, seg_len[b], RATIO)
+                mpos_np[off:off + len(mp)] = mp
+                off += len(mp)
+            mpos_d.copy_(mpos_h, non_blocking=True)
+            M.ms_compact_segment(ses.cache, ids, begin, seg_len, cnt, mem_k, mem_v, mpos_d)
+            for b in range(B):
+                next_pid[b] = M.ms_output_token_pid(next_pid[b] - 1) + 1   # <o> takes one position
+                seg_len[b] = 0
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    state.update(kv_bytes=0.0, accepted=0, attn_calls=0)
+    M.ms_profile_attention(ses.cache, args.steps * NL)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern_ms = M.ms_profile_read(ses.cache, args.steps * NL)
+    M.ms_profile_attention(ses.cache, 0)
+    M.ms_check_integrity(ses.cache)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    gbps = state["kv_bytes"] / (t1 - t0) / 1e9
+    lengths = ses.lengths(ids)
+    per_launch_bytes = algorithmic_bytes(lengths)
+    kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else float("nan")
+    achieved = per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9 if kern_ms else float("nan")
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_pv_attn_mfma_stream.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    result = {
+        "metric": "predict_verify_attn_hbm_gbps_b32_kv8k",
+        "value": round(gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": ("config3_ragged_1k_16k" if args.ragged else f"batch{B}_kv{args.kv}") +
+                        f"_layers{NL}_q{Hq}_kv{Hkv}_d{D}_verify{nv}_foresight{nf}",
+            "batch": B, "mean_kv_len": round(float(np.mean(lengths)), 1), "layers": NL,
+            "step": "28-layer attention + accept + commit, compaction 56->8 every 14 steps",
+        },
+        "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
+        "query_tokens_per_s": round(B * nq * args.steps / (t1 - t0), 1),
+        "decode_tokens_per_s": round(state["accepted"] / (t1 - t0), 1),
+        "accepted_per_step_per_seq": round(state["accepted"] / args.steps / B, 3),
+        "roofline": {
+            "kernel": "pv_attn_mfma_stream",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": traffic,
+            "avg_kernel_ms": round(kern_avg_ms, 5),
+            "launches": len(kern_ms),
+            "algorithmic_bytes_per_launch": per_launch_bytes,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args, ses, sh, ids, lengths, q, k_new, v_new, pos_d, out, M, S, W)
+    ses.close()
+    print(json.dumps(result))
+
+
+def cpu_baseline(args, ses, sh, ids, lengths, q, k_new, v_new, pos_d, out, M, S, W):
+    """The oracle as it stands, timed on the host cores over the first sequences of the batch
+    (layer 0, all 9 x 28 query rows each), and compared with what the GPU produced for them."""
+    import numpy as np
+    import torch
+    from threadpoolctl import threadpool_limits
+
+    from oracle import memosight_oracle as O
+
+    n = max(1, min(args.cpu_seqs, sh.batch))
+    cores = min(16, os.cpu_count() or 1)
+    nv, nf = sh.n_verify, sh.n_foresight
+    # fresh GPU result for layer 0 with the final cache state
+    ses.attention(0, ids, nv, nf, q, k_new[0], v_new[0], pos_d, None, 0.0, out)
+    torch.cuda.synchronize()
+    got = S.to_host_f32(out[:n])
+    tables = ses.page_tables(ids[:n])
+    used = sorted({p for t in tables for p in t})
+    remap = {p: i for i, p in enumerate(used)}
+    pool = S.to_host_f32(ses.pool[0, torch.tensor(used, device="cuda")])[None]
+    ora = O.PagedCache(1, sh.n_kv_heads, sh.head_dim, len(used), dtype=O.BF16, rope_base=sh.rope_base,
+                       max_seqs=n, pool=np.ascontiguousarray(pool))
+    oids = [ora.seq_import(lengths[b], [remap[p] for p in tables[b]]) for b in range(n)]
+    qh, kh, vh = S.to_host_f32(q[:n]), S.to_host_f32(k_new[0, :n]), S.to_host_f32(v_new[0, :n])
+    pos = pos_d[:n].cpu().numpy()
+    with threadpool_limits(limits=cores):
+        t0 = time.perf_counter()
+        want = O.attention(ora, 0, oids, nv, nf, qh, kh, vh, pos)
+        dt = time.perf_counter() - t0
+    nbytes = sum(2 * lengths[b] * sh.n_kv_heads * sh.head_dim * 2 for b in range(n))
+    err = float(np.abs(got - want).max())
+    rel = float(np.abs(got - want).mean() / np.abs(want).mean())
+    return {
+        "value": round(nbytes / dt / 1e9, 4),
+        "unit": "GB/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"{n} of {sh.batch} sequences, layer 0, all {nv + nf} x {sh.n_q_heads} query rows, "
+                  f"{nbytes / 1e6:.1f} MB of KV in {dt:.2f} s",
+        "gpu_vs_oracle_max_abs": round(err, 6),
+        "gpu_vs_oracle_mean_rel": round(rel, 6),
+    }
+
+
+if __name__ == "__main__":
+    main()

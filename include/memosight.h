@@ -204,6 +204,16 @@ int ms_peak_pages(ms_cache* cache, int* n);
  * synchronising `stream`) the device mirror equals the host tables.  MS_OK or MS_ERR_INVALID. */
 int ms_check_integrity(ms_cache* cache, void* stream);
 
+/* ---- profiling ------------------------------------------------------------------------------- */
+
+/* From now on, every ms_predict_verify_attention call on this cache that runs the streaming kernel
+ * records a pair of HIP events around that kernel alone (not the combine kernel), for up to
+ * `capacity` calls; capacity 0 switches profiling off.  Creates the events (synchronous). */
+int ms_profile_attention(ms_cache* cache, int capacity);
+/* Synchronises the recorded events and stores the kernel durations in milliseconds, in call order,
+ * in ms_out (host, up to cap entries); *n receives how many were recorded.  Resets the count. */
+int ms_profile_read(ms_cache* cache, float* ms_out, int cap, int* n);
+
 /* ---- position layout helpers (pure host integer functions) --------------------------------- */
 
 /* Adaptive Memory Allocation: ceil(n_tokens / c).  Negative on bad input. */

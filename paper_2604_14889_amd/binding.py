@@ -68,6 +68,8 @@ _SIGS = {
     "ms_free_page_count": (_I, [_P, _IP]),
     "ms_peak_pages": (_I, [_P, _IP]),
     "ms_check_integrity": (_I, [_P, _P]),
+    "ms_profile_attention": (_I, [_P, _I]),
+    "ms_profile_read": (_I, [_P, C.POINTER(C.c_float), _I, _IP]),
     "ms_ama_count": (_I, [_I, _I]),
     "ms_upl_positions": (_I, [_I, _I, _I, _IP, _I]),
     "ms_output_token_pid": (_I, [_I]),
@@ -220,6 +222,17 @@ def ms_peak_pages(cache) -> int:
 
 def ms_check_integrity(cache, stream=None) -> None:
     _check(lib.ms_check_integrity(cache, _stream(stream)))
+
+
+def ms_profile_attention(cache, capacity: int) -> None:
+    _check(lib.ms_profile_attention(cache, capacity))
+
+
+def ms_profile_read(cache, cap: int):
+    buf = (C.c_float * max(1, cap))()
+    n = C.c_int(0)
+    _check(lib.ms_profile_read(cache, buf, cap, C.byref(n)))
+    return list(buf[:min(n.value, cap)])
 
 
 def ms_ama_count(n_tokens: int, c: int) -> int:

@@ -54,6 +54,7 @@ constexpr int kMergeRegionBytes = (32 + 4) * 64 * 4;                     // 9216
 constexpr int kLdsMerge = kWaves * kMergeRegionBytes;                    // 73728
 constexpr int kLdsBytes = kLdsMerge > kLdsStream ? kLdsMerge : kLdsStream;
 constexpr int kThreads = kWaves * 64;
+static_assert(kThreads == kRows * 8, "the Q prologue maps one thread to one row and 8 rotation pairs");
 
 struct Seg {
     int b;      // index in the call's batch
@@ -90,6 +91,14 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     return __builtin_bit_cast(uint32_t, h);
 }
 
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+
+// 16-byte non-temporal global load.
+__device__ __forceinline__ uint4 load_stream(const uint16_t* p) {
+    const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 // Registers of one 32-token tile in flight.
 struct TileRegs {
     uint4 k[8];  // K operand: token = lane % 32, d = 16 kk + 8 (lane / 32) .. + 8
@@ -120,10 +129,11 @@ __device__ __forceinline__ void load_v(uint4 (&v)[8], const uint16_t* __restrict
     const size_t off = ((size_t)g * 2 + 1) * MS_PAGE_SIZE * kD + (lane >> 4) * kD + 8 * (lane & 15);
     const uint16_t* va = pool + (size_t)pa * page_elems + off;
     const uint16_t* vb = pool + (size_t)pb * page_elems + off;
+    // V is read exactly once per call: streaming (non-temporal) loads keep it out of the caches
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) v[rr] = *reinterpret_cast<const uint4*>(va + 4 * rr * kD);
+    for (int rr = 0; rr < 4; ++rr) v[rr] = load_stream(va + 4 * rr * kD);
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) v[4 + rr] = *reinterpret_cast<const uint4*>(vb + 4 * rr * kD);
+    for (int rr = 0; rr < 4; ++rr) v[4 + rr] = load_stream(vb + 4 * rr * kD);
 }
 
 struct WaveState {
@@ -242,27 +252,43 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         load_v(r.v, a.pool_layer, pa, pb, a.page_elems, g, lane);
         load_k(r.k, a.pool_layer, pa, pb, a.page_elems, g, lane);
 
-        // ---- rotate this (sequence, KV head)'s queries into the LDS Q tile ----
+        // ---- rotate this (sequence, KV head)'s queries into the LDS Q tile: thread t owns row
+        // t / 8, rotation pairs 8 (t % 8) .. + 8; its two 16-byte loads are issued before the
+        // cos/sin table is built ----
+        const int qr = tid >> 3, qc = tid & 7;
+        uint4 x0v = make_uint4(0, 0, 0, 0), x1v = make_uint4(0, 0, 0, 0);
+        const int qi = qr / a.group;
+        if (qr < n_rows) {
+            const uint16_t* qp = a.q + (((size_t)sg.b * a.n_q + qi) * a.n_q_heads + g * a.group + qr % a.group) * kD + 8 * qc;
+            x0v = *reinterpret_cast<const uint4*>(qp);
+            x1v = *reinterpret_cast<const uint4*>(qp + 64);
+        }
         for (int idx = tid; idx < a.n_q * 64; idx += kThreads) {
             float sn, cs;
             sincosf((float)a.pos[sg.b * a.n_q + (idx >> 6)] * a.inv_freq[idx & 63], &sn, &cs);
             cs_tab[idx] = make_float2(cs, sn);
         }
         __syncthreads();
-        for (int idx = tid; idx < kRows * 64; idx += kThreads) {
-            const int rr = idx >> 6, dd = idx & 63;
-            float y0 = 0.f, y1 = 0.f;
-            if (rr < n_rows) {
-                const int i = rr / a.group, h = g * a.group + rr % a.group;
-                const uint16_t* qp = a.q + (((size_t)sg.b * a.n_q + i) * a.n_q_heads + h) * kD;
-                const float x0 = bf16_bits_to_float(qp[dd]), x1 = bf16_bits_to_float(qp[dd + 64]);
-                const float2 c = cs_tab[i * 64 + dd];
-                y0 = (x0 * c.x - x1 * c.y) * a.scale_log2;
-                y1 = (x1 * c.x + x0 * c.y) * a.scale_log2;
+        {
+            const uint32_t w0[4] = {x0v.x, x0v.y, x0v.z, x0v.w}, w1[4] = {x1v.x, x1v.y, x1v.z, x1v.w};
+            uint32_t y0[4], y1[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                float r0[2], r1[2];
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    const float x0 = hh ? __uint_as_float(w0[e2] & 0xffff0000u) : __uint_as_float(w0[e2] << 16);
+                    const float x1 = hh ? __uint_as_float(w1[e2] & 0xffff0000u) : __uint_as_float(w1[e2] << 16);
+                    const float2 c = qr < n_rows ? cs_tab[qi * 64 + 8 * qc + 2 * e2 + hh] : make_float2(0.f, 0.f);
+                    r0[hh] = (x0 * c.x - x1 * c.y) * a.scale_log2;
+                    r1[hh] = (x1 * c.x + x0 * c.y) * a.scale_log2;
+                }
+                y0[e2] = pack_bf16x2(r0[0], r0[1]);
+                y1[e2] = pack_bf16x2(r1[0], r1[1]);
             }
-            uint16_t* qrow = reinterpret_cast<uint16_t*>(smem + kLdsQ + rr * kQRowBytes);
-            qrow[dd] = float_to_bf16_bits(y0);
-            qrow[dd + 64] = float_to_bf16_bits(y1);
+            char* qrow = smem + kLdsQ + qr * kQRowBytes + 16 * qc;
+            *reinterpret_cast<uint4*>(qrow) = make_uint4(y0[0], y0[1], y0[2], y0[3]);
+            *reinterpret_cast<uint4*>(qrow + 128) = make_uint4(y1[0], y1[1], y1[2], y1[3]);
         }
         __syncthreads();
 
@@ -365,43 +391,68 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
 
 // One workgroup per (sequence of the call, KV head): merges that pair's partials with the in-flight
 // block and writes the normalised bf16 output rows.  Wave w owns d block w; lanes own the same
-// (row, d) pairs as in the stream kernel's accumulator layout.
+// (row, d) pairs as in the stream kernel's accumulator layout.  All global loads of a phase are
+// issued together: the kernel is a chain of a few memory latencies, not a stream.
 __global__ __launch_bounds__(256) void pv_attn_mfma_combine(MfmaArgs a) {
     __shared__ float2 cs_tab[MS_MAX_QUERIES * 64];
-    __shared__ float k_rot[MS_MAX_QUERIES][kD + 1];
+    __shared__ float k_rot[MS_MAX_QUERIES][kD + 4];
     __shared__ float s_new[kRows][MS_MAX_QUERIES + 1];
     const int b = blockIdx.x, g = blockIdx.y;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
     const int n_q = a.n_q, n_rows = n_q * a.group;
 
+    // phase 0: raw loads -- this thread's 16 rotation pairs of query row tid / 4, and (threads
+    // below 8 n_q) 8 rotation pairs of one in-flight key
+    const int r = tid >> 2, qtr = tid & 3;
+    const int qi = r / a.group;
+    uint4 qx0[2], qx1[2];
+    qx0[0] = qx0[1] = qx1[0] = qx1[1] = make_uint4(0, 0, 0, 0);
+    if (r < n_rows) {
+        const uint16_t* qp = a.q + (((size_t)b * n_q + qi) * a.n_q_heads + g * a.group + r % a.group) * kD + 16 * qtr;
+        qx0[0] = *reinterpret_cast<const uint4*>(qp);
+        qx0[1] = *reinterpret_cast<const uint4*>(qp + 8);
+        qx1[0] = *reinterpret_cast<const uint4*>(qp + 64);
+        qx1[1] = *reinterpret_cast<const uint4*>(qp + 72);
+    }
+    const int kj = tid >> 3, kc = tid & 7;
+    uint4 kx0 = make_uint4(0, 0, 0, 0), kx1 = make_uint4(0, 0, 0, 0);
+    if (kj < n_q) {
+        const uint16_t* kp = a.k_new + (((size_t)b * n_q + kj) * a.n_kv_heads + g) * kD + 8 * kc;
+        kx0 = *reinterpret_cast<const uint4*>(kp);
+        kx1 = *reinterpret_cast<const uint4*>(kp + 64);
+    }
     for (int idx = tid; idx < n_q * 64; idx += 256) {
         float sn, cs;
         sincosf((float)a.pos[b * n_q + (idx >> 6)] * a.inv_freq[idx & 63], &sn, &cs);
         cs_tab[idx] = make_float2(cs, sn);
     }
     __syncthreads();
-    for (int idx = tid; idx < n_q * 64; idx += 256) {
-        const int j = idx >> 6, dd = idx & 63;
-        const uint16_t* kp = a.k_new + (((size_t)b * n_q + j) * a.n_kv_heads + g) * kD;
-        const float x0 = bf16_bits_to_float(kp[dd]), x1 = bf16_bits_to_float(kp[dd + 64]);
-        const float2 c = cs_tab[idx];
-        k_rot[j][dd] = x0 * c.x - x1 * c.y;
-        k_rot[j][dd + 64] = x1 * c.x + x0 * c.y;
+    if (kj < n_q) {
+        const uint32_t w0[4] = {kx0.x, kx0.y, kx0.z, kx0.w}, w1[4] = {kx1.x, kx1.y, kx1.z, kx1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float x0 = (e & 1) ? __uint_as_float(w0[e >> 1] & 0xffff0000u) : __uint_as_float(w0[e >> 1] << 16);
+            const float x1 = (e & 1) ? __uint_as_float(w1[e >> 1] & 0xffff0000u) : __uint_as_float(w1[e >> 1] << 16);
+            const float2 c = cs_tab[kj * 64 + 8 * kc + e];
+            k_rot[kj][8 * kc + e] = x0 * c.x - x1 * c.y;
+            k_rot[kj][8 * kc + e + 64] = x1 * c.x + x0 * c.y;
+        }
     }
     __syncthreads();
     {
         // scores of the in-flight keys: thread (row, quarter) covers 16 rotation pairs of its row
-        const int r = tid >> 2, qtr = tid & 3;
         float acc[MS_MAX_QUERIES];
 #pragma unroll
         for (int j = 0; j < MS_MAX_QUERIES; ++j) acc[j] = 0.f;
         if (r < n_rows) {
-            const int i = r / a.group, h = g * a.group + r % a.group;
-            const uint16_t* qp = a.q + (((size_t)b * n_q + i) * a.n_q_heads + h) * kD;
+            const uint32_t w0[8] = {qx0[0].x, qx0[0].y, qx0[0].z, qx0[0].w, qx0[1].x, qx0[1].y, qx0[1].z, qx0[1].w};
+            const uint32_t w1[8] = {qx1[0].x, qx1[0].y, qx1[0].z, qx1[0].w, qx1[1].x, qx1[1].y, qx1[1].z, qx1[1].w};
+#pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int dd = 16 * qtr + e;
-                const float x0 = bf16_bits_to_float(qp[dd]), x1 = bf16_bits_to_float(qp[dd + 64]);
-                const float2 c = cs_tab[i * 64 + dd];
+                const float x0 = (e & 1) ? __uint_as_float(w0[e >> 1] & 0xffff0000u) : __uint_as_float(w0[e >> 1] << 16);
+                const float x1 = (e & 1) ? __uint_as_float(w1[e >> 1] & 0xffff0000u) : __uint_as_float(w1[e >> 1] << 16);
+                const float2 c = cs_tab[qi * 64 + dd];
                 const float y0 = x0 * c.x - x1 * c.y, y1 = x1 * c.x + x0 * c.y;
 #pragma unroll
                 for (int j = 0; j < MS_MAX_QUERIES; ++j)
@@ -421,22 +472,22 @@ __global__ __launch_bounds__(256) void pv_attn_mfma_combine(MfmaArgs a) {
     const int p_begin = a.part_begin[b], p_end = a.part_begin[b + 1];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-        const int r = 32 * rb + l32;
-        if (r >= n_rows) continue;
-        const int i = r / a.group, h = g * a.group + r % a.group;
+        const int row = 32 * rb + l32;
+        if (row >= n_rows) continue;
+        const int i = row / a.group, h = g * a.group + row % a.group;
         const int ctx = a.ctx_new ? a.ctx_new[b * n_q + i] : (i < a.n_verify ? i : a.n_verify);
         float m = -INFINITY;
-        for (int p = p_begin; p < p_end; ++p) m = fmaxf(m, a.ws[((size_t)p * a.n_kv_heads + g) * kPartFloats + r]);
+        for (int p = p_begin; p < p_end; ++p) m = fmaxf(m, a.ws[((size_t)p * a.n_kv_heads + g) * kPartFloats + row]);
         for (int j = 0; j < n_q; ++j)
-            if (j < ctx || j == i) m = fmaxf(m, s_new[r][j]);
+            if (j < ctx || j == i) m = fmaxf(m, s_new[row][j]);
         float lsum = 0.f;
         float o[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[e] = 0.f;
         for (int p = p_begin; p < p_end; ++p) {
             const float* part = a.ws + ((size_t)p * a.n_kv_heads + g) * kPartFloats;
-            const float f = __builtin_amdgcn_exp2f(part[r] - m);
-            lsum += f * part[kRows + r];
+            const float f = __builtin_amdgcn_exp2f(part[row] - m);
+            lsum += f * part[kRows + row];
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
                 const int reg4 = rb * 16 + w * 4 + i4;
@@ -449,7 +500,7 @@ __global__ __launch_bounds__(256) void pv_attn_mfma_combine(MfmaArgs a) {
         }
         for (int j = 0; j < n_q; ++j) {
             if (!(j < ctx || j == i)) continue;
-            const float pj = __builtin_amdgcn_exp2f(s_new[r][j] - m);
+            const float pj = __builtin_amdgcn_exp2f(s_new[row][j] - m);
             lsum += pj;
             const uint16_t* vp = a.v_new + (((size_t)b * n_q + j) * a.n_kv_heads + g) * kD + 32 * w + 4 * hf;
 #pragma unroll
@@ -594,8 +645,11 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     a.page_elems = ga.page_elems;
     a.scale_log2 = ga.scale * 1.44269504088896340736f;
     if (c->plan_items > 0) {
+        const bool prof = c->prof_count < (int)c->prof_start.size();
+        if (prof) MS_HIP_TRY(hipEventRecord(c->prof_start[c->prof_count], stream));
         hipLaunchKernelGGL(pv_attn_mfma_stream, dim3(c->plan_items, a.n_kv_heads), dim3(kThreads), kLdsBytes, stream, a);
         MS_HIP_TRY(hipGetLastError());
+        if (prof) MS_HIP_TRY(hipEventRecord(c->prof_stop[c->prof_count++], stream));
     }
     hipLaunchKernelGGL(pv_attn_mfma_combine, dim3(B, a.n_kv_heads), dim3(256), 0, stream, a);
     MS_HIP_TRY(hipGetLastError());
@@ -603,3 +657,31 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
 }
 
 }  // namespace ms
+
+extern "C" int ms_profile_attention(ms_cache* c, int capacity) {
+    if (!c || capacity < 0) MS_FAIL(MS_ERR_INVALID, "ms_profile_attention: bad argument");
+    for (hipEvent_t e : c->prof_start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->prof_stop) (void)hipEventDestroy(e);
+    c->prof_start.clear();
+    c->prof_stop.clear();
+    c->prof_count = 0;
+    for (int i = 0; i < capacity; ++i) {
+        hipEvent_t a = nullptr, b = nullptr;
+        MS_HIP_TRY(hipEventCreate(&a));
+        c->prof_start.push_back(a);
+        MS_HIP_TRY(hipEventCreate(&b));
+        c->prof_stop.push_back(b);
+    }
+    return MS_OK;
+}
+
+extern "C" int ms_profile_read(ms_cache* c, float* ms_out, int cap, int* n) {
+    if (!c || !n || (cap > 0 && !ms_out)) MS_FAIL(MS_ERR_INVALID, "ms_profile_read: null argument");
+    *n = c->prof_count;
+    for (int i = 0; i < c->prof_count && i < cap; ++i) {
+        MS_HIP_TRY(hipEventSynchronize(c->prof_stop[i]));
+        MS_HIP_TRY(hipEventElapsedTime(&ms_out[i], c->prof_start[i], c->prof_stop[i]));
+    }
+    c->prof_count = 0;
+    return MS_OK;
+}

@@ -341,6 +341,8 @@ int ms_cache_destroy(ms_cache* c) {
     if (c->d_pt) (void)hipFree(c->d_pt);
     if (c->d_inv_freq) (void)hipFree(c->d_inv_freq);
     if (c->d_plan) (void)hipFree(c->d_plan);
+    for (hipEvent_t e : c->prof_start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->prof_stop) (void)hipEventDestroy(e);
     delete c;
     return MS_OK;
 }

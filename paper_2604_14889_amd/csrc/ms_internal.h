@@ -76,6 +76,8 @@ struct ms_cache {
     int* d_plan = nullptr;       // device copy of the streaming kernel's work plan
     std::vector<int> plan_key;   // batch (ids, lengths) the plan was built for
     int plan_items = 0, plan_parts = 0, plan_B = 0;
+    std::vector<hipEvent_t> prof_start, prof_stop;  // event pairs around the streaming kernel
+    int prof_count = 0;
 };
 
 namespace ms {
