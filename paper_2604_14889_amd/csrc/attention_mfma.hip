@@ -13,10 +13,14 @@
 //     query row: the online softmax needs one cross-lane exchange per tile and the rescale of the
 //     O^T = V^T . P^T accumulators is a per-lane scalar.  Rescaling is lazy (only when a row's
 //     maximum grows by more than 2^24), scores are kept in log2 units.
-//   * Each segment leaves one partial (row maxima, row sums, unnormalised O) in the workspace; the
-//     combine kernel merges the partials of a (sequence, KV head) with the in-flight block -- the
-//     step's own verify / foresight keys under the visibility rule -- in fp32 and writes bf16.
+//   * The step's own (in-flight) verify / foresight keys are one more tile: the workgroup that owns
+//     a sequence's first segment rotates them into an LDS K tile and one of its waves runs the
+//     tile with the visibility rule applied to the scores.
+//   * Each segment leaves one partial (row maxima, row sums, unnormalised O) in the workspace and
+//     bumps the arrival counter of its (sequence, KV head); the workgroup that arrives last merges
+//     that pair's partials, normalises and writes the bf16 output rows.  One launch per call.
 #include <math.h>
+#include <string.h>
 
 #include <vector>
 
@@ -44,26 +48,32 @@ constexpr int kVTileBytes = kTile * kVRowBytes;
 constexpr float kRescaleThreshold = 24.0f;  // log2 units: P stays below 2^24
 constexpr int kPartFloats = 2 * kRows + kRows * kD;  // m[64], l[64], O[128 regs][64 lanes]
 
-// LDS map.  Stream phase: [Q tile][cos/sin table][one V tile per wave].  Merge phase (overlays it):
-// per wave 32 accumulator registers (one d block of both row blocks) + 4 softmax scalars per lane.
+// LDS map.  Stream phase: [Q tile][cos/sin table][in-flight K tile][one V tile per wave].  Merge
+// phase (overlays it): per wave 64 accumulator registers (two d blocks of both row blocks) + 4
+// softmax scalars per lane.
 constexpr int kLdsQ = 0;
 constexpr int kLdsCs = kLdsQ + kRows * kQRowBytes;                       // 17408
-constexpr int kLdsV = kLdsCs + MS_MAX_QUERIES * 64 * 8;                  // + 8192
-constexpr int kLdsStream = kLdsV + kWaves * kVTileBytes;                 // + 73728 = 99328
-constexpr int kMergeRegionBytes = (32 + 4) * 64 * 4;                     // 9216
-constexpr int kLdsMerge = kWaves * kMergeRegionBytes;                    // 73728
-constexpr int kLdsBytes = kLdsMerge > kLdsStream ? kLdsMerge : kLdsStream;
+constexpr int kLdsKn = kLdsCs + MS_MAX_QUERIES * 64 * 8;                 // + 8192
+constexpr int kLdsV = kLdsKn + kTile * kQRowBytes;                       // + 8704
+constexpr int kLdsStream = kLdsV + kWaves * kVTileBytes;                 // + 73728 = 108032
+constexpr int kMergeRegionBytes = (64 + 4) * 64 * 4;                     // 17408
+constexpr int kLdsMerge = kWaves * kMergeRegionBytes;                    // 139264
+constexpr int kLdsFlag = kLdsMerge > kLdsStream ? kLdsMerge : kLdsStream;  // one word: "last arriver"
+constexpr int kLdsBytes = kLdsFlag + 16;
 constexpr int kThreads = kWaves * 64;
 static_assert(kThreads == kRows * 8, "the Q prologue maps one thread to one row and 8 rotation pairs");
+static_assert(kLdsBytes <= 160 * 1024, "LDS budget of one compute unit");
 
 struct Seg {
-    int b;      // index in the call's batch
-    int seq;    // sequence id
-    int t0;     // first token (multiple of 32)
-    int t1;     // one past the last token
-    int part;   // partial slot (per KV head)
-    int len;    // sequence length
-    int pad0, pad1;
+    int b;          // index in the call's batch
+    int seq;        // sequence id
+    int t0;         // first token (multiple of 32); 0 marks the sequence's first segment
+    int t1;         // one past the last token
+    int part;       // partial slot (per KV head)
+    int len;        // sequence length
+    int seg_begin;  // in an item's first record: the item's segment range in the full list
+    int seg_end;
+    int pages[2 * kWaves];  // page ids of the first tile of every wave (clamped like tile_pages)
 };
 
 struct MfmaArgs {
@@ -77,12 +87,16 @@ struct MfmaArgs {
     const int* ctx_new;
     uint16_t* out;
     float* ws;
-    const int* item_seg;    // [n_items + 1]
-    const Seg* segs;
+    const Seg* item_first;  // [n_items]: first segment of every work item
+    const Seg* segs;        // all segments in item order
     const int* part_begin;  // [B + 1]
+    int* arrive;            // [B][n_kv_heads] arrival counters, zero between calls
     int n_q, n_verify, n_q_heads, n_kv_heads, group, max_pages;
     long page_elems;
     float scale_log2;       // softmax scale * log2(e)
+#ifdef MS_TIMING
+    long long* dbg;         // [workgroup][4] wall-clock stamps (100 MHz)
+#endif
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
@@ -93,10 +107,69 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
+// sin and cos of an fp32 angle of any size (RoPE angles reach 1e5 rad): the reduction by pi/2 is
+// done in fp64 (two-term constant), the kernels on [-pi/4, pi/4] are the classic single-precision
+// minimax polynomials.  About 1e-7 absolute error, far below the bf16 rounding of the rotated rows,
+// and much cheaper than the library routine's large-argument path.
+__device__ __forceinline__ void sincos_reduced(float x, float* sn, float* cs) {
+    const double xd = (double)x;
+    const double n = rint(xd * 0.63661977236758134308);
+    double r = fma(n, -1.57079632679489655800e+00, xd);
+    r = fma(n, -6.12323399573676603587e-17, r);
+    const float t = (float)r, t2 = t * t;
+    const float sp = t + t * t2 * (-1.6666654611e-1f + t2 * (8.3321608736e-3f + t2 * -1.9515295891e-4f));
+    const float cp = 1.0f - 0.5f * t2 + t2 * t2 * (4.166664568298827e-2f + t2 * (-1.388731625493765e-3f + t2 * 2.443315711809948e-5f));
+    const int q = (int)n & 3;
+    const float s1 = (q & 1) ? cp : sp, c1 = (q & 1) ? sp : cp;
+    *sn = (q & 2) ? -s1 : s1;
+    *cs = ((q + 1) & 2) ? -c1 : c1;
+}
+
 // 16-byte non-temporal global load.
-__device__ __forceinline__ uint4 load_stream(const uint16_t* p) {
+__device__ __forceinline__ uint4 load_stream(const char* p) {
     const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
     return make_uint4(t.x, t.y, t.z, t.w);
+}
+
+// Partials travel between workgroups on different XCDs, whose L2 caches are not coherent with each
+// other.  They are written and read with device-scope relaxed atomic accesses (write-through /
+// cache-bypassing), which needs no cache write-back or invalidation; ordering comes from waiting
+// for the stores (workgroup barrier) before the arrival count is bumped.
+__device__ __forceinline__ void store_coherent(float* p, float4 v) {
+    unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
+    const unsigned long long lo = ((unsigned long long)__float_as_uint(v.y) << 32) | __float_as_uint(v.x);
+    const unsigned long long hi = ((unsigned long long)__float_as_uint(v.w) << 32) | __float_as_uint(v.z);
+    __hip_atomic_store(q, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(q + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_coherent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float4 load_coherent4(const float* p) {
+    const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
+    const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float4(__uint_as_float((uint32_t)lo), __uint_as_float((uint32_t)(lo >> 32)), __uint_as_float((uint32_t)hi),
+                       __uint_as_float((uint32_t)(hi >> 32)));
+}
+__device__ __forceinline__ float load_coherent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Read-only, wave-uniform control data (the work plan, position ids) is read through the constant
+// address space: scalar loads, which return out of order with respect to the vector loads and so do
+// not queue behind the tile loads in flight.
+template <typename T>
+__device__ __forceinline__ T uniform_load(const T* p) {
+    return *reinterpret_cast<const __attribute__((address_space(4))) T*>(reinterpret_cast<uintptr_t>(p));
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
+// global load, which would stall the set-up phases on the tile loads already in flight.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // Registers of one 32-token tile in flight.
@@ -115,25 +188,25 @@ __device__ __forceinline__ void tile_pages(const int* __restrict__ pt, int tile,
     pb = __builtin_amdgcn_readfirstlane(pt[pg0 + 1 < last_page ? pg0 + 1 : last_page]);
 }
 
-__device__ __forceinline__ void load_k(uint4 (&k)[8], const uint16_t* __restrict__ pool, int pa, int pb, long page_elems,
-                                       int g, int lane) {
-    const int tok = lane & 31;
-    const uint16_t* kp = pool + (size_t)(tok < 16 ? pa : pb) * page_elems + (size_t)g * 2 * MS_PAGE_SIZE * kD +
-                         (tok & 15) * kD + 8 * (lane >> 5);
+// K operand of a tile straight from the pool.  Addresses are a uniform base plus a 32-bit byte
+// offset per lane (page_bytes * page id + lane part), which keeps the per-lane address state to one
+// register; the host only takes this kernel when a layer's pool is below 4 GiB.
+__device__ __forceinline__ void load_k(uint4 (&k)[8], const char* __restrict__ pool, int pa, int pb,
+                                       uint32_t page_bytes, uint32_t lane_off_k, int lane) {
+    const uint32_t off = (uint32_t)((lane & 16) ? pb : pa) * page_bytes + lane_off_k;
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) k[kk] = *reinterpret_cast<const uint4*>(kp + 16 * kk);
+    for (int kk = 0; kk < 8; ++kk) k[kk] = *reinterpret_cast<const uint4*>(pool + off + 32 * kk);
 }
 
-__device__ __forceinline__ void load_v(uint4 (&v)[8], const uint16_t* __restrict__ pool, int pa, int pb, long page_elems,
-                                       int g, int lane) {
-    const size_t off = ((size_t)g * 2 + 1) * MS_PAGE_SIZE * kD + (lane >> 4) * kD + 8 * (lane & 15);
-    const uint16_t* va = pool + (size_t)pa * page_elems + off;
-    const uint16_t* vb = pool + (size_t)pb * page_elems + off;
-    // V is read exactly once per call: streaming (non-temporal) loads keep it out of the caches
+// V rows of a tile: tokens 4 rr + lane / 16 of page a (rr < 4) and of page b.  V is read exactly once
+// per call: streaming (non-temporal) loads keep it out of the caches.
+__device__ __forceinline__ void load_v(uint4 (&v)[8], const char* __restrict__ pool, int pa, int pb,
+                                       uint32_t page_bytes, uint32_t lane_off_v) {
+    const uint32_t oa = (uint32_t)pa * page_bytes + lane_off_v, ob = (uint32_t)pb * page_bytes + lane_off_v;
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) v[rr] = load_stream(va + 4 * rr * kD);
+    for (int rr = 0; rr < 4; ++rr) v[rr] = load_stream(pool + oa + 4 * rr * kD * 2);
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) v[4 + rr] = load_stream(vb + 4 * rr * kD);
+    for (int rr = 0; rr < 4; ++rr) v[4 + rr] = load_stream(pool + ob + 4 * rr * kD * 2);
 }
 
 struct WaveState {
@@ -205,9 +278,24 @@ __device__ __forceinline__ void qk_block(f32x16_t& s, const uint4 (&k)[8], const
     for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
+        // at most four Q operands in registers at a time
+        if (kk == 4) __builtin_amdgcn_sched_barrier(0);
         const bf16x8_t qb =
             __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(qbase + rb * 32 * kQRowBytes + 32 * kk));
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, k[kk]), qb, s, 0, 0, 0);
+    }
+}
+
+// Same with the K operand read from an LDS tile (row stride kQRowBytes) instead of registers.
+__device__ __forceinline__ void qk_block_lds(f32x16_t& s, const char* kbase, const char* qbase, const int rb) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        const bf16x8_t ka = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(kbase + 32 * kk));
+        const bf16x8_t qb =
+            __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(qbase + rb * 32 * kQRowBytes + 32 * kk));
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb, s, 0, 0, 0);
     }
 }
 
@@ -216,6 +304,70 @@ __device__ __forceinline__ void mask_tail(f32x16_t& s, int valid, int hf) {
 #pragma unroll
     for (int i = 0; i < 16; ++i)
         if (8 * (i >> 2) + 4 * hf + (i & 3) >= valid) s[i] = -INFINITY;
+}
+
+// Visibility of the in-flight tile (token j = in-flight query/key j): a row sees tokens below `lim`
+// and token `self` (lim = min(ctx, n_q), self = its own query index; padding rows: lim 0, self 0).
+__device__ __forceinline__ void mask_inflight(f32x16_t& s, int lim, int self, int hf) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int tok = 8 * (i >> 2) + 4 * hf + (i & 3);
+        s[i] = (tok < lim || tok == self) ? s[i] : -INFINITY;
+    }
+}
+
+// Merges the partials p_begin .. p_end of (sequence b, KV head g), normalises and writes the bf16
+// output rows.  Run by all 512 threads of the workgroup that arrived last for the pair: wave w owns
+// row block w / 4 and d block w % 4, a lane one row and 16 accumulators, laid out as in the stream.
+// Partials are taken two at a time so that their loads overlap.
+__device__ __forceinline__ void combine_partials(const MfmaArgs& a, int b, int g, int p_begin, int p_end, int w, int lane) {
+    const int n_rows = a.n_q * a.group;
+    const int rb = w >> 2, db = w & 3, l32 = lane & 31, hf = lane >> 5;
+    const int row = 32 * rb + l32;
+    float m = -INFINITY, lsum = 0.f, o[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[e] = 0.f;
+    for (int p0 = p_begin; p0 < p_end; p0 += 2) {
+        float pm[2], pl[2];
+        float4 px[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const bool live = p0 + u < p_end;
+            const float* part = a.ws + ((size_t)(live ? p0 + u : p0) * a.n_kv_heads + g) * kPartFloats;
+            const float pmu = load_coherent(part + row);
+            pm[u] = live ? pmu : -INFINITY;
+            pl[u] = load_coherent(part + kRows + row);
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4)
+                px[u][i4] = load_coherent4(part + 2 * kRows + ((rb * 16 + db * 4 + i4) * 64 + lane) * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const float mn = fmaxf(m, pm[u]);                       // the first partial is live and finite
+            const float fo = __builtin_amdgcn_exp2f(m - mn);
+            const float fp = __builtin_amdgcn_exp2f(pm[u] - mn);    // absent partial: 2^-inf = 0
+            m = mn;
+            lsum = lsum * fo + pl[u] * fp;
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                o[4 * i4 + 0] = o[4 * i4 + 0] * fo + px[u][i4].x * fp;
+                o[4 * i4 + 1] = o[4 * i4 + 1] * fo + px[u][i4].y * fp;
+                o[4 * i4 + 2] = o[4 * i4 + 2] * fo + px[u][i4].z * fp;
+                o[4 * i4 + 3] = o[4 * i4 + 3] * fo + px[u][i4].w * fp;
+            }
+        }
+    }
+    if (row < n_rows) {
+        const float inv = 1.f / lsum;
+        uint16_t* op = a.out + (((size_t)b * a.n_q + row / a.group) * a.n_q_heads + g * a.group + row % a.group) * kD + 32 * db + 4 * hf;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            uint2 pk;
+            pk.x = pack_bf16x2(o[4 * i4 + 0] * inv, o[4 * i4 + 1] * inv);
+            pk.y = pack_bf16x2(o[4 * i4 + 2] * inv, o[4 * i4 + 3] * inv);
+            *reinterpret_cast<uint2*>(op + 8 * i4) = pk;
+        }
+    }
 }
 
 __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
@@ -236,45 +388,74 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
     // Q^T operand: column = query row 32 rb + lane % 32, k = 16 kk + 8 (lane / 32) .. + 8
     const char* qbase = smem + kLdsQ + l32 * kQRowBytes + 16 * hf;
     char* vwrite = vl + (lane >> 4) * kVRowBytes + l16 * 16;
-
-    const int seg_end = a.item_seg[item + 1];
-    for (int si = a.item_seg[item]; si < seg_end; ++si) {
-        const Seg sg = a.segs[si];
-        const int* pt = a.d_pt + (size_t)sg.seq * a.max_pages;
-        const int last_page = (sg.len - 1) >> 4;
-        const int n_tok = sg.t1 - sg.t0;
+    // byte offsets inside a page: K operand row = token lane % 16 of the page, 16 bytes at d = 8 (lane / 32);
+    // V row = token lane / 16 (+ 4 rr), 16 bytes at d = 8 (lane % 16)
+    const char* pool = reinterpret_cast<const char*>(a.pool_layer);
+    const uint32_t page_bytes = (uint32_t)a.page_elems * 2;
+    const uint32_t lane_off_k = ((uint32_t)g * 2 * MS_PAGE_SIZE * kD + (lane & 15) * kD + 8 * hf) * 2;
+    const uint32_t lane_off_v = (((uint32_t)g * 2 + 1) * MS_PAGE_SIZE * kD + (lane >> 4) * kD + 8 * l16) * 2;
+#ifdef MS_TIMING
+    long long* dbg = a.dbg + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 4;
+    if (tid == 0) dbg[0] = wall_clock64();
+#endif
+    // The item's first segment record also holds the item's segment range and the page ids of the
+    // first tiles, so the first loads depend on this one record only.
+    const float inv_f = a.inv_freq[lane];   // rotation pair `lane`; issued before anything else
+    const int seg_begin = uniform_load(&a.item_first[item].seg_begin), seg_end = uniform_load(&a.item_first[item].seg_end);
+    for (int si = seg_begin; si < seg_end; ++si) {
+        const Seg* sp = si == seg_begin ? a.item_first + item : a.segs + si;
+        const int sg_b = uniform_load(&sp->b), sg_t0 = uniform_load(&sp->t0), sg_part = uniform_load(&sp->part);
+        const int* pt = a.d_pt + (size_t)uniform_load(&sp->seq) * a.max_pages;
+        const int last_page = (uniform_load(&sp->len) - 1) >> 4;
+        const int n_tok = uniform_load(&sp->t1) - sg_t0;
         const int n_tiles = (n_tok + kTile - 1) / kTile;
+        const bool first_seg = sg_t0 == 0;   // this workgroup also runs the sequence's in-flight tile
+        int pa = uniform_load(&sp->pages[2 * w]), pb = uniform_load(&sp->pages[2 * w + 1]);
 
-        // this wave's first tile goes in flight before anything else
-        TileRegs r;
-        int pa, pb;
-        tile_pages(pt, w, n_tiles, sg.t0, last_page, pa, pb);
-        load_v(r.v, a.pool_layer, pa, pb, a.page_elems, g, lane);
-        load_k(r.k, a.pool_layer, pa, pb, a.page_elems, g, lane);
-
-        // ---- rotate this (sequence, KV head)'s queries into the LDS Q tile: thread t owns row
-        // t / 8, rotation pairs 8 (t % 8) .. + 8; its two 16-byte loads are issued before the
-        // cos/sin table is built ----
-        const int qr = tid >> 3, qc = tid & 7;
-        uint4 x0v = make_uint4(0, 0, 0, 0), x1v = make_uint4(0, 0, 0, 0);
-        const int qi = qr / a.group;
-        if (qr < n_rows) {
-            const uint16_t* qp = a.q + (((size_t)sg.b * a.n_q + qi) * a.n_q_heads + g * a.group + qr % a.group) * kD + 8 * qc;
-            x0v = *reinterpret_cast<const uint4*>(qp);
-            x1v = *reinterpret_cast<const uint4*>(qp + 64);
-        }
-        for (int idx = tid; idx < a.n_q * 64; idx += kThreads) {
-            float sn, cs;
-            sincosf((float)a.pos[sg.b * a.n_q + (idx >> 6)] * a.inv_freq[idx & 63], &sn, &cs);
-            cs_tab[idx] = make_float2(cs, sn);
-        }
-        __syncthreads();
+        // ---- set-up loads.  Order matters: waiting for a load also waits for every load issued
+        // before it, so the small loads the Q rotation needs go first and this wave's first tile
+        // (16 loads, left in flight) goes last.  Thread t owns query row t / 8, rotation pairs
+        // 8 (t % 8) .. + 8; in a first segment, threads below 256 do the same for in-flight key t / 8
+        // (keys and queries share position ids, hence one cos/sin table).
+        // (lane-derived values of the set-up and merge phases are rebuilt from an opaque copy of the
+        // thread id, so that they are not computed at kernel entry and kept -- or spilled -- across
+        // the stream loop)
+        int tid_p = tid;
+        asm volatile("" : "+v"(tid_p));
+        const int qr = tid_p >> 3, qc = tid_p & 7;
+        // all of these loads are unconditional (out-of-range rows read row 0 and are zeroed by their
+        // rotation factors) so that the number of loads in flight is known and waits stay partial
+        const int qi = qr < n_rows ? qr / a.group : 0;
+        const int qh = qr < n_rows ? qr % a.group : 0;
+        const uint16_t* qp = a.q + (((size_t)sg_b * a.n_q + qi) * a.n_q_heads + g * a.group + qh) * kD + 8 * qc;
+        const uint4 x0v = *reinterpret_cast<const uint4*>(qp);
+        const uint4 x1v = *reinterpret_cast<const uint4*>(qp + 64);
+        const uint16_t* kp = a.k_new + (((size_t)sg_b * a.n_q + (qr < a.n_q ? qr : 0)) * a.n_kv_heads + g) * kD + 8 * qc;
+        const uint4 k0v = *reinterpret_cast<const uint4*>(kp);
+        const uint4 k1v = *reinterpret_cast<const uint4*>(kp + 64);
+        // position ids of queries w and w + 8 (wave-uniform: scalar loads)
+        int pos_w[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) pos_w[k] = w + 8 * k < a.n_q ? uniform_load(a.pos + sg_b * a.n_q + w + 8 * k) : 0;
+        TileRegs r;   // (an empty segment's record names page 0: loaded, never used)
+        load_v(r.v, pool, pa, pb, page_bytes, lane_off_v);
+        load_k(r.k, pool, pa, pb, page_bytes, lane_off_k, lane);
+        // cos/sin table: wave w fills the rows of queries w and w + 8, lane = rotation pair
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            if (w + 8 * k < a.n_q) {
+                float sn, cs;
+                sincos_reduced((float)pos_w[k] * inv_f, &sn, &cs);
+                cs_tab[(w + 8 * k) * 64 + (tid_p & 63)] = make_float2(cs, sn);
+            }
+        lds_barrier();
         {
             const uint32_t w0[4] = {x0v.x, x0v.y, x0v.z, x0v.w}, w1[4] = {x1v.x, x1v.y, x1v.z, x1v.w};
-            uint32_t y0[4], y1[4];
+            const uint32_t u0[4] = {k0v.x, k0v.y, k0v.z, k0v.w}, u1[4] = {k1v.x, k1v.y, k1v.z, k1v.w};
+            uint32_t y0[4], y1[4], z0[4], z1[4];
 #pragma unroll
             for (int e2 = 0; e2 < 4; ++e2) {
-                float r0[2], r1[2];
+                float r0[2], r1[2], s0[2], s1[2];
 #pragma unroll
                 for (int hh = 0; hh < 2; ++hh) {
                     const float x0 = hh ? __uint_as_float(w0[e2] & 0xffff0000u) : __uint_as_float(w0[e2] << 16);
@@ -282,16 +463,30 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
                     const float2 c = qr < n_rows ? cs_tab[qi * 64 + 8 * qc + 2 * e2 + hh] : make_float2(0.f, 0.f);
                     r0[hh] = (x0 * c.x - x1 * c.y) * a.scale_log2;
                     r1[hh] = (x1 * c.x + x0 * c.y) * a.scale_log2;
+                    const float k0 = hh ? __uint_as_float(u0[e2] & 0xffff0000u) : __uint_as_float(u0[e2] << 16);
+                    const float k1 = hh ? __uint_as_float(u1[e2] & 0xffff0000u) : __uint_as_float(u1[e2] << 16);
+                    const float2 ck = qr < a.n_q ? cs_tab[qr * 64 + 8 * qc + 2 * e2 + hh] : make_float2(0.f, 0.f);
+                    s0[hh] = k0 * ck.x - k1 * ck.y;
+                    s1[hh] = k1 * ck.x + k0 * ck.y;
                 }
                 y0[e2] = pack_bf16x2(r0[0], r0[1]);
                 y1[e2] = pack_bf16x2(r1[0], r1[1]);
+                z0[e2] = pack_bf16x2(s0[0], s0[1]);
+                z1[e2] = pack_bf16x2(s1[0], s1[1]);
             }
             char* qrow = smem + kLdsQ + qr * kQRowBytes + 16 * qc;
             *reinterpret_cast<uint4*>(qrow) = make_uint4(y0[0], y0[1], y0[2], y0[3]);
             *reinterpret_cast<uint4*>(qrow + 128) = make_uint4(y1[0], y1[1], y1[2], y1[3]);
+            if (first_seg && qr < kTile) {   // rows at and past n_q are zeros
+                char* krow = smem + kLdsKn + qr * kQRowBytes + 16 * qc;
+                *reinterpret_cast<uint4*>(krow) = make_uint4(z0[0], z0[1], z0[2], z0[3]);
+                *reinterpret_cast<uint4*>(krow + 128) = make_uint4(z1[0], z1[1], z1[2], z1[3]);
+            }
         }
-        __syncthreads();
-
+        lds_barrier();
+#ifdef MS_TIMING
+        if (tid == 0 && si == seg_begin) dbg[1] = wall_clock64();
+#endif
         WaveState st;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
@@ -303,225 +498,164 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
                 for (int i = 0; i < 16; ++i) st.o[rb][db][i] = 0.f;
         }
 
-        // ---- the stream: tiles w, w + 8, ...; the next tile's loads are issued as soon as the
-        // registers of the current one have been consumed ----
-        for (int j = w; j < n_tiles; j += kWaves) {
-            const int valid = n_tok - j * kTile;   // >= 32 except in the tail tile
-            // V rows -> wave-private LDS tile; rows past the segment end become zeros
+        // ---- the in-flight tile: the step's own keys and values, visibility rule on the scores;
+        // run by the last wave (it has the fewest stream tiles) of the first segment's workgroup,
+        // ahead of the stream so that nothing it needs stays live across the stream loop ----
+        if (first_seg && w == kWaves - 1) {
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            const int l16 = ln & 15, l32 = ln & 31, hf = ln >> 5;
 #pragma unroll
-            for (int rr = 0; rr < 8; ++rr) *reinterpret_cast<uint4*>(vwrite + 4 * rr * kVRowBytes) = r.v[rr];
-            if (valid < kTile) {
-                for (int rr = 0; rr < 8; ++rr)
-                    if (4 * rr + (lane >> 4) >= valid)
-                        *reinterpret_cast<uint4*>(vwrite + 4 * rr * kVRowBytes) = make_uint4(0, 0, 0, 0);
+            for (int rr = 0; rr < 8; ++rr) {
+                const int tok = 4 * rr + (ln >> 4);
+                const int tc = tok < a.n_q ? tok : a.n_q - 1;   // clamped: the load is unconditional
+                const uint4 val = *reinterpret_cast<const uint4*>(a.v_new + (((size_t)sg_b * a.n_q + tc) * a.n_kv_heads + g) * kD + 8 * l16);
+                *reinterpret_cast<uint4*>(vwrite + 4 * rr * kVRowBytes) = tok < a.n_q ? val : make_uint4(0, 0, 0, 0);
             }
-            tile_pages(pt, j + kWaves, n_tiles, sg.t0, last_page, pa, pb);
-            load_v(r.v, a.pool_layer, pa, pb, a.page_elems, g, lane);
-            f32x16_t s;
-            qk_block(s, r.k, qbase, 0);
-            if (valid < kTile) mask_tail(s, valid, hf);
-            softmax_pv(st, s, 0, vbase);
-            qk_block(s, r.k, qbase, 1);
-            load_k(r.k, a.pool_layer, pa, pb, a.page_elems, g, lane);
-            if (valid < kTile) mask_tail(s, valid, hf);
-            softmax_pv(st, s, 1, vbase);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                const int row = 32 * rb + l32;
+                const bool pad_row = row >= n_rows;
+                const int i = pad_row ? 0 : row / a.group;
+                int ctx = a.ctx_new ? a.ctx_new[sg_b * a.n_q + i] : (i < a.n_verify ? i : a.n_verify);
+                ctx = pad_row ? 0 : (ctx < a.n_q ? ctx : a.n_q);
+                f32x16_t s;
+                qk_block_lds(s, smem + kLdsKn + l32 * kQRowBytes + 16 * hf, qbase, rb);
+                mask_inflight(s, ctx, i, hf);
+                softmax_pv(st, s, rb, vbase);
+            }
         }
 
-        // ---- merge the waves' states through LDS (overlays the stream buffers), one d block per
-        // pass: every wave stores its 32 registers of the block, then wave w reduces one float4 per
-        // lane over all waves and writes it to the segment's partial ----
-        float* part = a.ws + ((size_t)sg.part * a.n_kv_heads + g) * kPartFloats;
-        float fw[2] = {0.f, 0.f};   // this wave's reduction weights are rebuilt per pass from m
-        (void)fw;
+        // ---- the stream: full tiles w, w + 8, ...; the next tile's loads are issued as soon as the
+        // registers of the current one have been consumed.  Refills are unconditional (clamped to
+        // the last tile), so a wave leaves the loop holding its next tile -- the segment's partial
+        // tail tile, if that one is its to do ----
+        const int full_tiles = n_tok / kTile;
+        for (int j = w; j < full_tiles; j += kWaves) {
+            // the two waves of a SIMD take turns at the higher issue priority, tile by tile; with
+            // equal priorities the older wave always wins and the younger one finishes late
+            if (((j >> 3) ^ (w >> 2)) & 1) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            __syncthreads();
+            for (int rr = 0; rr < 8; ++rr) *reinterpret_cast<uint4*>(vwrite + 4 * rr * kVRowBytes) = r.v[rr];
+            tile_pages(pt, j + kWaves, n_tiles, sg_t0, last_page, pa, pb);
+            load_v(r.v, pool, pa, pb, page_bytes, lane_off_v);
+            f32x16_t s;
+            qk_block(s, r.k, qbase, 0);
+            softmax_pv(st, s, 0, vbase);
+            qk_block(s, r.k, qbase, 1);
+            load_k(r.k, pool, pa, pb, page_bytes, lane_off_k, lane);
+            softmax_pv(st, s, 1, vbase);
+        }
+        __builtin_amdgcn_s_setprio(0);
+        // ---- the tail tile (fewer than 32 tokens): V rows past the end become zeros, their scores
+        // minus infinity ----
+        if (full_tiles < n_tiles && (full_tiles & (kWaves - 1)) == w) {
+            const int valid = n_tok - full_tiles * kTile;
+#pragma unroll
+            for (int rr = 0; rr < 8; ++rr)
+                *reinterpret_cast<uint4*>(vwrite + 4 * rr * kVRowBytes) =
+                    4 * rr + (lane >> 4) < valid ? r.v[rr] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                f32x16_t s;
+                qk_block(s, r.k, qbase, rb);
+                mask_tail(s, valid, hf);
+                softmax_pv(st, s, rb, vbase);
+            }
+        }
+
+        // ---- merge the waves' states through LDS (overlays the stream buffers), two d blocks per
+        // pass: every wave stores its 64 registers of the pair, then wave w reduces two float4 per
+        // lane over all waves and writes them to the segment's partial ----
+        float* part = a.ws + ((size_t)sg_part * a.n_kv_heads + g) * kPartFloats;
+        int lane_m = lane;
+        asm volatile("" : "+v"(lane_m));
+#ifdef MS_TIMING
+        if (tid == 0 && si == seg_begin) dbg[2] = wall_clock64();
+#endif
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            lds_barrier();
             {
                 float* reg = reinterpret_cast<float*>(smem + w * kMergeRegionBytes);
 #pragma unroll
                 for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-                    for (int i4 = 0; i4 < 4; ++i4)
-                        *reinterpret_cast<float4*>(reg + ((rb * 4 + i4) * 64 + lane) * 4) =
-                            make_float4(st.o[rb][db][4 * i4], st.o[rb][db][4 * i4 + 1], st.o[rb][db][4 * i4 + 2],
-                                        st.o[rb][db][4 * i4 + 3]);
-                if (db == 0)
-                    *reinterpret_cast<float4*>(reg + (8 * 64 + lane) * 4) = make_float4(st.m[0], st.m[1], st.l[0], st.l[1]);
+                    for (int d2 = 0; d2 < 2; ++d2)
+#pragma unroll
+                        for (int i4 = 0; i4 < 4; ++i4) {
+                            const f32x16_t& o = st.o[rb][2 * pass + d2];
+                            *reinterpret_cast<float4*>(reg + (((rb * 2 + d2) * 4 + i4) * 64 + lane_m) * 4) =
+                                make_float4(o[4 * i4], o[4 * i4 + 1], o[4 * i4 + 2], o[4 * i4 + 3]);
+                        }
+                if (pass == 0)
+                    *reinterpret_cast<float4*>(reg + (16 * 64 + lane_m) * 4) = make_float4(st.m[0], st.m[1], st.l[0], st.l[1]);
             }
-            __syncthreads();
+            lds_barrier();
             {
-                // wave w reduces float4 slot w: row block w / 4, accumulators 4 (w % 4) .. + 4
-                const int rb = w >> 2, i4 = w & 3;
-                float mn = -INFINITY;    // wave 0 always has a tile, so the maximum is finite
+                // wave w reduces slots 2 w and 2 w + 1 of the 16: slot = (rb * 2 + d2) * 4 + i4
+                const int rb = w >> 2;
+                float mn = -INFINITY;    // some wave had a tile (or the in-flight tile): finite
                 float mo[kWaves], lo[kWaves];
 #pragma unroll
                 for (int ow = 0; ow < kWaves; ++ow) {
-                    const float4 ml = *reinterpret_cast<const float4*>(smem + ow * kMergeRegionBytes + (8 * 64 + lane) * 16);
+                    const float4 ml = *reinterpret_cast<const float4*>(smem + ow * kMergeRegionBytes + (16 * 64 + lane_m) * 16);
                     mo[ow] = rb ? ml.y : ml.x;
                     lo[ow] = rb ? ml.w : ml.z;
                     mn = fmaxf(mn, mo[ow]);
                 }
-                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                float4 acc[2];
+                acc[0] = acc[1] = make_float4(0.f, 0.f, 0.f, 0.f);
                 float lt = 0.f;
 #pragma unroll
                 for (int ow = 0; ow < kWaves; ++ow) {
                     const float f = __builtin_amdgcn_exp2f(mo[ow] - mn);   // idle wave: 2^-inf = 0
                     lt += f * lo[ow];
-                    const float4 x =
-                        *reinterpret_cast<const float4*>(smem + ow * kMergeRegionBytes + ((rb * 4 + i4) * 64 + lane) * 16);
-                    acc.x += f * x.x;
-                    acc.y += f * x.y;
-                    acc.z += f * x.z;
-                    acc.w += f * x.w;
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const float4 x =
+                            *reinterpret_cast<const float4*>(smem + ow * kMergeRegionBytes + ((2 * w + u) * 64 + lane_m) * 16);
+                        acc[u].x += f * x.x;
+                        acc[u].y += f * x.y;
+                        acc[u].z += f * x.z;
+                        acc[u].w += f * x.w;
+                    }
                 }
-                const int reg4 = rb * 16 + db * 4 + i4;
-                *reinterpret_cast<float4*>(part + 2 * kRows + (reg4 * 64 + lane) * 4) = acc;
-                if (db == 0 && i4 == 0) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int slot = 2 * w + u, d2 = (slot >> 2) & 1, i4 = slot & 3;
+                    const int reg4 = rb * 16 + (2 * pass + d2) * 4 + i4;
+                    store_coherent(part + 2 * kRows + (reg4 * 64 + lane_m) * 4, acc[u]);
+                }
+                if (pass == 0 && (w & 3) == 0) {
                     lt += __shfl_xor(lt, 32, 64);
-                    if (hf == 0) {
-                        part[32 * rb + l32] = mn;
-                        part[kRows + 32 * rb + l32] = lt;
+                    if ((lane_m >> 5) == 0) {
+                        store_coherent(part + 32 * rb + (lane_m & 31), mn);
+                        store_coherent(part + kRows + 32 * rb + (lane_m & 31), lt);
                     }
                 }
             }
         }
-        __syncthreads();  // the next segment reuses the LDS
-    }
-}
-
-// One workgroup per (sequence of the call, KV head): merges that pair's partials with the in-flight
-// block and writes the normalised bf16 output rows.  Wave w owns d block w; lanes own the same
-// (row, d) pairs as in the stream kernel's accumulator layout.  All global loads of a phase are
-// issued together: the kernel is a chain of a few memory latencies, not a stream.
-__global__ __launch_bounds__(256) void pv_attn_mfma_combine(MfmaArgs a) {
-    __shared__ float2 cs_tab[MS_MAX_QUERIES * 64];
-    __shared__ float k_rot[MS_MAX_QUERIES][kD + 4];
-    __shared__ float s_new[kRows][MS_MAX_QUERIES + 1];
-    const int b = blockIdx.x, g = blockIdx.y;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
-    const int n_q = a.n_q, n_rows = n_q * a.group;
-
-    // phase 0: raw loads -- this thread's 16 rotation pairs of query row tid / 4, and (threads
-    // below 8 n_q) 8 rotation pairs of one in-flight key
-    const int r = tid >> 2, qtr = tid & 3;
-    const int qi = r / a.group;
-    uint4 qx0[2], qx1[2];
-    qx0[0] = qx0[1] = qx1[0] = qx1[1] = make_uint4(0, 0, 0, 0);
-    if (r < n_rows) {
-        const uint16_t* qp = a.q + (((size_t)b * n_q + qi) * a.n_q_heads + g * a.group + r % a.group) * kD + 16 * qtr;
-        qx0[0] = *reinterpret_cast<const uint4*>(qp);
-        qx0[1] = *reinterpret_cast<const uint4*>(qp + 8);
-        qx1[0] = *reinterpret_cast<const uint4*>(qp + 64);
-        qx1[1] = *reinterpret_cast<const uint4*>(qp + 72);
-    }
-    const int kj = tid >> 3, kc = tid & 7;
-    uint4 kx0 = make_uint4(0, 0, 0, 0), kx1 = make_uint4(0, 0, 0, 0);
-    if (kj < n_q) {
-        const uint16_t* kp = a.k_new + (((size_t)b * n_q + kj) * a.n_kv_heads + g) * kD + 8 * kc;
-        kx0 = *reinterpret_cast<const uint4*>(kp);
-        kx1 = *reinterpret_cast<const uint4*>(kp + 64);
-    }
-    for (int idx = tid; idx < n_q * 64; idx += 256) {
-        float sn, cs;
-        sincosf((float)a.pos[b * n_q + (idx >> 6)] * a.inv_freq[idx & 63], &sn, &cs);
-        cs_tab[idx] = make_float2(cs, sn);
-    }
-    __syncthreads();
-    if (kj < n_q) {
-        const uint32_t w0[4] = {kx0.x, kx0.y, kx0.z, kx0.w}, w1[4] = {kx1.x, kx1.y, kx1.z, kx1.w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float x0 = (e & 1) ? __uint_as_float(w0[e >> 1] & 0xffff0000u) : __uint_as_float(w0[e >> 1] << 16);
-            const float x1 = (e & 1) ? __uint_as_float(w1[e >> 1] & 0xffff0000u) : __uint_as_float(w1[e >> 1] << 16);
-            const float2 c = cs_tab[kj * 64 + 8 * kc + e];
-            k_rot[kj][8 * kc + e] = x0 * c.x - x1 * c.y;
-            k_rot[kj][8 * kc + e + 64] = x1 * c.x + x0 * c.y;
+        // ---- arrival: the last workgroup of this (sequence, KV head) merges its partials.  The
+        // barrier waits for every thread's partial stores before thread 0 bumps the count ----
+        __syncthreads();
+        if (tid == 0) {
+            const int p_cnt = a.part_begin[sg_b + 1] - a.part_begin[sg_b];
+            int* ctr = a.arrive + sg_b * a.n_kv_heads + g;
+            const int seen = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int last = seen == p_cnt - 1;
+            if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+            *reinterpret_cast<volatile int*>(smem + kLdsFlag) = last;
         }
+        lds_barrier();
+        if (*reinterpret_cast<volatile int*>(smem + kLdsFlag))
+            combine_partials(a, sg_b, g, a.part_begin[sg_b], a.part_begin[sg_b + 1], w, lane_m);
+        lds_barrier();  // the next segment reuses the LDS
     }
-    __syncthreads();
-    {
-        // scores of the in-flight keys: thread (row, quarter) covers 16 rotation pairs of its row
-        float acc[MS_MAX_QUERIES];
-#pragma unroll
-        for (int j = 0; j < MS_MAX_QUERIES; ++j) acc[j] = 0.f;
-        if (r < n_rows) {
-            const uint32_t w0[8] = {qx0[0].x, qx0[0].y, qx0[0].z, qx0[0].w, qx0[1].x, qx0[1].y, qx0[1].z, qx0[1].w};
-            const uint32_t w1[8] = {qx1[0].x, qx1[0].y, qx1[0].z, qx1[0].w, qx1[1].x, qx1[1].y, qx1[1].z, qx1[1].w};
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int dd = 16 * qtr + e;
-                const float x0 = (e & 1) ? __uint_as_float(w0[e >> 1] & 0xffff0000u) : __uint_as_float(w0[e >> 1] << 16);
-                const float x1 = (e & 1) ? __uint_as_float(w1[e >> 1] & 0xffff0000u) : __uint_as_float(w1[e >> 1] << 16);
-                const float2 c = cs_tab[qi * 64 + dd];
-                const float y0 = x0 * c.x - x1 * c.y, y1 = x1 * c.x + x0 * c.y;
-#pragma unroll
-                for (int j = 0; j < MS_MAX_QUERIES; ++j)
-                    if (j < n_q) acc[j] += y0 * k_rot[j][dd] + y1 * k_rot[j][dd + 64];
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < MS_MAX_QUERIES; ++j) {
-            float v = acc[j];
-            v += __shfl_xor(v, 1, 64);
-            v += __shfl_xor(v, 2, 64);
-            if (qtr == 0 && j < n_q) s_new[r][j] = v * a.scale_log2;
-        }
-    }
-    __syncthreads();
-
-    const int p_begin = a.part_begin[b], p_end = a.part_begin[b + 1];
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-        const int row = 32 * rb + l32;
-        if (row >= n_rows) continue;
-        const int i = row / a.group, h = g * a.group + row % a.group;
-        const int ctx = a.ctx_new ? a.ctx_new[b * n_q + i] : (i < a.n_verify ? i : a.n_verify);
-        float m = -INFINITY;
-        for (int p = p_begin; p < p_end; ++p) m = fmaxf(m, a.ws[((size_t)p * a.n_kv_heads + g) * kPartFloats + row]);
-        for (int j = 0; j < n_q; ++j)
-            if (j < ctx || j == i) m = fmaxf(m, s_new[row][j]);
-        float lsum = 0.f;
-        float o[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[e] = 0.f;
-        for (int p = p_begin; p < p_end; ++p) {
-            const float* part = a.ws + ((size_t)p * a.n_kv_heads + g) * kPartFloats;
-            const float f = __builtin_amdgcn_exp2f(part[row] - m);
-            lsum += f * part[kRows + row];
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const int reg4 = rb * 16 + w * 4 + i4;
-                const float4 x = *reinterpret_cast<const float4*>(part + 2 * kRows + (reg4 * 64 + lane) * 4);
-                o[4 * i4 + 0] += f * x.x;
-                o[4 * i4 + 1] += f * x.y;
-                o[4 * i4 + 2] += f * x.z;
-                o[4 * i4 + 3] += f * x.w;
-            }
-        }
-        for (int j = 0; j < n_q; ++j) {
-            if (!(j < ctx || j == i)) continue;
-            const float pj = __builtin_amdgcn_exp2f(s_new[row][j] - m);
-            lsum += pj;
-            const uint16_t* vp = a.v_new + (((size_t)b * n_q + j) * a.n_kv_heads + g) * kD + 32 * w + 4 * hf;
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const uint2 raw = *reinterpret_cast<const uint2*>(vp + 8 * i4);
-                o[4 * i4 + 0] += pj * bf16_bits_to_float(raw.x & 0xffffu);
-                o[4 * i4 + 1] += pj * bf16_bits_to_float(raw.x >> 16);
-                o[4 * i4 + 2] += pj * bf16_bits_to_float(raw.y & 0xffffu);
-                o[4 * i4 + 3] += pj * bf16_bits_to_float(raw.y >> 16);
-            }
-        }
-        const float inv = 1.f / lsum;
-        uint16_t* op = a.out + (((size_t)b * n_q + i) * a.n_q_heads + h) * kD + 32 * w + 4 * hf;
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-            uint2 pk;
-            pk.x = pack_bf16x2(o[4 * i4 + 0] * inv, o[4 * i4 + 1] * inv);
-            pk.y = pack_bf16x2(o[4 * i4 + 2] * inv, o[4 * i4 + 3] * inv);
-            *reinterpret_cast<uint2*>(op + 8 * i4) = pk;
-        }
-    }
+#ifdef MS_TIMING
+    if (tid == 0) dbg[3] = wall_clock64();
+#endif
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -540,12 +674,21 @@ static int mfma_items(const ms_cache* c) {
 
 // every share contributes one partial plus one per sequence boundary inside it
 size_t mfma_workspace_bytes(const ms_cache* c, int B) {
-    return (size_t)(mfma_items(c) + B) * c->d.n_kv_heads * kPartFloats * sizeof(float);
+    size_t n = (size_t)(mfma_items(c) + B) * c->d.n_kv_heads * kPartFloats * sizeof(float);
+#ifdef MS_TIMING
+    n += 1 << 20;
+#endif
+    return n;
 }
 
-int mfma_plan_ints(int B) { return (kMaxMfmaItems + 1) + (kMaxMfmaItems + B) * (int)(sizeof(Seg) / sizeof(int)) + (B + 1); }
+constexpr int kSegInts = (int)(sizeof(Seg) / sizeof(int));
 
-// Splits the batch's tiles into equal contiguous shares and lists each share's segments.
+// plan blob: [first segment of every item][all segments][partial range of every sequence]
+int mfma_plan_ints(int B) { return kMaxMfmaItems * kSegInts + (kMaxMfmaItems + B) * kSegInts + (B + 1); }
+
+// Splits the batch's 32-token tiles into equal contiguous shares (work items) and lists each share's
+// segments.  Every sequence gets at least one segment (an empty one if it has no cached tokens): the
+// first segment's workgroup also runs the sequence's in-flight tile.
 static void build_plan(const ms_cache* c, const BatchMeta& bm, int B, int n_items_target, std::vector<int>& blob,
                        int* n_items_out, int* n_parts_out) {
     std::vector<long> tile_prefix(B + 1, 0);
@@ -554,44 +697,65 @@ static void build_plan(const ms_cache* c, const BatchMeta& bm, int B, int n_item
     int n_items = n_items_target;
     const long min_tiles = 2 * kWaves;  // at least two tiles per wave in a share
     if ((long)n_items * min_tiles > nt) n_items = (int)(nt / min_tiles);
-    if (n_items < 1) n_items = nt > 0 ? 1 : 0;
-    std::vector<int> item_seg(n_items + 1, 0);
-    std::vector<Seg> segs;
-    std::vector<int> part_begin(B + 1, 0);
+    if (n_items < 1) n_items = 1;
+    std::vector<std::vector<Seg>> per_item(n_items);
     std::vector<int> part_count(B, 0);
+    auto make_seg = [&](int b, int t0, int t1) {
+        Seg s;
+        s.b = b;
+        s.seq = bm.seq[b];
+        s.t0 = t0;
+        s.t1 = t1;
+        s.part = part_count[b]++;   // rebased below
+        s.len = bm.len[b];
+        s.seg_begin = s.seg_end = 0;
+        const std::vector<int>& pt = c->pt[bm.seq[b]];
+        const int n_tiles = (t1 - t0 + kTile - 1) / kTile, last_page = (bm.len[b] - 1) >> 4;
+        for (int w = 0; w < kWaves; ++w) {
+            if (n_tiles == 0) {
+                s.pages[2 * w] = s.pages[2 * w + 1] = 0;
+                continue;
+            }
+            const int tc = w < n_tiles ? w : n_tiles - 1;
+            const int pg0 = (t0 >> 4) + 2 * tc;
+            s.pages[2 * w] = pt[pg0 < last_page ? pg0 : last_page];
+            s.pages[2 * w + 1] = pt[pg0 + 1 < last_page ? pg0 + 1 : last_page];
+        }
+        return s;
+    };
     int b = 0;
     for (int it = 0; it < n_items; ++it) {
         const long lo = nt * it / n_items, hi = nt * (it + 1) / n_items;
-        item_seg[it] = (int)segs.size();
         long cur = lo;
         while (cur < hi) {
             while (tile_prefix[b + 1] <= cur) ++b;
             const long end = hi < tile_prefix[b + 1] ? hi : tile_prefix[b + 1];
-            Seg s;
-            s.b = b;
-            s.seq = bm.seq[b];
-            s.t0 = (int)(cur - tile_prefix[b]) * kTile;
-            s.t1 = (int)(end - tile_prefix[b]) * kTile;
-            if (s.t1 > bm.len[b]) s.t1 = bm.len[b];
-            s.part = 0;
-            s.len = bm.len[b];
-            s.pad0 = s.pad1 = 0;
-            part_count[b]++;
-            segs.push_back(s);
+            int t1 = (int)(end - tile_prefix[b]) * kTile;
+            if (t1 > bm.len[b]) t1 = bm.len[b];
+            per_item[it].push_back(make_seg(b, (int)(cur - tile_prefix[b]) * kTile, t1));
             cur = end;
         }
     }
-    item_seg[n_items] = (int)segs.size();
+    for (int e = 0; e < B; ++e)
+        if (bm.len[e] == 0) per_item[e % n_items].push_back(make_seg(e, 0, 0));
+    std::vector<int> part_begin(B + 1, 0);
     for (int i = 0; i < B; ++i) part_begin[i + 1] = part_begin[i] + part_count[i];
-    // segments are generated in sequence order, so partial slots are simply their running index
-    for (size_t i = 0; i < segs.size(); ++i) segs[i].part = (int)i;
-    blob.clear();
-    blob.insert(blob.end(), item_seg.begin(), item_seg.end());
-    blob.resize(kMaxMfmaItems + 1, 0);
-    const int* sp = reinterpret_cast<const int*>(segs.data());
-    blob.insert(blob.end(), sp, sp + segs.size() * (sizeof(Seg) / sizeof(int)));
-    blob.resize((kMaxMfmaItems + 1) + (size_t)(kMaxMfmaItems + B) * (sizeof(Seg) / sizeof(int)), 0);
-    blob.insert(blob.end(), part_begin.begin(), part_begin.end());
+    std::vector<Seg> firsts(n_items), segs;
+    for (int it = 0; it < n_items; ++it) {
+        const int begin = (int)segs.size();
+        for (Seg s : per_item[it]) {
+            s.part += part_begin[s.b];
+            segs.push_back(s);
+        }
+        firsts[it] = per_item[it].empty() ? Seg{} : segs[begin];
+        firsts[it].seg_begin = begin;
+        firsts[it].seg_end = (int)segs.size();
+    }
+    blob.assign((size_t)mfma_plan_ints(B), 0);
+    memcpy(blob.data(), firsts.data(), firsts.size() * sizeof(Seg));
+    memcpy(blob.data() + kMaxMfmaItems * kSegInts, segs.data(), segs.size() * sizeof(Seg));
+    memcpy(blob.data() + kMaxMfmaItems * kSegInts + (size_t)(kMaxMfmaItems + B) * kSegInts, part_begin.data(),
+           part_begin.size() * sizeof(int));
     *n_items_out = n_items;
     *n_parts_out = (int)segs.size();
 }
@@ -604,12 +768,10 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     }
     // plan: rebuilt only when the batch (ids, lengths) changed since the last call on this cache
     std::vector<int> key;
-    key.reserve(2 * B + 1);
+    key.reserve(B + 2);
     key.push_back(B);
-    for (int b = 0; b < B; ++b) {
-        key.push_back(bm.seq[b]);
-        key.push_back(bm.len[b]);
-    }
+    key.push_back((int)c->version);   // any change of lengths or page tables bumps the version
+    for (int b = 0; b < B; ++b) key.push_back(bm.seq[b]);
     if (key != c->plan_key) {
         std::vector<int> blob;
         build_plan(c, bm, B, mfma_items(c), blob, &c->plan_items, &c->plan_parts);
@@ -633,9 +795,10 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     a.ctx_new = ga.ctx_new;
     a.out = (uint16_t*)ga.out;
     a.ws = ga.ws;
-    a.item_seg = c->d_plan;
-    a.segs = reinterpret_cast<const Seg*>(c->d_plan + (kMaxMfmaItems + 1));
-    a.part_begin = c->d_plan + (kMaxMfmaItems + 1) + (size_t)(kMaxMfmaItems + B) * (sizeof(Seg) / sizeof(int));
+    a.item_first = reinterpret_cast<const Seg*>(c->d_plan);
+    a.segs = reinterpret_cast<const Seg*>(c->d_plan + kMaxMfmaItems * kSegInts);
+    a.part_begin = c->d_plan + kMaxMfmaItems * kSegInts + (size_t)(kMaxMfmaItems + B) * kSegInts;
+    a.arrive = c->d_arrive;
     a.n_q = ga.n_q;
     a.n_verify = ga.n_verify;
     a.n_q_heads = ga.n_q_heads;
@@ -644,15 +807,16 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     a.max_pages = ga.max_pages;
     a.page_elems = ga.page_elems;
     a.scale_log2 = ga.scale * 1.44269504088896340736f;
-    if (c->plan_items > 0) {
+#ifdef MS_TIMING
+    a.dbg = (long long*)((char*)ga.ws + (size_t)(mfma_items(c) + B) * c->d.n_kv_heads * kPartFloats * sizeof(float));
+#endif
+    {
         const bool prof = c->prof_count < (int)c->prof_start.size();
         if (prof) MS_HIP_TRY(hipEventRecord(c->prof_start[c->prof_count], stream));
         hipLaunchKernelGGL(pv_attn_mfma_stream, dim3(c->plan_items, a.n_kv_heads), dim3(kThreads), kLdsBytes, stream, a);
         MS_HIP_TRY(hipGetLastError());
         if (prof) MS_HIP_TRY(hipEventRecord(c->prof_stop[c->prof_count++], stream));
     }
-    hipLaunchKernelGGL(pv_attn_mfma_combine, dim3(B, a.n_kv_heads), dim3(256), 0, stream, a);
-    MS_HIP_TRY(hipGetLastError());
     return MS_OK;
 }
 

@@ -187,6 +187,7 @@ int flush_page_table_patches(ms_cache* c, hipStream_t stream) {
 }
 
 static int take_page(ms_cache* c, int seq) {
+    c->version++;
     int page = *c->free_pages.begin();
     c->free_pages.erase(c->free_pages.begin());
     c->pending_pt.push_back(seq);
@@ -200,6 +201,7 @@ static int take_page(ms_cache* c, int seq) {
 
 // Grows `seq` by n rows (pages first-fit lowest); the caller has verified capacity.
 static void grow(ms_cache* c, int seq, int n) {
+    c->version++;
     for (int j = 0; j < n; ++j) {
         if (c->len[seq] % MS_PAGE_SIZE == 0) take_page(c, seq);
         c->len[seq]++;
@@ -330,6 +332,11 @@ int ms_cache_create(const ms_cache_desc* desc, ms_cache** out) {
         set_error("allocating the attention plan buffer failed");
         return fail(MS_ERR_HIP);
     }
+    const size_t arrive_bytes = (size_t)MS_MAX_BATCH * desc->n_kv_heads * sizeof(int);
+    if (hipMalloc((void**)&c->d_arrive, arrive_bytes) != hipSuccess || hipMemset(c->d_arrive, 0, arrive_bytes) != hipSuccess) {
+        set_error("allocating the arrival counters failed");
+        return fail(MS_ERR_HIP);
+    }
     *out = c;
     return MS_OK;
 }
@@ -341,6 +348,7 @@ int ms_cache_destroy(ms_cache* c) {
     if (c->d_pt) (void)hipFree(c->d_pt);
     if (c->d_inv_freq) (void)hipFree(c->d_inv_freq);
     if (c->d_plan) (void)hipFree(c->d_plan);
+    if (c->d_arrive) (void)hipFree(c->d_arrive);
     for (hipEvent_t e : c->prof_start) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->prof_stop) (void)hipEventDestroy(e);
     delete c;
@@ -351,6 +359,7 @@ int ms_seq_create(ms_cache* c, int* seq_id) {
     if (!c || !seq_id) MS_FAIL(MS_ERR_INVALID, "ms_seq_create: null argument");
     for (int s = 0; s < c->d.max_seqs; ++s)
         if (!c->live[s]) {
+            c->version++;
             c->live[s] = 1;
             c->len[s] = 0;
             c->pt[s].clear();
@@ -382,6 +391,7 @@ int ms_seq_import(ms_cache* c, int length, const int* pages, int n_pages, int* s
         c->pt[s].push_back(pages[i]);
     }
     c->len[s] = length;
+    c->version++;
     int in_use = c->d.n_pages - (int)c->free_pages.size();
     if (in_use > c->peak_pages) c->peak_pages = in_use;
     *seq_id = s;
@@ -392,6 +402,7 @@ int ms_seq_free(ms_cache* c, int seq_id) {
     if (!c) MS_FAIL(MS_ERR_INVALID, "ms_seq_free: null cache");
     int rc = check_seq(c, seq_id, "ms_seq_free");
     if (rc != MS_OK) return rc;
+    c->version++;
     for (int p : c->pt[seq_id]) c->free_pages.insert(p);
     c->pt[seq_id].clear();
     c->len[seq_id] = 0;
@@ -557,6 +568,7 @@ int ms_compact_segment(ms_cache* c, int B, const int* seq_ids, const int* seg_be
         const int L = c->len[s];
         const int t = L - seg_begin[b] - seg_len[b];
         const int keep = pages_for(seg_begin[b]);
+        c->version++;
         for (size_t i = keep; i < c->pt[s].size(); ++i) c->free_pages.insert(c->pt[s][i]);
         c->pt[s].resize(keep);
         c->len[s] = seg_begin[b];

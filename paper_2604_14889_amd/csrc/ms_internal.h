@@ -72,8 +72,10 @@ struct ms_cache {
     float* d_inv_freq = nullptr; // device [head_dim / 2]
     ms::StageRing stage;
     std::vector<int> pending_pt; // (seq, index, page) triples not yet sent to the mirror
+    unsigned version = 0;        // bumped by every call that changes lengths or page tables
     int n_cus = 256;             // compute units of the device
     int* d_plan = nullptr;       // device copy of the streaming kernel's work plan
+    int* d_arrive = nullptr;     // [MS_MAX_BATCH][n_kv_heads] arrival counters of the streaming kernel
     std::vector<int> plan_key;   // batch (ids, lengths) the plan was built for
     int plan_items = 0, plan_parts = 0, plan_B = 0;
     std::vector<hipEvent_t> prof_start, prof_stop;  // event pairs around the streaming kernel
