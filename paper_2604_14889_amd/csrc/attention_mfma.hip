@@ -682,6 +682,7 @@ size_t mfma_workspace_bytes(const ms_cache* c, int B) {
 }
 
 constexpr int kSegInts = (int)(sizeof(Seg) / sizeof(int));
+constexpr int kSegOverheadTiles = 24;   // set-up + merge of a segment, in units of one tile of streaming
 
 // plan blob: [first segment of every item][all segments][partial range of every sequence]
 int mfma_plan_ints(int B) { return kMaxMfmaItems * kSegInts + (kMaxMfmaItems + B) * kSegInts + (B + 1); }
@@ -723,18 +724,40 @@ static void build_plan(const ms_cache* c, const BatchMeta& bm, int B, int n_item
         }
         return s;
     };
-    int b = 0;
-    for (int it = 0; it < n_items; ++it) {
-        const long lo = nt * it / n_items, hi = nt * (it + 1) / n_items;
-        long cur = lo;
-        while (cur < hi) {
-            while (tile_prefix[b + 1] <= cur) ++b;
-            const long end = hi < tile_prefix[b + 1] ? hi : tile_prefix[b + 1];
-            int t1 = (int)(end - tile_prefix[b]) * kTile;
-            if (t1 > bm.len[b]) t1 = bm.len[b];
-            per_item[it].push_back(make_seg(b, (int)(cur - tile_prefix[b]) * kTile, t1));
-            cur = end;
+    // Shares are cut so that the largest cost, tiles + kSegOverheadTiles per segment, is as small
+    // as n_items shares allow (every segment costs a set-up and a merge phase worth about that many
+    // tiles of streaming): greedy packing under a cost cap, the cap found by bisection.
+    auto pack = [&](long cap, bool emit) {
+        int it = 0;
+        long cost = 0;
+        for (int b = 0; b < B; ++b) {
+            long left = tile_prefix[b + 1] - tile_prefix[b], at = 0;
+            while (left > 0) {
+                if (cost + kSegOverheadTiles + 1 > cap) {
+                    ++it;
+                    cost = 0;
+                }
+                long take = cap - cost - kSegOverheadTiles;
+                if (take > left) take = left;
+                if (emit) {
+                    int t1 = (int)(at + take) * kTile;
+                    if (t1 > bm.len[b]) t1 = bm.len[b];
+                    per_item[it].push_back(make_seg(b, (int)at * kTile, t1));
+                }
+                cost += kSegOverheadTiles + take;
+                left -= take;
+                at += take;
+            }
         }
+        return it + 1;
+    };
+    if (nt > 0) {
+        long lo = kSegOverheadTiles + 1, hi = nt + (long)kSegOverheadTiles * (B + 1);
+        while (lo < hi) {
+            const long mid = (lo + hi) / 2;
+            if (pack(mid, false) <= n_items) hi = mid; else lo = mid + 1;
+        }
+        pack(lo, true);
     }
     for (int e = 0; e < B; ++e)
         if (bm.len[e] == 0) per_item[e % n_items].push_back(make_seg(e, 0, 0));
