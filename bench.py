@@ -42,7 +42,9 @@ def parse():
     ap.add_argument("--kv", type=int, default=8192)
     ap.add_argument("--ragged", action="store_true", help="lengths uniform in [1k, 16k] instead of --kv")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=2, help="sequences the CPU oracle is timed on")
+    ap.add_argument("--cpu-seqs", type=int, default=32, help="sequences the CPU oracle is timed on")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain 1 GiB device copies, for scaling rocprofv3 byte counters")
     return ap.parse_args()
 
 
@@ -175,7 +177,7 @@ def main():
     achieved = per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9 if kern_ms else float("nan")
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_pv_attn_mfma_stream.json")
+    tpath = os.path.join(ROOT, "profiles", "pv_attn_mfma_stream_batch32_kv8192_traffic.json")
     if os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
@@ -219,6 +221,13 @@ def main():
         },
     }
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0, generator=gen)   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, ses, sh, ids, lengths, q, k_new, v_new, pos_d, out, M, S, W)
     ses.close()
@@ -263,7 +272,7 @@ def cpu_baseline(args, ses, sh, ids, lengths, q, k_new, v_new, pos_d, out, M, S,
         "cores": cores,
         "kind": "oracle",
         "sample": f"{n} of {sh.batch} sequences, layer 0, all {nv + nf} x {sh.n_q_heads} query rows, "
-                  f"{nbytes / 1e6:.1f} MB of KV in {dt:.2f} s",
+                  f"{nbytes / 1e6:.1f} MB of KV in {dt:.2f} s (1 of {sh.n_layers} layers of one step)",
         "gpu_vs_oracle_max_abs": round(err, 6),
         "gpu_vs_oracle_mean_rel": round(rel, 6),
     }

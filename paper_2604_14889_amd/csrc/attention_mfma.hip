@@ -662,8 +662,11 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
 // host side
 // ---------------------------------------------------------------------------------------------
 
+// bf16, head_dim 128, at most 64 query rows per KV head, and a layer's pool below 4 GiB (the kernel
+// addresses pages with 32-bit byte offsets from the layer base).
 bool mfma_eligible(const ms_cache* c, int n_q) {
-    return c->d.dtype == MS_BF16 && c->d.head_dim == kD && n_q * c->group <= kRows;
+    return c->d.dtype == MS_BF16 && c->d.head_dim == kD && n_q * c->group <= kRows &&
+           (unsigned long long)c->layer_elems * 2ull < (1ull << 32);
 }
 
 static int mfma_items(const ms_cache* c) {
