@@ -777,11 +777,11 @@ static void build_plan(const ms_cache* c, const BatchMeta& bm, int B, int n_item
         firsts[it].seg_begin = begin;
         firsts[it].seg_end = (int)segs.size();
     }
-    blob.assign((size_t)mfma_plan_ints(B), 0);
+    // compact blob: [first segment of every item][all segments][partial range of every sequence]
+    blob.assign((size_t)(n_items + segs.size()) * kSegInts + part_begin.size(), 0);
     memcpy(blob.data(), firsts.data(), firsts.size() * sizeof(Seg));
-    memcpy(blob.data() + kMaxMfmaItems * kSegInts, segs.data(), segs.size() * sizeof(Seg));
-    memcpy(blob.data() + kMaxMfmaItems * kSegInts + (size_t)(kMaxMfmaItems + B) * kSegInts, part_begin.data(),
-           part_begin.size() * sizeof(int));
+    memcpy(blob.data() + (size_t)n_items * kSegInts, segs.data(), segs.size() * sizeof(Seg));
+    memcpy(blob.data() + (size_t)(n_items + segs.size()) * kSegInts, part_begin.data(), part_begin.size() * sizeof(int));
     *n_items_out = n_items;
     *n_parts_out = (int)segs.size();
 }
@@ -803,10 +803,8 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
         build_plan(c, bm, B, mfma_items(c), blob, &c->plan_items, &c->plan_parts);
         const size_t bytes = blob.size() * sizeof(int);
         if (bytes > StageRing::kSlotBytes) MS_FAIL(MS_ERR_UNSUPPORTED, "attention plan of %zu bytes too large", bytes);
-        void* dev = nullptr;
-        int rc = c->stage.upload(blob.data(), bytes, stream, &dev);
+        int rc = c->stage.upload_to(c->d_plan, blob.data(), bytes, stream);
         if (rc != MS_OK) return rc;
-        MS_HIP_TRY(hipMemcpyAsync(c->d_plan, dev, bytes, hipMemcpyDeviceToDevice, stream));
         c->plan_key = key;
         c->plan_B = B;
     }
@@ -822,8 +820,8 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     a.out = (uint16_t*)ga.out;
     a.ws = ga.ws;
     a.item_first = reinterpret_cast<const Seg*>(c->d_plan);
-    a.segs = reinterpret_cast<const Seg*>(c->d_plan + kMaxMfmaItems * kSegInts);
-    a.part_begin = c->d_plan + kMaxMfmaItems * kSegInts + (size_t)(kMaxMfmaItems + B) * kSegInts;
+    a.segs = reinterpret_cast<const Seg*>(c->d_plan + (size_t)c->plan_items * kSegInts);
+    a.part_begin = c->d_plan + (size_t)(c->plan_items + c->plan_parts) * kSegInts;
     a.arrive = c->d_arrive;
     a.n_q = ga.n_q;
     a.n_verify = ga.n_verify;

@@ -64,6 +64,18 @@ int StageRing::upload(const void* src, size_t bytes, hipStream_t stream, void** 
     return MS_OK;
 }
 
+int StageRing::upload_to(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+    if (bytes > kSlotBytes) MS_FAIL(MS_ERR_INVALID, "internal: staging upload of %zu bytes", bytes);
+    int s = next;
+    next = (next + 1) % kSlots;
+    if (used[s]) MS_HIP_TRY(hipEventSynchronize(ev[s]));
+    memcpy(h + s * kSlotBytes, src, bytes);
+    MS_HIP_TRY(hipMemcpyAsync(dst, h + s * kSlotBytes, bytes, hipMemcpyHostToDevice, stream));
+    MS_HIP_TRY(hipEventRecord(ev[s], stream));
+    used[s] = true;
+    return MS_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
 // kernels
 // ---------------------------------------------------------------------------------------------
@@ -113,6 +125,58 @@ __global__ __launch_bounds__(256) void kv_scatter(ScatterArgs a) {
     const long src_row = (long)layer * a.buf_layer_rows + de.buf_first + j;
     const int t = de.cache_begin + j;
     const int page = a.d_pt[(size_t)de.seq * a.max_pages + t / MS_PAGE_SIZE];
+    const int slot = t % MS_PAGE_SIZE;
+    T* pool = (T*)a.pool + (size_t)layer * a.layer_elems + (size_t)page * a.page_elems;
+    const T* ks = (const T*)a.k + src_row * a.n_kv_heads * D;
+    const T* vs = (const T*)a.v + src_row * a.n_kv_heads * D;
+    const float posf = a.rope ? (float)a.pos[de.buf_first + j] : 0.f;
+    constexpr int H2 = D / 2;
+    for (int e = threadIdx.x; e < a.n_kv_heads * H2; e += blockDim.x) {
+        const int g = e / H2, i = e % H2;
+        float x0 = to_float(ks[g * D + i]), x1 = to_float(ks[g * D + i + H2]);
+        if (a.rope) {
+            float sn, cs;
+            sincosf(posf * a.inv_freq[i], &sn, &cs);
+            const float y0 = x0 * cs - x1 * sn, y1 = x1 * cs + x0 * sn;
+            x0 = y0;
+            x1 = y1;
+        }
+        T* kd = pool + ((size_t)g * 2 + 0) * MS_PAGE_SIZE * D + slot * D;
+        T* vd = pool + ((size_t)g * 2 + 1) * MS_PAGE_SIZE * D + slot * D;
+        kd[i] = from_float<T>(x0);
+        kd[i + H2] = from_float<T>(x1);
+        vd[i] = vs[g * D + i];
+        vd[i + H2] = vs[g * D + i + H2];
+    }
+}
+
+// Small calls (the decode-step case) carry their row descriptors and page-table patches in the
+// kernel arguments: one launch, no staging copy.  A workgroup finds its destination page among the
+// call's patches first (the mirror does not hold them yet) and in the mirror otherwise; workgroup
+// (0, 0) writes the patches into the mirror for the launches that follow.
+constexpr int kInlineSeqs = 64;
+constexpr int kInlinePatches = 128;
+struct InlineTables {
+    RowDesc desc[kInlineSeqs];
+    int patch[3 * kInlinePatches];
+    int n_patch;
+};
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void kv_scatter_inline(ScatterArgs a, InlineTables tb) {
+    const int r = blockIdx.x, layer = blockIdx.y;
+    const int b = find_seq(tb.desc, a.n_seq, r);
+    const RowDesc de = tb.desc[b];
+    const int j = r - de.prefix;
+    const long src_row = (long)layer * a.buf_layer_rows + de.buf_first + j;
+    const int t = de.cache_begin + j;
+    int page = -1;
+    for (int i = 0; i < tb.n_patch; ++i)
+        if (tb.patch[3 * i] == de.seq && tb.patch[3 * i + 1] == t / MS_PAGE_SIZE) page = tb.patch[3 * i + 2];
+    if (page < 0) page = a.d_pt[(size_t)de.seq * a.max_pages + t / MS_PAGE_SIZE];
+    if (r == 0 && layer == 0)
+        for (int i = threadIdx.x; i < tb.n_patch; i += blockDim.x)
+            const_cast<int*>(a.d_pt)[(size_t)tb.patch[3 * i] * a.max_pages + tb.patch[3 * i + 1]] = tb.patch[3 * i + 2];
     const int slot = t % MS_PAGE_SIZE;
     T* pool = (T*)a.pool + (size_t)layer * a.layer_elems + (size_t)page * a.page_elems;
     const T* ks = (const T*)a.k + src_row * a.n_kv_heads * D;
@@ -248,6 +312,48 @@ static int launch_rows(ms_cache* c, bool gather, const std::vector<RowDesc>& des
             hipLaunchKernelGGL((kv_gather<T, D>), grid, dim3(256), 0, stream, a);
         else
             hipLaunchKernelGGL((kv_scatter<T, D>), grid, dim3(256), 0, stream, a);
+        MS_HIP_TRY(hipGetLastError());
+        return (int)MS_OK;
+    });
+}
+
+// Patches the mirror and scatters rows in one launch when the call is small enough for its tables
+// to travel in the kernel arguments; otherwise patch launch(es) + staged descriptors + scatter.
+static int patch_and_scatter(ms_cache* c, const std::vector<RowDesc>& desc, int total_rows, const void* k,
+                             const void* v, const int* pos, long buf_layer_rows, int rope, hipStream_t stream) {
+    const size_t n_patch = c->pending_pt.size() / 3;
+    if (total_rows == 0 || desc.size() > (size_t)kInlineSeqs || n_patch > (size_t)kInlinePatches) {
+        int rc = flush_page_table_patches(c, stream);
+        if (rc != MS_OK) return rc;
+        return launch_rows(c, false, desc, total_rows, k, v, pos, buf_layer_rows, rope, stream);
+    }
+    InlineTables tb;
+    memset(&tb, 0, sizeof(tb));
+    memcpy(tb.desc, desc.data(), desc.size() * sizeof(RowDesc));
+    memcpy(tb.patch, c->pending_pt.data(), n_patch * 3 * sizeof(int));
+    tb.n_patch = (int)n_patch;
+    c->pending_pt.clear();
+    ScatterArgs a;
+    a.pool = c->d.pool;
+    a.d_pt = c->d_pt;
+    a.inv_freq = c->d_inv_freq;
+    a.desc = nullptr;
+    a.n_seq = (int)desc.size();
+    a.total_rows = total_rows;
+    a.k = k;
+    a.v = v;
+    a.pos = pos;
+    a.buf_layer_rows = buf_layer_rows;
+    a.n_kv_heads = c->d.n_kv_heads;
+    a.max_pages = c->d.max_pages_per_seq;
+    a.page_elems = (long)c->page_elems;
+    a.layer_elems = (long)c->layer_elems;
+    a.rope = rope;
+    dim3 grid((unsigned)total_rows, (unsigned)c->d.n_layers);
+    return dispatch(c, [&](auto* tp, auto dc) -> int {
+        using T = std::remove_pointer_t<decltype(tp)>;
+        constexpr int D = decltype(dc)::value;
+        hipLaunchKernelGGL((kv_scatter_inline<T, D>), grid, dim3(256), 0, stream, a, tb);
         MS_HIP_TRY(hipGetLastError());
         return (int)MS_OK;
     });
@@ -442,9 +548,7 @@ static int append_rows(ms_cache* c, const char* what, int B, const int* seq_ids,
         grow(c, seq_ids[b], counts[b]);
         total += counts[b];
     }
-    int rc = flush_page_table_patches(c, stream);
-    if (rc != MS_OK) return rc;
-    return launch_rows(c, false, desc, total, k, v, pos, buf_layer_rows, rope, stream);
+    return patch_and_scatter(c, desc, total, k, v, pos, buf_layer_rows, rope, stream);
 }
 
 int ms_append_kv(ms_cache* c, int B, const int* seq_ids, const int* n_tok, const void* k, const void* v,
@@ -584,9 +688,11 @@ int ms_compact_segment(ms_cache* c, int B, const int* seq_ids, const int* seg_be
         }
         grow(c, s, t);
     }
+    // ---- 3. scatter memory rows (rotated at their UPL position ids), then the saved tails ----
+    if (total_tail == 0 && total_mem > 0)
+        return patch_and_scatter(c, mems, (int)total_mem, mem_k, mem_v, mem_pos, total_mem, flags == MS_ROPE_APPLY, stream);
     rc = flush_page_table_patches(c, stream);
     if (rc != MS_OK) return rc;
-    // ---- 3. scatter memory rows (rotated at their UPL position ids), then the saved tails ----
     rc = launch_rows(c, false, mems, (int)total_mem, mem_k, mem_v, mem_pos, total_mem, flags == MS_ROPE_APPLY, stream);
     if (rc != MS_OK) return rc;
     return launch_rows(c, false, tails_dst, (int)total_tail, tail_k, tail_v, nullptr, total_tail, 0, stream);

@@ -44,6 +44,8 @@ struct StageRing {
     void destroy();
     // Copies `bytes` (<= kSlotBytes) to a device slot on `stream`; *dev receives the slot address.
     int upload(const void* src, size_t bytes, hipStream_t stream, void** dev);
+    // Same through a pinned slot, but to a device address of the caller's.
+    int upload_to(void* dst, const void* src, size_t bytes, hipStream_t stream);
 };
 
 // Which rows of a packed [rows][Hkv][D] buffer go to / come from which logical cache rows.
