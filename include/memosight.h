@@ -167,7 +167,7 @@ size_t ms_compact_workspace_bytes(ms_cache* cache, int B, const int* seq_ids, co
  * sees the i verify tokens before it; each foresight token sees the whole verify block and no
  * other foresight token.  The cache is only read.
  *   seq_ids : host [B], B <= MS_MAX_BATCH;  n_q <= MS_MAX_QUERIES, n_verify >= 0, n_q >= 1
- *   q       : device [B][n_q][n_q_heads][head_dim]
+ *   q       : device [B][n_q][n_q_heads][head_dim]            (q, k_new, v_new, out: 16-byte aligned)
  *   k_new, v_new : device [B][n_q][n_kv_heads][head_dim]
  *   pos_ids : device [B][n_q];  ctx_new : device [B][n_q] or NULL
  *   scale   : 0 means 1/sqrt(head_dim)

@@ -279,6 +279,8 @@ extern "C" int ms_predict_verify_attention(ms_cache* c, int layer, int B, const 
     a.n_splits = 1;
     a.chunk = 0;
     a.scale = scale != 0.f ? scale : 1.0f / sqrtf((float)c->d.head_dim);
+    if ((((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)out) & 15) != 0)
+        MS_FAIL(MS_ERR_INVALID, "ms_predict_verify_attention: q, k_new, v_new and out must be 16-byte aligned");
     if (mfma_eligible(c, n_q)) return launch_mfma(c, a, bm, B, stream);
     const int D = c->d.head_dim;
     if (c->d.dtype == MS_F32)

@@ -119,6 +119,10 @@ SMALL = [
     ("bf16", 28, 4, 128, 0, 3, [260]),
     ("bf16", 28, 4, 128, 9, 0, [515, 31]),
     ("bf16", 4, 4, 128, 12, 4, [100, 1500]),
+    ("bf16", 28, 4, 128, 1, 0, [777, 32, 33]),          # plain decode: one query, 7 rows per KV head
+    ("bf16", 28, 4, 128, 4, 3, [0, 0]),                 # nothing cached yet: in-flight tokens only
+    ("bf16", 32, 8, 128, 5, 4, [4096 + 17, 31, 2048]),  # group of 4: 36 rows per KV head
+    ("bf16", 28, 4, 128, 5, 4, [5000, 64, 3000, 9000, 130, 7000, 1, 2500]),  # shares cross sequences
 ]
 
 
