@@ -599,3 +599,101 @@ def test_errors_are_reported_and_leave_state_unchanged():
         with pytest.raises(M.MsError):
             M.ms_seq_len(ses.cache, s)
         assert M.ms_free_page_count(ses.cache) == 3
+
+
+# ------------------------------------------------------------------ Algorithm 1 as a state machine ---
+
+def test_algorithm1_loop_keeps_gpu_and_oracle_in_step():
+    """Drives both sides through the paper's inference loop (Appendix A, Algorithm 1) with random
+    stand-ins for the model: speculative steps (attention, acceptance, commit of the accepted rows),
+    and, whenever a sequence's step closes, the memory-token pass (l + 1 causal queries, no foresight)
+    followed by compaction of that sequence only.  After every call the page tables, lengths and
+    attention outputs must agree; this also exercises the cached work plan across cache changes."""
+    M, S = _mods()
+    rng = W.make_rng(500)
+    B, L, Hq, Hkv, D, NP = 3, 2, 28, 4, 128, 96
+    nv, nf, c_ratio = 4, 3, 5
+    nq = nv + nf
+    ses = S.Session(L, Hq, Hkv, D, NP, M.MS_BF16, 1000000.0, max_seqs=B, max_pages_per_seq=40)
+    ora = O.PagedCache(L, Hkv, D, NP, dtype=O.BF16, rope_base=1000000.0, max_seqs=B)
+    bf = O.bf16_bits_to_f32
+    with ses:
+        ids = [M.ms_seq_create(ses.cache) for _ in range(B)]
+        assert ids == [ora.seq_create() for _ in range(B)]
+        # "prefill": prompts of different lengths
+        prompt = [37, 5, 64]
+        n = sum(prompt)
+        k, v = W.normal_bf16_bits(rng, (L, n, Hkv, D)), W.normal_bf16_bits(rng, (L, n, Hkv, D))
+        pos = np.concatenate([np.arange(1, p + 1) for p in prompt]).astype(np.int32)
+        M.ms_append_kv(ses.cache, ids, prompt, S.to_device(k, M.MS_BF16), S.to_device(v, M.MS_BF16), S.ints_dev(pos))
+        ora.append(ids, prompt, bf(k), bf(v), pos)
+        next_pid = [p + 1 for p in prompt]
+        seg_start_len = list(prompt)            # cache length at which the open step began
+        seg_first_pid = list(next_pid)
+        close_at = [11, 23, 17]                 # a step closes once it holds this many tokens
+        n_compactions = 0
+        for step in range(30):
+            q = W.normal_bf16_bits(rng, (B, nq, Hq, D))
+            kn = W.normal_bf16_bits(rng, (L, B, nq, Hkv, D))
+            vn = W.normal_bf16_bits(rng, (L, B, nq, Hkv, D))
+            pq = np.asarray([list(range(p, p + nv)) + M.ms_foresight_pids(p + nv - 1, nf) for p in next_pid], np.int32)
+            for layer in range(L):
+                out = ses.attention(layer, ids, nv, nf, S.to_device(q, M.MS_BF16), S.to_device(kn[layer], M.MS_BF16),
+                                    S.to_device(vn[layer], M.MS_BF16), S.ints_dev(pq).view(B, nq))
+                want = O.attention(ora, layer, ids, nv, nf, bf(q), bf(kn[layer]), bf(vn[layer]), pq)
+                check_out(S.to_host_f32(out), want, "bf16", f"step {step} layer {layer}")
+            forced = [int(x) for x in rng.integers(0, nv + 1, size=B)]
+            draft, target = W.draft_and_target(rng, B, nv, 1000, forced)
+            acc_d = torch.empty(B, dtype=torch.int32, device="cuda")
+            nxt_d = torch.empty(B, dtype=torch.int32, device="cuda")
+            M.ms_accept(B, nv, S.ints_dev(draft), S.ints_dev(target), None, acc_d, nxt_d)
+            acc = acc_d.cpu().numpy()
+            wa, _ = O.accept(draft, target)
+            assert np.array_equal(acc, wa)
+            acc = [max(1, int(a)) for a in acc]          # the first draft is the previous bonus token
+            M.ms_commit_accepted(ses.cache, ids, acc, nq, S.to_device(kn, M.MS_BF16), S.to_device(vn, M.MS_BF16),
+                                 S.ints_dev(pq).view(B, nq))
+            for b in range(B):
+                ora.append([ids[b]], [acc[b]], bf(kn)[:, b, :acc[b]], bf(vn)[:, b, :acc[b]], pq[b, :acc[b]])
+                next_pid[b] += acc[b]
+            # close finished steps: memory-token pass, then compaction, for those sequences only
+            closing = [b for b in range(B) if M.ms_seq_len(ses.cache, ids[b]) - seg_start_len[b] >= close_at[b]]
+            if closing:
+                seg_len = [M.ms_seq_len(ses.cache, ids[b]) - seg_start_len[b] for b in closing]
+                n_mem = [M.ms_ama_count(s_, c_ratio) for s_ in seg_len]
+                assert n_mem == [O.ama_count(s_, c_ratio) for s_ in seg_len]
+                cids = [ids[b] for b in closing]
+                # memory tokens take UPL position ids, <o> the position after the step
+                mpos = [M.ms_upl_positions(seg_first_pid[b], s_, c_ratio) for b, s_ in zip(closing, seg_len)]
+                assert mpos == [O.upl_positions(seg_first_pid[b], s_, c_ratio) for b, s_ in zip(closing, seg_len)]
+                for bi, b in enumerate(closing):        # memory-token forward: l + 1 causal queries, one sequence
+                    lq = n_mem[bi] + 1
+                    if lq > 16:
+                        continue
+                    qm = W.normal_bf16_bits(rng, (1, lq, Hq, D))
+                    km = W.normal_bf16_bits(rng, (1, lq, Hkv, D))
+                    vm = W.normal_bf16_bits(rng, (1, lq, Hkv, D))
+                    pm = np.asarray([mpos[bi] + [M.ms_output_token_pid(next_pid[b] - 1)]], np.int32)
+                    out = ses.attention(1, [ids[b]], lq, 0, S.to_device(qm, M.MS_BF16), S.to_device(km, M.MS_BF16),
+                                        S.to_device(vm, M.MS_BF16), S.ints_dev(pm).view(1, lq))
+                    want = O.attention(ora, 1, [ids[b]], lq, 0, bf(qm), bf(km), bf(vm), pm)
+                    check_out(S.to_host_f32(out), want, "bf16", f"memory-token pass, step {step}, seq {b}")
+                tot = sum(n_mem)
+                mk, mv = W.normal_bf16_bits(rng, (L, tot, Hkv, D)), W.normal_bf16_bits(rng, (L, tot, Hkv, D))
+                flat = sum(mpos, [])
+                begin = [seg_start_len[b] for b in closing]
+                M.ms_compact_segment(ses.cache, cids, begin, seg_len, n_mem, S.to_device(mk, M.MS_BF16),
+                                     S.to_device(mv, M.MS_BF16), S.ints_dev(flat))
+                ora.compact(cids, begin, seg_len, n_mem, bf(mk), bf(mv), flat)
+                n_compactions += len(closing)
+                for b in closing:
+                    next_pid[b] = M.ms_output_token_pid(next_pid[b] - 1) + 1
+                    seg_start_len[b] = M.ms_seq_len(ses.cache, ids[b])
+                    seg_first_pid[b] = next_pid[b]
+            for b in range(B):
+                assert M.ms_seq_page_table(ses.cache, ids[b]) == ora.page_table[ids[b]]
+                assert M.ms_seq_len(ses.cache, ids[b]) == ora.seq_len[ids[b]]
+            assert M.ms_free_page_count(ses.cache) == ora.free_page_count()
+            M.ms_check_integrity(ses.cache)
+        assert n_compactions >= 6
+        assert M.ms_peak_pages(ses.cache) == ora.peak_pages
