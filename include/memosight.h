@@ -42,7 +42,7 @@ extern "C" {
 
 #define MS_PAGE_SIZE 16
 #define MS_MAX_BATCH 256        /* sequences per call */
-#define MS_MAX_QUERIES 16       /* n_verify + n_foresight per sequence */
+#define MS_MAX_QUERIES 64       /* n_verify + n_foresight per sequence */
 
 enum { MS_F32 = 0, MS_BF16 = 1 };
 

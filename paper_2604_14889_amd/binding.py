@@ -19,7 +19,7 @@ from . import build as _build
 
 MS_PAGE_SIZE = 16
 MS_MAX_BATCH = 256
-MS_MAX_QUERIES = 16
+MS_MAX_QUERIES = 64
 MS_F32, MS_BF16 = 0, 1
 MS_OK, MS_ERR_INVALID, MS_ERR_OOM_PAGES, MS_ERR_RANGE = 0, -1, -2, -3
 MS_ERR_HIP, MS_ERR_UNSUPPORTED, MS_ERR_WORKSPACE = -4, -5, -6
@@ -102,6 +102,21 @@ def _dev(t) -> Optional[int]:
     return t.data_ptr()
 
 
+_DESC = {}   # cache handle -> (n_layers, n_q_heads, n_kv_heads, head_dim, element size)
+
+
+def _sized(cache, t, what: str, n_elems: int, elem_size: Optional[int] = None) -> Optional[int]:
+    """Device address of a tensor that must hold at least n_elems elements.  The C functions take
+    bare pointers and trust the sizes they are told, so the extents are checked here."""
+    if t is None:
+        return None
+    want = _DESC[cache][4] if elem_size is None else elem_size
+    if t.numel() < n_elems or t.element_size() != want:
+        raise MsError(MS_ERR_INVALID, f"{what}: expected at least {n_elems} elements of {want} bytes, got "
+                                      f"{t.numel()} of {t.element_size()}")
+    return _dev(t)
+
+
 def _stream(stream) -> Optional[int]:
     if stream is None:
         if not torch.cuda.is_available():
@@ -131,11 +146,13 @@ def ms_pool_bytes(desc: ms_cache_desc) -> int:
 def ms_cache_create(desc: ms_cache_desc) -> int:
     h = _P()
     _check(lib.ms_cache_create(C.byref(desc), C.byref(h)))
+    _DESC[h.value] = (desc.n_layers, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, 2 if desc.dtype == MS_BF16 else 4)
     return h.value
 
 
 def ms_cache_destroy(cache: int) -> None:
     _check(lib.ms_cache_destroy(cache))
+    _DESC.pop(cache, None)
 
 
 def ms_seq_create(cache: int) -> int:
@@ -155,13 +172,19 @@ def ms_seq_free(cache: int, seq_id: int) -> None:
 
 
 def ms_append_kv(cache, seq_ids, n_tok, k, v, pos_ids, flags=MS_ROPE_APPLY, stream=None) -> None:
-    _check(lib.ms_append_kv(cache, len(seq_ids), _ints(seq_ids), _ints(n_tok), _dev(k), _dev(v),
-                            _dev(pos_ids), flags, _stream(stream)))
+    L, _, hkv, d, _ = _DESC[cache]
+    rows = sum(int(n) for n in n_tok)
+    _check(lib.ms_append_kv(cache, len(seq_ids), _ints(seq_ids), _ints(n_tok),
+                            _sized(cache, k, "k", L * rows * hkv * d), _sized(cache, v, "v", L * rows * hkv * d),
+                            _sized(cache, pos_ids, "pos_ids", rows, 4), flags, _stream(stream)))
 
 
 def ms_commit_accepted(cache, seq_ids, accept_len, n_q, k_new, v_new, pos_ids, stream=None) -> None:
+    L, _, hkv, d, _ = _DESC[cache]
+    n = L * len(seq_ids) * n_q * hkv * d
     _check(lib.ms_commit_accepted(cache, len(seq_ids), _ints(seq_ids), _ints(accept_len), n_q,
-                                  _dev(k_new), _dev(v_new), _dev(pos_ids), _stream(stream)))
+                                  _sized(cache, k_new, "k_new", n), _sized(cache, v_new, "v_new", n),
+                                  _sized(cache, pos_ids, "pos_ids", len(seq_ids) * n_q, 4), _stream(stream)))
 
 
 def ms_compact_workspace_bytes(cache, seq_ids, seg_begin, seg_len) -> int:
@@ -171,8 +194,12 @@ def ms_compact_workspace_bytes(cache, seq_ids, seg_begin, seg_len) -> int:
 def ms_compact_segment(cache, seq_ids, seg_begin, seg_len, n_mem, mem_k, mem_v, mem_pos,
                        flags=MS_ROPE_APPLY, workspace=None, stream=None) -> None:
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    L, _, hkv, d, _ = _DESC[cache]
+    rows = sum(int(n) for n in n_mem)
     _check(lib.ms_compact_segment(cache, len(seq_ids), _ints(seq_ids), _ints(seg_begin), _ints(seg_len),
-                                  _ints(n_mem), _dev(mem_k), _dev(mem_v), _dev(mem_pos), flags,
+                                  _ints(n_mem), _sized(cache, mem_k, "mem_k", L * rows * hkv * d),
+                                  _sized(cache, mem_v, "mem_v", L * rows * hkv * d),
+                                  _sized(cache, mem_pos, "mem_pos", rows, 4), flags,
                                   _dev(workspace), ws_bytes, _stream(stream)))
 
 
@@ -183,15 +210,21 @@ def ms_attention_workspace_bytes(cache, B: int, n_q: int) -> int:
 def ms_predict_verify_attention(cache, layer, seq_ids, n_verify, n_foresight, q, k_new, v_new, pos_ids,
                                 ctx_new, scale, out, workspace, stream=None) -> None:
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _, hq, hkv, d, _ = _DESC[cache]
+    rows = len(seq_ids) * (n_verify + n_foresight)
     _check(lib.ms_predict_verify_attention(cache, layer, len(seq_ids), _ints(seq_ids), n_verify, n_foresight,
-                                           _dev(q), _dev(k_new), _dev(v_new), _dev(pos_ids), _dev(ctx_new),
-                                           float(scale), _dev(out), _dev(workspace), ws_bytes, _stream(stream)))
+                                           _sized(cache, q, "q", rows * hq * d), _sized(cache, k_new, "k_new", rows * hkv * d),
+                                           _sized(cache, v_new, "v_new", rows * hkv * d), _sized(cache, pos_ids, "pos_ids", rows, 4),
+                                           _sized(cache, ctx_new, "ctx_new", rows, 4), float(scale),
+                                           _sized(cache, out, "out", rows * hq * d), _dev(workspace), ws_bytes,
+                                           _stream(stream)))
 
 
 def ms_accept(B, n, draft, target, stop_ids, accept_len, next_token, stream=None) -> None:
     n_stop = 0 if stop_ids is None else stop_ids.numel()
-    _check(lib.ms_accept(B, n, _dev(draft), _dev(target), _dev(stop_ids), n_stop, _dev(accept_len),
-                         _dev(next_token), _stream(stream)))
+    _check(lib.ms_accept(B, n, _sized(None, draft, "draft", B * n, 4), _sized(None, target, "target", B * n, 4),
+                         _sized(None, stop_ids, "stop_ids", n_stop, 4), n_stop, _sized(None, accept_len, "accept_len", B, 4),
+                         _sized(None, next_token, "next_token", B, 4), _stream(stream)))
 
 
 def ms_seq_len(cache, seq_id: int) -> int:

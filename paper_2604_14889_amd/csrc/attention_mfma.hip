@@ -51,18 +51,30 @@ constexpr int kPartFloats = 2 * kRows + kRows * kD;  // m[64], l[64], O[128 regs
 // LDS map.  Stream phase: [Q tile][cos/sin table][in-flight K tile][one V tile per wave].  Merge
 // phase (overlays it): per wave 64 accumulator registers (two d blocks of both row blocks) + 4
 // softmax scalars per lane.
-constexpr int kLdsQ = 0;
-constexpr int kLdsCs = kLdsQ + kRows * kQRowBytes;                       // 17408
-constexpr int kLdsKn = kLdsCs + MS_MAX_QUERIES * 64 * 8;                 // + 8192
-constexpr int kLdsV = kLdsKn + kTile * kQRowBytes;                       // + 8704
-constexpr int kLdsStream = kLdsV + kWaves * kVTileBytes;                 // + 73728 = 108032
+//
+// The kernel comes in two builds.  The decode build takes all of a step's queries in one launch
+// (at most 16 queries, 64 rows).  The wide build (memory-token pass, per-position foresight: up to
+// 64 queries) is launched once per chunk of 64 / group queries; every launch sees all of the
+// step's in-flight keys, in up to two 32-token tiles.
+constexpr int kDecodeQueries = 16;
 constexpr int kMergeRegionBytes = (64 + 4) * 64 * 4;                     // 17408
 constexpr int kLdsMerge = kWaves * kMergeRegionBytes;                    // 139264
-constexpr int kLdsFlag = kLdsMerge > kLdsStream ? kLdsMerge : kLdsStream;  // one word: "last arriver"
-constexpr int kLdsBytes = kLdsFlag + 16;
+template <bool kWide>
+struct Lds {
+    static constexpr int kQueries = kWide ? MS_MAX_QUERIES : kDecodeQueries;   // rows of the cos/sin table
+    static constexpr int kNewTiles = kWide ? (MS_MAX_QUERIES + kTile - 1) / kTile : 1;
+    static constexpr int kQ = 0;
+    static constexpr int kCs = kQ + kRows * kQRowBytes;                  // 17408
+    static constexpr int kKn = kCs + kQueries * 64 * 8;                  // + 8192 (wide: 32768)
+    static constexpr int kV = kKn + kNewTiles * kTile * kQRowBytes;      // + 8704 (wide: 17408)
+    static constexpr int kStream = kV + kWaves * kVTileBytes;            // + 73728 = 108032 (wide: 141312)
+    static constexpr int kFlag = kLdsMerge > kStream ? kLdsMerge : kStream;  // one word: "last arriver"
+    static constexpr int kBytes = kFlag + 16;
+    static_assert(kBytes <= 160 * 1024, "LDS budget of one compute unit");
+};
 constexpr int kThreads = kWaves * 64;
 static_assert(kThreads == kRows * 8, "the Q prologue maps one thread to one row and 8 rotation pairs");
-static_assert(kLdsBytes <= 160 * 1024, "LDS budget of one compute unit");
+static_assert(MS_MAX_QUERIES * 8 <= kThreads, "the K prologue maps one thread to one in-flight key and 8 rotation pairs");
 
 struct Seg {
     int b;          // index in the call's batch
@@ -92,6 +104,7 @@ struct MfmaArgs {
     const int* part_begin;  // [B + 1]
     int* arrive;            // [B][n_kv_heads] arrival counters, zero between calls
     int n_q, n_verify, n_q_heads, n_kv_heads, group, max_pages;
+    int q0, n_qc;           // this launch computes queries q0 .. q0 + n_qc (decode build: all of them)
     long page_elems;
     float scale_log2;       // softmax scale * log2(e)
 #ifdef MS_TIMING
@@ -320,8 +333,8 @@ __device__ __forceinline__ void mask_inflight(f32x16_t& s, int lim, int self, in
 // output rows.  Run by all 512 threads of the workgroup that arrived last for the pair: wave w owns
 // row block w / 4 and d block w % 4, a lane one row and 16 accumulators, laid out as in the stream.
 // Partials are taken two at a time so that their loads overlap.
-__device__ __forceinline__ void combine_partials(const MfmaArgs& a, int b, int g, int p_begin, int p_end, int w, int lane) {
-    const int n_rows = a.n_q * a.group;
+__device__ __forceinline__ void combine_partials(const MfmaArgs& a, int q0, int n_rows, int b, int g, int p_begin, int p_end,
+                                                 int w, int lane) {
     const int rb = w >> 2, db = w & 3, l32 = lane & 31, hf = lane >> 5;
     const int row = 32 * rb + l32;
     float m = -INFINITY, lsum = 0.f, o[16];
@@ -359,7 +372,7 @@ __device__ __forceinline__ void combine_partials(const MfmaArgs& a, int b, int g
     }
     if (row < n_rows) {
         const float inv = 1.f / lsum;
-        uint16_t* op = a.out + (((size_t)b * a.n_q + row / a.group) * a.n_q_heads + g * a.group + row % a.group) * kD + 32 * db + 4 * hf;
+        uint16_t* op = a.out + (((size_t)b * a.n_q + q0 + row / a.group) * a.n_q_heads + g * a.group + row % a.group) * kD + 32 * db + 4 * hf;
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
             uint2 pk;
@@ -370,15 +383,18 @@ __device__ __forceinline__ void combine_partials(const MfmaArgs& a, int b, int g
     }
 }
 
+template <bool kWide>
 __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    typedef Lds<kWide> L;
+    const int q0 = kWide ? a.q0 : 0, n_qc = kWide ? a.n_qc : a.n_q;
     const int item = blockIdx.x, g = blockIdx.y;
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, hf = lane >> 5, l32 = lane & 31, l16 = lane & 15;
-    const int n_rows = a.n_q * a.group;
-    char* vl = smem + kLdsV + w * kVTileBytes;
-    float2* cs_tab = reinterpret_cast<float2*>(smem + kLdsCs);
+    const int n_rows = n_qc * a.group;
+    char* vl = smem + L::kV + w * kVTileBytes;
+    float2* cs_tab = reinterpret_cast<float2*>(smem + L::kCs);
     // V^T operand addressing.  Within a 16-lane group the transposing load gives lane i, element j
     // the value M[4 j + i / 4][i % 4] of the 16 x 4 block whose row r is addressed by lane r.
     // Source lane r points at token T[r / 4], columns d0 + 4 (r % 4) .. + 4, so result lane i holds
@@ -386,7 +402,7 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
     // operand element 4 w + j is score accumulator 8 ks + 4 w + j.
     const char* vbase = vl + (4 * hf + (l16 >> 2)) * kVRowBytes + (16 * ((lane >> 4) & 1) + 4 * (l16 & 3)) * 2;
     // Q^T operand: column = query row 32 rb + lane % 32, k = 16 kk + 8 (lane / 32) .. + 8
-    const char* qbase = smem + kLdsQ + l32 * kQRowBytes + 16 * hf;
+    const char* qbase = smem + L::kQ + l32 * kQRowBytes + 16 * hf;
     char* vwrite = vl + (lane >> 4) * kVRowBytes + l16 * 16;
     // byte offsets inside a page: K operand row = token lane % 16 of the page, 16 bytes at d = 8 (lane / 32);
     // V row = token lane / 16 (+ 4 rr), 16 bytes at d = 8 (lane % 16)
@@ -425,7 +441,7 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         const int qr = tid_p >> 3, qc = tid_p & 7;
         // all of these loads are unconditional (out-of-range rows read row 0 and are zeroed by their
         // rotation factors) so that the number of loads in flight is known and waits stay partial
-        const int qi = qr < n_rows ? qr / a.group : 0;
+        const int qi = q0 + (qr < n_rows ? qr / a.group : 0);
         const int qh = qr < n_rows ? qr % a.group : 0;
         const uint16_t* qp = a.q + (((size_t)sg_b * a.n_q + qi) * a.n_q_heads + g * a.group + qh) * kD + 8 * qc;
         const uint4 x0v = *reinterpret_cast<const uint4*>(qp);
@@ -433,16 +449,17 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         const uint16_t* kp = a.k_new + (((size_t)sg_b * a.n_q + (qr < a.n_q ? qr : 0)) * a.n_kv_heads + g) * kD + 8 * qc;
         const uint4 k0v = *reinterpret_cast<const uint4*>(kp);
         const uint4 k1v = *reinterpret_cast<const uint4*>(kp + 64);
-        // position ids of queries w and w + 8 (wave-uniform: scalar loads)
-        int pos_w[2];
+        // position ids of queries w, w + 8, ... (wave-uniform: scalar loads)
+        constexpr int kPosPerWave = L::kQueries / kWaves;
+        int pos_w[kPosPerWave];
 #pragma unroll
-        for (int k = 0; k < 2; ++k) pos_w[k] = w + 8 * k < a.n_q ? uniform_load(a.pos + sg_b * a.n_q + w + 8 * k) : 0;
+        for (int k = 0; k < kPosPerWave; ++k) pos_w[k] = w + 8 * k < a.n_q ? uniform_load(a.pos + sg_b * a.n_q + w + 8 * k) : 0;
         TileRegs r;   // (an empty segment's record names page 0: loaded, never used)
         load_v(r.v, pool, pa, pb, page_bytes, lane_off_v);
         load_k(r.k, pool, pa, pb, page_bytes, lane_off_k, lane);
-        // cos/sin table: wave w fills the rows of queries w and w + 8, lane = rotation pair
+        // cos/sin table: wave w fills the rows of queries w, w + 8, ..., lane = rotation pair
 #pragma unroll
-        for (int k = 0; k < 2; ++k)
+        for (int k = 0; k < kPosPerWave; ++k)
             if (w + 8 * k < a.n_q) {
                 float sn, cs;
                 sincos_reduced((float)pos_w[k] * inv_f, &sn, &cs);
@@ -474,11 +491,11 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
                 z0[e2] = pack_bf16x2(s0[0], s0[1]);
                 z1[e2] = pack_bf16x2(s1[0], s1[1]);
             }
-            char* qrow = smem + kLdsQ + qr * kQRowBytes + 16 * qc;
+            char* qrow = smem + L::kQ + qr * kQRowBytes + 16 * qc;
             *reinterpret_cast<uint4*>(qrow) = make_uint4(y0[0], y0[1], y0[2], y0[3]);
             *reinterpret_cast<uint4*>(qrow + 128) = make_uint4(y1[0], y1[1], y1[2], y1[3]);
-            if (first_seg && qr < kTile) {   // rows at and past n_q are zeros
-                char* krow = smem + kLdsKn + qr * kQRowBytes + 16 * qc;
+            if (first_seg && qr < L::kNewTiles * kTile) {   // rows at and past n_q are zeros
+                char* krow = smem + L::kKn + qr * kQRowBytes + 16 * qc;
                 *reinterpret_cast<uint4*>(krow) = make_uint4(z0[0], z0[1], z0[2], z0[3]);
                 *reinterpret_cast<uint4*>(krow + 128) = make_uint4(z1[0], z1[1], z1[2], z1[3]);
             }
@@ -490,7 +507,9 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         WaveState st;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
-            st.m[rb] = -INFINITY;
+            // wide build: an in-flight tile may be wholly invisible to a row whose state is still
+            // empty; a finite floor keeps 2^(s - m) at zero there instead of 2^(inf - inf)
+            st.m[rb] = kWide ? -1e30f : -INFINITY;
             st.l[rb] = 0.f;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
@@ -505,24 +524,30 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
             int ln = lane;
             asm volatile("" : "+v"(ln));
             const int l16 = ln & 15, l32 = ln & 31, hf = ln >> 5;
+            const int new_tiles = kWide ? (a.n_q + kTile - 1) / kTile : 1;
+            for (int it = 0; it < new_tiles; ++it) {
 #pragma unroll
-            for (int rr = 0; rr < 8; ++rr) {
-                const int tok = 4 * rr + (ln >> 4);
-                const int tc = tok < a.n_q ? tok : a.n_q - 1;   // clamped: the load is unconditional
-                const uint4 val = *reinterpret_cast<const uint4*>(a.v_new + (((size_t)sg_b * a.n_q + tc) * a.n_kv_heads + g) * kD + 8 * l16);
-                *reinterpret_cast<uint4*>(vwrite + 4 * rr * kVRowBytes) = tok < a.n_q ? val : make_uint4(0, 0, 0, 0);
-            }
+                for (int rr = 0; rr < 8; ++rr) {
+                    const int tok = kTile * it + 4 * rr + (ln >> 4);
+                    const int tc = tok < a.n_q ? tok : a.n_q - 1;   // clamped: the load is unconditional
+                    const uint4 val = *reinterpret_cast<const uint4*>(a.v_new + (((size_t)sg_b * a.n_q + tc) * a.n_kv_heads + g) * kD + 8 * l16);
+                    *reinterpret_cast<uint4*>(vwrite + 4 * rr * kVRowBytes) = tok < a.n_q ? val : make_uint4(0, 0, 0, 0);
+                }
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-                const int row = 32 * rb + l32;
-                const bool pad_row = row >= n_rows;
-                const int i = pad_row ? 0 : row / a.group;
-                int ctx = a.ctx_new ? a.ctx_new[sg_b * a.n_q + i] : (i < a.n_verify ? i : a.n_verify);
-                ctx = pad_row ? 0 : (ctx < a.n_q ? ctx : a.n_q);
-                f32x16_t s;
-                qk_block_lds(s, smem + kLdsKn + l32 * kQRowBytes + 16 * hf, qbase, rb);
-                mask_inflight(s, ctx, i, hf);
-                softmax_pv(st, s, rb, vbase);
+                for (int rb = 0; rb < 2; ++rb) {
+                    const int row = 32 * rb + l32;
+                    const bool pad_row = row >= n_rows;
+                    const int i = q0 + (pad_row ? 0 : row / a.group);
+                    int ctx = a.ctx_new ? a.ctx_new[sg_b * a.n_q + i] : (i < a.n_verify ? i : a.n_verify);
+                    ctx = pad_row ? 0 : (ctx < a.n_q ? ctx : a.n_q);
+                    f32x16_t s;
+                    qk_block_lds(s, smem + L::kKn + (kTile * it + l32) * kQRowBytes + 16 * hf, qbase, rb);
+                    // a tile none of whose tokens a row may see leaves that row's state untouched:
+                    // its scores are all minus infinity and its running maximum is already finite
+                    // or, on the first tile, made finite by the row's own token or an earlier one
+                    mask_inflight(s, ctx - kTile * it, i - kTile * it, hf);
+                    softmax_pv(st, s, rb, vbase);
+                }
             }
         }
 
@@ -646,11 +671,11 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
             const int seen = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const int last = seen == p_cnt - 1;
             if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
-            *reinterpret_cast<volatile int*>(smem + kLdsFlag) = last;
+            *reinterpret_cast<volatile int*>(smem + L::kFlag) = last;
         }
         lds_barrier();
-        if (*reinterpret_cast<volatile int*>(smem + kLdsFlag))
-            combine_partials(a, sg_b, g, a.part_begin[sg_b], a.part_begin[sg_b + 1], w, lane_m);
+        if (*reinterpret_cast<volatile int*>(smem + L::kFlag))
+            combine_partials(a, q0, n_rows, sg_b, g, a.part_begin[sg_b], a.part_begin[sg_b + 1], w, lane_m);
         lds_barrier();  // the next segment reuses the LDS
     }
 #ifdef MS_TIMING
@@ -662,10 +687,10 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
 // host side
 // ---------------------------------------------------------------------------------------------
 
-// bf16, head_dim 128, at most 64 query rows per KV head, and a layer's pool below 4 GiB (the kernel
-// addresses pages with 32-bit byte offsets from the layer base).
+// bf16, head_dim 128, at most 64 grouped heads per KV head, and a layer's pool below 4 GiB (the
+// kernel addresses pages with 32-bit byte offsets from the layer base).
 bool mfma_eligible(const ms_cache* c, int n_q) {
-    return c->d.dtype == MS_BF16 && c->d.head_dim == kD && n_q * c->group <= kRows &&
+    return c->d.dtype == MS_BF16 && c->d.head_dim == kD && c->group <= kRows && n_q <= MS_MAX_QUERIES &&
            (unsigned long long)c->layer_elems * 2ull < (1ull << 32);
 }
 
@@ -789,7 +814,10 @@ static void build_plan(const ms_cache* c, const BatchMeta& bm, int B, int n_item
 int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        MS_HIP_TRY(hipFuncSetAttribute((const void*)pv_attn_mfma_stream, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+        MS_HIP_TRY(hipFuncSetAttribute((const void*)pv_attn_mfma_stream<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       Lds<false>::kBytes));
+        MS_HIP_TRY(hipFuncSetAttribute((const void*)pv_attn_mfma_stream<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       Lds<true>::kBytes));
         attr_set = true;
     }
     // plan: rebuilt only when the batch (ids, lengths) changed since the last call on this cache
@@ -837,7 +865,20 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     {
         const bool prof = c->prof_count < (int)c->prof_start.size();
         if (prof) MS_HIP_TRY(hipEventRecord(c->prof_start[c->prof_count], stream));
-        hipLaunchKernelGGL(pv_attn_mfma_stream, dim3(c->plan_items, a.n_kv_heads), dim3(kThreads), kLdsBytes, stream, a);
+        const dim3 grid(c->plan_items, a.n_kv_heads);
+        if (a.n_q <= kDecodeQueries && a.n_q * a.group <= kRows) {
+            a.q0 = 0;
+            a.n_qc = a.n_q;
+            hipLaunchKernelGGL(pv_attn_mfma_stream<false>, grid, dim3(kThreads), Lds<false>::kBytes, stream, a);
+        } else {
+            // wide steps: one launch per chunk of queries; launches on one stream run in order, so
+            // they can share the partial workspace and the arrival counters
+            const int per_launch = kRows / a.group;
+            for (a.q0 = 0; a.q0 < a.n_q; a.q0 += per_launch) {
+                a.n_qc = a.n_q - a.q0 < per_launch ? a.n_q - a.q0 : per_launch;
+                hipLaunchKernelGGL(pv_attn_mfma_stream<true>, grid, dim3(kThreads), Lds<true>::kBytes, stream, a);
+            }
+        }
         MS_HIP_TRY(hipGetLastError());
         if (prof) MS_HIP_TRY(hipEventRecord(c->prof_stop[c->prof_count++], stream));
     }

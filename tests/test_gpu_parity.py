@@ -123,6 +123,14 @@ SMALL = [
     ("bf16", 28, 4, 128, 4, 3, [0, 0]),                 # nothing cached yet: in-flight tokens only
     ("bf16", 32, 8, 128, 5, 4, [4096 + 17, 31, 2048]),  # group of 4: 36 rows per KV head
     ("bf16", 28, 4, 128, 5, 4, [5000, 64, 3000, 9000, 130, 7000, 1, 2500]),  # shares cross sequences
+    # wide steps (more than 64 rows per KV head or more than 16 queries): several query chunks
+    ("bf16", 28, 4, 128, 10, 0, [100, 33]),             # 70 rows: two chunks, one in-flight tile
+    ("bf16", 28, 4, 128, 41, 0, [700]),                 # memory-token pass, l + 1 = 41: two in-flight tiles
+    ("bf16", 28, 4, 128, 64, 0, [300, 0, 2100]),        # the largest step
+    ("bf16", 32, 8, 128, 5, 20, [513, 64]),             # 25 queries, group of 4
+    ("bf16", 4, 4, 128, 33, 7, [90]),                   # one head per KV head, 40 queries in one chunk
+    ("f32", 8, 2, 64, 30, 10, [70, 5]),                 # general kernel, 40 queries
+    ("bf16", 8, 2, 64, 17, 0, [129]),
 ]
 
 
@@ -154,6 +162,37 @@ def test_attention_custom_ctx_new_and_peaked_scores():
         got = run_gpu_attention(ses, inp, ids, pos, ctx_new=ctx)
         want = oracle_attention(ora, inp, ids, pos, ctx_new=ctx)
         check_out(got, want, "bf16", "custom ctx_new, peaked")
+
+
+def test_per_position_foresight_layout_wide_step():
+    """Foresight tokens after every verify token (the layout the model is trained on, Section 2.3
+    "MTP Attention"; at inference it keeps drafts alive after a partial acceptance): 5 verify
+    tokens, 4 foresight tokens behind each, plus rows that see no other in-flight token at all,
+    some of them in the second in-flight tile."""
+    M, S = _mods()
+    nv, d = 5, 4
+    n_extra = 12                      # rows with ctx 0 at query indices 25 .. 36
+    nq = nv + nv * d + n_extra
+    sh = W.AttnShape("ppf", "bf16", 2, 28, 4, 128, nv, nq - nv, [450, 40], 0.5, 1000000.0)
+    inp = W.attention_inputs(sh, 402)
+    ses, ora, ids = setup_pair(inp)
+    with ses:
+        pos = np.zeros((2, nq), np.int32)
+        ctx = np.zeros((2, nq), np.int32)
+        for b in range(2):
+            p0 = inp.first_pid[b]
+            pos[b, :nv] = np.arange(p0, p0 + nv)
+            ctx[b, :nv] = np.arange(nv)
+            for j in range(nv):
+                lib = M.ms_foresight_pids(p0 + j, d)
+                assert lib == O.foresight_pids(p0 + j, d)
+                pos[b, nv + j * d: nv + (j + 1) * d] = lib
+                ctx[b, nv + j * d: nv + (j + 1) * d] = j + 1
+            pos[b, nv + nv * d:] = p0 + nv + np.arange(n_extra)
+        got = run_gpu_attention(ses, inp, ids, pos, ctx_new=ctx)
+        want = oracle_attention(ora, inp, ids, pos, ctx_new=ctx)
+        assert np.isfinite(got).all()
+        check_out(got, want, "bf16", "per-position foresight")
 
 
 def test_gpu_foresight_rows_independent_and_page_permutation_invariant():
