@@ -228,6 +228,23 @@ int ms_output_token_pid(int last_pid);
 int ms_foresight_pids(int last_prefix_pid, int d, int* out, int cap);
 /* Default ctx_new row for n_verify + n_foresight queries. */
 int ms_default_ctx_new(int n_verify, int n_foresight, int* out, int cap);
+/* Per-position foresight step (Section 2.2 "CoT Augmentation", Section 2.3 "MTP Attention": the
+ * layout the model is trained on, used at inference so that drafts survive a partial acceptance):
+ * queries are the n_verify verify tokens (PIDs first_pid ..) followed by d foresight tokens for
+ * every verify token j in turn, foresight k = 1..d holding PID pid_j + k and seeing verify tokens
+ * 0..j (ctx_new = j + 1).  Call ms_predict_verify_attention with n_verify, n_foresight =
+ * n_verify * d, these pos_ids and this ctx_new.  Either output may be NULL; at most cap entries are
+ * written to each; returns n_verify * (1 + d), negative on bad input. */
+int ms_per_position_layout(int first_pid, int n_verify, int d, int* pos_out, int* ctx_out, int cap);
+/* Memory-token PIDs without UPL (Appendix B, "w/o UPL"): last_pid + 1 .. last_pid + n_mem, the
+ * consecutive PIDs after the step's last token; <o> then takes ms_output_token_pid(last_pid +
+ * n_mem).  Returns n_mem, negative on bad input. */
+int ms_consecutive_memory_positions(int last_pid, int n_mem, int* out, int cap);
+/* UPL for a fixed budget of n_mem memory tokens per step (Appendix B, "w/o AMA"): the step's
+ * n_tokens >= 1 tokens are cut into n_mem contiguous groups at floor(g * n_tokens / n_mem); out[g] =
+ * centre PID of group g (lower middle), a group left empty standing for its boundary token.
+ * Returns n_mem, negative on bad input. */
+int ms_upl_positions_fixed(int first_pid, int n_tokens, int n_mem, int* out, int cap);
 
 #ifdef __cplusplus
 }

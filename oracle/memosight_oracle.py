@@ -136,6 +136,50 @@ def default_ctx_new(n_verify: int, n_foresight: int) -> List[int]:
     return list(range(n_verify)) + [n_verify] * n_foresight
 
 
+def per_position_layout(first_pid: int, n_verify: int, d: int):
+    """Step layout with d foresight tokens behind every verify token (Section 2.2, "CoT
+    Augmentation" and "Position ID Assignment"; Section 2.3, "MTP Attention").
+
+    Queries: the n_verify verify tokens (PIDs first_pid ..), then, for verify token j in turn, its
+    d foresight tokens.  Foresight token k = 1..d behind verify token j plays the role of the
+    training-time foresight token placed before the token after j with offset d' = k: it holds the
+    PID just before its target, pid_j + k, and sees what that next token would see of the step --
+    verify tokens 0..j -- plus itself.  Returns (pids, ctx_new).
+    """
+    pids = [first_pid + j for j in range(n_verify)]
+    ctx = list(range(n_verify))
+    for j in range(n_verify):
+        for k in range(1, d + 1):
+            pids.append(first_pid + j + k)
+            ctx.append(j + 1)
+    return pids, ctx
+
+
+def consecutive_memory_positions(last_pid: int, n_mem: int) -> List[int]:
+    """Memory-token PIDs without UPL (Appendix B, "w/o UPL"; Section 2.1.2 on prior methods):
+    consecutive new PIDs after the step's last token.  <o> then follows the last memory token."""
+    return [last_pid + 1 + j for j in range(n_mem)]
+
+
+def upl_positions_fixed(first_pid: int, n_tokens: int, n_mem: int) -> List[int]:
+    """UPL for a fixed budget of n_mem memory tokens (Appendix B, "w/o AMA": 9 per step).
+
+    A reading: the paper defines the groups only through the ratio c.  Here the step is cut into
+    n_mem contiguous groups whose boundaries are floor(g * n / n_mem); a group left empty because
+    the step has fewer tokens than memory tokens stands for the single token at its boundary.
+    """
+    if n_tokens < 1 or n_mem < 1:
+        raise ValueError("need n_tokens >= 1 and n_mem >= 1")
+    out = []
+    for g in range(n_mem):
+        lo = g * n_tokens // n_mem
+        hi = (g + 1) * n_tokens // n_mem - 1
+        if hi < lo:
+            hi = lo
+        out.append(first_pid + (lo + hi) // 2)
+    return out
+
+
 # --------------------------------------------------------------------------
 # RoPE
 # --------------------------------------------------------------------------

@@ -75,6 +75,9 @@ _SIGS = {
     "ms_output_token_pid": (_I, [_I]),
     "ms_foresight_pids": (_I, [_I, _I, _IP, _I]),
     "ms_default_ctx_new": (_I, [_I, _I, _IP, _I]),
+    "ms_per_position_layout": (_I, [_I, _I, _I, _IP, _IP, _I]),
+    "ms_consecutive_memory_positions": (_I, [_I, _I, _IP, _I]),
+    "ms_upl_positions_fixed": (_I, [_I, _I, _I, _IP, _I]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(lib, _name)
@@ -299,4 +302,29 @@ def ms_default_ctx_new(n_verify: int, n_foresight: int):
     r = lib.ms_default_ctx_new(n_verify, n_foresight, buf, n)
     if r < 0:
         raise MsError(r, "bad arguments")
+    return list(buf[:n])
+
+
+def ms_per_position_layout(first_pid: int, n_verify: int, d: int):
+    n = lib.ms_per_position_layout(first_pid, n_verify, d, None, None, 0)
+    if n < 0:
+        raise MsError(n, "bad arguments")
+    pos, ctx = (C.c_int * max(1, n))(), (C.c_int * max(1, n))()
+    lib.ms_per_position_layout(first_pid, n_verify, d, pos, ctx, n)
+    return list(pos[:n]), list(ctx[:n])
+
+
+def ms_consecutive_memory_positions(last_pid: int, n_mem: int):
+    buf = (C.c_int * max(1, n_mem))()
+    n = lib.ms_consecutive_memory_positions(last_pid, n_mem, buf, max(0, n_mem))
+    if n < 0:
+        raise MsError(n, "bad arguments")
+    return list(buf[:n])
+
+
+def ms_upl_positions_fixed(first_pid: int, n_tokens: int, n_mem: int):
+    buf = (C.c_int * max(1, n_mem))()
+    n = lib.ms_upl_positions_fixed(first_pid, n_tokens, n_mem, buf, max(0, n_mem))
+    if n < 0:
+        raise MsError(n, "bad arguments")
     return list(buf[:n])

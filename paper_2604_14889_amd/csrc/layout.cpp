@@ -5,6 +5,9 @@
 //   <o>  -- Section 2.2: the output token takes the PID after the step's last token
 //   <f>  -- Section 2.1.1: foresight PIDs increase by one from the prefix's last PID; a foresight
 //           token holds the PID just before the token it predicts
+//   per-position foresight -- Section 2.2 "CoT Augmentation" / Section 2.3 "MTP Attention": the
+//           training layout (foresight tokens at every position of the step) as a decode step
+//   ablation layouts -- Appendix B: consecutive memory PIDs (w/o UPL), fixed budget (w/o AMA)
 #include "memosight.h"
 
 extern "C" {
@@ -39,6 +42,41 @@ int ms_default_ctx_new(int n_verify, int n_foresight, int* out, int cap) {
     const int n = n_verify + n_foresight;
     for (int i = 0; i < n && i < cap; ++i) out[i] = i < n_verify ? i : n_verify;
     return n;
+}
+
+int ms_per_position_layout(int first_pid, int n_verify, int d, int* pos_out, int* ctx_out, int cap) {
+    if (n_verify < 0 || d < 0) return MS_ERR_INVALID;
+    const long n = (long)n_verify * (1 + d);
+    if (n > 0x7fffffffL) return MS_ERR_INVALID;
+    int at = 0;
+    auto put = [&](int pid, int ctx) {
+        if (at < cap) {
+            if (pos_out) pos_out[at] = pid;
+            if (ctx_out) ctx_out[at] = ctx;
+        }
+        ++at;
+    };
+    for (int j = 0; j < n_verify; ++j) put(first_pid + j, j);
+    for (int j = 0; j < n_verify; ++j)
+        for (int k = 1; k <= d; ++k) put(first_pid + j + k, j + 1);
+    return at;
+}
+
+int ms_consecutive_memory_positions(int last_pid, int n_mem, int* out, int cap) {
+    if (n_mem < 0) return MS_ERR_INVALID;
+    for (int j = 0; j < n_mem && j < cap; ++j) out[j] = last_pid + 1 + j;
+    return n_mem;
+}
+
+int ms_upl_positions_fixed(int first_pid, int n_tokens, int n_mem, int* out, int cap) {
+    if (n_tokens < 1 || n_mem < 1) return MS_ERR_INVALID;
+    for (int g = 0; g < n_mem && g < cap; ++g) {
+        const long lo = (long)g * n_tokens / n_mem;
+        long hi = (long)(g + 1) * n_tokens / n_mem - 1;
+        if (hi < lo) hi = lo;   // more memory tokens than step tokens: the group is its boundary token
+        out[g] = first_pid + (int)((lo + hi) / 2);
+    }
+    return n_mem;
 }
 
 }  // extern "C"

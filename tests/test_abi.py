@@ -53,6 +53,15 @@ def test_helpers_match_oracle_exhaustively():
                 continue
             assert M.ms_default_ctx_new(nv, d) == O.default_ctx_new(nv, d)
             assert M.ms_foresight_pids(100 + nv, d) == O.foresight_pids(100 + nv, d)
+            pos, ctx = M.ms_per_position_layout(100, nv, d)
+            assert (pos, ctx) == O.per_position_layout(100, nv, d)
+    for n in range(1, 60):
+        for l in (1, 2, 9, 13):
+            assert M.ms_upl_positions_fixed(3, n, l) == O.upl_positions_fixed(3, n, l)
+    for l in range(0, 12):
+        assert M.ms_consecutive_memory_positions(41, l) == O.consecutive_memory_positions(41, l)
+    with pytest.raises(M.MsError):
+        M.ms_upl_positions_fixed(1, 0, 9)
 
 
 def test_bad_arguments_return_errors_not_crashes():

@@ -181,13 +181,9 @@ def test_per_position_foresight_layout_wide_step():
         ctx = np.zeros((2, nq), np.int32)
         for b in range(2):
             p0 = inp.first_pid[b]
-            pos[b, :nv] = np.arange(p0, p0 + nv)
-            ctx[b, :nv] = np.arange(nv)
-            for j in range(nv):
-                lib = M.ms_foresight_pids(p0 + j, d)
-                assert lib == O.foresight_pids(p0 + j, d)
-                pos[b, nv + j * d: nv + (j + 1) * d] = lib
-                ctx[b, nv + j * d: nv + (j + 1) * d] = j + 1
+            lay = M.ms_per_position_layout(p0, nv, d)
+            assert lay == O.per_position_layout(p0, nv, d)
+            pos[b, :nv * (1 + d)], ctx[b, :nv * (1 + d)] = lay
             pos[b, nv + nv * d:] = p0 + nv + np.arange(n_extra)
         got = run_gpu_attention(ses, inp, ids, pos, ctx_new=ctx)
         want = oracle_attention(ora, inp, ids, pos, ctx_new=ctx)

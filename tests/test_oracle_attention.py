@@ -140,6 +140,54 @@ def test_oracle_equals_dense_masked_softmax_over_full_sequence(n_kv_heads, group
             assert np.abs(out[r, h] - np.asarray(dense[h][i])).max() < 3e-6
 
 
+@pytest.mark.parametrize("n_kv_heads,group,d,n_verify,depth", [(1, 2, 8, 3, 2), (2, 1, 16, 4, 3), (1, 1, 8, 1, 4)])
+def test_per_position_layout_equals_training_style_sequence(n_kv_heads, group, d, n_verify, depth):
+    """The per-position foresight step against the dense reference over the training-style
+    sequence: foresight tokens sit between the step's tokens (Section 2.2, "CoT Augmentation"),
+    hold PID t + d' - 1 when placed before token t with offset d' (Section 2.2, Foresight
+    Tokens), and are masked from everyone else (Section 2.3).  PIDs and mask on the dense side are
+    written from those rules, not from the oracle's helper."""
+    base = 10000.0
+    rng = W.make_rng(111, n_kv_heads, group, d, n_verify)
+    n_prompt, n_cached = 5, 4
+    first = n_prompt + n_cached + 1                     # PID of the first verify token (PIDs from 1)
+    kinds = ["P"] * n_prompt + ["R"] * n_cached
+    steps = [-1] * n_prompt + [0] * n_cached
+    pids = list(range(1, first))
+    where_verify, where_foresight = [], {}
+    for j in range(n_verify):
+        where_verify.append(len(kinds))
+        kinds.append("R"); steps.append(0); pids.append(first + j)
+        t_next = first + j + 1                           # the foresight tokens stand before token t_next
+        for dp in range(1, depth + 1):
+            where_foresight[(j, dp)] = len(kinds)
+            kinds.append("F"); steps.append(0); pids.append(t_next + dp - 1)
+    n = len(kinds)
+    hq = n_kv_heads * group
+    q = rng.standard_normal((n, hq, d))
+    k = rng.standard_normal((n, n_kv_heads, d))
+    v = rng.standard_normal((n, n_kv_heads, d))
+    mask = H.paper_mask(kinds, steps)
+    qr, kr = H.hf_rope(q, pids, base), H.hf_rope(k, pids, base)
+    scale = 1.0 / np.sqrt(d)
+    # the step's queries in the helper's order: verify tokens, then each verify token's foresight block
+    order = where_verify + [where_foresight[(j, dp)] for j in range(n_verify) for dp in range(1, depth + 1)]
+    dense = {h: H.dense_masked_attention(qr[:, h].tolist(), kr[:, h // group].tolist(), v[:, h // group].tolist(),
+                                         mask, order, scale) for h in range(hq)}
+    lay_pids, lay_ctx = O.per_position_layout(first, n_verify, depth)
+    assert lay_pids == [pids[i] for i in order]
+    cache = O.PagedCache(1, n_kv_heads, d, n_pages=4, dtype=O.F32, rope_base=base)
+    sid = cache.seq_create()
+    nc = n_prompt + n_cached
+    cache.append([sid], [nc], k[None, :nc], v[None, :nc], pids[:nc])
+    f32 = lambda x: x[order].astype(np.float32)[None]
+    out = O.attention(cache, 0, [sid], n_verify, n_verify * depth, f32(q), f32(k), f32(v),
+                      np.asarray(lay_pids)[None], np.asarray(lay_ctx)[None], None)[0]
+    for h in range(hq):
+        for r, i in enumerate(order):
+            assert np.abs(out[r, h] - np.asarray(dense[h][i])).max() < 3e-6
+
+
 # ------------------------------------------------- textbook reductions ------
 
 def sdpa_reference(cache, sid, q_rot, k_new_rot, v_new, group, causal_new):

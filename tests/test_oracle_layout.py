@@ -123,3 +123,58 @@ def test_ama_rejects_bad_input():
         O.ama_count(3, 0)
     with pytest.raises(ValueError):
         O.ama_count(-1, 2)
+
+
+def test_per_position_layout_from_the_training_rule():
+    # foresight before token t with offset d' holds PID t + d' - 1 (golden row foresight_train_pid
+    # is the d' = 1, t = 1 case) and sees what token t sees of the step: the tokens before t
+    inp, exp = G["foresight_train_pid"]
+    pids, ctx = O.per_position_layout(inp["t"] - 1, 1, 1)      # one verify token r_0 at PID t - 1
+    assert pids == [inp["t"] - 1, exp] and ctx == [0, 1]
+    for first in (1, 40):
+        for nv in (1, 2, 5):
+            for d in (0, 1, 4):
+                pids, ctx = O.per_position_layout(first, nv, d)
+                assert len(pids) == len(ctx) == nv * (1 + d)
+                assert pids[:nv] == list(range(first, first + nv)) and ctx[:nv] == list(range(nv))
+                at = nv
+                for j in range(nv):
+                    t = first + j + 1                          # the token these foresight tokens precede
+                    for dp in range(1, d + 1):
+                        assert pids[at] == t + dp - 1
+                        assert ctx[at] == t - first            # verify tokens with PID below t
+                        at += 1
+    # with a single verify token it is the plain step layout
+    assert O.per_position_layout(7, 1, 3) == ([7] + O.foresight_pids(7, 3), O.default_ctx_new(1, 3))
+
+
+def test_consecutive_memory_positions():
+    assert O.consecutive_memory_positions(10, 3) == [11, 12, 13]
+    assert O.consecutive_memory_positions(10, 0) == []
+
+
+def test_upl_fixed_budget_reduces_to_ratio_rule_and_stays_in_span():
+    # whenever the budget divides the step evenly the groups are the ratio rule's groups
+    for c in range(1, 8):
+        for groups in range(1, 10):
+            for first in (1, 33):
+                assert O.upl_positions_fixed(first, groups * c, groups) == O.upl_positions(first, groups * c, c)
+    assert O.upl_positions_fixed(1, 56, 8) == [1 + 7 * g + 3 for g in range(8)]      # closed form, c = 7
+    for n in range(1, 40):
+        for l in range(1, 12):
+            pids = O.upl_positions_fixed(5, n, l)
+            assert len(pids) == l and pids == sorted(pids)
+            assert 5 <= pids[0] and pids[-1] <= 5 + n - 1
+            # brute force: token t belongs to the last group whose boundary floor(g n / l) is <= t
+            members = [[] for _ in range(l)]
+            for t in range(n):
+                members[max(g for g in range(l) if g * n // l <= t)].append(t)
+            for g in range(l):
+                if members[g]:
+                    assert pids[g] == 5 + members[g][(len(members[g]) - 1) // 2]
+                else:
+                    assert pids[g] == 5 + g * n // l
+            if l <= n:
+                assert len(set(pids)) == l and all(members)
+    with pytest.raises(ValueError):
+        O.upl_positions_fixed(1, 0, 9)
