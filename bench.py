@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--kv", type=int, default=8192)
     ap.add_argument("--ragged", action="store_true", help="lengths uniform in [1k, 16k] instead of --kv")
+    ap.add_argument("--event-stride", type=int, default=13,
+                    help="time every n-th attention launch with HIP events (an event pair costs the stream a few microseconds)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=32, help="sequences the CPU oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -102,63 +104,65 @@ def main():
     pos_np, mpos_np = pos_h.numpy(), mpos_h.numpy()     # views of the pinned buffers
     ses.ensure_workspace(B, nq)
 
-    # raw position of each sequence's next token (about 3x the compressed length) and the open segment
-    next_pid = [sh.first_query_pid(b) for b in range(B)]
-    seg_len = [0] * B
+    # raw position of each sequence's next token (about 3x the compressed length) and the open segment;
+    # the host keeps its own copy of the lengths (it knows every append and compaction it asks for)
+    next_pid = np.asarray([sh.first_query_pid(b) for b in range(B)], dtype=np.int32)
+    seg_len = np.zeros(B, dtype=np.int64)
+    cur_len = np.asarray(ses.lengths(ids), dtype=np.int64)
+    acc_np = acc_h.numpy()
     state = {"kv_bytes": 0.0, "accepted": 0, "attn_calls": 0}
+    layer_args = [(k_new[layer], v_new[layer]) for layer in range(NL)]
+    stream = torch.cuda.current_stream()
 
     def algorithmic_bytes(lengths):
         es = 2
-        per_call = sum(2 * L * Hkv * D * es + 4 * (-(-L // 16)) for L in lengths)
+        per_call = int(np.sum(2 * lengths * Hkv * D * es + 4 * (-(-lengths // 16))))
         per_call += B * nq * (2 * Hq + 2 * Hkv) * D * es
         return per_call
 
     def step():
         # a1: position layout (verify block, then foresight tokens right after it)
-        for b in range(B):
-            ver = list(range(next_pid[b], next_pid[b] + nv))
-            pos_np[b, :nv] = ver
-            pos_np[b, nv:] = M.ms_foresight_pids(ver[-1], nf)
+        M.ms_step_positions(next_pid, nv, nf, pos_np)
         pos_d.copy_(pos_h, non_blocking=True)
-        lengths = ses.lengths(ids)
         # a2-a5: attention in every layer
         for layer in range(NL):
-            ses.attention(layer, ids, nv, nf, q, k_new[layer], v_new[layer], pos_d, None, 0.0, out)
-        state["kv_bytes"] += NL * algorithmic_bytes(lengths)
+            kl, vl = layer_args[layer]
+            ses.attention(layer, ids, nv, nf, q, kl, vl, pos_d, None, 0.0, out)
+        state["kv_bytes"] += NL * algorithmic_bytes(cur_len)
         state["attn_calls"] += NL
         # a6: acceptance on the device, lengths back to the host
         M.ms_accept(B, nv, draft, target, None, acc_d, nxt_d)
         acc_h.copy_(acc_d, non_blocking=True)
-        torch.cuda.current_stream().synchronize()
-        acc = acc_h.tolist()
+        stream.synchronize()
         # a7: commit accepted verify rows in every layer
-        M.ms_commit_accepted(ses.cache, ids, acc, nq, k_new, v_new, pos_d)
-        for b in range(B):
-            next_pid[b] += acc[b]
-            seg_len[b] += acc[b]
-        state["accepted"] += sum(acc)
+        M.ms_commit_accepted(ses.cache, ids, acc_np, nq, k_new, v_new, pos_d)
+        next_pid[:] += acc_np
+        seg_len[:] += acc_np
+        cur_len[:] += acc_np
+        state["accepted"] += int(acc_np.sum())
         # a8: close and compact the segment once it holds 56 tokens
-        if all(s >= SEG_TOKENS for s in seg_len):
-            begin = [M.ms_seq_len(ses.cache, s) - n for s, n in zip(ids, seg_len)]
-            cnt = [M.ms_ama_count(n, RATIO) for n in seg_len]
+        if seg_len.min() >= SEG_TOKENS:
+            begin = cur_len - seg_len
+            cnt = [M.ms_ama_count(int(n), RATIO) for n in seg_len]
             assert all(c == n_mem for c in cnt)
             off = 0
             for b in range(B):
-                first = next_pid[b] - seg_len[b]
-                mp = M.ms_upl_positions(first, seg_len[b], RATIO)
+                first = int(next_pid[b] - seg_len[b])
+                mp = M.ms_upl_positions(first, int(seg_len[b]), RATIO)
                 mpos_np[off:off + len(mp)] = mp
                 off += len(mp)
             mpos_d.copy_(mpos_h, non_blocking=True)
             M.ms_compact_segment(ses.cache, ids, begin, seg_len, cnt, mem_k, mem_v, mpos_d)
-            for b in range(B):
-                next_pid[b] = M.ms_output_token_pid(next_pid[b] - 1) + 1   # <o> takes one position
-                seg_len[b] = 0
+            next_pid[:] = [M.ms_output_token_pid(int(p) - 1) + 1 for p in next_pid]   # <o> takes one position
+            cur_len[:] += np.asarray(cnt) - seg_len
+            seg_len[:] = 0
+
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     state.update(kv_bytes=0.0, accepted=0, attn_calls=0)
-    M.ms_profile_attention(ses.cache, args.steps * NL)
+    M.ms_profile_attention(ses.cache, args.steps * NL, args.event_stride)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -166,12 +170,13 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kern_ms = M.ms_profile_read(ses.cache, args.steps * NL)
-    M.ms_profile_attention(ses.cache, 0)
+    M.ms_profile_attention(ses.cache, 0, 1)
     M.ms_check_integrity(ses.cache)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     gbps = state["kv_bytes"] / (t1 - t0) / 1e9
-    lengths = ses.lengths(ids)
+    lengths = np.asarray(ses.lengths(ids), dtype=np.int64)
+    assert np.array_equal(lengths, cur_len), "host copy of the lengths drifted from the cache's"
     per_launch_bytes = algorithmic_bytes(lengths)
     kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else float("nan")
     achieved = per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9 if kern_ms else float("nan")

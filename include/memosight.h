@@ -206,10 +206,11 @@ int ms_check_integrity(ms_cache* cache, void* stream);
 
 /* ---- profiling ------------------------------------------------------------------------------- */
 
-/* From now on, every ms_predict_verify_attention call on this cache that runs the streaming kernel
- * records a pair of HIP events around that kernel alone (not the combine kernel), for up to
- * `capacity` calls; capacity 0 switches profiling off.  Creates the events (synchronous). */
-int ms_profile_attention(ms_cache* cache, int capacity);
+/* From now on, every stride-th ms_predict_verify_attention call on this cache that runs the
+ * streaming kernel (the first such call included) records a pair of HIP events around that kernel's
+ * launch(es), for up to `capacity` recorded calls; capacity 0 switches profiling off.  An event
+ * pair costs the stream a few microseconds, hence the stride.  Creates the events (synchronous). */
+int ms_profile_attention(ms_cache* cache, int capacity, int stride);
 /* Synchronises the recorded events and stores the kernel durations in milliseconds, in call order,
  * in ms_out (host, up to cap entries); *n receives how many were recorded.  Resets the count. */
 int ms_profile_read(ms_cache* cache, float* ms_out, int cap, int* n);
@@ -226,6 +227,10 @@ int ms_upl_positions(int first_pid, int n_tokens, int c, int* out, int cap);
 int ms_output_token_pid(int last_pid);
 /* PIDs of d foresight tokens after a prefix ending at last_prefix_pid: last + 1 .. last + d. */
 int ms_foresight_pids(int last_prefix_pid, int d, int* out, int cap);
+/* Position ids of a whole batch's step, out[B][n_verify + n_foresight] (host): sequence b's verify
+ * tokens hold first_pid[b] .. and its foresight tokens follow by the rule of ms_foresight_pids.
+ * Returns the number of entries written, negative on bad input. */
+int ms_step_positions(int B, const int* first_pid, int n_verify, int n_foresight, int* out);
 /* Default ctx_new row for n_verify + n_foresight queries. */
 int ms_default_ctx_new(int n_verify, int n_foresight, int* out, int cap);
 /* Per-position foresight step (Section 2.2 "CoT Augmentation", Section 2.3 "MTP Attention": the

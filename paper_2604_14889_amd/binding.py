@@ -8,6 +8,8 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+
+import numpy as np
 from typing import Optional, Sequence
 
 # torch ships its own HIP runtime (same SONAME as the system one).  It is imported first so that
@@ -68,13 +70,14 @@ _SIGS = {
     "ms_free_page_count": (_I, [_P, _IP]),
     "ms_peak_pages": (_I, [_P, _IP]),
     "ms_check_integrity": (_I, [_P, _P]),
-    "ms_profile_attention": (_I, [_P, _I]),
+    "ms_profile_attention": (_I, [_P, _I, _I]),
     "ms_profile_read": (_I, [_P, C.POINTER(C.c_float), _I, _IP]),
     "ms_ama_count": (_I, [_I, _I]),
     "ms_upl_positions": (_I, [_I, _I, _I, _IP, _I]),
     "ms_output_token_pid": (_I, [_I]),
     "ms_foresight_pids": (_I, [_I, _I, _IP, _I]),
     "ms_default_ctx_new": (_I, [_I, _I, _IP, _I]),
+    "ms_step_positions": (_I, [_I, _IP, _I, _I, _IP]),
     "ms_per_position_layout": (_I, [_I, _I, _I, _IP, _IP, _I]),
     "ms_consecutive_memory_positions": (_I, [_I, _I, _IP, _I]),
     "ms_upl_positions_fixed": (_I, [_I, _I, _I, _IP, _I]),
@@ -260,8 +263,8 @@ def ms_check_integrity(cache, stream=None) -> None:
     _check(lib.ms_check_integrity(cache, _stream(stream)))
 
 
-def ms_profile_attention(cache, capacity: int) -> None:
-    _check(lib.ms_profile_attention(cache, capacity))
+def ms_profile_attention(cache, capacity: int, stride: int = 1) -> None:
+    _check(lib.ms_profile_attention(cache, capacity, stride))
 
 
 def ms_profile_read(cache, cap: int):
@@ -328,3 +331,18 @@ def ms_upl_positions_fixed(first_pid: int, n_tokens: int, n_mem: int):
     if n < 0:
         raise MsError(n, "bad arguments")
     return list(buf[:n])
+
+
+def ms_step_positions(first_pid, n_verify: int, n_foresight: int, out=None):
+    """first_pid: int32 numpy array [B]; out: int32 numpy array [B, n_q] (e.g. a view of pinned
+    memory), allocated when omitted.  Returns out."""
+    first = np.ascontiguousarray(first_pid, dtype=np.int32)
+    B, n_q = first.shape[0], n_verify + n_foresight
+    if out is None:
+        out = np.empty((B, n_q), dtype=np.int32)
+    if out.dtype != np.int32 or out.size < B * n_q or not out.flags["C_CONTIGUOUS"]:
+        raise MsError(MS_ERR_INVALID, "ms_step_positions: out must be a contiguous int32 array of B * n_q entries")
+    r = lib.ms_step_positions(B, first.ctypes.data_as(_IP), n_verify, n_foresight, out.ctypes.data_as(_IP))
+    if r < 0:
+        raise MsError(r, "bad arguments")
+    return out

@@ -863,7 +863,7 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     a.dbg = (long long*)((char*)ga.ws + (size_t)(mfma_items(c) + B) * c->d.n_kv_heads * kPartFloats * sizeof(float));
 #endif
     {
-        const bool prof = c->prof_count < (int)c->prof_start.size();
+        const bool prof = c->prof_count < (int)c->prof_start.size() && c->prof_seen++ % c->prof_stride == 0;
         if (prof) MS_HIP_TRY(hipEventRecord(c->prof_start[c->prof_count], stream));
         const dim3 grid(c->plan_items, a.n_kv_heads);
         if (a.n_q <= kDecodeQueries && a.n_q * a.group <= kRows) {
@@ -887,8 +887,10 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
 
 }  // namespace ms
 
-extern "C" int ms_profile_attention(ms_cache* c, int capacity) {
-    if (!c || capacity < 0) MS_FAIL(MS_ERR_INVALID, "ms_profile_attention: bad argument");
+extern "C" int ms_profile_attention(ms_cache* c, int capacity, int stride) {
+    if (!c || capacity < 0 || stride < 1) MS_FAIL(MS_ERR_INVALID, "ms_profile_attention: bad argument");
+    c->prof_stride = stride;
+    c->prof_seen = 0;
     for (hipEvent_t e : c->prof_start) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->prof_stop) (void)hipEventDestroy(e);
     c->prof_start.clear();

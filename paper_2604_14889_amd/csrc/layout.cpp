@@ -37,6 +37,18 @@ int ms_foresight_pids(int last_prefix_pid, int d, int* out, int cap) {
     return d;
 }
 
+int ms_step_positions(int B, const int* first_pid, int n_verify, int n_foresight, int* out) {
+    if (B < 0 || n_verify < 0 || n_foresight < 0 || (B > 0 && (!first_pid || !out))) return MS_ERR_INVALID;
+    const int n_q = n_verify + n_foresight;
+    for (int b = 0; b < B; ++b) {
+        int* row = out + (long)b * n_q;
+        for (int i = 0; i < n_verify; ++i) row[i] = first_pid[b] + i;
+        // the prefix ends at the last verify token (or just before first_pid if there is none)
+        ms_foresight_pids(first_pid[b] + n_verify - 1, n_foresight, row + n_verify, n_foresight);
+    }
+    return B * n_q;
+}
+
 int ms_default_ctx_new(int n_verify, int n_foresight, int* out, int cap) {
     if (n_verify < 0 || n_foresight < 0) return MS_ERR_INVALID;
     const int n = n_verify + n_foresight;

@@ -82,6 +82,8 @@ struct ms_cache {
     int plan_items = 0, plan_parts = 0, plan_B = 0;
     std::vector<hipEvent_t> prof_start, prof_stop;  // event pairs around the streaming kernel
     int prof_count = 0;
+    int prof_stride = 1;   // every prof_stride-th eligible launch is timed
+    int prof_seen = 0;
 };
 
 namespace ms {

@@ -60,6 +60,13 @@ def test_helpers_match_oracle_exhaustively():
             assert M.ms_upl_positions_fixed(3, n, l) == O.upl_positions_fixed(3, n, l)
     for l in range(0, 12):
         assert M.ms_consecutive_memory_positions(41, l) == O.consecutive_memory_positions(41, l)
+    import numpy as np
+    first = np.asarray([1, 50, 7000], dtype=np.int32)
+    for nv, d in ((5, 4), (1, 0), (0, 3), (4, 3)):
+        got = M.ms_step_positions(first, nv, d)
+        for b, p0 in enumerate(first):
+            ver = list(range(p0, p0 + nv))
+            assert got[b].tolist() == ver + O.foresight_pids(int(p0) + nv - 1, d)
     with pytest.raises(M.MsError):
         M.ms_upl_positions_fixed(1, 0, 9)
 
