@@ -182,6 +182,13 @@ int ms_predict_verify_attention(ms_cache* cache, int layer, int B, const int* se
 
 size_t ms_attention_workspace_bytes(ms_cache* cache, int B, int n_q);
 
+/* By default attention results are reproducible to rounding only: the streaming kernel (bf16,
+ * head_dim 128) lets the waves of a workgroup take KV tiles first come, first served, so the
+ * order in which a row's partial sums are added varies from call to call.  on != 0 fixes the
+ * assignment instead: calls with the same inputs, cache contents and page tables then return the
+ * same bits, a few percent slower.  The general kernel is always reproducible. */
+int ms_attention_set_deterministic(ms_cache* cache, int on);
+
 /* ---- greedy longest-prefix acceptance (footnote of Section 2.1.1) -------------------------- */
 
 /* accept_len[b] = number of leading j with draft[b][j] == target[b][j] (target[b][j] being the

@@ -70,6 +70,7 @@ _SIGS = {
     "ms_free_page_count": (_I, [_P, _IP]),
     "ms_peak_pages": (_I, [_P, _IP]),
     "ms_check_integrity": (_I, [_P, _P]),
+    "ms_attention_set_deterministic": (_I, [_P, _I]),
     "ms_profile_attention": (_I, [_P, _I, _I]),
     "ms_profile_read": (_I, [_P, C.POINTER(C.c_float), _I, _IP]),
     "ms_ama_count": (_I, [_I, _I]),
@@ -224,6 +225,10 @@ def ms_predict_verify_attention(cache, layer, seq_ids, n_verify, n_foresight, q,
                                            _sized(cache, ctx_new, "ctx_new", rows, 4), float(scale),
                                            _sized(cache, out, "out", rows * hq * d), _dev(workspace), ws_bytes,
                                            _stream(stream)))
+
+
+def ms_attention_set_deterministic(cache, on: bool) -> None:
+    _check(lib.ms_attention_set_deterministic(cache, 1 if on else 0))
 
 
 def ms_accept(B, n, draft, target, stop_ids, accept_len, next_token, stream=None) -> None:

@@ -223,6 +223,12 @@ size_t rowwave_workspace_bytes(const ms_cache* c, int B, int n_q) {
 
 using namespace ms;
 
+extern "C" int ms_attention_set_deterministic(ms_cache* c, int on) {
+    if (!c) MS_FAIL(MS_ERR_INVALID, "ms_attention_set_deterministic: null cache");
+    c->deterministic = on != 0;
+    return MS_OK;
+}
+
 extern "C" size_t ms_attention_workspace_bytes(ms_cache* c, int B, int n_q) {
     if (!c || B < 1 || B > MS_MAX_BATCH || n_q < 1 || n_q > MS_MAX_QUERIES) return 0;
     size_t need = mfma_eligible(c, n_q) ? mfma_workspace_bytes(c, B) : rowwave_workspace_bytes(c, B, n_q);

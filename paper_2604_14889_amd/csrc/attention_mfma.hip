@@ -383,7 +383,17 @@ __device__ __forceinline__ void combine_partials(const MfmaArgs& a, int q0, int 
     }
 }
 
-template <bool kWide>
+// Next tile of the segment for the calling wave: one lane bumps the workgroup's counter in LDS.
+__device__ __forceinline__ int claim_tile(int* counter, int lane) {
+    int v = 0;
+    if (lane == 0) v = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return __builtin_amdgcn_readfirstlane(v);
+}
+
+// kWide: see the LDS map.  kClaim: the waves of a workgroup take the segment's tiles first come,
+// first served instead of every 8th tile each; this evens out the waves' finishing times, at the
+// price of results that depend on the order the tiles happened to be taken in (rounding only).
+template <bool kWide, bool kClaim>
 __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     typedef Lds<kWide> L;
@@ -457,6 +467,8 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         TileRegs r;   // (an empty segment's record names page 0: loaded, never used)
         load_v(r.v, pool, pa, pb, page_bytes, lane_off_v);
         load_k(r.k, pool, pa, pb, page_bytes, lane_off_k, lane);
+        int* tile_counter = reinterpret_cast<int*>(smem + L::kFlag + 4);
+        if (kClaim && tid_p == 0) *tile_counter = kWaves;   // tiles 0 .. 7 are the waves' first ones
         // cos/sin table: wave w fills the rows of queries w, w + 8, ..., lane = rotation pair
 #pragma unroll
         for (int k = 0; k < kPosPerWave; ++k)
@@ -556,14 +568,17 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         // the last tile), so a wave leaves the loop holding its next tile -- the segment's partial
         // tail tile, if that one is its to do ----
         const int full_tiles = n_tok / kTile;
-        for (int j = w; j < full_tiles; j += kWaves) {
+        int cur = w;   // every wave's first tile is fixed: its loads were issued during the set-up
+        for (int turn = 0; cur < full_tiles; ++turn) {
+            int nxt = cur + kWaves;
+            if (kClaim) nxt = claim_tile(tile_counter, lane);
             // the two waves of a SIMD take turns at the higher issue priority, tile by tile; with
             // equal priorities the older wave always wins and the younger one finishes late
-            if (((j >> 3) ^ (w >> 2)) & 1) __builtin_amdgcn_s_setprio(1);
+            if ((turn ^ (w >> 2)) & 1) __builtin_amdgcn_s_setprio(1);
             else __builtin_amdgcn_s_setprio(0);
 #pragma unroll
             for (int rr = 0; rr < 8; ++rr) *reinterpret_cast<uint4*>(vwrite + 4 * rr * kVRowBytes) = r.v[rr];
-            tile_pages(pt, j + kWaves, n_tiles, sg_t0, last_page, pa, pb);
+            tile_pages(pt, nxt, n_tiles, sg_t0, last_page, pa, pb);
             load_v(r.v, pool, pa, pb, page_bytes, lane_off_v);
             f32x16_t s;
             qk_block(s, r.k, qbase, 0);
@@ -571,11 +586,12 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
             qk_block(s, r.k, qbase, 1);
             load_k(r.k, pool, pa, pb, page_bytes, lane_off_k, lane);
             softmax_pv(st, s, 1, vbase);
+            cur = nxt;
         }
         __builtin_amdgcn_s_setprio(0);
-        // ---- the tail tile (fewer than 32 tokens): V rows past the end become zeros, their scores
-        // minus infinity ----
-        if (full_tiles < n_tiles && (full_tiles & (kWaves - 1)) == w) {
+        // ---- the tail tile (fewer than 32 tokens), for the wave whose next tile it is: V rows past
+        // the end become zeros, their scores minus infinity ----
+        if (full_tiles < n_tiles && cur == full_tiles) {
             const int valid = n_tok - full_tiles * kTile;
 #pragma unroll
             for (int rr = 0; rr < 8; ++rr)
@@ -814,10 +830,12 @@ static void build_plan(const ms_cache* c, const BatchMeta& bm, int B, int n_item
 int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        MS_HIP_TRY(hipFuncSetAttribute((const void*)pv_attn_mfma_stream<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       Lds<false>::kBytes));
-        MS_HIP_TRY(hipFuncSetAttribute((const void*)pv_attn_mfma_stream<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       Lds<true>::kBytes));
+        MS_HIP_TRY(hipFuncSetAttribute((const void*)pv_attn_mfma_stream<false, false>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Lds<false>::kBytes));
+        MS_HIP_TRY(hipFuncSetAttribute((const void*)pv_attn_mfma_stream<false, true>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Lds<false>::kBytes));
+        MS_HIP_TRY(hipFuncSetAttribute((const void*)pv_attn_mfma_stream<true, false>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Lds<true>::kBytes));
         attr_set = true;
     }
     // plan: rebuilt only when the batch (ids, lengths) changed since the last call on this cache
@@ -869,14 +887,17 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
         if (a.n_q <= kDecodeQueries && a.n_q * a.group <= kRows) {
             a.q0 = 0;
             a.n_qc = a.n_q;
-            hipLaunchKernelGGL(pv_attn_mfma_stream<false>, grid, dim3(kThreads), Lds<false>::kBytes, stream, a);
+            if (c->deterministic)
+                hipLaunchKernelGGL((pv_attn_mfma_stream<false, false>), grid, dim3(kThreads), Lds<false>::kBytes, stream, a);
+            else
+                hipLaunchKernelGGL((pv_attn_mfma_stream<false, true>), grid, dim3(kThreads), Lds<false>::kBytes, stream, a);
         } else {
             // wide steps: one launch per chunk of queries; launches on one stream run in order, so
             // they can share the partial workspace and the arrival counters
             const int per_launch = kRows / a.group;
             for (a.q0 = 0; a.q0 < a.n_q; a.q0 += per_launch) {
                 a.n_qc = a.n_q - a.q0 < per_launch ? a.n_q - a.q0 : per_launch;
-                hipLaunchKernelGGL(pv_attn_mfma_stream<true>, grid, dim3(kThreads), Lds<true>::kBytes, stream, a);
+                hipLaunchKernelGGL((pv_attn_mfma_stream<true, false>), grid, dim3(kThreads), Lds<true>::kBytes, stream, a);
             }
         }
         MS_HIP_TRY(hipGetLastError());

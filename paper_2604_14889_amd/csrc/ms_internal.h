@@ -81,6 +81,7 @@ struct ms_cache {
     std::vector<int> plan_key;   // batch (ids, lengths) the plan was built for
     int plan_items = 0, plan_parts = 0, plan_B = 0;
     std::vector<hipEvent_t> prof_start, prof_stop;  // event pairs around the streaming kernel
+    bool deterministic = false;   // attention: fixed tile-to-wave assignment (bitwise reproducible)
     int prof_count = 0;
     int prof_stride = 1;   // every prof_stride-th eligible launch is timed
     int prof_seen = 0;

@@ -198,7 +198,11 @@ def test_gpu_foresight_rows_independent_and_page_permutation_invariant():
     ses, _, ids = setup_pair(inp, with_oracle_pool=False)
     with ses:
         pos = pids_for(inp, M)
+        loose = run_gpu_attention(ses, inp, ids, pos)       # default mode: reproducible to rounding
+        M.ms_attention_set_deterministic(ses.cache, True)   # bitwise statements need the fixed tile order
         base = run_gpu_attention(ses, inp, ids, pos)
+        assert np.array_equal(run_gpu_attention(ses, inp, ids, pos), base)
+        check_out(loose, base, "bf16", "default against deterministic mode")
         inp2 = W.attention_inputs(sh, 402)
         inp2.q[0, 5] ^= 0x0100          # perturb foresight query 5 and its key / value
         inp2.k_new[0, 5] ^= 0x0080
@@ -216,6 +220,7 @@ def test_gpu_foresight_rows_independent_and_page_permutation_invariant():
                         inp.first_pid)
     ses3, _, ids3 = setup_pair(inp3, with_oracle_pool=False)
     with ses3:
+        M.ms_attention_set_deterministic(ses3.cache, True)
         got3 = run_gpu_attention(ses3, inp3, ids3, pos)
     assert np.array_equal(got3, base)
 
@@ -484,6 +489,7 @@ def test_compaction_content_attention_and_recompute_equivalence():
     inp = W.attention_inputs(sh, 41)
     ses, ora, ids = setup_pair(inp)
     with ses:
+        M.ms_attention_set_deterministic(ses.cache, True)   # for the bitwise comparison at the end
         n_mem = [8] * B
         begin = [n - 256 for n in lens]
         mpos = sum((M.ms_upl_positions(3 * n, 256, 32) for n in lens), [])
@@ -513,6 +519,7 @@ def test_compaction_content_attention_and_recompute_equivalence():
         new_lens = ses.lengths(ids)
     ses2 = S.Session(L, Hq, Hkv, D, sh.n_pages, M.MS_BF16, 1000000.0, max_seqs=B, max_pages_per_seq=200)
     with ses2:
+        M.ms_attention_set_deterministic(ses2.cache, True)
         ids2 = [M.ms_seq_create(ses2.cache) for _ in range(B)]
         for b in range(B):
             pt = np.asarray(tables[b])
@@ -524,6 +531,9 @@ def test_compaction_content_attention_and_recompute_equivalence():
         for layer in range(L):
             again = run_gpu_attention(ses2, inp2, ids2, pos, layer)
             assert np.array_equal(again, outs[layer]), "compaction must equal recomputation over the kept KV"
+        M.ms_attention_set_deterministic(ses2.cache, False)
+        for layer in range(L):
+            check_out(run_gpu_attention(ses2, inp2, ids2, pos, layer), outs[layer], "bf16", "default mode, recomputation")
 
 
 def test_compaction_in_the_middle_moves_the_tail():
