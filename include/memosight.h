@@ -211,6 +211,32 @@ int ms_peak_pages(ms_cache* cache, int* n);
  * synchronising `stream`) the device mirror equals the host tables.  MS_OK or MS_ERR_INVALID. */
 int ms_check_integrity(ms_cache* cache, void* stream);
 
+/* ---- the decoder block around the attention (full decode step) ------------------------------
+ *
+ * Algorithm 1 (Appendix A) runs the whole model once per speculative step.  Around the attention
+ * the block of the paper's models (Section 4.1) is: RMSNorm, Q/K/V projections, output projection,
+ * residual, RMSNorm, SwiGLU MLP, residual; then the final norm, the LM head and the greedy token.
+ * The projections are dense GEMMs the caller runs; these are the memory-bound pieces between them.
+ * All tensors are device pointers, 16-byte aligned, rows contiguous; activations and weights are
+ * bf16, the residual stream h is fp32; arithmetic is fp32.  Bad sizes or pointers return
+ * MS_ERR_INVALID and launch nothing. */
+
+/* h_out[r][:] = table[tokens[r]][:] (bf16 -> fp32), r < n.  table [vocab][hidden], tokens device
+ * [n]; ids outside [0, vocab) are clamped (the caller validates them).  hidden % 8 == 0. */
+int ms_embed_rows(const void* table, int vocab, int hidden, const int* tokens, int n, float* h_out,
+                  void* stream);
+/* h[r] += delta[r] (bf16 [n][hidden]; NULL: nothing is added), then
+ * out[r] = h[r] / sqrt(mean(h[r]^2) + eps) * weight (bf16 [n][hidden]).  hidden % 8 == 0,
+ * hidden <= 8192. */
+int ms_add_rmsnorm(float* h, const void* delta, const void* weight, float eps, void* out, int n,
+                   int hidden, void* stream);
+/* out[r][i] = silu(gate_up[r][i]) * gate_up[r][inter + i]: gate_up bf16 [n][2 * inter] (the gate
+ * and up projections side by side), out bf16 [n][inter].  inter % 8 == 0, n <= 65535. */
+int ms_swiglu(const void* gate_up, void* out, int n, int inter, void* stream);
+/* out[r] = index of the largest of logits[r][0 .. vocab) (bf16, row stride ld elements, ld % 8 ==
+ * 0), the lowest index among equal maxima; NaN never wins.  out device int32 [n]. */
+int ms_argmax_rows(const void* logits, int n, int vocab, long ld, int* out, void* stream);
+
 /* ---- profiling ------------------------------------------------------------------------------- */
 
 /* From now on, every stride-th ms_predict_verify_attention call on this cache that runs the

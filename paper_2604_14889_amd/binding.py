@@ -71,6 +71,10 @@ _SIGS = {
     "ms_peak_pages": (_I, [_P, _IP]),
     "ms_check_integrity": (_I, [_P, _P]),
     "ms_attention_set_deterministic": (_I, [_P, _I]),
+    "ms_embed_rows": (_I, [_P, _I, _I, _P, _I, _P, _P]),
+    "ms_add_rmsnorm": (_I, [_P, _P, _P, _F, _P, _I, _I, _P]),
+    "ms_swiglu": (_I, [_P, _P, _I, _I, _P]),
+    "ms_argmax_rows": (_I, [_P, _I, _I, C.c_long, _P, _P]),
     "ms_profile_attention": (_I, [_P, _I, _I]),
     "ms_profile_read": (_I, [_P, C.POINTER(C.c_float), _I, _IP]),
     "ms_ama_count": (_I, [_I, _I]),
@@ -225,6 +229,34 @@ def ms_predict_verify_attention(cache, layer, seq_ids, n_verify, n_foresight, q,
                                            _sized(cache, ctx_new, "ctx_new", rows, 4), float(scale),
                                            _sized(cache, out, "out", rows * hq * d), _dev(workspace), ws_bytes,
                                            _stream(stream)))
+
+
+def ms_embed_rows(table, tokens, h_out, stream=None) -> None:
+    vocab, hidden = table.shape
+    n = tokens.numel()
+    _check(lib.ms_embed_rows(_sized(None, table, "table", vocab * hidden, 2), vocab, hidden,
+                             _sized(None, tokens, "tokens", n, 4), n, _sized(None, h_out, "h_out", n * hidden, 4),
+                             _stream(stream)))
+
+
+def ms_add_rmsnorm(h, delta, weight, eps: float, out, stream=None) -> None:
+    n, hidden = h.shape
+    _check(lib.ms_add_rmsnorm(_sized(None, h, "h", n * hidden, 4), _sized(None, delta, "delta", n * hidden, 2),
+                              _sized(None, weight, "weight", hidden, 2), float(eps),
+                              _sized(None, out, "out", n * hidden, 2), n, hidden, _stream(stream)))
+
+
+def ms_swiglu(gate_up, out, stream=None) -> None:
+    n, two_i = gate_up.shape
+    inter = two_i // 2
+    _check(lib.ms_swiglu(_sized(None, gate_up, "gate_up", n * 2 * inter, 2), _sized(None, out, "out", n * inter, 2),
+                         n, inter, _stream(stream)))
+
+
+def ms_argmax_rows(logits, vocab: int, out, stream=None) -> None:
+    n, ld = logits.shape
+    _check(lib.ms_argmax_rows(_sized(None, logits, "logits", n * ld, 2), n, vocab, ld,
+                              _sized(None, out, "out", n, 4), _stream(stream)))
 
 
 def ms_attention_set_deterministic(cache, on: bool) -> None:

@@ -1,0 +1,150 @@
+"""One full decode step (Algorithm 1, SpeculativeStep, of the MemoSight paper) on the GPU.
+
+The attention, the residual/RMSNorm, SwiGLU and greedy-token kernels, acceptance and the cache
+update are this library's HIP kernels.  The dense projections (Q/K/V, output, MLP, LM head) are
+plain bf16 GEMMs and are run through torch (hipBLASLt underneath): they are library GEMMs, not
+part of the hand-written path, and stand in until hand-written MFMA GEMMs replace them.
+
+Nothing here computes on the CPU; every call fails if the HIP library is missing.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as M
+from .session import Session
+
+
+@dataclass
+class DecoderConfig:
+    n_layers: int
+    hidden: int
+    inter: int
+    vocab: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    eps: float = 1e-6
+    rope_base: float = 1000000.0
+
+    @staticmethod
+    def qwen2_5_7b() -> "DecoderConfig":
+        return DecoderConfig(28, 3584, 18944, 152064, 28, 4, 128, 1e-6, 1000000.0)
+
+
+class LayerTensors:
+    """bf16 device tensors of one block; projection weights are [out_features, in_features]."""
+
+    def __init__(self, ln1, wq, bq, wk, bk, wv, bv, wo, ln2, w_gate_up, w_down):
+        self.ln1, self.wq, self.bq, self.wk, self.bk, self.wv, self.bv = ln1, wq, bq, wk, bk, wv, bv
+        self.wo, self.ln2, self.w_gate_up, self.w_down = wo, ln2, w_gate_up, w_down
+
+
+class DecoderTensors:
+    def __init__(self, embed, layers: List[LayerTensors], norm, lm_head):
+        self.embed, self.layers, self.norm, self.lm_head = embed, layers, norm, lm_head
+
+    @staticmethod
+    def random(cfg: DecoderConfig, seed: int, device="cuda:0") -> "DecoderTensors":
+        """Random-init weights of the given shape, drawn on the device: projections N(0, 1/sqrt(fan_in)),
+        biases N(0, 0.1), norm weights 1."""
+        gen = torch.Generator(device=device)
+        gen.manual_seed(seed)
+
+        def w(out_f, in_f):
+            return torch.empty(out_f, in_f, dtype=torch.bfloat16, device=device).normal_(0.0, in_f ** -0.5, generator=gen)
+
+        def b(n):
+            return torch.empty(n, dtype=torch.bfloat16, device=device).normal_(0.0, 0.1, generator=gen)
+
+        def ones(n):
+            return torch.ones(n, dtype=torch.bfloat16, device=device)
+
+        qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+        layers = [LayerTensors(ones(cfg.hidden), w(qd, cfg.hidden), b(qd), w(kd, cfg.hidden), b(kd), w(kd, cfg.hidden), b(kd),
+                               w(cfg.hidden, qd), ones(cfg.hidden), w(2 * cfg.inter, cfg.hidden), w(cfg.hidden, cfg.inter))
+                  for _ in range(cfg.n_layers)]
+        embed = torch.empty(cfg.vocab, cfg.hidden, dtype=torch.bfloat16, device=device).normal_(0.0, 1.0, generator=gen)
+        return DecoderTensors(embed, layers, ones(cfg.hidden), w(cfg.vocab, cfg.hidden))
+
+
+class Decoder:
+    """Buffers and the step driver for up to max_rows = B * n_q tokens per step."""
+
+    def __init__(self, cfg: DecoderConfig, weights: DecoderTensors, session: Session, max_rows: int):
+        self.cfg, self.w, self.ses = cfg, weights, session
+        dev = weights.embed.device
+        qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+
+        def buf(*shape, dtype=torch.bfloat16):
+            return torch.empty(*shape, dtype=dtype, device=dev)
+
+        self.max_rows = max_rows
+        self.h = buf(max_rows, cfg.hidden, dtype=torch.float32)
+        self.x = buf(max_rows, cfg.hidden)
+        self.q = buf(max_rows, qd)
+        self._kv = {}             # rows -> (k_new, v_new), each [L, rows, Hkv*D] contiguous for the commit
+        self.attn = buf(max_rows, qd)
+        self.proj = buf(max_rows, cfg.hidden)
+        self.gate_up = buf(max_rows, 2 * cfg.inter)
+        self.act = buf(max_rows, cfg.inter)
+        self.logits = buf(max_rows, cfg.vocab)
+        self.targets = buf(max_rows, dtype=torch.int32)
+        self.attn_events = None   # optional list of (start, stop) events around every attention call
+
+    def step(self, seq_ids: Sequence[int], tokens: torch.Tensor, pos: torch.Tensor, n_verify: int, n_foresight: int,
+             ctx_new: Optional[torch.Tensor] = None):
+        """tokens, pos: int32 device [B, n_q].  Returns (logits [B*n_q, vocab] bf16, greedy tokens
+        [B*n_q] int32), both views of this object's buffers; step_kv() gives the step's keys and
+        values for ms_commit_accepted."""
+        cfg, w = self.cfg, self.w
+        B = len(seq_ids)
+        n_q = n_verify + n_foresight
+        rows = B * n_q
+        if rows > self.max_rows:
+            raise M.MsError(M.MS_ERR_INVALID, f"step of {rows} rows exceeds the buffers ({self.max_rows})")
+        hq, hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+        h, x, q, attn, proj = self.h[:rows], self.x[:rows], self.q[:rows], self.attn[:rows], self.proj[:rows]
+        gate_up, act = self.gate_up[:rows], self.act[:rows]
+        if rows not in self._kv:
+            kd = hkv * d
+            self._kv[rows] = (torch.empty(cfg.n_layers, rows, kd, dtype=torch.bfloat16, device=h.device),
+                              torch.empty(cfg.n_layers, rows, kd, dtype=torch.bfloat16, device=h.device))
+        self.k_new, self.v_new = self._kv[rows]
+        M.ms_embed_rows(w.embed, tokens, h)
+        delta = None
+        for li, lw in enumerate(w.layers):
+            M.ms_add_rmsnorm(h, delta, lw.ln1, cfg.eps, x)
+            k, v = self.k_new[li], self.v_new[li]
+            torch.addmm(lw.bq, x, lw.wq.t(), out=q)
+            torch.addmm(lw.bk, x, lw.wk.t(), out=k)
+            torch.addmm(lw.bv, x, lw.wv.t(), out=v)
+            if self.attn_events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            self.ses.attention(li, seq_ids, n_verify, n_foresight, q.view(B, n_q, hq, d), k.view(B, n_q, hkv, d),
+                               v.view(B, n_q, hkv, d), pos, ctx_new, 0.0, attn.view(B, n_q, hq, d))
+            if self.attn_events is not None:
+                e1.record()
+                self.attn_events.append((e0, e1))
+            torch.mm(attn, lw.wo.t(), out=proj)
+            M.ms_add_rmsnorm(h, proj, lw.ln2, cfg.eps, x)
+            torch.mm(x, lw.w_gate_up.t(), out=gate_up)
+            M.ms_swiglu(gate_up, act)
+            torch.mm(act, lw.w_down.t(), out=proj)
+            delta = proj
+        M.ms_add_rmsnorm(h, delta, w.norm, cfg.eps, x)
+        logits = self.logits[:rows]
+        torch.mm(x, w.lm_head.t(), out=logits)
+        M.ms_argmax_rows(logits, cfg.vocab, self.targets[:rows])
+        return logits, self.targets[:rows]
+
+    def step_kv(self):
+        """The last step's K / V as contiguous [L, rows, Hkv, D] tensors (input of ms_commit_accepted)."""
+        cfg = self.cfg
+        rows = self.k_new.shape[1]
+        return (self.k_new.view(cfg.n_layers, rows, cfg.n_kv_heads, cfg.head_dim),
+                self.v_new.view(cfg.n_layers, rows, cfg.n_kv_heads, cfg.head_dim))
