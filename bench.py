@@ -43,6 +43,10 @@ def parse():
     ap.add_argument("--ragged", action="store_true", help="lengths uniform in [1k, 16k] instead of --kv")
     ap.add_argument("--event-stride", type=int, default=13,
                     help="time every n-th attention launch with HIP events (an event pair costs the stream a few microseconds)")
+    ap.add_argument("--workload", choices=["attention", "decode_step"], default="attention",
+                    help="attention: the metric's workload (default); decode_step: the whole model step "
+                         "(Qwen2.5-7B shapes, batch 64, 8k cached tokens, 4 verify + 3 foresight) with torch GEMMs around "
+                         "the hand-written kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=32, help="sequences the CPU oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -55,6 +59,8 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one MI355X per box); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "decode_step":
+        return decode_step_bench(args)
     import numpy as np
     import torch
 
@@ -235,6 +241,128 @@ def main():
         del src, dst
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, ses, sh, ids, lengths, q, k_new, v_new, pos_d, out, M, S, W)
+    ses.close()
+    print(json.dumps(result))
+
+
+def decode_step_bench(args):
+    """The whole model step of Algorithm 1's SpeculativeStep at Qwen2.5-7B shapes with random bf16
+    weights: embedding, 28 x (RMSNorm, Q/K/V GEMMs, fused attention, output GEMM, RMSNorm, MLP GEMMs
+    with SwiGLU), final norm, LM head GEMM, greedy tokens, acceptance against them, commit of the
+    accepted rows; the next verify block is built on the device from the step's own predictions.
+    GEMMs run through torch (hipBLASLt); everything else is this library's kernels."""
+    import numpy as np
+    import torch
+
+    import workloads as W
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import decoder as D
+    from paper_2604_14889_amd import session as S
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = D.DecoderConfig.qwen2_5_7b()
+    if args.layers != 28:
+        cfg.n_layers = args.layers
+    B = 64 if args.batch == 32 else args.batch           # this workload's default batch is 64
+    L0, nv, nf = args.kv, 4, 3
+    nq = nv + nf
+    NL, Hq, Hkv, Dh = cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    lengths = [L0] * B
+    pages_per_seq = -(-L0 // 16)
+    n_pages = B * (pages_per_seq + 16)
+    rng = W.make_rng(1005, B, NL)
+    page_tables = W.shuffled_page_tables(rng, n_pages, lengths)
+    ses = S.Session(NL, Hq, Hkv, Dh, n_pages, M.MS_BF16, cfg.rope_base, max_seqs=B, max_pages_per_seq=pages_per_seq + 64)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(W.BASE_SEED + 5)
+    for layer in range(NL):
+        ses.pool[layer].normal_(0.0, 0.5, generator=gen)
+    ids = [M.ms_seq_import(ses.cache, n, pt) for n, pt in zip(lengths, page_tables)]
+    weights = D.DecoderTensors.random(cfg, W.BASE_SEED + 6, dev)
+    dec = D.Decoder(cfg, weights, ses, B * nq)
+    ses.ensure_workspace(B, nq)
+
+    foresight_id = cfg.vocab - 1                           # stands for the <f> token
+    tokens = torch.randint(0, cfg.vocab - 1, (B, nq), dtype=torch.int32, device=dev, generator=gen)
+    tokens[:, nv:] = foresight_id
+    acc_d = torch.empty(B, dtype=torch.int32, device=dev)
+    nxt_d = torch.empty(B, dtype=torch.int32, device=dev)
+    acc_h = torch.empty(B, dtype=torch.int32, pin_memory=True)
+    pos_h = torch.empty(B, nq, dtype=torch.int32, pin_memory=True)
+    pos_d = torch.empty(B, nq, dtype=torch.int32, device=dev)
+    pos_np, acc_np = pos_h.numpy(), acc_h.numpy()
+    next_pid = np.asarray([3 * n + 1 for n in lengths], dtype=np.int32)
+    cur_len = np.asarray(lengths, dtype=np.int64)
+    stream = torch.cuda.current_stream()
+    state = {"committed": 0, "kv_bytes": 0.0}
+
+    def step():
+        M.ms_step_positions(next_pid, nv, nf, pos_np)
+        pos_d.copy_(pos_h, non_blocking=True)
+        _, targets = dec.step(ids, tokens, pos_d, nv, nf)
+        state["kv_bytes"] += NL * float(np.sum(2 * cur_len * Hkv * Dh * 2))
+        tg = targets.view(B, nq)
+        M.ms_accept(B, nv - 1, tokens[:, 1:nv].contiguous(), tg[:, :nv - 1].contiguous(), None, acc_d, nxt_d)
+        acc_h.copy_(acc_d, non_blocking=True)
+        # next verify block: the token after the accepted ones, then the foresight rows' predictions
+        tokens[:, 0] = torch.gather(tg, 1, acc_d.long().unsqueeze(1)).squeeze(1)
+        tokens[:, 1:nv] = tg[:, nv:]
+        stream.synchronize()
+        n_commit = acc_np + 1                               # the block's first token is always kept
+        k_new, v_new = dec.step_kv()
+        M.ms_commit_accepted(ses.cache, ids, n_commit, nq, k_new, v_new, pos_d)
+        next_pid[:] += n_commit
+        cur_len[:] += n_commit
+        state["committed"] += int(n_commit.sum())
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    state.update(committed=0, kv_bytes=0.0)
+    dec.attn_events = []
+    M.ms_profile_attention(ses.cache, args.steps * NL, args.event_stride)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern_ms = M.ms_profile_read(ses.cache, args.steps * NL)
+    M.ms_profile_attention(ses.cache, 0, 1)
+    attn_ms = sum(a.elapsed_time(b) for a, b in dec.attn_events) / args.steps
+    M.ms_check_integrity(ses.cache)
+    assert np.array_equal(np.asarray(ses.lengths(ids)), cur_len)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    per_launch_bytes = int(np.sum(2 * cur_len * Hkv * Dh * 2 + 4 * (-(-cur_len // 16)))) + B * nq * (2 * Hq + 2 * Hkv) * Dh * 2
+    kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else float("nan")
+    achieved = per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9
+    n_params = sum(t.numel() for lw in weights.layers for t in vars(lw).values()) + weights.lm_head.numel() + weights.norm.numel()
+    result = {
+        "metric": "full_decode_step_tokens_per_s_b64_kv8k",
+        "value": round(state["committed"] / (t1 - t0), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {
+            "workload": f"decode_step_qwen2.5-7b_shapes_batch{B}_kv{L0}_layers{NL}_verify{nv}_foresight{nf}",
+            "batch": B, "mean_kv_len": round(float(cur_len.mean()), 1), "layers": NL,
+            "step": "embedding, 28 blocks (hand-written norm / attention / SwiGLU kernels, torch GEMMs), LM head, greedy "
+                    "tokens, accept, commit; random weights, so about one token per sequence is accepted per step",
+        },
+        "query_tokens_per_s": round(B * nq * args.steps / (t1 - t0), 1),
+        "committed_per_step_per_seq": round(state["committed"] / args.steps / B, 3),
+        "attention_ms_per_step": round(attn_ms, 4),
+        "attention_share_of_step": round(attn_ms / ms_per_step, 4),
+        "weight_bytes_streamed_per_step": int(n_params * 2),
+        "roofline": {
+            "kernel": "pv_attn_mfma_stream", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+            "avg_kernel_ms": round(kern_avg_ms, 5), "launches": len(kern_ms),
+            "algorithmic_bytes_per_launch": per_launch_bytes,
+        },
+        "cpu_baseline": None,
+    }
     ses.close()
     print(json.dumps(result))
 
