@@ -677,6 +677,7 @@ def test_algorithm1_loop_keeps_gpu_and_oracle_in_step():
         seg_first_pid = list(next_pid)
         close_at = [11, 23, 17]                 # a step closes once it holds this many tokens
         n_compactions = 0
+        closed = [0] * B                        # steps closed so far: each took one position id for <o>
         for step in range(30):
             q = W.normal_bf16_bits(rng, (B, nq, Hq, D))
             kn = W.normal_bf16_bits(rng, (L, B, nq, Hkv, D))
@@ -732,6 +733,7 @@ def test_algorithm1_loop_keeps_gpu_and_oracle_in_step():
                 ora.compact(cids, begin, seg_len, n_mem, bf(mk), bf(mv), flat)
                 n_compactions += len(closing)
                 for b in closing:
+                    closed[b] += 1
                     next_pid[b] = M.ms_output_token_pid(next_pid[b] - 1) + 1
                     seg_start_len[b] = M.ms_seq_len(ses.cache, ids[b])
                     seg_first_pid[b] = next_pid[b]
@@ -742,3 +744,10 @@ def test_algorithm1_loop_keeps_gpu_and_oracle_in_step():
             M.ms_check_integrity(ses.cache)
         assert n_compactions >= 6
         assert M.ms_peak_pages(ses.cache) == ora.peak_pages
+        # what compression buys (Appendix C.1 reports it as peak context tokens): without it every
+        # committed token would still be cached
+        raw_tokens = [p - 1 - n_o for p, n_o in zip(next_pid, closed)]
+        pages_without = sum(-(-t // 16) for t in raw_tokens)
+        assert ora.peak_pages < pages_without
+        kept = sum(M.ms_seq_len(ses.cache, s) for s in ids)
+        assert kept - sum(prompt) < (sum(raw_tokens) - sum(prompt)) / 2     # prompts are never compressed
