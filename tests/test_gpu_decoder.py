@@ -1,6 +1,6 @@
 """Full decode step on the GPU against the fp64 decoder oracle (reduced model, bf16).
 
-Tolerances (derived in the design doc): the GPU rounds every GEMM output and activation to bf16 (relative
+Tolerances: the GPU rounds every GEMM output and activation to bf16 (relative
 2^-9 each) through 2 layers and the LM head, so logits carry an error of a few 1e-3 of their scale;
 the test allows max-abs 4e-2 x max|ref| and mean-rel 2e-2.  Greedy tokens must agree wherever the
 oracle's margin between best and second-best logit exceeds twice the measured max-abs error; accept
