@@ -348,6 +348,13 @@ def test_config3_ragged_batch32_sampled():
     sampled_rows_check(sh, 3, picks, 4)
 
 
+def test_one_very_long_sequence_sampled():
+    """131k cached tokens in one sequence next to a short one: every workgroup but one works on the
+    same sequence (64 partials per KV head to combine), position ids near 4e5 (large RoPE angles)."""
+    sh = W.AttnShape("long", "bf16", 2, 28, 4, 128, 5, 4, [131072 + 13, 100], 0.5, 1000000.0)
+    sampled_rows_check(sh, 6, [0, 1], 4)
+
+
 def test_metric_point_batch32_kv8192_sampled():
     sampled_rows_check(W.metric_point(), 5, [0, 13, 31], 4)
 
