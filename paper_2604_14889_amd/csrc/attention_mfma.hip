@@ -102,7 +102,7 @@ struct MfmaArgs {
     const Seg* item_first;  // [n_items]: first segment of every work item
     const Seg* segs;        // all segments in item order
     const int* part_begin;  // [B + 1]
-    int* arrive;            // [B][n_kv_heads] arrival counters, zero between calls
+    int* arrive;            // [B][n_kv_heads][2] counters (shares finished, partials published), zero between calls
     int n_q, n_verify, n_q_heads, n_kv_heads, group, max_pages;
     int q0, n_qc;           // this launch computes queries q0 .. q0 + n_qc (decode build: all of them)
     long page_elems;
@@ -329,57 +329,78 @@ __device__ __forceinline__ void mask_inflight(f32x16_t& s, int lim, int self, in
     }
 }
 
-// Merges the partials p_begin .. p_end of (sequence b, KV head g), normalises and writes the bf16
-// output rows.  Run by all 512 threads of the workgroup that arrived last for the pair: wave w owns
-// row block w / 4 and d block w % 4, a lane one row and 16 accumulators, laid out as in the stream.
-// Partials are taken two at a time so that their loads overlap.
-__device__ __forceinline__ void combine_partials(const MfmaArgs& a, int q0, int n_rows, int b, int g, int p_begin, int p_end,
-                                                 int w, int lane) {
-    const int rb = w >> 2, db = w & 3, l32 = lane & 31, hf = lane >> 5;
+// Closing a (sequence, KV head) pair: the workgroup that finished its share last keeps its own merged
+// state in registers (`own`, laid out as the LDS merge leaves it: wave w, pass p, u holds register
+// group reg4 = 16 (w / 4) + 4 (2 p + (w / 2) % 2) + 2 (w % 2) + u of row block w / 4), reads the other
+// partials p_begin .. p_end of the pair, folds everything in partial-index order (so the result does
+// not depend on who closes), normalises and writes the bf16 output rows.  Partials are taken four
+// at a time so that their loads overlap.
+__device__ __forceinline__ void close_pair(const MfmaArgs& a, int q0, int n_rows, int b, int g, int p_begin, int p_end,
+                                           int p_own, const float4 (&own)[2][2], float own_m, float own_l, int w, int lane) {
+    const int rb = w >> 2, d2 = (w >> 1) & 1, i4b = 2 * (w & 1), l32 = lane & 31, hf = lane >> 5;
     const int row = 32 * rb + l32;
-    float m = -INFINITY, lsum = 0.f, o[16];
+    float m = -INFINITY, lsum = 0.f;
+    float4 o[2][2];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) o[e] = 0.f;
-    for (int p0 = p_begin; p0 < p_end; p0 += 2) {
-        float pm[2], pl[2];
-        float4 px[2][4];
+    for (int ps = 0; ps < 2; ++ps)
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const bool live = p0 + u < p_end;
-            const float* part = a.ws + ((size_t)(live ? p0 + u : p0) * a.n_kv_heads + g) * kPartFloats;
-            const float pmu = load_coherent(part + row);
-            pm[u] = live ? pmu : -INFINITY;
-            pl[u] = load_coherent(part + kRows + row);
+        for (int u = 0; u < 2; ++u) o[ps][u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int p0 = p_begin; p0 < p_end; p0 += 4) {
+        float pm[4], pl[4];
+        float4 px[4][2][2];
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4)
-                px[u][i4] = load_coherent4(part + 2 * kRows + ((rb * 16 + db * 4 + i4) * 64 + lane) * 4);
+        for (int k = 0; k < 4; ++k) {
+            const int p = p0 + k;
+            if (p < p_end && p != p_own) {
+                const float* part = a.ws + ((size_t)p * a.n_kv_heads + g) * kPartFloats;
+                pm[k] = load_coherent(part + row);
+                pl[k] = load_coherent(part + kRows + row);
+#pragma unroll
+                for (int ps = 0; ps < 2; ++ps)
+#pragma unroll
+                    for (int u = 0; u < 2; ++u)
+                        px[k][ps][u] = load_coherent4(part + 2 * kRows + ((rb * 16 + (2 * ps + d2) * 4 + i4b + u) * 64 + lane) * 4);
+            } else {
+                const bool mine = p == p_own;
+                pm[k] = mine ? own_m : -INFINITY;   // past the end: weight 2^-inf = 0
+                pl[k] = mine ? own_l : 0.f;
+#pragma unroll
+                for (int ps = 0; ps < 2; ++ps)
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) px[k][ps][u] = mine ? own[ps][u] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
         }
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const float mn = fmaxf(m, pm[u]);                       // the first partial is live and finite
+        for (int k = 0; k < 4; ++k) {
+            const float mn = fmaxf(m, pm[k]);                       // the first partial exists and is finite
             const float fo = __builtin_amdgcn_exp2f(m - mn);
-            const float fp = __builtin_amdgcn_exp2f(pm[u] - mn);    // absent partial: 2^-inf = 0
+            const float fp = __builtin_amdgcn_exp2f(pm[k] - mn);
             m = mn;
-            lsum = lsum * fo + pl[u] * fp;
+            lsum = lsum * fo + pl[k] * fp;
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                o[4 * i4 + 0] = o[4 * i4 + 0] * fo + px[u][i4].x * fp;
-                o[4 * i4 + 1] = o[4 * i4 + 1] * fo + px[u][i4].y * fp;
-                o[4 * i4 + 2] = o[4 * i4 + 2] * fo + px[u][i4].z * fp;
-                o[4 * i4 + 3] = o[4 * i4 + 3] * fo + px[u][i4].w * fp;
-            }
+            for (int ps = 0; ps < 2; ++ps)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    o[ps][u].x = o[ps][u].x * fo + px[k][ps][u].x * fp;
+                    o[ps][u].y = o[ps][u].y * fo + px[k][ps][u].y * fp;
+                    o[ps][u].z = o[ps][u].z * fo + px[k][ps][u].z * fp;
+                    o[ps][u].w = o[ps][u].w * fo + px[k][ps][u].w * fp;
+                }
         }
     }
     if (row < n_rows) {
         const float inv = 1.f / lsum;
-        uint16_t* op = a.out + (((size_t)b * a.n_q + q0 + row / a.group) * a.n_q_heads + g * a.group + row % a.group) * kD + 32 * db + 4 * hf;
+        uint16_t* op = a.out + (((size_t)b * a.n_q + q0 + row / a.group) * a.n_q_heads + g * a.group + row % a.group) * kD;
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-            uint2 pk;
-            pk.x = pack_bf16x2(o[4 * i4 + 0] * inv, o[4 * i4 + 1] * inv);
-            pk.y = pack_bf16x2(o[4 * i4 + 2] * inv, o[4 * i4 + 3] * inv);
-            *reinterpret_cast<uint2*>(op + 8 * i4) = pk;
-        }
+        for (int ps = 0; ps < 2; ++ps)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                // register group -> d = 32 (2 ps + d2) + 8 (i4b + u) + 4 (lane / 32) .. + 4
+                uint2 pk;
+                pk.x = pack_bf16x2(o[ps][u].x * inv, o[ps][u].y * inv);
+                pk.y = pack_bf16x2(o[ps][u].z * inv, o[ps][u].w * inv);
+                *reinterpret_cast<uint2*>(op + 32 * (2 * ps + d2) + 8 * (i4b + u) + 4 * hf) = pk;
+            }
     }
 }
 
@@ -610,14 +631,22 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         // pass: every wave stores its 64 registers of the pair, then wave w reduces two float4 per
         // lane over all waves and writes them to the segment's partial ----
         float* part = a.ws + ((size_t)sg_part * a.n_kv_heads + g) * kPartFloats;
+        const int p_begin = uniform_load(a.part_begin + sg_b), p_end = uniform_load(a.part_begin + sg_b + 1);
+        int* ctr = a.arrive + 2 * (sg_b * a.n_kv_heads + g);   // [0] shares finished, [1] partials published
         int lane_m = lane;
         asm volatile("" : "+v"(lane_m));
 #ifdef MS_TIMING
         if (tid == 0 && si == seg_begin) dbg[2] = wall_clock64();
 #endif
+        int ticket = 0;
+        float4 own[2][2];
+        float own_m = 0.f, own_l = 0.f;
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
             lds_barrier();
+            // every wave has left the stream: take this share's place in the pair's finishing order.
+            // The answer is not needed before the merge is done, which hides the round trip.
+            if (pass == 0 && tid == 0) ticket = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             {
                 float* reg = reinterpret_cast<float*>(smem + w * kMergeRegionBytes);
 #pragma unroll
@@ -663,35 +692,49 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
                         acc[u].w += f * x.w;
                     }
                 }
+                own[pass][0] = acc[0];
+                own[pass][1] = acc[1];
+                if (pass == 0) {
+                    own_m = mn;
+                    own_l = lt + __shfl_xor(lt, 32, 64);   // the two half-waves hold the two halves of a row's sum
+                }
+            }
+        }
+        // ---- closing the pair.  The share that finished last (by ticket) folds the others' partials
+        // into its registers and writes the output; every other share publishes its partial.  The
+        // closing workgroup only ever waits for workgroups that took their ticket before it, and those
+        // publish without waiting for anything, so the wait is bounded by their store latency ----
+        if (tid == 0) *reinterpret_cast<volatile int*>(smem + L::kFlag) = ticket;
+        lds_barrier();
+        const bool closing = *reinterpret_cast<volatile int*>(smem + L::kFlag) == p_end - p_begin - 1;
+        if (!closing) {
+            const int rb = w >> 2;
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass)
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const int slot = 2 * w + u, d2 = (slot >> 2) & 1, i4 = slot & 3;
                     const int reg4 = rb * 16 + (2 * pass + d2) * 4 + i4;
-                    store_coherent(part + 2 * kRows + (reg4 * 64 + lane_m) * 4, acc[u]);
+                    store_coherent(part + 2 * kRows + (reg4 * 64 + lane_m) * 4, own[pass][u]);
                 }
-                if (pass == 0 && (w & 3) == 0) {
-                    lt += __shfl_xor(lt, 32, 64);
-                    if ((lane_m >> 5) == 0) {
-                        store_coherent(part + 32 * rb + (lane_m & 31), mn);
-                        store_coherent(part + kRows + 32 * rb + (lane_m & 31), lt);
-                    }
-                }
+            if ((w & 3) == 0 && (lane_m >> 5) == 0) {
+                store_coherent(part + 32 * rb + (lane_m & 31), own_m);
+                store_coherent(part + kRows + 32 * rb + (lane_m & 31), own_l);
             }
+            __syncthreads();   // waits for every thread's partial stores
+            if (tid == 0) __hip_atomic_fetch_add(ctr + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            if (tid == 0) {
+                const int others = p_end - p_begin - 1;
+                // (the bound only guards against a corrupted counter: about a second of polling)
+                for (int spin = 0; spin < (1 << 22) && __hip_atomic_load(ctr + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != others; ++spin)
+                    __builtin_amdgcn_s_sleep(2);
+                __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);       // ready for the next call
+                __hip_atomic_store(ctr + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            lds_barrier();
+            close_pair(a, q0, n_rows, sg_b, g, p_begin, p_end, sg_part, own, own_m, own_l, w, lane_m);
         }
-        // ---- arrival: the last workgroup of this (sequence, KV head) merges its partials.  The
-        // barrier waits for every thread's partial stores before thread 0 bumps the count ----
-        __syncthreads();
-        if (tid == 0) {
-            const int p_cnt = a.part_begin[sg_b + 1] - a.part_begin[sg_b];
-            int* ctr = a.arrive + sg_b * a.n_kv_heads + g;
-            const int seen = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int last = seen == p_cnt - 1;
-            if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
-            *reinterpret_cast<volatile int*>(smem + L::kFlag) = last;
-        }
-        lds_barrier();
-        if (*reinterpret_cast<volatile int*>(smem + L::kFlag))
-            combine_partials(a, q0, n_rows, sg_b, g, a.part_begin[sg_b], a.part_begin[sg_b + 1], w, lane_m);
         lds_barrier();  // the next segment reuses the LDS
     }
 #ifdef MS_TIMING

@@ -438,7 +438,7 @@ int ms_cache_create(const ms_cache_desc* desc, ms_cache** out) {
         set_error("allocating the attention plan buffer failed");
         return fail(MS_ERR_HIP);
     }
-    const size_t arrive_bytes = (size_t)MS_MAX_BATCH * desc->n_kv_heads * sizeof(int);
+    const size_t arrive_bytes = (size_t)2 * MS_MAX_BATCH * desc->n_kv_heads * sizeof(int);   // two counters per (sequence, KV head)
     if (hipMalloc((void**)&c->d_arrive, arrive_bytes) != hipSuccess || hipMemset(c->d_arrive, 0, arrive_bytes) != hipSuccess) {
         set_error("allocating the arrival counters failed");
         return fail(MS_ERR_HIP);

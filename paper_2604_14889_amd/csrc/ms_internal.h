@@ -77,7 +77,7 @@ struct ms_cache {
     unsigned version = 0;        // bumped by every call that changes lengths or page tables
     int n_cus = 256;             // compute units of the device
     int* d_plan = nullptr;       // device copy of the streaming kernel's work plan
-    int* d_arrive = nullptr;     // [MS_MAX_BATCH][n_kv_heads] arrival counters of the streaming kernel
+    int* d_arrive = nullptr;     // [MS_MAX_BATCH][n_kv_heads][2] counters of the streaming kernel: shares finished, partials published
     std::vector<int> plan_key;   // batch (ids, lengths) the plan was built for
     int plan_items = 0, plan_parts = 0, plan_B = 0;
     std::vector<hipEvent_t> prof_start, prof_stop;  // event pairs around the streaming kernel
