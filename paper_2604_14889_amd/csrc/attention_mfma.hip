@@ -5,7 +5,7 @@
 //   * The host cuts the batch's cached tokens, flattened over sequences in 32-token tiles, into
 //     equal contiguous shares, one workgroup per (share, KV head).  A share that crosses sequence
 //     boundaries is processed as several segments.
-//   * Each of a workgroup's 8 waves streams every 8th tile of a segment on its own: K goes from
+//   * Each of a workgroup's 8 waves streams tiles of a segment on its own: K goes from
 //     HBM straight into MFMA operand registers, V is staged through a wave-private LDS tile and
 //     read back transposed (ds_read_b64_tr_b16); a wave refills its registers for its next tile as
 //     soon as the current tile has consumed them.  There is no barrier inside the stream.
@@ -16,9 +16,13 @@
 //   * The step's own (in-flight) verify / foresight keys are one more tile: the workgroup that owns
 //     a sequence's first segment rotates them into an LDS K tile and one of its waves runs the
 //     tile with the visibility rule applied to the scores.
-//   * Each segment leaves one partial (row maxima, row sums, unnormalised O) in the workspace and
-//     bumps the arrival counter of its (sequence, KV head); the workgroup that arrives last merges
-//     that pair's partials, normalises and writes the bf16 output rows.  One launch per call.
+//   * Each segment takes a ticket in the finishing order of its (sequence, KV head) pair.  All but
+//     the last leave a partial (row maxima, row sums, unnormalised O) in the workspace; the last
+//     one folds the others' partials into its own registers, normalises and writes the bf16 output
+//     rows.  One launch per call.
+//   * Each wave's first tile of a segment is fixed; by default the waves then take further tiles
+//     first come, first served (results reproducible to rounding), optionally every 8th tile each
+//     (bit-reproducible).
 #include <math.h>
 #include <string.h>
 
