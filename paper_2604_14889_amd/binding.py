@@ -99,7 +99,20 @@ def _check(rc: int) -> None:
         raise MsError(rc, lib.ms_last_error().decode())
 
 
-def _ints(xs: Sequence[int]):
+def int_array(xs: Sequence[int]):
+    """A C int array holding xs.  Pass the result instead of a list to skip the conversion on every call
+    (sequence ids, for instance, are the same for all layers of a step)."""
+    xs = [int(x) for x in xs]
+    if not xs:
+        raise ValueError("int_array needs at least one element")
+    return (C.c_int * len(xs))(*xs)
+
+
+def _ints(xs):
+    if isinstance(xs, C.Array):                       # already marshalled (int_array)
+        return xs
+    if isinstance(xs, np.ndarray) and xs.dtype == np.int32 and xs.flags["C_CONTIGUOUS"] and xs.size > 0:
+        return xs.ctypes.data_as(_IP)                 # read during the call only
     xs = [int(x) for x in xs]
     return (C.c_int * max(1, len(xs)))(*xs)
 
@@ -129,6 +142,8 @@ def _sized(cache, t, what: str, n_elems: int, elem_size: Optional[int] = None) -
 
 
 def _stream(stream) -> Optional[int]:
+    if type(stream) is int:                           # a raw hipStream_t value
+        return stream or None
     if stream is None:
         if not torch.cuda.is_available():
             return None

@@ -51,6 +51,7 @@ class Session:
         assert M.ms_pool_bytes(desc) == self.pool.numel() * self.pool.element_size()
         self.cache = M.ms_cache_create(desc)
         self.workspace: Optional[torch.Tensor] = None
+        self._ws_need = {}
 
     def close(self) -> None:
         if self.cache:
@@ -64,7 +65,9 @@ class Session:
         self.close()
 
     def ensure_workspace(self, B: int, n_q: int) -> torch.Tensor:
-        need = M.ms_attention_workspace_bytes(self.cache, B, n_q)
+        need = self._ws_need.get((B, n_q))
+        if need is None:
+            need = self._ws_need[(B, n_q)] = M.ms_attention_workspace_bytes(self.cache, B, n_q)
         if self.workspace is None or self.workspace.numel() < need:
             self.workspace = torch.empty(need, dtype=torch.uint8, device="cuda")
         return self.workspace
@@ -72,12 +75,12 @@ class Session:
     def attention(self, layer: int, seq_ids: Sequence[int], n_verify: int, n_foresight: int, q: torch.Tensor,
                   k_new: torch.Tensor, v_new: torch.Tensor, pos_ids: torch.Tensor,
                   ctx_new: Optional[torch.Tensor] = None, scale: float = 0.0,
-                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                  out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
         ws = self.ensure_workspace(len(seq_ids), n_verify + n_foresight)
         if out is None:
             out = torch.empty_like(q)
         M.ms_predict_verify_attention(self.cache, layer, seq_ids, n_verify, n_foresight, q, k_new, v_new,
-                                      pos_ids, ctx_new, scale, out, ws)
+                                      pos_ids, ctx_new, scale, out, ws, stream)
         return out
 
     def page_tables(self, seq_ids: Sequence[int]) -> List[List[int]]:
