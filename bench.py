@@ -47,6 +47,8 @@ def parse():
                     help="attention: the metric's workload (default); decode_step: the whole model step "
                          "(Qwen2.5-7B shapes, batch 64, 8k cached tokens, 4 verify + 3 foresight) with torch GEMMs around "
                          "the hand-written kernels")
+    ap.add_argument("--deterministic", action="store_true",
+                    help="fixed tile-to-wave assignment in the attention kernel (bit-reproducible results, about 1.5 %% slower)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=32, help="sequences the CPU oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -88,6 +90,7 @@ def main():
         ses.pool[layer].normal_(0.0, sh.sigma, generator=gen)
     ids = [M.ms_seq_import(ses.cache, n, pt) for n, pt in zip(sh.lengths, page_tables)]
     ids = M.int_array(ids)      # marshalled once: the same ids go into every call
+    M.ms_attention_set_deterministic(ses.cache, args.deterministic)
 
     def dev_normal(*shape):
         return torch.empty(*shape, dtype=torch.bfloat16, device=dev).normal_(0.0, sh.sigma, generator=gen)
@@ -215,6 +218,8 @@ def main():
                         f"_layers{NL}_q{Hq}_kv{Hkv}_d{D}_verify{nv}_foresight{nf}",
             "batch": B, "mean_kv_len": round(float(np.mean(lengths)), 1), "layers": NL,
             "step": "28-layer attention + accept + commit, compaction 56->8 every 14 steps",
+            "attention_tile_assignment": "fixed (bit-reproducible)" if args.deterministic else
+                                         "first come, first served (reproducible to rounding)",
         },
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "query_tokens_per_s": round(B * nq * args.steps / (t1 - t0), 1),
