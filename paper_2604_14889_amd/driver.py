@@ -49,7 +49,7 @@ class SeqState:
 
 
 class Observer:
-    def forward(self, kind, seq_ids, tokens, pos, n_verify, n_foresight, logits, targets):  # noqa: D401
+    def forward(self, kind, seq_ids, tokens, pos, n_verify, n_foresight, logits, targets, ctx_new=None):  # noqa: D401
         pass
 
     def commit(self, seq_ids, n_commit, pos):
@@ -60,9 +60,17 @@ class Observer:
 
 
 class MemoSightDriver:
-    def __init__(self, decoder: Decoder, d: int, c: int, special: SpecialTokens, observer: Optional[Observer] = None):
+    def __init__(self, decoder: Decoder, d: int, c: int, special: SpecialTokens, observer: Optional[Observer] = None,
+                 per_position: bool = False):
+        """per_position: put d foresight tokens behind EVERY verify token (the layout the model is
+        trained on, Section 2.2) instead of behind the block only, so that the drafts for the next
+        pass are valid whatever number of verify tokens was kept; costs (d + 1) d instead of d extra
+        queries per pass."""
         if d < 0 or c < 1:
             raise ValueError("need d >= 0 and c >= 1")
+        if per_position and (d + 1) * (d + 1) > M.MS_MAX_QUERIES:
+            raise ValueError("too many queries per pass")
+        self.per_position = per_position
         self.dec, self.ses, self.d, self.c, self.sp = decoder, decoder.ses, d, c, special
         self.obs = observer or Observer()
         self.state: Dict[int, SeqState] = {}
@@ -70,12 +78,13 @@ class MemoSightDriver:
         self.raw_tokens = 0        # tokens that would be cached without compression
 
     # ---- helpers --------------------------------------------------------------------------------
-    def _forward(self, kind, seq_ids, tokens: np.ndarray, pos: np.ndarray, n_verify: int, n_foresight: int):
+    def _forward(self, kind, seq_ids, tokens: np.ndarray, pos: np.ndarray, n_verify: int, n_foresight: int, ctx_d=None):
         tok_d = torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).cuda()
         pos_d = torch.from_numpy(np.ascontiguousarray(pos, dtype=np.int32)).cuda()
-        logits, targets = self.dec.step(seq_ids, tok_d, pos_d, n_verify, n_foresight)
+        logits, targets = self.dec.step(seq_ids, tok_d, pos_d, n_verify, n_foresight, ctx_d)
         self.passes[kind] += 1
-        self.obs.forward(kind, list(seq_ids), tokens, pos, n_verify, n_foresight, logits, targets)
+        ctx = None if ctx_d is None else ctx_d.cpu().numpy()
+        self.obs.forward(kind, list(seq_ids), tokens, pos, n_verify, n_foresight, logits, targets, ctx)
         return pos_d, targets
 
     # ---- Algorithm 1, line 1: prefill -------------------------------------------------------------
@@ -109,10 +118,17 @@ class MemoSightDriver:
             return []
         d, nv = self.d, self.d + 1
         ids = [s.seq_id for s in act]
-        tokens = np.asarray([[s.next_token] + s.drafts + [self.sp.foresight] * d for s in act], np.int32)
-        pos = M.ms_step_positions(np.asarray([s.next_pid for s in act], np.int32), nv, d)
-        pos_d, targets = self._forward("speculative", ids, tokens, pos, nv, d)
-        B, nq = len(act), nv + d
+        nf = nv * d if self.per_position else d
+        tokens = np.asarray([[s.next_token] + s.drafts + [self.sp.foresight] * nf for s in act], np.int32)
+        ctx_d = None
+        if self.per_position:
+            lay = [M.ms_per_position_layout(s.next_pid, nv, d) for s in act]
+            pos = np.asarray([p for p, _ in lay], np.int32)
+            ctx_d = torch.tensor([c_ for _, c_ in lay], dtype=torch.int32, device="cuda")
+        else:
+            pos = M.ms_step_positions(np.asarray([s.next_pid for s in act], np.int32), nv, d)
+        pos_d, targets = self._forward("speculative", ids, tokens, pos, nv, nf, ctx_d)
+        B, nq = len(act), nv + nf
         tg = targets.view(B, nq)
         n_commit = [1] * B
         if d > 0:
@@ -138,9 +154,11 @@ class MemoSightDriver:
             last = kept[-1]
             s.next_pid += len(kept)
             s.next_token = int(tg_h[b, len(kept) - 1])          # the greedy token after the last kept one
-            # drafts for the next pass: the foresight rows' greedy tokens (they are conditioned on the
-            # whole verify block, so they only have a chance when all of it was kept)
-            s.drafts = [int(t) for t in tg_h[b, nv:nv + d]]
+            # drafts for the next pass: the greedy tokens of the foresight rows behind the last kept
+            # verify token; with foresight tokens behind the block only, those are conditioned on the
+            # whole block and only have a chance when all of it was kept
+            f0 = nv + (len(kept) - 1) * d if self.per_position else nv
+            s.drafts = [int(t) for t in tg_h[b, f0:f0 + d]]
             if last == self.sp.eos:
                 s.finished = True
             elif last in self.sp.delimiters:

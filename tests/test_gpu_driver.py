@@ -15,7 +15,8 @@ from tests.test_gpu_decoder import make_weights
 pytestmark = pytest.mark.gpu
 
 
-def test_algorithm1_driver_runs_in_lockstep_with_the_oracle():
+@pytest.mark.parametrize("per_position", [False, True])
+def test_algorithm1_driver_runs_in_lockstep_with_the_oracle(per_position):
     from paper_2604_14889_amd import binding as M
     from paper_2604_14889_amd import decoder as D
     from paper_2604_14889_amd import driver as DR
@@ -60,9 +61,11 @@ def test_algorithm1_driver_runs_in_lockstep_with_the_oracle():
                 assert M.ms_seq_len(ses.cache, s) == ora.seq_len[s]
             assert M.ms_free_page_count(ses.cache) == ora.free_page_count()
 
-        def forward(self, kind, seq_ids, tokens, pos, nv, nf, logits, targets):
+        def forward(self, kind, seq_ids, tokens, pos, nv, nf, logits, targets, ctx_new=None):
             torch.cuda.synchronize()
-            r = DO.speculative_step(wts, ora, seq_ids, tokens, pos, nv, nf)
+            if kind == "speculative":
+                assert nf == ((d_off + 1) * d_off if per_position else d_off) and (ctx_new is not None) == per_position
+            r = DO.speculative_step(wts, ora, seq_ids, tokens, pos, nv, nf, ctx_new)
             got = logits.float().cpu().numpy().reshape(r.logits.shape).astype(np.float64)
             err = np.abs(got - r.logits)
             scale = np.abs(r.logits).max()
@@ -93,7 +96,7 @@ def test_algorithm1_driver_runs_in_lockstep_with_the_oracle():
     with ses:
         obs = Lockstep()
         dec = D.Decoder(cfg, gw, ses, 64)
-        drv = DR.MemoSightDriver(dec, d_off, ratio, special, obs)
+        drv = DR.MemoSightDriver(dec, d_off, ratio, special, obs, per_position=per_position)
         ids = [M.ms_seq_create(ses.cache) for _ in range(2)]
         assert ids == [ora.seq_create() for _ in range(2)]
         prompts = [rng.integers(100, 990, size=70).tolist(), rng.integers(100, 990, size=9).tolist()]
