@@ -194,7 +194,8 @@ def main():
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "pv_attn_mfma_stream_batch32_kv8192_traffic.json")
-    if os.path.exists(tpath):
+    # the committed counter summary covers the default workload only
+    if os.path.exists(tpath) and not args.ragged and B == 32 and args.kv == 8192:
         try:
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
         except Exception:
