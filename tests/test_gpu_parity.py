@@ -153,6 +153,37 @@ def test_attention_small_shapes_match_oracle(dtype, hq, hkv, d, nv, nf, lengths)
         M.ms_check_integrity(ses.cache)
 
 
+BOUNDARY_LENGTHS = [0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 511, 512, 513, 1000, 2047, 2048, 4095, 4096, 4097]
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_attention_random_batches_of_boundary_lengths(case):
+    """Seeded random batches whose lengths sit on page (16), tile (32) and round (256) boundaries,
+    with random head groupings and step shapes: exercises the share planner (empty sequences,
+    segments that end exactly on a tile, shares crossing several sequences) on the streaming kernel."""
+    M, S = _mods()
+    rng = W.make_rng(450, case)
+    hq, hkv = [(28, 4), (32, 8), (8, 8), (16, 2), (64, 1)][case % 5]
+    g = hq // hkv
+    batch = int(rng.integers(1, 13))
+    lengths = [int(rng.choice(BOUNDARY_LENGTHS)) for _ in range(batch)]
+    if case % 4 == 0:
+        lengths[int(rng.integers(batch))] = int(rng.integers(5000, 12000))   # one long sequence among short ones
+    n_q = int(rng.integers(1, 17 if g <= 4 else max(2, 64 // g + 3)))
+    nv = int(rng.integers(0, n_q + 1))
+    nf = n_q - nv
+    sh = W.AttnShape(f"rand{case}", "bf16", batch, hq, hkv, 128, nv, nf, lengths, 0.5, 1000000.0)
+    inp = W.attention_inputs(sh, 451, case)
+    ses, ora, ids = setup_pair(inp)
+    with ses:
+        pos = pids_for(inp, M)
+        got = run_gpu_attention(ses, inp, ids, pos)
+        want = oracle_attention(ora, inp, ids, pos)
+        assert np.isfinite(got).all()
+        check_out(got, want, "bf16", f"case {case}: heads {hq}/{hkv}, verify {nv} foresight {nf}, lengths {lengths}")
+        M.ms_check_integrity(ses.cache)
+
+
 def test_attention_custom_ctx_new_and_peaked_scores():
     M, S = _mods()
     sh = W.AttnShape("ctx", "bf16", 2, 28, 4, 128, 4, 3, [450, 130], 0.5, 1000000.0)
