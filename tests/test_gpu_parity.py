@@ -616,6 +616,104 @@ def test_compaction_in_the_middle_moves_the_tail():
         M.ms_check_integrity(ses.cache)
 
 
+def test_random_cache_operation_sequence_stays_in_step_with_the_oracle():
+    """300 seeded random cache operations -- create, free, append (batched), compaction of a random
+    segment (suffix or middle, batched), failing calls (pool exhausted, segment out of range) --
+    applied to both sides; page tables, lengths and free counts must agree after every one, the
+    stored rows at the end."""
+    M, S = _mods()
+    rng = W.make_rng(414)
+    L, Hkv, D, NP, MAXS = 2, 2, 64, 40, 6
+    ses = S.Session(L, 4, Hkv, D, NP, M.MS_F32, 10000.0, max_seqs=MAXS, max_pages_per_seq=NP)
+    ora = O.PagedCache(L, Hkv, D, NP, dtype=O.F32, rope_base=10000.0, max_seqs=MAXS)
+    live, next_pos = [], {}
+    n_ops = {"create": 0, "free": 0, "append": 0, "compact": 0, "oom": 0, "range": 0}
+    with ses:
+        for op_i in range(300):
+            r = rng.random()
+            if (r < 0.12 and len(live) < MAXS) or not live:
+                s = M.ms_seq_create(ses.cache)
+                assert s == ora.seq_create()
+                live.append(s)
+                next_pos[s] = 1
+                n_ops["create"] += 1
+            elif r < 0.2:
+                s = live.pop(int(rng.integers(len(live))))
+                M.ms_seq_free(ses.cache, s)
+                ora.seq_free(s)
+                n_ops["free"] += 1
+            elif r < 0.65:
+                k_seqs = int(rng.integers(1, len(live) + 1))
+                seqs = [int(x) for x in rng.choice(live, size=k_seqs, replace=False)]
+                counts = [int(rng.integers(0, 41)) for _ in seqs]
+                tot = sum(counts)
+                k, v = W.normal_f32(rng, (L, max(tot, 1), Hkv, D)), W.normal_f32(rng, (L, max(tot, 1), Hkv, D))
+                pos = np.concatenate([np.arange(next_pos[s], next_pos[s] + c) for s, c in zip(seqs, counts)] + [np.zeros(0)]).astype(np.int32)
+                pos_d = S.ints_dev(pos if tot else [0])
+                try:
+                    ora.append(seqs, counts, k[:, :tot], v[:, :tot], pos)
+                except O.OutOfPages:
+                    with pytest.raises(M.MsError) as e:
+                        M.ms_append_kv(ses.cache, seqs, counts, S.to_device(k, M.MS_F32), S.to_device(v, M.MS_F32), pos_d)
+                    assert e.value.code == M.MS_ERR_OOM_PAGES
+                    n_ops["oom"] += 1
+                else:
+                    M.ms_append_kv(ses.cache, seqs, counts, S.to_device(k, M.MS_F32), S.to_device(v, M.MS_F32), pos_d)
+                    for s, c in zip(seqs, counts):
+                        next_pos[s] += c
+                    n_ops["append"] += 1
+            else:
+                cands = [s for s in live if ora.seq_len[s] >= 4]
+                if not cands:
+                    continue
+                k_seqs = int(rng.integers(1, min(3, len(cands)) + 1))
+                seqs = [int(x) for x in rng.choice(cands, size=k_seqs, replace=False)]
+                begin, seg, n_mem = [], [], []
+                for s in seqs:
+                    n = ora.seq_len[s]
+                    b0 = int(rng.integers(0, n - 1))
+                    ln = n - b0 if rng.random() < 0.5 else int(rng.integers(1, n - b0 + 1))    # suffix or middle
+                    begin.append(b0)
+                    seg.append(ln)
+                    n_mem.append(int(rng.integers(0, max(1, ln // 3) + 1)))
+                bad = rng.random() < 0.1
+                if bad:
+                    seg[0] = ora.seq_len[seqs[0]] - begin[0] + 1                               # one past the end
+                tot = sum(n_mem)
+                mk, mv = W.normal_f32(rng, (L, max(tot, 1), Hkv, D)), W.normal_f32(rng, (L, max(tot, 1), Hkv, D))
+                mpos = rng.integers(1, 500, size=max(tot, 1)).astype(np.int32)
+                args = (seqs, begin, seg, n_mem)
+                if bad:
+                    big = torch.empty(1 << 22, dtype=torch.uint8, device="cuda")
+                    with pytest.raises(M.MsError) as e:
+                        M.ms_compact_segment(ses.cache, *args, S.to_device(mk, M.MS_F32), S.to_device(mv, M.MS_F32), S.ints_dev(mpos),
+                                             workspace=big)
+                    assert e.value.code == M.MS_ERR_RANGE
+                    n_ops["range"] += 1
+                else:
+                    need = M.ms_compact_workspace_bytes(ses.cache, *args[:3])
+                    ws = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda")
+                    M.ms_compact_segment(ses.cache, *args, S.to_device(mk, M.MS_F32), S.to_device(mv, M.MS_F32), S.ints_dev(mpos),
+                                         workspace=ws)
+                    ora.compact(*args, mk[:, :tot], mv[:, :tot], mpos[:tot])
+                    n_ops["compact"] += 1
+            for s in live:
+                assert M.ms_seq_page_table(ses.cache, s) == ora.page_table[s], f"op {op_i}"
+                assert M.ms_seq_len(ses.cache, s) == ora.seq_len[s]
+            assert M.ms_free_page_count(ses.cache) == ora.free_page_count()
+        M.ms_check_integrity(ses.cache)
+        assert M.ms_peak_pages(ses.cache) == ora.peak_pages
+        assert min(n_ops["append"], n_ops["compact"]) > 40 and n_ops["free"] > 5, n_ops
+        torch.cuda.synchronize()
+        gp = ses.pool_host_f32()
+        for s in live:
+            for li in range(L):
+                for t in range(ora.seq_len[s]):
+                    p, sl = ora.page_table[s][t // 16], t % 16
+                    assert np.abs(gp[li, p, :, :, sl] - ora.pool[li, p, :, :, sl]).max() < 3e-5
+        print("operations:", n_ops)
+
+
 # ------------------------------------------------------------------ acceptance ---------------
 
 def test_accept_matches_oracle_including_stop_ids():
