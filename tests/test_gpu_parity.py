@@ -259,6 +259,32 @@ def test_gpu_foresight_rows_independent_and_page_permutation_invariant():
     assert np.array_equal(got3, base)
 
 
+def test_repeated_launches_agree_with_many_partials_per_pair():
+    """Race check for the closing of (sequence, KV head) pairs: long sequences in a small batch are
+    cut into many shares (up to ~25 partials per pair here), and whichever share finishes last folds
+    the others.  Thirty launches in a row must give the same bits with the fixed tile assignment and
+    stay within rounding of them with the default one."""
+    M, S = _mods()
+    sh = W.AttnShape("rep", "bf16", 5, 28, 4, 128, 5, 4, [9000, 100, 4000, 33, 7000], 0.5, 1000000.0, n_layers=2)
+    inp = W.attention_inputs(sh, 403)
+    ses, ora, ids = setup_pair(inp)
+    with ses:
+        pos = pids_for(inp, M)
+        want = oracle_attention(ora, inp, ids, pos, 1)
+        M.ms_attention_set_deterministic(ses.cache, True)
+        base = run_gpu_attention(ses, inp, ids, pos, 1)
+        check_out(base, want, "bf16", "fixed assignment")
+        for i in range(30):
+            again = run_gpu_attention(ses, inp, ids, pos, i % 2)
+            if i % 2 == 1:
+                assert np.array_equal(again, base), f"launch {i} differs"
+        M.ms_attention_set_deterministic(ses.cache, False)
+        for i in range(30):
+            again = run_gpu_attention(ses, inp, ids, pos, 1)
+            assert np.abs(again - base).max() <= 2e-3, f"launch {i}: {np.abs(again - base).max():.3e}"
+            check_out(again, want, "bf16", f"default assignment, launch {i}")
+
+
 # ------------------------------------------------------------------ the named configurations ---
 
 def test_config1_fp32_built_through_append_and_compact():
