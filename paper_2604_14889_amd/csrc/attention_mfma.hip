@@ -207,18 +207,39 @@ __device__ __forceinline__ void tile_pages(const int* __restrict__ pt, int tile,
 
 // K operand of a tile straight from the pool.  Addresses are a uniform base plus a 32-bit byte
 // offset per lane (page_bytes * page id + lane part), which keeps the per-lane address state to one
-// register; the host only takes this kernel when a layer's pool is below 4 GiB.
+// register; layer pools of 4 GiB and more take the kBigPool build below.
+template <bool kBigPool>
 __device__ __forceinline__ void load_k(uint4 (&k)[8], const char* __restrict__ pool, int pa, int pb,
                                        uint32_t page_bytes, uint32_t lane_off_k, int lane) {
-    const uint32_t off = (uint32_t)((lane & 16) ? pb : pa) * page_bytes + lane_off_k;
+    if (!kBigPool) {
+        const uint32_t off = (uint32_t)((lane & 16) ? pb : pa) * page_bytes + lane_off_k;
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) k[kk] = *reinterpret_cast<const uint4*>(pool + off + 32 * kk);
+        for (int kk = 0; kk < 8; ++kk) k[kk] = *reinterpret_cast<const uint4*>(pool + off + 32 * kk);
+    } else {
+        // layer pools of 4 GiB and more: the page's base is a 64-bit (wave-uniform) address, the
+        // half-waves pick theirs, the lane part stays a 32-bit offset
+        const char* base_a = pool + (size_t)(uint32_t)pa * page_bytes;
+        const char* base_b = pool + (size_t)(uint32_t)pb * page_bytes;
+        const char* base = (lane & 16) ? base_b : base_a;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) k[kk] = *reinterpret_cast<const uint4*>(base + lane_off_k + 32 * kk);
+    }
 }
 
 // V rows of a tile: tokens 4 rr + lane / 16 of page a (rr < 4) and of page b.  V is read exactly once
 // per call: streaming (non-temporal) loads keep it out of the caches.
+template <bool kBigPool>
 __device__ __forceinline__ void load_v(uint4 (&v)[8], const char* __restrict__ pool, int pa, int pb,
                                        uint32_t page_bytes, uint32_t lane_off_v) {
+    if (kBigPool) {
+        const char* base_a = pool + (size_t)(uint32_t)pa * page_bytes;
+        const char* base_b = pool + (size_t)(uint32_t)pb * page_bytes;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) v[rr] = load_stream(base_a + lane_off_v + 4 * rr * kD * 2);
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) v[4 + rr] = load_stream(base_b + lane_off_v + 4 * rr * kD * 2);
+        return;
+    }
     const uint32_t oa = (uint32_t)pa * page_bytes + lane_off_v, ob = (uint32_t)pb * page_bytes + lane_off_v;
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) v[rr] = load_stream(pool + oa + 4 * rr * kD * 2);
@@ -418,7 +439,7 @@ __device__ __forceinline__ int claim_tile(int* counter, int lane) {
 // kWide: see the LDS map.  kClaim: the waves of a workgroup take the segment's tiles first come,
 // first served instead of every 8th tile each; this evens out the waves' finishing times, at the
 // price of results that depend on the order the tiles happened to be taken in (rounding only).
-template <bool kWide, bool kClaim>
+template <bool kWide, bool kClaim, bool kBigPool = false>
 __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     typedef Lds<kWide> L;
@@ -490,8 +511,8 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
 #pragma unroll
         for (int k = 0; k < kPosPerWave; ++k) pos_w[k] = w + 8 * k < a.n_q ? uniform_load(a.pos + sg_b * a.n_q + w + 8 * k) : 0;
         TileRegs r;   // (an empty segment's record names page 0: loaded, never used)
-        load_v(r.v, pool, pa, pb, page_bytes, lane_off_v);
-        load_k(r.k, pool, pa, pb, page_bytes, lane_off_k, lane);
+        load_v<kBigPool>(r.v, pool, pa, pb, page_bytes, lane_off_v);
+        load_k<kBigPool>(r.k, pool, pa, pb, page_bytes, lane_off_k, lane);
         int* tile_counter = reinterpret_cast<int*>(smem + L::kFlag + 4);
         if (kClaim && tid_p == 0) *tile_counter = kWaves;   // tiles 0 .. 7 are the waves' first ones
         // cos/sin table: wave w fills the rows of queries w, w + 8, ..., lane = rotation pair
@@ -604,12 +625,12 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
 #pragma unroll
             for (int rr = 0; rr < 8; ++rr) *reinterpret_cast<uint4*>(vwrite + 4 * rr * kVRowBytes) = r.v[rr];
             tile_pages(pt, nxt, n_tiles, sg_t0, last_page, pa, pb);
-            load_v(r.v, pool, pa, pb, page_bytes, lane_off_v);
+            load_v<kBigPool>(r.v, pool, pa, pb, page_bytes, lane_off_v);
             f32x16_t s;
             qk_block(s, r.k, qbase, 0);
             softmax_pv(st, s, 0, vbase);
             qk_block(s, r.k, qbase, 1);
-            load_k(r.k, pool, pa, pb, page_bytes, lane_off_k, lane);
+            load_k<kBigPool>(r.k, pool, pa, pb, page_bytes, lane_off_k, lane);
             softmax_pv(st, s, 1, vbase);
             cur = nxt;
         }
@@ -750,12 +771,14 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
 // host side
 // ---------------------------------------------------------------------------------------------
 
-// bf16, head_dim 128, at most 64 grouped heads per KV head, and a layer's pool below 4 GiB (the
-// kernel addresses pages with 32-bit byte offsets from the layer base).
+// bf16, head_dim 128, at most 64 grouped heads per KV head.
 bool mfma_eligible(const ms_cache* c, int n_q) {
-    return c->d.dtype == MS_BF16 && c->d.head_dim == kD && c->group <= kRows && n_q <= MS_MAX_QUERIES &&
-           (unsigned long long)c->layer_elems * 2ull < (1ull << 32);
+    return c->d.dtype == MS_BF16 && c->d.head_dim == kD && c->group <= kRows && n_q <= MS_MAX_QUERIES;
 }
+
+// Layer pools below 4 GiB are addressed with 32-bit byte offsets from the layer base (one register
+// per lane); larger ones take the build with 64-bit page bases.
+static bool big_pool(const ms_cache* c) { return (unsigned long long)c->layer_elems * 2ull >= (1ull << 32); }
 
 static int mfma_items(const ms_cache* c) {
     int target = c->n_cus / c->d.n_kv_heads;
@@ -877,12 +900,13 @@ static void build_plan(const ms_cache* c, const BatchMeta& bm, int B, int n_item
 int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        MS_HIP_TRY(hipFuncSetAttribute((const void*)pv_attn_mfma_stream<false, false>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Lds<false>::kBytes));
-        MS_HIP_TRY(hipFuncSetAttribute((const void*)pv_attn_mfma_stream<false, true>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Lds<false>::kBytes));
-        MS_HIP_TRY(hipFuncSetAttribute((const void*)pv_attn_mfma_stream<true, false>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Lds<true>::kBytes));
+        const void* decode_builds[] = {(const void*)pv_attn_mfma_stream<false, false, false>, (const void*)pv_attn_mfma_stream<false, true, false>,
+                                       (const void*)pv_attn_mfma_stream<false, false, true>, (const void*)pv_attn_mfma_stream<false, true, true>};
+        for (const void* f : decode_builds)
+            MS_HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Lds<false>::kBytes));
+        const void* wide_builds[] = {(const void*)pv_attn_mfma_stream<true, false, false>, (const void*)pv_attn_mfma_stream<true, false, true>};
+        for (const void* f : wide_builds)
+            MS_HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Lds<true>::kBytes));
         attr_set = true;
     }
     // plan: rebuilt only when the batch (ids, lengths) changed since the last call on this cache
@@ -934,17 +958,18 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
         if (a.n_q <= kDecodeQueries && a.n_q * a.group <= kRows) {
             a.q0 = 0;
             a.n_qc = a.n_q;
-            if (c->deterministic)
-                hipLaunchKernelGGL((pv_attn_mfma_stream<false, false>), grid, dim3(kThreads), Lds<false>::kBytes, stream, a);
-            else
-                hipLaunchKernelGGL((pv_attn_mfma_stream<false, true>), grid, dim3(kThreads), Lds<false>::kBytes, stream, a);
+            const bool big = big_pool(c);
+            auto kern = c->deterministic ? (big ? pv_attn_mfma_stream<false, false, true> : pv_attn_mfma_stream<false, false, false>)
+                                         : (big ? pv_attn_mfma_stream<false, true, true> : pv_attn_mfma_stream<false, true, false>);
+            hipLaunchKernelGGL(kern, grid, dim3(kThreads), Lds<false>::kBytes, stream, a);
         } else {
             // wide steps: one launch per chunk of queries; launches on one stream run in order, so
             // they can share the partial workspace and the arrival counters
             const int per_launch = kRows / a.group;
             for (a.q0 = 0; a.q0 < a.n_q; a.q0 += per_launch) {
                 a.n_qc = a.n_q - a.q0 < per_launch ? a.n_q - a.q0 : per_launch;
-                hipLaunchKernelGGL((pv_attn_mfma_stream<true, false>), grid, dim3(kThreads), Lds<true>::kBytes, stream, a);
+                auto kern = big_pool(c) ? pv_attn_mfma_stream<true, false, true> : pv_attn_mfma_stream<true, false, false>;
+                hipLaunchKernelGGL(kern, grid, dim3(kThreads), Lds<true>::kBytes, stream, a);
             }
         }
         MS_HIP_TRY(hipGetLastError());

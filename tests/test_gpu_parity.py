@@ -259,6 +259,38 @@ def test_gpu_foresight_rows_independent_and_page_permutation_invariant():
     assert np.array_equal(got3, base)
 
 
+def test_layer_pool_above_4_gib():
+    """A 4.6 GB layer pool (140 000 pages): byte offsets of pages no longer fit 32 bits, the
+    streaming kernel's build with 64-bit page bases runs.  The same logical content is placed once
+    in a small pool and once on pages spread over the large one (some beyond the 4 GiB mark); with
+    the fixed tile assignment both must give the same bits, and match the oracle."""
+    M, S = _mods()
+    sh = W.AttnShape("bigpool", "bf16", 3, 28, 4, 128, 5, 4, [3000, 70, 1500], 0.5, 1000000.0)
+    inp = W.attention_inputs(sh, 404)
+    ses, ora, ids = setup_pair(inp)
+    with ses:
+        M.ms_attention_set_deterministic(ses.cache, True)
+        pos = pids_for(inp, M)
+        base = run_gpu_attention(ses, inp, ids, pos)
+        check_out(base, oracle_attention(ora, inp, ids, pos), "bf16", "small pool")
+    n_big = 140000
+    assert n_big * 4 * 2 * 16 * 128 * 2 > 1 << 32
+    to_big = lambda p: n_big - 1 - 440 * p               # page 0 -> the last page, later ones further down
+    assert sh.n_pages * 440 < n_big and to_big(10) * 32768 > 1 << 32
+    big = S.Session(1, 28, 4, 128, n_big, M.MS_BF16, 1000000.0, max_seqs=4, max_pages_per_seq=256)
+    with big:
+        small_pool = S.to_device(inp.pool, M.MS_BF16)
+        big.pool[0, torch.tensor([to_big(p) for p in range(sh.n_pages)], device="cuda")] = small_pool[0]
+        del small_pool
+        gids = [M.ms_seq_import(big.cache, n, [to_big(p) for p in pt]) for n, pt in zip(sh.lengths, inp.page_tables)]
+        M.ms_attention_set_deterministic(big.cache, True)
+        got = run_gpu_attention(big, inp, gids, pos)
+        assert np.array_equal(got, base)
+        M.ms_attention_set_deterministic(big.cache, False)
+        check_out(run_gpu_attention(big, inp, gids, pos), base, "bf16", "large pool, default assignment")
+        M.ms_check_integrity(big.cache)
+
+
 def test_repeated_launches_agree_with_many_partials_per_pair():
     """Race check for the closing of (sequence, KV head) pairs: long sequences in a small batch are
     cut into many shares (up to ~25 partials per pair here), and whichever share finishes last folds
