@@ -313,7 +313,8 @@ def test_repeated_launches_agree_with_many_partials_per_pair():
         M.ms_attention_set_deterministic(ses.cache, False)
         for i in range(30):
             again = run_gpu_attention(ses, inp, ids, pos, 1)
-            assert np.abs(again - base).max() <= 2e-3, f"launch {i}: {np.abs(again - base).max():.3e}"
+            # a different summation order moves a result by a bf16 unit in the last place at most
+            assert (np.abs(again - base) <= 2.0 ** -7 * np.abs(base) + 2e-4).all(), f"launch {i}: {np.abs(again - base).max():.3e}"
             check_out(again, want, "bf16", f"default assignment, launch {i}")
 
 
