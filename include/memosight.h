@@ -237,6 +237,21 @@ int ms_swiglu(const void* gate_up, void* out, int n, int inter, void* stream);
  * 0), the lowest index among equal maxima; NaN never wins.  out device int32 [n]. */
 int ms_argmax_rows(const void* logits, int n, int vocab, long ld, int* out, void* stream);
 
+/* Dense projection of a step's rows: C[M][N] = A[M][K] . W[N][K]^T (+ bias[N]), bf16 operands and
+ * results, fp32 accumulation on the matrix cores.  A, W, bias, the destinations and the workspace
+ * are device pointers; out and out_col are host arrays.  The N columns may go to up to 4
+ * destinations: columns out_col[i] .. out_col[i + 1] are written to out[i], a row-major
+ * [M][out_col[i + 1] - out_col[i]] bf16 tensor (out_col[0] = 0, out_col[n_out] = N, boundaries
+ * multiples of 128) -- one fused Q/K/V projection fills three tensors.  N % 128 == 0,
+ * K % (32 * split_k) == 0; A and W 16-byte, bias and destinations 8-byte aligned.  split_k > 1
+ * divides K over that many workgroups per output tile (for few output tiles and a deep K, such as
+ * the MLP down projection) and needs ms_gemm_workspace_bytes(M, N, split_k) bytes of 16-byte
+ * aligned workspace; the partial sums are added in a fixed order. */
+size_t ms_gemm_workspace_bytes(int M, int N, int split_k);
+int ms_gemm_bf16(const void* a, const void* w, const void* bias, int M, int N, int K, int n_out,
+                 void* const* out, const int* out_col, int split_k, void* workspace, size_t ws_bytes,
+                 void* stream);
+
 /* ---- profiling ------------------------------------------------------------------------------- */
 
 /* From now on, every stride-th ms_predict_verify_attention call on this cache that runs the

@@ -75,6 +75,8 @@ _SIGS = {
     "ms_add_rmsnorm": (_I, [_P, _P, _P, _F, _P, _I, _I, _P]),
     "ms_swiglu": (_I, [_P, _P, _I, _I, _P]),
     "ms_argmax_rows": (_I, [_P, _I, _I, C.c_long, _P, _P]),
+    "ms_gemm_workspace_bytes": (_SZ, [_I, _I, _I]),
+    "ms_gemm_bf16": (_I, [_P, _P, _P, _I, _I, _I, _I, C.POINTER(_P), _IP, _I, _P, _SZ, _P]),
     "ms_profile_attention": (_I, [_P, _I, _I]),
     "ms_profile_read": (_I, [_P, C.POINTER(C.c_float), _I, _IP]),
     "ms_ama_count": (_I, [_I, _I]),
@@ -272,6 +274,25 @@ def ms_argmax_rows(logits, vocab: int, out, stream=None) -> None:
     n, ld = logits.shape
     _check(lib.ms_argmax_rows(_sized(None, logits, "logits", n * ld, 2), n, vocab, ld,
                               _sized(None, out, "out", n, 4), _stream(stream)))
+
+
+def ms_gemm_workspace_bytes(M: int, N: int, split_k: int) -> int:
+    return lib.ms_gemm_workspace_bytes(M, N, split_k)
+
+
+def ms_gemm_bf16(a, w, bias, outs, split_k: int = 1, workspace=None, stream=None) -> None:
+    """outs: list of [M, n_i] bf16 tensors that take consecutive column ranges of the product."""
+    M_, K = a.shape
+    N = w.shape[0]
+    cols = [0]
+    for o in outs:
+        cols.append(cols[-1] + o.shape[1])
+    ptrs = (_P * len(outs))(*[_sized(None, o, "out", M_ * o.shape[1], 2) for o in outs])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    if w.shape[1] != K or cols[-1] != N:
+        raise MsError(MS_ERR_INVALID, "ms_gemm_bf16: shapes do not match")
+    _check(lib.ms_gemm_bf16(_sized(None, a, "a", M_ * K, 2), _sized(None, w, "w", N * K, 2), _sized(None, bias, "bias", N, 2),
+                            M_, N, K, len(outs), ptrs, _ints(cols), split_k, _dev(workspace), ws_bytes, _stream(stream)))
 
 
 def ms_attention_set_deterministic(cache, on: bool) -> None:
