@@ -69,36 +69,43 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
     const int k_begin = blockIdx.z * g.k_per_split;
     const int steps = g.k_per_split / kGemmBK;
 
-    // global -> LDS staging: thread t brings 64 bytes of activation row m0 + t and 32 bytes of
-    // weight row n0 + t / 2 per step.  Rows past M are clamped (read again, never stored).
-    const int a_row = m0 + tid < g.M ? m0 + tid : g.M - 1;
-    const uint16_t* a_src = g.a + (size_t)a_row * g.K + k_begin;
-    const uint16_t* w_src = g.w + (size_t)(n0 + (tid >> 1)) * g.K + k_begin + 16 * (tid & 1);
-    char* a_dst = smem + tid * kGemmRowBytes;
-    char* w_dst = smem + kGemmBM * kGemmRowBytes + (tid >> 1) * kGemmRowBytes + 32 * (tid & 1);
+    // global -> LDS staging.  Four consecutive threads bring the 64 bytes one row contributes to a
+    // step, so a load instruction of a wave covers 16 rows x 64 contiguous bytes; thread t handles
+    // chunk t % 4 of activation rows t / 4 + 64 i (i < 4) and of weight rows t / 4 + 64 i (i < 2).
+    // Rows past M are clamped (read again, never stored).
+    const int sr = tid >> 2, sc = tid & 3;
+    const uint16_t* a_src[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = m0 + sr + 64 * i < g.M ? m0 + sr + 64 * i : g.M - 1;
+        a_src[i] = g.a + (size_t)row * g.K + k_begin + 8 * sc;
+    }
+    const uint16_t* w_src = g.w + (size_t)(n0 + sr) * g.K + k_begin + 8 * sc;
+    const size_t w_row64 = (size_t)64 * g.K;
+    char* a_dst = smem + sr * kGemmRowBytes + 16 * sc;
+    char* w_dst = smem + kGemmBM * kGemmRowBytes + sr * kGemmRowBytes + 16 * sc;
 
     uint4 ra0, ra1, ra2, ra3, rw0, rw1;   // (named registers: an array taken by reference ends up in memory)
 #define MS_GEMM_FETCH(step_)                                                    \
     do {                                                                        \
-        const uint16_t* ap_ = a_src + (step_) * kGemmBK;                        \
-        const uint16_t* wp_ = w_src + (step_) * kGemmBK;                        \
-        ra0 = *reinterpret_cast<const uint4*>(ap_);                             \
-        ra1 = *reinterpret_cast<const uint4*>(ap_ + 8);                         \
-        ra2 = *reinterpret_cast<const uint4*>(ap_ + 16);                        \
-        ra3 = *reinterpret_cast<const uint4*>(ap_ + 24);                        \
-        rw0 = *reinterpret_cast<const uint4*>(wp_);                             \
-        rw1 = *reinterpret_cast<const uint4*>(wp_ + 8);                         \
+        const int ko_ = (step_) * kGemmBK;                                      \
+        ra0 = *reinterpret_cast<const uint4*>(a_src[0] + ko_);                  \
+        ra1 = *reinterpret_cast<const uint4*>(a_src[1] + ko_);                  \
+        ra2 = *reinterpret_cast<const uint4*>(a_src[2] + ko_);                  \
+        ra3 = *reinterpret_cast<const uint4*>(a_src[3] + ko_);                  \
+        rw0 = *reinterpret_cast<const uint4*>(w_src + ko_);                     \
+        rw1 = *reinterpret_cast<const uint4*>(w_src + w_row64 + ko_);           \
     } while (0)
 #define MS_GEMM_STASH(buf_)                                                     \
     do {                                                                        \
         char* ad_ = a_dst + (buf_) * kGemmStageBytes;                           \
         char* wd_ = w_dst + (buf_) * kGemmStageBytes;                           \
         *reinterpret_cast<uint4*>(ad_) = ra0;                                   \
-        *reinterpret_cast<uint4*>(ad_ + 16) = ra1;                              \
-        *reinterpret_cast<uint4*>(ad_ + 32) = ra2;                              \
-        *reinterpret_cast<uint4*>(ad_ + 48) = ra3;                              \
+        *reinterpret_cast<uint4*>(ad_ + 64 * kGemmRowBytes) = ra1;              \
+        *reinterpret_cast<uint4*>(ad_ + 128 * kGemmRowBytes) = ra2;             \
+        *reinterpret_cast<uint4*>(ad_ + 192 * kGemmRowBytes) = ra3;             \
         *reinterpret_cast<uint4*>(wd_) = rw0;                                   \
-        *reinterpret_cast<uint4*>(wd_ + 16) = rw1;                              \
+        *reinterpret_cast<uint4*>(wd_ + 64 * kGemmRowBytes) = rw1;              \
     } while (0)
 
     g_f32x16_t acc[2][4];
