@@ -6,8 +6,8 @@
 // widths, both operands are K-contiguous.  One workgroup of 4 waves computes a 256 (M) x 128 (N)
 // tile over a K range; grid = (N / 128, ceil(M / 256), split_k).  K is walked in steps of 32:
 // both tiles go global -> registers -> LDS (row stride 80 bytes: conflict-free for the 16-byte
-// operand reads), the next step's global loads are in flight while the current one is multiplied,
-// one barrier per step.  A wave owns 128 (M) x 64 (N): 4 x 2 accumulator tiles of
+// operand reads); the global loads run three steps ahead of the multiplication, one LDS-only
+// barrier per step.  A wave owns 128 (M) x 64 (N): 4 x 2 accumulator tiles of
 // v_mfma_f32_32x32x16_bf16 with W as the A operand (rows = n) and the activations as the B operand
 // (columns = m), so a lane ends up with four consecutive n of one row m per register quad.
 // split_k > 1 (deep K, few output tiles: the MLP down projection) writes fp32 partials that a
@@ -59,6 +59,14 @@ __device__ __forceinline__ uint32_t g_pack_bf16x2(float a, float b) {
     return (uint32_t)float_to_bf16_bits(a) | ((uint32_t)float_to_bf16_bits(b) << 16);
 }
 
+// Workgroup barrier that orders LDS traffic only (a plain __syncthreads() would also wait for the
+// global loads of the steps ahead).
+__device__ __forceinline__ void gemm_lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 template <bool kSplit>
 __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
     __shared__ __attribute__((aligned(16))) char smem[2 * kGemmStageBytes];
@@ -85,27 +93,33 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
     char* a_dst = smem + sr * kGemmRowBytes + 16 * sc;
     char* w_dst = smem + kGemmBM * kGemmRowBytes + sr * kGemmRowBytes + 16 * sc;
 
-    uint4 ra0, ra1, ra2, ra3, rw0, rw1;   // (named registers: an array taken by reference ends up in memory)
-#define MS_GEMM_FETCH(step_)                                                    \
+    // Three register sets of staged tiles: while step s is multiplied out of LDS, the tiles of
+    // steps s + 1 and s + 2 are in registers or on their way and those of s + 3 are requested.  Only
+    // LDS traffic is ordered by the barriers, so a step waits for the oldest loads alone.
+    // (plain named registers: aggregates handed around by name ended up in scratch memory)
+    uint4 r0a0, r0a1, r0a2, r0a3, r0w0, r0w1;
+    uint4 r1a0, r1a1, r1a2, r1a3, r1w0, r1w1;
+    uint4 r2a0, r2a1, r2a2, r2a3, r2w0, r2w1;
+#define MS_GEMM_FETCH(R, step_)                                                 \
     do {                                                                        \
         const int ko_ = (step_) * kGemmBK;                                      \
-        ra0 = *reinterpret_cast<const uint4*>(a_src[0] + ko_);                  \
-        ra1 = *reinterpret_cast<const uint4*>(a_src[1] + ko_);                  \
-        ra2 = *reinterpret_cast<const uint4*>(a_src[2] + ko_);                  \
-        ra3 = *reinterpret_cast<const uint4*>(a_src[3] + ko_);                  \
-        rw0 = *reinterpret_cast<const uint4*>(w_src + ko_);                     \
-        rw1 = *reinterpret_cast<const uint4*>(w_src + w_row64 + ko_);           \
+        R##a0 = *reinterpret_cast<const uint4*>(a_src[0] + ko_);                 \
+        R##a1 = *reinterpret_cast<const uint4*>(a_src[1] + ko_);                 \
+        R##a2 = *reinterpret_cast<const uint4*>(a_src[2] + ko_);                 \
+        R##a3 = *reinterpret_cast<const uint4*>(a_src[3] + ko_);                 \
+        R##w0 = *reinterpret_cast<const uint4*>(w_src + ko_);                    \
+        R##w1 = *reinterpret_cast<const uint4*>(w_src + w_row64 + ko_);          \
     } while (0)
-#define MS_GEMM_STASH(buf_)                                                     \
+#define MS_GEMM_STASH(R, buf_)                                                  \
     do {                                                                        \
         char* ad_ = a_dst + (buf_) * kGemmStageBytes;                           \
         char* wd_ = w_dst + (buf_) * kGemmStageBytes;                           \
-        *reinterpret_cast<uint4*>(ad_) = ra0;                                   \
-        *reinterpret_cast<uint4*>(ad_ + 64 * kGemmRowBytes) = ra1;              \
-        *reinterpret_cast<uint4*>(ad_ + 128 * kGemmRowBytes) = ra2;             \
-        *reinterpret_cast<uint4*>(ad_ + 192 * kGemmRowBytes) = ra3;             \
-        *reinterpret_cast<uint4*>(wd_) = rw0;                                   \
-        *reinterpret_cast<uint4*>(wd_ + 64 * kGemmRowBytes) = rw1;              \
+        *reinterpret_cast<uint4*>(ad_) = R##a0;                                  \
+        *reinterpret_cast<uint4*>(ad_ + 64 * kGemmRowBytes) = R##a1;             \
+        *reinterpret_cast<uint4*>(ad_ + 128 * kGemmRowBytes) = R##a2;            \
+        *reinterpret_cast<uint4*>(ad_ + 192 * kGemmRowBytes) = R##a3;            \
+        *reinterpret_cast<uint4*>(wd_) = R##w0;                                  \
+        *reinterpret_cast<uint4*>(wd_ + 64 * kGemmRowBytes) = R##w1;             \
     } while (0)
 
     g_f32x16_t acc[2][4];
@@ -120,33 +134,44 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
     const int a_op = (128 * wm + l32) * kGemmRowBytes + 16 * hf;
     const int w_op = kGemmBM * kGemmRowBytes + (64 * wn + l32) * kGemmRowBytes + 16 * hf;
 
-    MS_GEMM_FETCH(0);
-    MS_GEMM_STASH(0);
-    __syncthreads();
-    for (int step = 0; step < steps; ++step) {
-        const int cur = step & 1;
-        const bool more = step + 1 < steps;
-        if (more) MS_GEMM_FETCH(step + 1);
-        const char* base = smem + cur * kGemmStageBytes;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            g_bf16x8_t wf[2], af[4];
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-                wf[ni] = __builtin_bit_cast(g_bf16x8_t, *reinterpret_cast<const uint4*>(base + w_op + ni * 32 * kGemmRowBytes + 32 * kk));
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-                af[mi] = __builtin_bit_cast(g_bf16x8_t, *reinterpret_cast<const uint4*>(base + a_op + mi * 32 * kGemmRowBytes + 32 * kk));
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-                for (int mi = 0; mi < 4; ++mi)
-                    acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], af[mi], acc[ni][mi], 0, 0, 0);
-        }
-        if (more) MS_GEMM_STASH(cur ^ 1);   // that stage was last read before the previous barrier
-        __syncthreads();
+    // steps past the end re-read the last one (clamped): loads stay unconditional, nothing is used
+    const int last = steps - 1;
+#define MS_GEMM_CLAMP(s_) ((s_) < last ? (s_) : last)
+    MS_GEMM_FETCH(r0, 0);
+    MS_GEMM_FETCH(r1, MS_GEMM_CLAMP(1));
+    MS_GEMM_FETCH(r2, MS_GEMM_CLAMP(2));
+    MS_GEMM_STASH(r0, 0);
+    gemm_lds_barrier();
+    // one pipeline turn: multiply step s out of LDS[s & 1], request step s + 3 into the set that
+    // step s came from (FREE), move step s + 1 (NEXT) into the other LDS stage
+#define MS_GEMM_TURN(step_, FREE, NEXT)                                                                                     \
+    do {                                                                                                                    \
+        MS_GEMM_FETCH(FREE, MS_GEMM_CLAMP((step_) + 3));                                                                    \
+        const char* base_ = smem + ((step_) & 1) * kGemmStageBytes;                                                         \
+        _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                                                  \
+            g_bf16x8_t wf[2], af[4];                                                                                        \
+            _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) wf[ni] = __builtin_bit_cast(                                   \
+                g_bf16x8_t, *reinterpret_cast<const uint4*>(base_ + w_op + ni * 32 * kGemmRowBytes + 32 * kk));             \
+            _Pragma("unroll") for (int mi = 0; mi < 4; ++mi) af[mi] = __builtin_bit_cast(                                   \
+                g_bf16x8_t, *reinterpret_cast<const uint4*>(base_ + a_op + mi * 32 * kGemmRowBytes + 32 * kk));             \
+            _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)               \
+                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], af[mi], acc[ni][mi], 0, 0, 0);                \
+        }                                                                                                                   \
+        MS_GEMM_STASH(NEXT, ((step_) + 1) & 1); /* that stage was last read before the previous barrier */                  \
+        gemm_lds_barrier();                                                                                                 \
+    } while (0)
+    int step = 0;
+    for (; step + 3 <= steps; step += 3) {
+        MS_GEMM_TURN(step, r0, r1);
+        MS_GEMM_TURN(step + 1, r1, r2);
+        MS_GEMM_TURN(step + 2, r2, r0);
     }
-
+    if (step < steps) {
+        MS_GEMM_TURN(step, r0, r1);
+        if (step + 1 < steps) MS_GEMM_TURN(step + 1, r1, r2);
+    }
+#undef MS_GEMM_TURN
+#undef MS_GEMM_CLAMP
 #undef MS_GEMM_FETCH
 #undef MS_GEMM_STASH
 
