@@ -345,7 +345,8 @@ def decode_step_bench(args):
     per_launch_bytes = int(np.sum(2 * cur_len * Hkv * Dh * 2 + 4 * (-(-cur_len // 16)))) + B * nq * (2 * Hq + 2 * Hkv) * Dh * 2
     kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else float("nan")
     achieved = per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9
-    n_params = sum(t.numel() for lw in weights.layers for t in vars(lw).values()) + weights.lm_head.numel() + weights.norm.numel()
+    n_params = (sum(t.numel() for lw in weights.layers for name, t in vars(lw).items() if name not in ("wqkv", "bqkv")) +
+                weights.lm_head.numel() + weights.norm.numel())
     result = {
         "metric": "full_decode_step_tokens_per_s_b64_kv8k",
         "value": round(state["committed"] / (t1 - t0), 1),
@@ -355,7 +356,8 @@ def decode_step_bench(args):
         "config": {
             "workload": f"decode_step_qwen2.5-7b_shapes_batch{B}_kv{L0}_layers{NL}_verify{nv}_foresight{nf}",
             "batch": B, "mean_kv_len": round(float(cur_len.mean()), 1), "layers": NL,
-            "step": "embedding, 28 blocks (hand-written norm / attention / SwiGLU kernels, torch GEMMs), LM head, greedy "
+            "step": "embedding, 28 blocks (hand-written norm / attention / SwiGLU kernels, hand-written GEMM for the fused "
+                    "Q/K/V and the down projection, torch GEMMs for the output, gate/up and LM-head projections), greedy "
                     "tokens, accept, commit; random weights, so about one token per sequence is accepted per step",
         },
         "query_tokens_per_s": round(B * nq * args.steps / (t1 - t0), 1),

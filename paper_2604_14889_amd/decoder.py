@@ -1,9 +1,11 @@
 """One full decode step (Algorithm 1, SpeculativeStep, of the MemoSight paper) on the GPU.
 
 The attention, the residual/RMSNorm, SwiGLU and greedy-token kernels, acceptance and the cache
-update are this library's HIP kernels.  The dense projections (Q/K/V, output, MLP, LM head) are
-plain bf16 GEMMs and are run through torch (hipBLASLt underneath): they are library GEMMs, not
-part of the hand-written path, and stand in until hand-written MFMA GEMMs replace them.
+update are this library's HIP kernels.  Of the dense projections, the fused Q/K/V projection and
+the MLP down projection run on this library's MFMA GEMM (ms_gemm_bf16: one launch fills the three
+Q/K/V tensors; the down projection's deep K is split over workgroups), where it is faster than the
+library GEMM at a few hundred rows; the output, gate/up and LM-head projections go through torch
+(hipBLASLt underneath), which is still ahead on those shapes.
 
 Nothing here computes on the CPU; every call fails if the HIP library is missing.
 """
@@ -41,6 +43,9 @@ class LayerTensors:
     def __init__(self, ln1, wq, bq, wk, bk, wv, bv, wo, ln2, w_gate_up, w_down):
         self.ln1, self.wq, self.bq, self.wk, self.bk, self.wv, self.bv = ln1, wq, bq, wk, bk, wv, bv
         self.wo, self.ln2, self.w_gate_up, self.w_down = wo, ln2, w_gate_up, w_down
+        # one weight for the fused Q/K/V projection (rows: Q heads, then K heads, then V heads)
+        self.wqkv = torch.cat([wq, wk, wv], dim=0).contiguous()
+        self.bqkv = torch.cat([bq, bk, bv], dim=0).contiguous()
 
 
 class DecoderTensors:
@@ -74,7 +79,11 @@ class DecoderTensors:
 class Decoder:
     """Buffers and the step driver for up to max_rows = B * n_q tokens per step."""
 
-    def __init__(self, cfg: DecoderConfig, weights: DecoderTensors, session: Session, max_rows: int):
+    def __init__(self, cfg: DecoderConfig, weights: DecoderTensors, session: Session, max_rows: int,
+                 hand_gemm: bool = True):
+        """hand_gemm: run the Q/K/V and down projections on this library's GEMM (needs widths that
+        are multiples of 128 and depths that are multiples of 128); otherwise everything dense goes
+        through torch."""
         self.cfg, self.w, self.ses = cfg, weights, session
         dev = weights.embed.device
         qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
@@ -94,6 +103,14 @@ class Decoder:
         self.logits = buf(max_rows, cfg.vocab)
         self.targets = buf(max_rows, dtype=torch.int32)
         self.attn_events = None   # optional list of (start, stop) events around every attention call
+        self.qkv_split, self.down_split = 2, 4
+        self.hand_gemm = (hand_gemm and qd % 128 == 0 and kd % 128 == 0 and cfg.hidden % 128 == 0 and
+                          cfg.hidden % (32 * self.qkv_split) == 0 and cfg.inter % (32 * self.down_split) == 0)
+        self.gemm_ws = None
+        if self.hand_gemm:
+            need = max(M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, self.qkv_split),
+                       M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, self.down_split))
+            self.gemm_ws = torch.empty(need, dtype=torch.uint8, device=dev)
 
     def step(self, seq_ids: Sequence[int], tokens: torch.Tensor, pos: torch.Tensor, n_verify: int, n_foresight: int,
              ctx_new: Optional[torch.Tensor] = None):
@@ -119,9 +136,12 @@ class Decoder:
         for li, lw in enumerate(w.layers):
             M.ms_add_rmsnorm(h, delta, lw.ln1, cfg.eps, x)
             k, v = self.k_new[li], self.v_new[li]
-            torch.addmm(lw.bq, x, lw.wq.t(), out=q)
-            torch.addmm(lw.bk, x, lw.wk.t(), out=k)
-            torch.addmm(lw.bv, x, lw.wv.t(), out=v)
+            if self.hand_gemm:
+                M.ms_gemm_bf16(x, lw.wqkv, lw.bqkv, [q, k, v], self.qkv_split, self.gemm_ws)
+            else:
+                torch.addmm(lw.bq, x, lw.wq.t(), out=q)
+                torch.addmm(lw.bk, x, lw.wk.t(), out=k)
+                torch.addmm(lw.bv, x, lw.wv.t(), out=v)
             if self.attn_events is not None:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
@@ -134,7 +154,10 @@ class Decoder:
             M.ms_add_rmsnorm(h, proj, lw.ln2, cfg.eps, x)
             torch.mm(x, lw.w_gate_up.t(), out=gate_up)
             M.ms_swiglu(gate_up, act)
-            torch.mm(act, lw.w_down.t(), out=proj)
+            if self.hand_gemm:
+                M.ms_gemm_bf16(act, lw.w_down, None, [proj], self.down_split, self.gemm_ws)
+            else:
+                torch.mm(act, lw.w_down.t(), out=proj)
             delta = proj
         M.ms_add_rmsnorm(h, delta, w.norm, cfg.eps, x)
         logits = self.logits[:rows]
