@@ -4,7 +4,7 @@
 //
 // Shape of the problem: M is small (batch x queries, a few hundred rows), N and K are the model's
 // widths, both operands are K-contiguous.  One workgroup of 4 waves computes a 256 (M) x 128 (N)
-// tile over a K range; grid = (N / 128, ceil(M / 256), split_k).  K is walked in steps of 32:
+// tile over a K range; grid = (column tiles x row tiles, 1, split_k).  K is walked in steps of 32:
 // both tiles go global -> registers -> LDS (row stride 80 bytes: conflict-free for the 16-byte
 // operand reads); the global loads run three steps ahead of the multiplication, one LDS-only
 // barrier per step.  A wave owns 128 (M) x 64 (N): 4 x 2 accumulator tiles of
@@ -73,7 +73,14 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = w >> 1, wn = w & 1;                  // wave tile: rows 128 wm .. + 128, columns 64 wn .. + 64
-    const int n0 = blockIdx.x * kGemmBN, m0 = blockIdx.y * kGemmBM;
+    // Tile mapping.  Workgroups are handed to the 8 XCDs (each with its own L2) round robin, so
+    // workgroups 8 apart share an L2: the row tiles of one column tile are placed 8 apart, and the
+    // weight tile they share comes from HBM once.
+    const int m_tiles = (g.M + kGemmBM - 1) / kGemmBM, n_tiles = g.N / kGemmBN;
+    const int in_group = blockIdx.x % (8 * m_tiles);
+    const int n_tile = blockIdx.x / (8 * m_tiles) * 8 + in_group % 8, m_tile = in_group / 8;
+    if (n_tile >= n_tiles) return;   // padding of the last group (the whole workgroup leaves)
+    const int n0 = n_tile * kGemmBN, m0 = m_tile * kGemmBM;
     const int k_begin = blockIdx.z * g.k_per_split;
     const int steps = g.k_per_split / kGemmBK;
 
@@ -251,7 +258,8 @@ extern "C" int ms_gemm_bf16(const void* a, const void* w, const void* bias, int 
     if (M == 0) return MS_OK;
     if (N % kGemmBN || K % (kGemmBK * split_k))
         MS_FAIL(MS_ERR_UNSUPPORTED, "ms_gemm_bf16: N must be a multiple of %d and K of %d x split_k", kGemmBN, kGemmBK);
-    if ((long long)M * N >= (1ll << 40) || N / kGemmBN > 65535 * 32 || split_k > 64 || (M + kGemmBM - 1) / kGemmBM > 65535)
+    if ((long long)M * N >= (1ll << 40) || split_k > 64 ||
+        (long long)((N / kGemmBN + 7) / 8) * 8 * ((M + kGemmBM - 1) / kGemmBM) > 2000000000ll)
         MS_FAIL(MS_ERR_UNSUPPORTED, "ms_gemm_bf16: shape too large");
     if (!a || !w || !g_aligned16(a) || !g_aligned16(w) || (bias && (reinterpret_cast<uintptr_t>(bias) & 7u)))
         MS_FAIL(MS_ERR_INVALID, "ms_gemm_bf16: null or misaligned operand");
@@ -278,7 +286,8 @@ extern "C" int ms_gemm_bf16(const void* a, const void* w, const void* bias, int 
         g.out_col[i + 1] = N;
     }
     g.partial = nullptr;
-    const dim3 grid(N / kGemmBN, (M + kGemmBM - 1) / kGemmBM, split_k);
+    const int m_tiles = (M + kGemmBM - 1) / kGemmBM, n_groups = (N / kGemmBN + 7) / 8;
+    const dim3 grid((unsigned)(n_groups * 8 * m_tiles), 1, split_k);
     if (split_k == 1) {
         hipLaunchKernelGGL(gemm_tn_bf16<false>, grid, dim3(kGemmThreads), 0, (hipStream_t)stream, g);
     } else {
