@@ -3,11 +3,11 @@
 // runs the model's projections over the few hundred tokens of a step; Section 4.1 names the models).
 //
 // Shape of the problem: M is small (batch x queries, a few hundred rows), N and K are the model's
-// widths, both operands are K-contiguous.  One workgroup of 4 waves computes a 256 (M) x 128 (N)
+// widths, both operands are K-contiguous.  One workgroup of 8 waves computes a 256 (M) x 128 (N)
 // tile over a K range; grid = (column tiles x row tiles, 1, split_k).  K is walked in steps of 32:
 // both tiles go global -> registers -> LDS (row stride 80 bytes: conflict-free for the 16-byte
 // operand reads); the global loads run three steps ahead of the multiplication, one LDS-only
-// barrier per step.  A wave owns 128 (M) x 64 (N): 4 x 2 accumulator tiles of
+// barrier per step.  A wave owns 64 (M) x 64 (N): 2 x 2 accumulator tiles of
 // v_mfma_f32_32x32x16_bf16 with W as the A operand (rows = n) and the activations as the B operand
 // (columns = m), so a lane ends up with four consecutive n of one row m per register quad.
 // split_k > 1 (deep K, few output tiles: the MLP down projection) writes fp32 partials that a
@@ -23,7 +23,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 g_bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float g_f32x16_t;
 
 constexpr int kGemmBM = 256, kGemmBN = 128, kGemmBK = 32;
-constexpr int kGemmThreads = 256;
+constexpr int kGemmThreads = 512;
 constexpr int kGemmRowBytes = kGemmBK * 2 + 16;                      // 80
 constexpr int kGemmStageBytes = (kGemmBM + kGemmBN) * kGemmRowBytes;  // 30720
 constexpr int kGemmMaxOut = 4;
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
     __shared__ __attribute__((aligned(16))) char smem[2 * kGemmStageBytes];
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = w >> 1, wn = w & 1;                  // wave tile: rows 128 wm .. + 128, columns 64 wn .. + 64
+    const int wm = w >> 1, wn = w & 1;                  // wave tile: rows 64 wm .. + 64, columns 64 wn .. + 64
     // Tile mapping.  Workgroups are handed to the 8 XCDs (each with its own L2) round robin, so
     // workgroups 8 apart share an L2: the row tiles of one column tile are placed 8 apart, and the
     // weight tile they share comes from HBM once.
@@ -86,17 +86,16 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
 
     // global -> LDS staging.  Four consecutive threads bring the 64 bytes one row contributes to a
     // step, so a load instruction of a wave covers 16 rows x 64 contiguous bytes; thread t handles
-    // chunk t % 4 of activation rows t / 4 + 64 i (i < 4) and of weight rows t / 4 + 64 i (i < 2).
+    // chunk t % 4 of activation rows t / 4 and t / 4 + 128 and of weight row t / 4.
     // Rows past M are clamped (read again, never stored).
     const int sr = tid >> 2, sc = tid & 3;
-    const uint16_t* a_src[4];
+    const uint16_t* a_src[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = m0 + sr + 64 * i < g.M ? m0 + sr + 64 * i : g.M - 1;
+    for (int i = 0; i < 2; ++i) {
+        const int row = m0 + sr + 128 * i < g.M ? m0 + sr + 128 * i : g.M - 1;
         a_src[i] = g.a + (size_t)row * g.K + k_begin + 8 * sc;
     }
     const uint16_t* w_src = g.w + (size_t)(n0 + sr) * g.K + k_begin + 8 * sc;
-    const size_t w_row64 = (size_t)64 * g.K;
     char* a_dst = smem + sr * kGemmRowBytes + 16 * sc;
     char* w_dst = smem + kGemmBM * kGemmRowBytes + sr * kGemmRowBytes + 16 * sc;
 
@@ -104,41 +103,35 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
     // steps s + 1 and s + 2 are in registers or on their way and those of s + 3 are requested.  Only
     // LDS traffic is ordered by the barriers, so a step waits for the oldest loads alone.
     // (plain named registers: aggregates handed around by name ended up in scratch memory)
-    uint4 r0a0, r0a1, r0a2, r0a3, r0w0, r0w1;
-    uint4 r1a0, r1a1, r1a2, r1a3, r1w0, r1w1;
-    uint4 r2a0, r2a1, r2a2, r2a3, r2w0, r2w1;
+    uint4 r0a0, r0a1, r0w0;
+    uint4 r1a0, r1a1, r1w0;
+    uint4 r2a0, r2a1, r2w0;
 #define MS_GEMM_FETCH(R, step_)                                                 \
     do {                                                                        \
         const int ko_ = (step_) * kGemmBK;                                      \
-        R##a0 = *reinterpret_cast<const uint4*>(a_src[0] + ko_);                 \
-        R##a1 = *reinterpret_cast<const uint4*>(a_src[1] + ko_);                 \
-        R##a2 = *reinterpret_cast<const uint4*>(a_src[2] + ko_);                 \
-        R##a3 = *reinterpret_cast<const uint4*>(a_src[3] + ko_);                 \
-        R##w0 = *reinterpret_cast<const uint4*>(w_src + ko_);                    \
-        R##w1 = *reinterpret_cast<const uint4*>(w_src + w_row64 + ko_);          \
+        R##a0 = *reinterpret_cast<const uint4*>(a_src[0] + ko_);                \
+        R##a1 = *reinterpret_cast<const uint4*>(a_src[1] + ko_);                \
+        R##w0 = *reinterpret_cast<const uint4*>(w_src + ko_);                   \
     } while (0)
 #define MS_GEMM_STASH(R, buf_)                                                  \
     do {                                                                        \
         char* ad_ = a_dst + (buf_) * kGemmStageBytes;                           \
         char* wd_ = w_dst + (buf_) * kGemmStageBytes;                           \
-        *reinterpret_cast<uint4*>(ad_) = R##a0;                                  \
-        *reinterpret_cast<uint4*>(ad_ + 64 * kGemmRowBytes) = R##a1;             \
-        *reinterpret_cast<uint4*>(ad_ + 128 * kGemmRowBytes) = R##a2;            \
-        *reinterpret_cast<uint4*>(ad_ + 192 * kGemmRowBytes) = R##a3;            \
-        *reinterpret_cast<uint4*>(wd_) = R##w0;                                  \
-        *reinterpret_cast<uint4*>(wd_ + 64 * kGemmRowBytes) = R##w1;             \
+        *reinterpret_cast<uint4*>(ad_) = R##a0;                                 \
+        *reinterpret_cast<uint4*>(ad_ + 128 * kGemmRowBytes) = R##a1;           \
+        *reinterpret_cast<uint4*>(wd_) = R##w0;                                 \
     } while (0)
 
-    g_f32x16_t acc[2][4];
+    g_f32x16_t acc[2][2];
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
+        for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[ni][mi][i] = 0.f;
 
     // operand addresses inside a stage: 16 bytes at k = 16 kk + 8 (lane / 32) of row (lane % 32)
-    const int a_op = (128 * wm + l32) * kGemmRowBytes + 16 * hf;
+    const int a_op = (64 * wm + l32) * kGemmRowBytes + 16 * hf;
     const int w_op = kGemmBM * kGemmRowBytes + (64 * wn + l32) * kGemmRowBytes + 16 * hf;
 
     // steps past the end re-read the last one (clamped): loads stay unconditional, nothing is used
@@ -156,12 +149,12 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
         MS_GEMM_FETCH(FREE, MS_GEMM_CLAMP((step_) + 3));                                                                    \
         const char* base_ = smem + ((step_) & 1) * kGemmStageBytes;                                                         \
         _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                                                  \
-            g_bf16x8_t wf[2], af[4];                                                                                        \
+            g_bf16x8_t wf[2], af[2];                                                                                        \
             _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) wf[ni] = __builtin_bit_cast(                                   \
                 g_bf16x8_t, *reinterpret_cast<const uint4*>(base_ + w_op + ni * 32 * kGemmRowBytes + 32 * kk));             \
-            _Pragma("unroll") for (int mi = 0; mi < 4; ++mi) af[mi] = __builtin_bit_cast(                                   \
+            _Pragma("unroll") for (int mi = 0; mi < 2; ++mi) af[mi] = __builtin_bit_cast(                                   \
                 g_bf16x8_t, *reinterpret_cast<const uint4*>(base_ + a_op + mi * 32 * kGemmRowBytes + 32 * kk));             \
-            _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)               \
+            _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) _Pragma("unroll") for (int mi = 0; mi < 2; ++mi)               \
                 acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], af[mi], acc[ni][mi], 0, 0, 0);                \
         }                                                                                                                   \
         MS_GEMM_STASH(NEXT, ((step_) + 1) & 1); /* that stage was last read before the previous barrier */                  \
@@ -187,8 +180,8 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
     int col0 = 0, ld = 0;
     if (!kSplit) pick_destination(g, n0, dst, col0, ld);
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-        const int m = m0 + 128 * wm + 32 * mi + l32;
+    for (int mi = 0; mi < 2; ++mi) {
+        const int m = m0 + 64 * wm + 32 * mi + l32;
         if (m >= g.M) continue;
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
