@@ -238,19 +238,33 @@ int ms_swiglu(const void* gate_up, void* out, int n, int inter, void* stream);
 int ms_argmax_rows(const void* logits, int n, int vocab, long ld, int* out, void* stream);
 
 /* Dense projection of a step's rows: C[M][N] = A[M][K] . W[N][K]^T (+ bias[N]), bf16 operands and
- * results, fp32 accumulation on the matrix cores.  A, W, bias, the destinations and the workspace
+ * results, fp32 accumulation on the matrix cores (the model's projections inside Algorithm 1's
+ * SpeculativeStep; Section 4.1 names the models).  A, W, bias, the destinations and the workspace
  * are device pointers; out and out_col are host arrays.  The N columns may go to up to 4
  * destinations: columns out_col[i] .. out_col[i + 1] are written to out[i], a row-major
  * [M][out_col[i + 1] - out_col[i]] bf16 tensor (out_col[0] = 0, out_col[n_out] = N, boundaries
  * multiples of 128) -- one fused Q/K/V projection fills three tensors.  N % 128 == 0,
- * K % (32 * split_k) == 0; A and W 16-byte, bias and destinations 8-byte aligned.  split_k > 1
- * divides K over that many workgroups per output tile (for few output tiles and a deep K, such as
- * the MLP down projection) and needs ms_gemm_workspace_bytes(M, N, split_k) bytes of 16-byte
- * aligned workspace; the partial sums are added in a fixed order. */
-size_t ms_gemm_workspace_bytes(int M, int N, int split_k);
+ * K % (32 * split_k) == 0; A and W 16-byte, bias and destinations 8-byte aligned.
+ * split_k > 1 divides K over that many workgroups per output tile (for few output tiles and a deep
+ * K, such as the MLP down projection); the partial sums are added in a fixed order and the call
+ * fails with MS_ERR_WORKSPACE without ms_gemm_workspace_bytes(M, N, K, split_k) bytes of 16-byte
+ * aligned workspace.  With split_k == 1 that function returns what the call can use to split the
+ * tiles of a partly filled last round over K (0 if the shape has none on the current device);
+ * without that much workspace the call computes whole tiles throughout, with the same result up to
+ * the order of the fp32 additions. */
+size_t ms_gemm_workspace_bytes(int M, int N, int K, int split_k);
 int ms_gemm_bf16(const void* a, const void* w, const void* bias, int M, int N, int K, int n_out,
                  void* const* out, const int* out_col, int split_k, void* workspace, size_t ws_bytes,
                  void* stream);
+
+/* The MLP's gate and up projections with SwiGLU applied to the fp32 sums:
+ * out[m][j] = silu(A[m] . Wg[j]) * (A[m] . Wu[j]), bf16 [M][inter].  w_gate_up is the bf16
+ * [2 * inter][K] weight with the rows of both projections interleaved in blocks of 32: rows
+ * 64 b .. 64 b + 32 are gate rows 32 b .. 32 b + 32, rows 64 b + 32 .. 64 b + 64 the up rows of the
+ * same outputs.  inter % 64 == 0, K % 32 == 0; workspace as for ms_gemm_bf16 with N = 2 * inter and
+ * split_k = 1 (optional). */
+int ms_gemm_swiglu_bf16(const void* a, const void* w_gate_up, int M, int inter, int K, void* out,
+                        void* workspace, size_t ws_bytes, void* stream);
 
 /* ---- profiling ------------------------------------------------------------------------------- */
 

@@ -75,7 +75,8 @@ _SIGS = {
     "ms_add_rmsnorm": (_I, [_P, _P, _P, _F, _P, _I, _I, _P]),
     "ms_swiglu": (_I, [_P, _P, _I, _I, _P]),
     "ms_argmax_rows": (_I, [_P, _I, _I, C.c_long, _P, _P]),
-    "ms_gemm_workspace_bytes": (_SZ, [_I, _I, _I]),
+    "ms_gemm_workspace_bytes": (_SZ, [_I, _I, _I, _I]),
+    "ms_gemm_swiglu_bf16": (_I, [_P, _P, _I, _I, _I, _P, _P, _SZ, _P]),
     "ms_gemm_bf16": (_I, [_P, _P, _P, _I, _I, _I, _I, C.POINTER(_P), _IP, _I, _P, _SZ, _P]),
     "ms_profile_attention": (_I, [_P, _I, _I]),
     "ms_profile_read": (_I, [_P, C.POINTER(C.c_float), _I, _IP]),
@@ -276,8 +277,8 @@ def ms_argmax_rows(logits, vocab: int, out, stream=None) -> None:
                               _sized(None, out, "out", n, 4), _stream(stream)))
 
 
-def ms_gemm_workspace_bytes(M: int, N: int, split_k: int) -> int:
-    return lib.ms_gemm_workspace_bytes(M, N, split_k)
+def ms_gemm_workspace_bytes(M: int, N: int, K: int, split_k: int) -> int:
+    return lib.ms_gemm_workspace_bytes(M, N, K, split_k)
 
 
 def ms_gemm_bf16(a, w, bias, outs, split_k: int = 1, workspace=None, stream=None) -> None:
@@ -293,6 +294,27 @@ def ms_gemm_bf16(a, w, bias, outs, split_k: int = 1, workspace=None, stream=None
         raise MsError(MS_ERR_INVALID, "ms_gemm_bf16: shapes do not match")
     _check(lib.ms_gemm_bf16(_sized(None, a, "a", M_ * K, 2), _sized(None, w, "w", N * K, 2), _sized(None, bias, "bias", N, 2),
                             M_, N, K, len(outs), ptrs, _ints(cols), split_k, _dev(workspace), ws_bytes, _stream(stream)))
+
+
+def ms_gemm_swiglu_bf16(a, w_gate_up, out, workspace=None, stream=None) -> None:
+    """out[M, inter] = silu(a . Wg^T) * (a . Wu^T); w_gate_up [2 * inter, K] with gate and up rows
+    interleaved in blocks of 32 (see interleave_gate_up)."""
+    M_, K = a.shape
+    inter = out.shape[1]
+    if w_gate_up.shape[0] != 2 * inter or w_gate_up.shape[1] != K or out.shape[0] != M_:
+        raise MsError(MS_ERR_INVALID, "ms_gemm_swiglu_bf16: shapes do not match")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.ms_gemm_swiglu_bf16(_sized(None, a, "a", M_ * K, 2), _sized(None, w_gate_up, "w_gate_up", 2 * inter * K, 2), M_, inter, K,
+                                   _sized(None, out, "out", M_ * inter, 2), _dev(workspace), ws_bytes, _stream(stream)))
+
+
+def interleave_gate_up(w_gate, w_up):
+    """The weight layout ms_gemm_swiglu_bf16 reads: blocks of 32 gate rows followed by the 32 up rows
+    of the same outputs.  A one-off re-ordering of rows at load time (no arithmetic)."""
+    inter, K = w_gate.shape
+    if inter % 32 or w_up.shape != w_gate.shape:
+        raise MsError(MS_ERR_INVALID, "interleave_gate_up: widths must match and be multiples of 32")
+    return torch.stack([w_gate.view(inter // 32, 32, K), w_up.view(inter // 32, 32, K)], dim=1).reshape(2 * inter, K).contiguous()
 
 
 def ms_attention_set_deterministic(cache, on: bool) -> None:

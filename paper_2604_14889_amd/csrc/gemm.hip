@@ -11,7 +11,12 @@
 // v_mfma_f32_32x32x16_bf16 with W as the A operand (rows = n) and the activations as the B operand
 // (columns = m), so a lane ends up with four consecutive n of one row m per register quad.
 // split_k > 1 (deep K, few output tiles: the MLP down projection) writes fp32 partials that a
-// second kernel sums, adds the bias to and rounds.
+// second kernel sums, adds the bias to and rounds.  With split_k = 1 and more tiles than the chip
+// holds at once, the tiles of the last, partly filled round are split over K inside the same launch
+// (their workgroups start as soon as slots free up), so that a round with few tiles does not cost a
+// whole tile's time.  The gate/up projection of the MLP can apply SwiGLU in the epilogue: with the
+// weight rows interleaved in blocks of 32 (gate block, up block), a lane holds gate and up of the
+// same output element in two accumulators and writes silu(gate) * up directly.
 #include <stdint.h>
 
 #include "ms_device.h"
@@ -36,8 +41,13 @@ struct GemmArgs {
     int n_out;
     uint16_t* out[kGemmMaxOut];     // destination of columns out_col[i] .. out_col[i + 1]
     int out_col[kGemmMaxOut + 1];
-    float* partial;         // [split_k][M][N] when split_k > 1
+    float* partial;         // split_k > 1: [split_k][M][N]; K-split last round: [tail_split][M][N - tail_col0]
+    // K-split last round (split_k == 1 only): blocks from tail_first on compute K part
+    // (block - tail_first) / tail_blocks of tile tail_first + (block - tail_first) % tail_blocks
+    int tail_first, tail_blocks, tail_k, tail_col0;
 };
+
+enum GemmMode { kGemmPlain = 0, kGemmAllPartial = 1, kGemmSwiglu = 2 };
 
 // Destination of column n: base pointer, first column and width.  Written as a chain of selects
 // over constant indices (a run-time index into the argument arrays would move them to memory).
@@ -59,6 +69,9 @@ __device__ __forceinline__ uint32_t g_pack_bf16x2(float a, float b) {
     return (uint32_t)float_to_bf16_bits(a) | ((uint32_t)float_to_bf16_bits(b) << 16);
 }
 
+// silu(gate) * up in fp32 (SwiGLU of the models' MLP)
+__device__ __forceinline__ float swiglu_value(float gate, float up) { return gate / (1.f + __expf(-gate)) * up; }
+
 // Workgroup barrier that orders LDS traffic only (a plain __syncthreads() would also wait for the
 // global loads of the steps ahead).
 __device__ __forceinline__ void gemm_lds_barrier() {
@@ -67,8 +80,9 @@ __device__ __forceinline__ void gemm_lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <bool kSplit>
+template <int kMode>
 __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
+    constexpr bool kSplit = kMode == kGemmAllPartial;
     __shared__ __attribute__((aligned(16))) char smem[2 * kGemmStageBytes];
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -77,12 +91,21 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
     // workgroups 8 apart share an L2: the row tiles of one column tile are placed 8 apart, and the
     // weight tile they share comes from HBM once.
     const int m_tiles = (g.M + kGemmBM - 1) / kGemmBM, n_tiles = g.N / kGemmBN;
-    const int in_group = blockIdx.x % (8 * m_tiles);
-    const int n_tile = blockIdx.x / (8 * m_tiles) * 8 + in_group % 8, m_tile = in_group / 8;
+    int block = blockIdx.x, k_part = blockIdx.z, k_len = g.k_per_split;
+    bool to_partial = kSplit;
+    if (!kSplit && block >= g.tail_first) {   // a K part of a tile of the last round
+        const int t = block - g.tail_first;
+        k_part = t / g.tail_blocks;
+        block = g.tail_first + t % g.tail_blocks;
+        k_len = g.tail_k;
+        to_partial = true;
+    }
+    const int in_group = block % (8 * m_tiles);
+    const int n_tile = block / (8 * m_tiles) * 8 + in_group % 8, m_tile = in_group / 8;
     if (n_tile >= n_tiles) return;   // padding of the last group (the whole workgroup leaves)
     const int n0 = n_tile * kGemmBN, m0 = m_tile * kGemmBM;
-    const int k_begin = blockIdx.z * g.k_per_split;
-    const int steps = g.k_per_split / kGemmBK;
+    const int k_begin = k_part * k_len;
+    const int steps = k_len / kGemmBK;
 
     // global -> LDS staging.  Four consecutive threads bring the 64 bytes one row contributes to a
     // step, so a load instruction of a wave covers 16 rows x 64 contiguous bytes; thread t handles
@@ -176,9 +199,46 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
 #undef MS_GEMM_STASH
 
     // accumulator i of a lane: n = 8 (i / 4) + 4 (lane / 32) + i % 4, m = lane % 32 (within the 32 x 32 tile)
+    if (to_partial) {
+        const int p_col0 = kSplit ? 0 : g.tail_col0, p_ld = g.N - p_col0;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+            const int m = m0 + 64 * wm + 32 * mi + l32;
+            if (m >= g.M) continue;
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n0 + 64 * wn + 32 * ni + 8 * q + 4 * hf;
+                    *reinterpret_cast<float4*>(g.partial + ((size_t)k_part * g.M + m) * p_ld + (n - p_col0)) =
+                        make_float4(acc[ni][mi][4 * q], acc[ni][mi][4 * q + 1], acc[ni][mi][4 * q + 2], acc[ni][mi][4 * q + 3]);
+                }
+        }
+        return;
+    }
+    if (kMode == kGemmSwiglu) {
+        // weight rows 64 wn .. + 32 of the tile are gate rows, the next 32 the matching up rows:
+        // accumulators [0][mi] and [1][mi] hold gate and up of output column n0 / 2 + 32 wn + ...
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+            const int m = m0 + 64 * wm + 32 * mi + l32;
+            if (m >= g.M) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float o[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i] = swiglu_value(acc[0][mi][4 * q + i], acc[1][mi][4 * q + i]);
+                uint2 pk;
+                pk.x = g_pack_bf16x2(o[0], o[1]);
+                pk.y = g_pack_bf16x2(o[2], o[3]);
+                *reinterpret_cast<uint2*>(g.out[0] + (size_t)m * (g.N / 2) + n0 / 2 + 32 * wn + 8 * q + 4 * hf) = pk;
+            }
+        }
+        return;
+    }
     uint16_t* dst = nullptr;   // the whole tile goes to one destination: boundaries are multiples of 128
     int col0 = 0, ld = 0;
-    if (!kSplit) pick_destination(g, n0, dst, col0, ld);
+    pick_destination(g, n0, dst, col0, ld);
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi) {
         const int m = m0 + 64 * wm + 32 * mi + l32;
@@ -189,35 +249,51 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
             for (int q = 0; q < 4; ++q) {
                 const int n = n0 + 64 * wn + 32 * ni + 8 * q + 4 * hf;
                 float4 v = make_float4(acc[ni][mi][4 * q], acc[ni][mi][4 * q + 1], acc[ni][mi][4 * q + 2], acc[ni][mi][4 * q + 3]);
-                if (kSplit) {
-                    *reinterpret_cast<float4*>(g.partial + ((size_t)blockIdx.z * g.M + m) * g.N + n) = v;
-                } else {
-                    if (g.bias) {
-                        const uint2 b = *reinterpret_cast<const uint2*>(g.bias + n);
-                        v.x += bf16_bits_to_float(b.x & 0xffffu);
-                        v.y += bf16_bits_to_float(b.x >> 16);
-                        v.z += bf16_bits_to_float(b.y & 0xffffu);
-                        v.w += bf16_bits_to_float(b.y >> 16);
-                    }
-                    uint2 pk;
-                    pk.x = g_pack_bf16x2(v.x, v.y);
-                    pk.y = g_pack_bf16x2(v.z, v.w);
-                    *reinterpret_cast<uint2*>(dst + (size_t)m * ld + (n - col0)) = pk;
+                if (g.bias) {
+                    const uint2 b = *reinterpret_cast<const uint2*>(g.bias + n);
+                    v.x += bf16_bits_to_float(b.x & 0xffffu);
+                    v.y += bf16_bits_to_float(b.x >> 16);
+                    v.z += bf16_bits_to_float(b.y & 0xffffu);
+                    v.w += bf16_bits_to_float(b.y >> 16);
                 }
+                uint2 pk;
+                pk.x = g_pack_bf16x2(v.x, v.y);
+                pk.y = g_pack_bf16x2(v.z, v.w);
+                *reinterpret_cast<uint2*>(dst + (size_t)m * ld + (n - col0)) = pk;
             }
     }
 }
 
-// Sums the split-K partials, adds the bias, rounds to bf16 and writes to the destination(s).
-__global__ __launch_bounds__(256) void gemm_reduce(GemmArgs g, int split_k) {
-    const size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;   // 4 consecutive columns
-    if (idx >= (size_t)g.M * g.N) return;
-    const int m = (int)(idx / g.N), n = (int)(idx % g.N);
-    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int z = 0; z < split_k; ++z) {
-        const float4 p = *reinterpret_cast<const float4*>(g.partial + ((size_t)z * g.M + m) * g.N + n);
-        s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+// Sums the K parts of columns col0 .. N (partials [parts][M][N - col0]), adds the bias, rounds to
+// bf16 and writes to the destination(s); in SwiGLU mode a thread sums four gate columns and the four
+// matching up columns and writes silu(gate) * up.
+template <bool kSwiglu>
+__global__ __launch_bounds__(256) void gemm_reduce(GemmArgs g, int parts, int col0) {
+    const int width = g.N - col0;
+    const size_t quad = (size_t)blockIdx.x * 256 + threadIdx.x;   // 4 consecutive columns (of the output in SwiGLU mode)
+    const int row_quads = (kSwiglu ? width / 2 : width) / 4;
+    if (quad >= (size_t)g.M * row_quads) return;
+    const int m = (int)(quad / row_quads), c = (int)(quad % row_quads) * 4;
+    // SwiGLU: output column c of this range <- gate column 64 (c / 32) + c % 32 and the up column 32 further
+    const int n_rel = kSwiglu ? 64 * (c / 32) + c % 32 : c;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f), u = s;
+    for (int z = 0; z < parts; ++z) {
+        const float* p = g.partial + ((size_t)z * g.M + m) * width + n_rel;
+        const float4 a = *reinterpret_cast<const float4*>(p);
+        s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+        if (kSwiglu) {
+            const float4 b = *reinterpret_cast<const float4*>(p + 32);
+            u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
+        }
     }
+    uint2 pk;
+    if (kSwiglu) {
+        pk.x = g_pack_bf16x2(swiglu_value(s.x, u.x), swiglu_value(s.y, u.y));
+        pk.y = g_pack_bf16x2(swiglu_value(s.z, u.z), swiglu_value(s.w, u.w));
+        *reinterpret_cast<uint2*>(g.out[0] + (size_t)m * (g.N / 2) + col0 / 2 + c) = pk;
+        return;
+    }
+    const int n = col0 + c;
     if (g.bias) {
         const uint2 b = *reinterpret_cast<const uint2*>(g.bias + n);
         s.x += bf16_bits_to_float(b.x & 0xffffu);
@@ -226,34 +302,132 @@ __global__ __launch_bounds__(256) void gemm_reduce(GemmArgs g, int split_k) {
         s.w += bf16_bits_to_float(b.y >> 16);
     }
     uint16_t* dst;
-    int col0, ld;
-    pick_destination(g, n, dst, col0, ld);
-    uint2 pk;
+    int dcol0, ld;
+    pick_destination(g, n, dst, dcol0, ld);
     pk.x = g_pack_bf16x2(s.x, s.y);
     pk.y = g_pack_bf16x2(s.z, s.w);
-    *reinterpret_cast<uint2*>(dst + (size_t)m * ld + (n - col0)) = pk;
+    *reinterpret_cast<uint2*>(dst + (size_t)m * ld + (n - dcol0)) = pk;
 }
 
 static bool g_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Workgroups the chip holds at once (two per compute unit), for the current device.
+static int gemm_slots() {
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 512;
+    if (!cached[dev]) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        cached[dev] = 2 * cus;
+    }
+    return cached[dev];
+}
+
+// The launch shape.  Blocks come in groups of 8 column tiles x m_tiles row tiles.  When the groups
+// fill the chip at least once and the last round is at most 60 % full, the groups of that round are
+// split over K: tail_split parts, chosen so that the round still fits the chip.
+struct GemmPlan {
+    int m_tiles, n_groups, group_blocks;
+    int main_groups, tail_groups, tail_split;
+    size_t workspace_bytes;
+};
+
+static GemmPlan gemm_plan(int M, int N, int K, int split_k) {
+    GemmPlan p;
+    p.m_tiles = (M + kGemmBM - 1) / kGemmBM;
+    p.n_groups = (N / kGemmBN + 7) / 8;
+    p.group_blocks = 8 * p.m_tiles;
+    p.main_groups = p.n_groups;
+    p.tail_groups = 0;
+    p.tail_split = 1;
+    p.workspace_bytes = split_k > 1 ? (size_t)split_k * M * N * sizeof(float) : 0;
+    if (split_k != 1) return p;
+    const int per_round = gemm_slots() / p.group_blocks;
+    if (per_round < 1 || p.n_groups <= per_round) return p;
+    const int rem = p.n_groups % per_round;
+    if (rem == 0 || 10 * rem > 6 * per_round) return p;
+    const int steps = K / kGemmBK;
+    for (int s = 8; s >= 2; s >>= 1)
+        if (steps % s == 0 && steps / s >= 8 && rem * s <= per_round) {
+            p.tail_split = s;
+            break;
+        }
+    if (p.tail_split == 1) return p;
+    p.tail_groups = rem;
+    p.main_groups = p.n_groups - rem;
+    const long tail_cols = (long)N - (long)p.main_groups * 8 * kGemmBN;
+    p.workspace_bytes = (size_t)p.tail_split * M * tail_cols * sizeof(float);
+    return p;
+}
+
+static int gemm_check_shape(const char* what, int M, int N, int K, int split_k) {
+    if (M < 0 || N < 1 || K < 1 || split_k < 1) MS_FAIL(MS_ERR_INVALID, "%s: bad size", what);
+    if (N % kGemmBN || K % (kGemmBK * split_k))
+        MS_FAIL(MS_ERR_UNSUPPORTED, "%s: N must be a multiple of %d and K of %d x split_k", what, kGemmBN, kGemmBK);
+    if ((long long)M * N >= (1ll << 40) || split_k > 64 ||
+        (long long)((N / kGemmBN + 7) / 8) * 8 * ((M + kGemmBM - 1) / kGemmBM) * 9 > 2000000000ll)
+        MS_FAIL(MS_ERR_UNSUPPORTED, "%s: shape too large", what);
+    return MS_OK;
+}
+
+// Launches the tiles (and the reduction of the parts, if any).  g holds operands and destinations.
+static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, size_t ws_bytes, hipStream_t stream) {
+    GemmPlan p = gemm_plan(g.M, g.N, g.K, split_k);
+    if (split_k == 1 && p.tail_groups && (!workspace || ws_bytes < p.workspace_bytes || !g_aligned16(workspace))) {
+        p.main_groups = p.n_groups;   // no room for the parts: whole tiles throughout
+        p.tail_groups = 0;
+        p.tail_split = 1;
+    }
+    g.k_per_split = g.K / split_k;
+    g.partial = nullptr;
+    const int main_blocks = p.main_groups * p.group_blocks;
+    g.tail_first = main_blocks;
+    g.tail_blocks = p.tail_groups * p.group_blocks;
+    g.tail_k = g.K / p.tail_split;
+    g.tail_col0 = p.main_groups * 8 * kGemmBN;
+    const dim3 grid((unsigned)(main_blocks + g.tail_blocks * p.tail_split), 1, (unsigned)split_k);
+    if (split_k > 1) {
+        if (!workspace || ws_bytes < p.workspace_bytes || !g_aligned16(workspace))
+            MS_FAIL(MS_ERR_WORKSPACE, "ms_gemm_bf16: split-K workspace of %zu bytes needed", p.workspace_bytes);
+        g.partial = (float*)workspace;
+        g.tail_first = (int)grid.x;   // unused by this build of the kernel
+        hipLaunchKernelGGL((gemm_tn_bf16<kGemmAllPartial>), grid, dim3(kGemmThreads), 0, stream, g);
+        const size_t quads = (size_t)g.M * g.N / 4;
+        hipLaunchKernelGGL((gemm_reduce<false>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, g, split_k, 0);
+    } else {
+        if (p.tail_groups) g.partial = (float*)workspace;
+        if (swiglu)
+            hipLaunchKernelGGL((gemm_tn_bf16<kGemmSwiglu>), grid, dim3(kGemmThreads), 0, stream, g);
+        else
+            hipLaunchKernelGGL((gemm_tn_bf16<kGemmPlain>), grid, dim3(kGemmThreads), 0, stream, g);
+        if (p.tail_groups) {
+            const size_t quads = (size_t)g.M * (g.N - g.tail_col0) / (swiglu ? 8 : 4);
+            const dim3 rgrid((unsigned)((quads + 255) / 256));
+            if (swiglu)
+                hipLaunchKernelGGL((gemm_reduce<true>), rgrid, dim3(256), 0, stream, g, p.tail_split, g.tail_col0);
+            else
+                hipLaunchKernelGGL((gemm_reduce<false>), rgrid, dim3(256), 0, stream, g, p.tail_split, g.tail_col0);
+        }
+    }
+    MS_HIP_TRY(hipGetLastError());
+    return MS_OK;
+}
+
 }  // namespace ms
 
-extern "C" size_t ms_gemm_workspace_bytes(int M, int N, int split_k) {
-    if (M < 1 || N < 1 || split_k < 2) return 0;
-    return (size_t)split_k * M * N * sizeof(float);
+extern "C" size_t ms_gemm_workspace_bytes(int M, int N, int K, int split_k) {
+    if (M < 1 || N < 1 || K < 1 || split_k < 1 || N % ms::kGemmBN || K % (ms::kGemmBK * split_k)) return 0;
+    return ms::gemm_plan(M, N, K, split_k).workspace_bytes;
 }
 
 extern "C" int ms_gemm_bf16(const void* a, const void* w, const void* bias, int M, int N, int K, int n_out, void* const* out,
                             const int* out_col, int split_k, void* workspace, size_t ws_bytes, void* stream) {
     using namespace ms;
-    if (M < 0 || N < 1 || K < 1 || split_k < 1 || n_out < 1 || n_out > kGemmMaxOut || !out || !out_col)
-        MS_FAIL(MS_ERR_INVALID, "ms_gemm_bf16: bad size or null table");
+    if (n_out < 1 || n_out > kGemmMaxOut || !out || !out_col) MS_FAIL(MS_ERR_INVALID, "ms_gemm_bf16: bad destination table");
+    int rc = gemm_check_shape("ms_gemm_bf16", M, N, K, split_k);
+    if (rc != MS_OK) return rc;
     if (M == 0) return MS_OK;
-    if (N % kGemmBN || K % (kGemmBK * split_k))
-        MS_FAIL(MS_ERR_UNSUPPORTED, "ms_gemm_bf16: N must be a multiple of %d and K of %d x split_k", kGemmBN, kGemmBK);
-    if ((long long)M * N >= (1ll << 40) || split_k > 64 ||
-        (long long)((N / kGemmBN + 7) / 8) * 8 * ((M + kGemmBM - 1) / kGemmBM) > 2000000000ll)
-        MS_FAIL(MS_ERR_UNSUPPORTED, "ms_gemm_bf16: shape too large");
     if (!a || !w || !g_aligned16(a) || !g_aligned16(w) || (bias && (reinterpret_cast<uintptr_t>(bias) & 7u)))
         MS_FAIL(MS_ERR_INVALID, "ms_gemm_bf16: null or misaligned operand");
     GemmArgs g;
@@ -263,7 +437,6 @@ extern "C" int ms_gemm_bf16(const void* a, const void* w, const void* bias, int 
     g.M = M;
     g.N = N;
     g.K = K;
-    g.k_per_split = K / split_k;
     g.n_out = n_out;
     if (out_col[0] != 0 || out_col[n_out] != N) MS_FAIL(MS_ERR_INVALID, "ms_gemm_bf16: destinations must cover columns 0 .. N");
     for (int i = 0; i < n_out; ++i) {
@@ -278,20 +451,31 @@ extern "C" int ms_gemm_bf16(const void* a, const void* w, const void* bias, int 
         g.out[i] = nullptr;
         g.out_col[i + 1] = N;
     }
-    g.partial = nullptr;
-    const int m_tiles = (M + kGemmBM - 1) / kGemmBM, n_groups = (N / kGemmBN + 7) / 8;
-    const dim3 grid((unsigned)(n_groups * 8 * m_tiles), 1, split_k);
-    if (split_k == 1) {
-        hipLaunchKernelGGL(gemm_tn_bf16<false>, grid, dim3(kGemmThreads), 0, (hipStream_t)stream, g);
-    } else {
-        const size_t need = ms_gemm_workspace_bytes(M, N, split_k);
-        if (!workspace || ws_bytes < need || !g_aligned16(workspace))
-            MS_FAIL(MS_ERR_WORKSPACE, "ms_gemm_bf16: split-K workspace of %zu bytes needed", need);
-        g.partial = (float*)workspace;
-        hipLaunchKernelGGL(gemm_tn_bf16<true>, grid, dim3(kGemmThreads), 0, (hipStream_t)stream, g);
-        const size_t quads = (size_t)M * N / 4;
-        hipLaunchKernelGGL(gemm_reduce, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, (hipStream_t)stream, g, split_k);
-    }
-    MS_HIP_TRY(hipGetLastError());
-    return MS_OK;
+    return gemm_launch(g, split_k, false, workspace, ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" int ms_gemm_swiglu_bf16(const void* a, const void* w_gate_up, int M, int inter, int K, void* out, void* workspace,
+                                   size_t ws_bytes, void* stream) {
+    using namespace ms;
+    if (inter < 1 || inter > (1 << 29)) MS_FAIL(MS_ERR_INVALID, "ms_gemm_swiglu_bf16: bad size");
+    if (inter % 64) MS_FAIL(MS_ERR_UNSUPPORTED, "ms_gemm_swiglu_bf16: the MLP width must be a multiple of 64");
+    const int N = 2 * inter;
+    int rc = gemm_check_shape("ms_gemm_swiglu_bf16", M, N, K, 1);
+    if (rc != MS_OK) return rc;
+    if (M == 0) return MS_OK;
+    if (!a || !w_gate_up || !out || !g_aligned16(a) || !g_aligned16(w_gate_up) || (reinterpret_cast<uintptr_t>(out) & 7u))
+        MS_FAIL(MS_ERR_INVALID, "ms_gemm_swiglu_bf16: null or misaligned operand");
+    GemmArgs g;
+    g.a = (const uint16_t*)a;
+    g.w = (const uint16_t*)w_gate_up;
+    g.bias = nullptr;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.n_out = 1;
+    g.out[0] = (uint16_t*)out;
+    g.out_col[0] = 0;
+    for (int i = 1; i < kGemmMaxOut; ++i) g.out[i] = nullptr;
+    for (int i = 1; i <= kGemmMaxOut; ++i) g.out_col[i] = N;
+    return gemm_launch(g, 1, true, workspace, ws_bytes, (hipStream_t)stream);
 }

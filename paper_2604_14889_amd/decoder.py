@@ -5,7 +5,9 @@ update are this library's HIP kernels.  Of the dense projections, the fused Q/K/
 the MLP down projection run on this library's MFMA GEMM (ms_gemm_bf16: one launch fills the three
 Q/K/V tensors; the down projection's deep K is split over workgroups), where it is faster than the
 library GEMM at a few hundred rows; the output, gate/up and LM-head projections go through torch
-(hipBLASLt underneath), which is still ahead on those shapes.
+(hipBLASLt underneath), which is still ahead on those shapes.  fused_mlp=True moves the gate/up
+projection onto this library's GEMM as well, with SwiGLU applied in its epilogue
+(ms_gemm_swiglu_bf16): no hipBLASLt in the MLP, about a tenth slower on that projection.
 
 Nothing here computes on the CPU; every call fails if the HIP library is missing.
 """
@@ -46,6 +48,13 @@ class LayerTensors:
         # one weight for the fused Q/K/V projection (rows: Q heads, then K heads, then V heads)
         self.wqkv = torch.cat([wq, wk, wv], dim=0).contiguous()
         self.bqkv = torch.cat([bq, bk, bv], dim=0).contiguous()
+        self.w_gate_up_blocked = None   # rows re-ordered for the fused gate/up + SwiGLU GEMM, made on demand
+
+    def gate_up_blocked(self):
+        if self.w_gate_up_blocked is None:
+            inter = self.w_gate_up.shape[0] // 2
+            self.w_gate_up_blocked = M.interleave_gate_up(self.w_gate_up[:inter], self.w_gate_up[inter:])
+        return self.w_gate_up_blocked
 
 
 class DecoderTensors:
@@ -80,7 +89,7 @@ class Decoder:
     """Buffers and the step driver for up to max_rows = B * n_q tokens per step."""
 
     def __init__(self, cfg: DecoderConfig, weights: DecoderTensors, session: Session, max_rows: int,
-                 hand_gemm: bool = True):
+                 hand_gemm: bool = True, fused_mlp: bool = False):
         """hand_gemm: run the Q/K/V and down projections on this library's GEMM (needs widths that
         are multiples of 128 and depths that are multiples of 128); otherwise everything dense goes
         through torch."""
@@ -106,11 +115,14 @@ class Decoder:
         self.qkv_split, self.down_split = 2, 4
         self.hand_gemm = (hand_gemm and qd % 128 == 0 and kd % 128 == 0 and cfg.hidden % 128 == 0 and
                           cfg.hidden % (32 * self.qkv_split) == 0 and cfg.inter % (32 * self.down_split) == 0)
+        # gate/up + SwiGLU in one GEMM: keeps a second, row-interleaved copy of the gate/up weights
+        self.fused_mlp = fused_mlp and self.hand_gemm and cfg.inter % 64 == 0
         self.gemm_ws = None
         if self.hand_gemm:
-            need = max(M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, self.qkv_split),
-                       M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, self.down_split))
-            self.gemm_ws = torch.empty(need, dtype=torch.uint8, device=dev)
+            need = max(M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, cfg.hidden, self.qkv_split),
+                       M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.down_split),
+                       M.ms_gemm_workspace_bytes(max_rows, 2 * cfg.inter, cfg.hidden, 1) if self.fused_mlp else 0)
+            self.gemm_ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
     def step(self, seq_ids: Sequence[int], tokens: torch.Tensor, pos: torch.Tensor, n_verify: int, n_foresight: int,
              ctx_new: Optional[torch.Tensor] = None):
@@ -152,8 +164,11 @@ class Decoder:
                 self.attn_events.append((e0, e1))
             torch.mm(attn, lw.wo.t(), out=proj)
             M.ms_add_rmsnorm(h, proj, lw.ln2, cfg.eps, x)
-            torch.mm(x, lw.w_gate_up.t(), out=gate_up)
-            M.ms_swiglu(gate_up, act)
+            if self.fused_mlp:
+                M.ms_gemm_swiglu_bf16(x, lw.gate_up_blocked(), act, self.gemm_ws)
+            else:
+                torch.mm(x, lw.w_gate_up.t(), out=gate_up)
+                M.ms_swiglu(gate_up, act)
             if self.hand_gemm:
                 M.ms_gemm_bf16(act, lw.w_down, None, [proj], self.down_split, self.gemm_ws)
             else:

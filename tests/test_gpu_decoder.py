@@ -117,6 +117,14 @@ def test_decode_step_matches_oracle_and_commits_accepted_rows():
         max_abs, mean_rel = err.max(), err.mean() / np.abs(ref.logits).mean()
         print(f"logits: max-abs {max_abs:.3e} (scale {scale:.2f}), mean-rel {mean_rel:.3e}")
         assert max_abs <= 4e-2 * scale and mean_rel <= 2e-2
+        # the same step with the gate/up projection and SwiGLU in one GEMM of the library
+        dec_f = D.Decoder(cfg, gw, ses, B * nq, fused_mlp=True)
+        assert dec_f.fused_mlp
+        logits_f, _ = dec_f.step(ids, S.ints_dev(tokens).view(B, nq), S.ints_dev(pos).view(B, nq), nv, nf)
+        torch.cuda.synchronize()
+        err_f = np.abs(logits_f.float().cpu().numpy().reshape(B, nq, cfg.vocab).astype(np.float64) - ref.logits)
+        print(f"logits (fused MLP): max-abs {err_f.max():.3e}, mean-rel {err_f.mean() / np.abs(ref.logits).mean():.3e}")
+        assert err_f.max() <= 4e-2 * scale and err_f.mean() / np.abs(ref.logits).mean() <= 2e-2
         # greedy tokens wherever the oracle's decision has a margin
         srt = np.sort(ref.logits, axis=-1)
         margin = srt[..., -1] - srt[..., -2]

@@ -20,6 +20,8 @@ CASES = [
     (448, 4608, 3584, [3584, 512, 512], 1, True),  # fused Q / K / V projection into three tensors
     (448, 3584, 18944, [3584], 4, False),         # MLP down projection, K split four ways
     (300, 1024, 2048, [128, 512, 256, 128], 8, True),
+    (448, 37888, 512, [37888], 1, True),          # gate/up width: 592 tiles, the last 80 split over K
+    (100, 67584, 512, [67584], 1, False),         # one row tile: 528 tiles, the last 16 split over K
 ]
 
 
@@ -35,9 +37,12 @@ def test_gemm_matches_fp64_definition(m, n, k, widths, split, with_bias):
     ref = f64(a) @ f64(w).T + (f64(b) if with_bias else 0.0)
     outs = [torch.full((m, wd), float("nan"), dtype=torch.bfloat16, device="cuda") for wd in widths]
     ws = None
+    need = M.ms_gemm_workspace_bytes(m, n, k, split)
     if split > 1:
-        need = M.ms_gemm_workspace_bytes(m, n, split)
         assert need == split * m * n * 4
+    elif n >= 37888:
+        assert need > 0, "this shape is meant to exercise the K-split last round"
+    if need:
         ws = torch.empty(need, dtype=torch.uint8, device="cuda")
     M.ms_gemm_bf16(S.to_device(a, M.MS_BF16), S.to_device(w, M.MS_BF16), None if b is None else S.to_device(b, M.MS_BF16),
                    outs, split, ws)
@@ -46,6 +51,61 @@ def test_gemm_matches_fp64_definition(m, n, k, widths, split, with_bias):
     assert np.isfinite(got).all()
     err = np.abs(got - ref)
     bound = 2.0 ** -8 * np.abs(ref) + 1e-5 * np.abs(ref).max()
+    assert (err <= bound).all(), f"max excess {np.max(err - bound):.3e} at {np.unravel_index(np.argmax(err - bound), err.shape)}"
+
+
+def test_gemm_last_round_split_is_optional():
+    """Without workspace the same shape runs whole tiles throughout; both ways give the product."""
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import session as S
+    m, n, k = 448, 37888, 512
+    rng = W.make_rng(901)
+    a = W.normal_bf16_bits(rng, (m, k), 1.0)
+    w = W.normal_bf16_bits(rng, (n, k), k ** -0.5)
+    ad, wd = S.to_device(a, M.MS_BF16), S.to_device(w, M.MS_BF16)
+    ws = torch.empty(M.ms_gemm_workspace_bytes(m, n, k, 1), dtype=torch.uint8, device="cuda")
+    assert ws.numel() > 0
+    o1 = torch.zeros(m, n, dtype=torch.bfloat16, device="cuda")
+    o2 = torch.zeros_like(o1)
+    M.ms_gemm_bf16(ad, wd, None, [o1], 1, ws)
+    M.ms_gemm_bf16(ad, wd, None, [o2], 1, None)
+    torch.cuda.synchronize()
+    main_cols = 32 * 8 * 128    # the first round's columns do not depend on the workspace
+    assert torch.equal(o1[:, :main_cols], o2[:, :main_cols])
+    d = (o1.float() - o2.float()).abs()
+    assert float(d.max()) <= 2.0 ** -7 * float(o2.float().abs().max())   # other order of fp32 additions: one bf16 step at most
+
+
+SWIGLU_CASES = [(7, 64, 32), (300, 1088, 256), (448, 18944, 512)]
+
+
+@pytest.mark.parametrize("m,inter,k", SWIGLU_CASES)
+def test_gate_up_gemm_with_swiglu_epilogue(m, inter, k):
+    """silu(A Wg^T) * (A Wu^T) (the models' MLP, Section 4.1) in fp64 against the fused GEMM, which
+    applies SwiGLU to its fp32 sums and rounds once."""
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import session as S
+    from oracle import decoder_oracle as DO
+    rng = W.make_rng(902, m, inter, k)
+    a = W.normal_bf16_bits(rng, (m, k), 1.0)
+    wg = W.normal_bf16_bits(rng, (inter, k), k ** -0.5)
+    wu = W.normal_bf16_bits(rng, (inter, k), k ** -0.5)
+    f64 = lambda x: O.bf16_bits_to_f32(x).astype(np.float64)
+    gate, up = f64(a) @ f64(wg).T, f64(a) @ f64(wu).T
+    ref = DO.silu(gate) * up
+    blocked = M.interleave_gate_up(S.to_device(wg, M.MS_BF16), S.to_device(wu, M.MS_BF16))
+    out = torch.full((m, inter), float("nan"), dtype=torch.bfloat16, device="cuda")
+    need = M.ms_gemm_workspace_bytes(m, 2 * inter, k, 1)
+    if inter == 18944:
+        assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+    M.ms_gemm_swiglu_bf16(S.to_device(a, M.MS_BF16), blocked, out, ws)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref)
+    # one bf16 rounding of the result + the fp32 sums' error carried through silu and the product
+    bound = 2.0 ** -8 * np.abs(ref) + 2e-5 * (np.abs(gate) + 1.0) * (np.abs(up) + 1.0)
     assert (err <= bound).all(), f"max excess {np.max(err - bound):.3e} at {np.unravel_index(np.argmax(err - bound), err.shape)}"
 
 
