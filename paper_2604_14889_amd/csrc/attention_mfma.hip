@@ -112,7 +112,7 @@ struct MfmaArgs {
     long page_elems;
     float scale_log2;       // softmax scale * log2(e)
 #ifdef MS_TIMING
-    long long* dbg;         // [workgroup][4] wall-clock stamps (100 MHz)
+    long long* dbg;         // [workgroup][8] wall-clock stamps (100 MHz)
 #endif
 };
 
@@ -467,7 +467,7 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
     const uint32_t lane_off_k = ((uint32_t)g * 2 * MS_PAGE_SIZE * kD + (lane & 15) * kD + 8 * hf) * 2;
     const uint32_t lane_off_v = (((uint32_t)g * 2 + 1) * MS_PAGE_SIZE * kD + (lane >> 4) * kD + 8 * l16) * 2;
 #ifdef MS_TIMING
-    long long* dbg = a.dbg + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 4;
+    long long* dbg = a.dbg + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8;
     if (tid == 0) dbg[0] = wall_clock64();
 #endif
     // The item's first segment record also holds the item's segment range and the page ids of the
@@ -483,6 +483,9 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         const int n_tiles = (n_tok + kTile - 1) / kTile;
         const bool first_seg = sg_t0 == 0;   // this workgroup also runs the sequence's in-flight tile
         int pa = uniform_load(&sp->pages[2 * w]), pb = uniform_load(&sp->pages[2 * w + 1]);
+#ifdef MS_TIMING
+        if (tid == 0 && si == seg_begin) dbg[4] = wall_clock64() + (pa & 0) + (n_tok & 0);
+#endif
 
         // ---- set-up loads.  Order matters: waiting for a load also waits for every load issued
         // before it, so the small loads the Q rotation needs go first and this wave's first tile
@@ -524,6 +527,10 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
                 cs_tab[(w + 8 * k) * 64 + (tid_p & 63)] = make_float2(cs, sn);
             }
         lds_barrier();
+#ifdef MS_TIMING
+        if (tid == 0 && si == seg_begin) dbg[5] = wall_clock64();
+        if (tid == 0 && si == seg_begin) dbg[6] = wall_clock64() + (x0v.x & 0) + (k1v.w & 0);
+#endif
         {
             const uint32_t w0[4] = {x0v.x, x0v.y, x0v.z, x0v.w}, w1[4] = {x1v.x, x1v.y, x1v.z, x1v.w};
             const uint32_t u0[4] = {k0v.x, k0v.y, k0v.z, k0v.w}, u1[4] = {k1v.x, k1v.y, k1v.z, k1v.w};
