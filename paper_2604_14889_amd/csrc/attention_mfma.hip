@@ -152,25 +152,27 @@ __device__ __forceinline__ uint4 load_stream(const char* p) {
 // other.  They are written and read with device-scope relaxed atomic accesses (write-through /
 // cache-bypassing), which needs no cache write-back or invalidation; ordering comes from waiting
 // for the stores (workgroup barrier) before the arrival count is bumped.
-__device__ __forceinline__ void store_coherent(float* p, float4 v) {
-    unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
-    const unsigned long long lo = ((unsigned long long)__float_as_uint(v.y) << 32) | __float_as_uint(v.x);
-    const unsigned long long hi = ((unsigned long long)__float_as_uint(v.w) << 32) | __float_as_uint(v.z);
-    __hip_atomic_store(q, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(q + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 __device__ __forceinline__ void store_coherent(float* p, float v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float4 load_coherent4(const float* p) {
-    const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
-    const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_float4(__uint_as_float((uint32_t)lo), __uint_as_float((uint32_t)(lo >> 32)), __uint_as_float((uint32_t)hi),
-                       __uint_as_float((uint32_t)(hi >> 32)));
-}
 __device__ __forceinline__ float load_coherent(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// 16-byte accesses with the same cache policy (the bit device-scope atomics carry: the other XCDs'
+// L2s are bypassed), through a buffer descriptor over the partials: one instruction per float4
+// instead of two 8-byte atomics.  byte_off < 2 GiB.
+typedef uint32_t pv_u32x4_t __attribute__((ext_vector_type(4)));
+constexpr int kCoherentPolicy = 16;   // sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t partials_descriptor(float* ws) {
+    return __builtin_amdgcn_make_buffer_rsrc(ws, 0, 0x7fffffff, 0x00020000);
+}
+__device__ __forceinline__ float4 load_coherent4(__amdgpu_buffer_rsrc_t rs, uint32_t byte_off) {
+    const pv_u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)byte_off, 0, kCoherentPolicy);
+    return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+__device__ __forceinline__ void store_coherent4(__amdgpu_buffer_rsrc_t rs, uint32_t byte_off, float4 f) {
+    pv_u32x4_t v = {__float_as_uint(f.x), __float_as_uint(f.y), __float_as_uint(f.z), __float_as_uint(f.w)};
+    __builtin_amdgcn_raw_buffer_store_b128(v, rs, (int)byte_off, 0, kCoherentPolicy);
 }
 
 // Read-only, wave-uniform control data (the work plan, position ids) is read through the constant
@@ -370,13 +372,16 @@ __device__ __forceinline__ void close_pair(const MfmaArgs& a, int q0, int n_rows
     for (int ps = 0; ps < 2; ++ps)
 #pragma unroll
         for (int u = 0; u < 2; ++u) o[ps][u] = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int p0 = p_begin; p0 < p_end; p0 += 4) {
-        float pm[4], pl[4];
-        float4 px[4][2][2];
+    const __amdgpu_buffer_rsrc_t rs = partials_descriptor(a.ws);
+    constexpr int kBatch = 8;   // partials requested together: one memory round trip per batch
+    for (int p0 = p_begin; p0 < p_end; p0 += kBatch) {
+        float pm[kBatch], pl[kBatch];
+        float4 px[kBatch][2][2];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < kBatch; ++k) {
             const int p = p0 + k;
             if (p < p_end && p != p_own) {
+                const uint32_t base = (uint32_t)(((size_t)p * a.n_kv_heads + g) * kPartFloats * sizeof(float));
                 const float* part = a.ws + ((size_t)p * a.n_kv_heads + g) * kPartFloats;
                 pm[k] = load_coherent(part + row);
                 pl[k] = load_coherent(part + kRows + row);
@@ -384,7 +389,7 @@ __device__ __forceinline__ void close_pair(const MfmaArgs& a, int q0, int n_rows
                 for (int ps = 0; ps < 2; ++ps)
 #pragma unroll
                     for (int u = 0; u < 2; ++u)
-                        px[k][ps][u] = load_coherent4(part + 2 * kRows + ((rb * 16 + (2 * ps + d2) * 4 + i4b + u) * 64 + lane) * 4);
+                        px[k][ps][u] = load_coherent4(rs, base + (2 * kRows + ((rb * 16 + (2 * ps + d2) * 4 + i4b + u) * 64 + lane) * 4) * 4);
             } else {
                 const bool mine = p == p_own;
                 pm[k] = mine ? own_m : -INFINITY;   // past the end: weight 2^-inf = 0
@@ -396,7 +401,7 @@ __device__ __forceinline__ void close_pair(const MfmaArgs& a, int q0, int n_rows
             }
         }
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < kBatch; ++k) {
             const float mn = fmaxf(m, pm[k]);                       // the first partial exists and is finite
             const float fo = __builtin_amdgcn_exp2f(m - mn);
             const float fp = __builtin_amdgcn_exp2f(pm[k] - mn);
@@ -741,13 +746,15 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         const bool closing = *reinterpret_cast<volatile int*>(smem + L::kFlag) == p_end - p_begin - 1;
         if (!closing) {
             const int rb = w >> 2;
+            const __amdgpu_buffer_rsrc_t rs = partials_descriptor(a.ws);
+            const uint32_t base = (uint32_t)(((size_t)sg_part * a.n_kv_heads + g) * kPartFloats * sizeof(float));
 #pragma unroll
             for (int pass = 0; pass < 2; ++pass)
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const int slot = 2 * w + u, d2 = (slot >> 2) & 1, i4 = slot & 3;
                     const int reg4 = rb * 16 + (2 * pass + d2) * 4 + i4;
-                    store_coherent(part + 2 * kRows + (reg4 * 64 + lane_m) * 4, own[pass][u]);
+                    store_coherent4(rs, base + (2 * kRows + (reg4 * 64 + lane_m) * 4) * 4, own[pass][u]);
                 }
             if ((w & 3) == 0 && (lane_m >> 5) == 0) {
                 store_coherent(part + 32 * rb + (lane_m & 31), own_m);
@@ -765,6 +772,7 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
                 __hip_atomic_store(ctr + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             lds_barrier();
+            asm volatile("" ::: "memory");   // the partials are read after the wait, also in the compiler's order
             close_pair(a, q0, n_rows, sg_b, g, p_begin, p_end, sg_part, own, own_m, own_l, w, lane_m);
         }
         lds_barrier();  // the next segment reuses the LDS
@@ -778,9 +786,10 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
 // host side
 // ---------------------------------------------------------------------------------------------
 
-// bf16, head_dim 128, at most 64 grouped heads per KV head.
+// bf16, head_dim 128, at most 64 grouped heads per KV head; at most 128 KV heads keeps the partials
+// of the largest batch below the 2 GiB a buffer descriptor's 32-bit offsets reach.
 bool mfma_eligible(const ms_cache* c, int n_q) {
-    return c->d.dtype == MS_BF16 && c->d.head_dim == kD && c->group <= kRows && n_q <= MS_MAX_QUERIES;
+    return c->d.dtype == MS_BF16 && c->d.head_dim == kD && c->group <= kRows && n_q <= MS_MAX_QUERIES && c->d.n_kv_heads <= 128;
 }
 
 // Layer pools below 4 GiB are addressed with 32-bit byte offsets from the layer base (one register
@@ -790,6 +799,9 @@ static bool big_pool(const ms_cache* c) { return (unsigned long long)c->layer_el
 static int mfma_items(const ms_cache* c) {
     int target = c->n_cus / c->d.n_kv_heads;
     if (target < 1) target = 1;
+#ifdef MS_TIMING
+    if (const char* e = getenv("MS_ITEMS")) target = atoi(e);
+#endif
     return target > kMaxMfmaItems ? kMaxMfmaItems : target;
 }
 
