@@ -345,7 +345,8 @@ def decode_step_bench(args):
     per_launch_bytes = int(np.sum(2 * cur_len * Hkv * Dh * 2 + 4 * (-(-cur_len // 16)))) + B * nq * (2 * Hq + 2 * Hkv) * Dh * 2
     kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else float("nan")
     achieved = per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9
-    n_params = (sum(t.numel() for lw in weights.layers for name, t in vars(lw).items() if name not in ("wqkv", "bqkv")) +
+    n_params = (sum(t.numel() for lw in weights.layers for name, t in vars(lw).items()
+                     if name not in ("wqkv", "bqkv", "w_gate_up_blocked")) +
                 weights.lm_head.numel() + weights.norm.numel())
     result = {
         "metric": "full_decode_step_tokens_per_s_b64_kv8k",
