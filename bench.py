@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--kv", type=int, default=8192)
     ap.add_argument("--ragged", action="store_true", help="lengths uniform in [1k, 16k] instead of --kv")
+    ap.add_argument("--q-heads", type=int, default=28, help="query heads (28 / 4: Qwen2.5-7B, 32 / 8: Llama-3.1-8B)")
+    ap.add_argument("--kv-heads", type=int, default=4)
     ap.add_argument("--event-stride", type=int, default=13,
                     help="time every n-th attention launch with HIP events (an event pair costs the stream a few microseconds)")
     ap.add_argument("--workload", choices=["attention", "decode_step"], default="attention",
@@ -74,6 +76,10 @@ def main():
     dev = torch.device("cuda:0")
     sh = W.config3(n_layers=args.layers, batch=args.batch) if args.ragged else \
         W.metric_point(args.batch, args.kv, n_layers=args.layers)
+    if (args.q_heads, args.kv_heads) != (sh.n_q_heads, sh.n_kv_heads):
+        if args.q_heads % args.kv_heads or args.kv_heads < 1:
+            raise SystemExit("--q-heads must be a multiple of --kv-heads")
+        sh.n_q_heads, sh.n_kv_heads = args.q_heads, args.kv_heads
     B, nq, nv, nf = sh.batch, sh.n_q, sh.n_verify, sh.n_foresight
     Hq, Hkv, D, NL = sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.n_layers
     growth_pages = 8 * B                      # room for the tokens appended while the bench runs
@@ -195,7 +201,7 @@ def main():
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "pv_attn_mfma_stream_batch32_kv8192_traffic.json")
     # the committed counter summary covers the default workload only
-    if os.path.exists(tpath) and not args.ragged and B == 32 and args.kv == 8192:
+    if os.path.exists(tpath) and not args.ragged and B == 32 and args.kv == 8192 and (Hq, Hkv) == (28, 4):
         try:
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
         except Exception:
@@ -218,7 +224,7 @@ def main():
             "workload": ("config3_ragged_1k_16k" if args.ragged else f"batch{B}_kv{args.kv}") +
                         f"_layers{NL}_q{Hq}_kv{Hkv}_d{D}_verify{nv}_foresight{nf}",
             "batch": B, "mean_kv_len": round(float(np.mean(lengths)), 1), "layers": NL,
-            "step": "28-layer attention + accept + commit, compaction 56->8 every 14 steps",
+            "step": f"{NL}-layer attention + accept + commit, compaction 56->8 every 14 steps",
             "attention_tile_assignment": "fixed (bit-reproducible)" if args.deterministic else
                                          "first come, first served (reproducible to rounding)",
         },
