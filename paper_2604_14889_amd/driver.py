@@ -87,7 +87,7 @@ class MemoSightDriver:
         self.obs.forward(kind, list(seq_ids), tokens, pos, n_verify, n_foresight, logits, targets, ctx)
         return pos_d, targets
 
-    # ---- Algorithm 1, line 1: prefill -------------------------------------------------------------
+    # ---- Algorithm 1, initialisation: prefill -------------------------------------------------------------
     def prefill(self, seq_ids: Sequence[int], prompts: Sequence[Sequence[int]], chunk: int = M.MS_MAX_QUERIES):
         """Runs each prompt through the model in causal chunks and caches all of it; the greedy token
         after the prompt's last token becomes the first token of the first reasoning step."""
