@@ -112,15 +112,17 @@ class Decoder:
         self.logits = buf(max_rows, cfg.vocab)
         self.targets = buf(max_rows, dtype=torch.int32)
         self.attn_events = None   # optional list of (start, stop) events around every attention call
-        self.qkv_split, self.down_split = 2, 4
+        # K is split further when a step has few rows (one row tile: half as many workgroups);
+        # measured at Qwen2.5-7B widths: Q/K/V 4 ways up to 256 rows, 2 above; down 8 and 4
+        self.splits_few, self.splits_many = (4, 8), (2, 4)
         self.hand_gemm = (hand_gemm and qd % 128 == 0 and kd % 128 == 0 and cfg.hidden % 128 == 0 and
-                          cfg.hidden % (32 * self.qkv_split) == 0 and cfg.inter % (32 * self.down_split) == 0)
+                          cfg.hidden % (32 * 4) == 0 and cfg.inter % (32 * 8) == 0)
         # gate/up + SwiGLU in one GEMM: keeps a second, row-interleaved copy of the gate/up weights
         self.fused_mlp = fused_mlp and self.hand_gemm and cfg.inter % 64 == 0
         self.gemm_ws = None
         if self.hand_gemm:
-            need = max(M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, cfg.hidden, self.qkv_split),
-                       M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.down_split),
+            need = max(M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, cfg.hidden, self.splits_few[0]),
+                       M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[1]),
                        M.ms_gemm_workspace_bytes(max_rows, 2 * cfg.inter, cfg.hidden, 1) if self.fused_mlp else 0)
             self.gemm_ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
@@ -143,13 +145,14 @@ class Decoder:
             self._kv[rows] = (torch.empty(cfg.n_layers, rows, kd, dtype=torch.bfloat16, device=h.device),
                               torch.empty(cfg.n_layers, rows, kd, dtype=torch.bfloat16, device=h.device))
         self.k_new, self.v_new = self._kv[rows]
+        qkv_split, down_split = self.splits_few if rows <= 256 else self.splits_many
         M.ms_embed_rows(w.embed, tokens, h)
         delta = None
         for li, lw in enumerate(w.layers):
             M.ms_add_rmsnorm(h, delta, lw.ln1, cfg.eps, x)
             k, v = self.k_new[li], self.v_new[li]
             if self.hand_gemm:
-                M.ms_gemm_bf16(x, lw.wqkv, lw.bqkv, [q, k, v], self.qkv_split, self.gemm_ws)
+                M.ms_gemm_bf16(x, lw.wqkv, lw.bqkv, [q, k, v], qkv_split, self.gemm_ws)
             else:
                 torch.addmm(lw.bq, x, lw.wq.t(), out=q)
                 torch.addmm(lw.bk, x, lw.wk.t(), out=k)
@@ -170,7 +173,7 @@ class Decoder:
                 torch.mm(x, lw.w_gate_up.t(), out=gate_up)
                 M.ms_swiglu(gate_up, act)
             if self.hand_gemm:
-                M.ms_gemm_bf16(act, lw.w_down, None, [proj], self.down_split, self.gemm_ws)
+                M.ms_gemm_bf16(act, lw.w_down, None, [proj], down_split, self.gemm_ws)
             else:
                 torch.mm(act, lw.w_down.t(), out=proj)
             delta = proj
