@@ -52,6 +52,8 @@ def parse():
     ap.add_argument("--deterministic", action="store_true",
                     help="fixed tile-to-wave assignment in the attention kernel (bit-reproducible results, about 1.5 %% slower)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gemm-tuning", action="store_true",
+                    help="decode_step: take torch's default pick for the library GEMMs instead of timing the candidates once")
     ap.add_argument("--cpu-seqs", type=int, default=32, help="sequences the CPU oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 1 GiB device copies, for scaling rocprofv3 byte counters")
@@ -294,7 +296,7 @@ def decode_step_bench(args):
         ses.pool[layer].normal_(0.0, 0.5, generator=gen)
     ids = [M.ms_seq_import(ses.cache, n, pt) for n, pt in zip(lengths, page_tables)]
     weights = D.DecoderTensors.random(cfg, W.BASE_SEED + 6, dev)
-    dec = D.Decoder(cfg, weights, ses, B * nq)
+    dec = D.Decoder(cfg, weights, ses, B * nq, tune_library_gemms=not args.no_gemm_tuning)
     ses.ensure_workspace(B, nq)
 
     foresight_id = cfg.vocab - 1                           # stands for the <f> token
@@ -366,6 +368,7 @@ def decode_step_bench(args):
             "step": "embedding, 28 blocks (hand-written norm / attention / SwiGLU kernels, hand-written GEMM for the fused "
                     "Q/K/V and the down projection, torch GEMMs for the output, gate/up and LM-head projections), greedy "
                     "tokens, accept, commit; random weights, so about one token per sequence is accepted per step",
+            "library_gemms": "default pick" if args.no_gemm_tuning else "candidates timed once per shape (torch.cuda.tunable), in the warm-up",
         },
         "query_tokens_per_s": round(B * nq * args.steps / (t1 - t0), 1),
         "committed_per_step_per_seq": round(state["committed"] / args.steps / B, 3),

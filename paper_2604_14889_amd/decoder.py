@@ -89,12 +89,22 @@ class Decoder:
     """Buffers and the step driver for up to max_rows = B * n_q tokens per step."""
 
     def __init__(self, cfg: DecoderConfig, weights: DecoderTensors, session: Session, max_rows: int,
-                 hand_gemm: bool = True, fused_mlp: bool = False):
+                 hand_gemm: bool = True, fused_mlp: bool = False, tune_library_gemms: bool = False):
         """hand_gemm: run the Q/K/V and down projections on this library's GEMM (needs widths that
         are multiples of 128 and depths that are multiples of 128); otherwise everything dense goes
         through torch."""
         self.cfg, self.w, self.ses = cfg, weights, session
         dev = weights.embed.device
+        if tune_library_gemms:
+            # the projections left to torch: let it time the library's solutions for each new shape
+            # once (a few seconds at the first call) instead of taking the default pick.  Process-wide.
+            import torch.cuda.tunable as tunable
+            tunable.enable(True)
+            tunable.tuning_enable(True)
+            tunable.set_max_tuning_duration(200)
+            import os
+            import tempfile
+            tunable.set_filename(os.path.join(tempfile.gettempdir(), "memosight_library_gemms.csv"))   # its results file
         qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
 
         def buf(*shape, dtype=torch.bfloat16):
