@@ -54,6 +54,40 @@ def test_gemm_matches_fp64_definition(m, n, k, widths, split, with_bias):
     assert (err <= bound).all(), f"max excess {np.max(err - bound):.3e} at {np.unravel_index(np.argmax(err - bound), err.shape)}"
 
 
+@pytest.mark.parametrize("case", range(10))
+def test_gemm_random_shapes(case):
+    """Seeded random shapes: ragged row counts (also across the 256-row tile), several destinations,
+    every split depth the shape allows."""
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import session as S
+    rng = W.make_rng(905, case)
+    m = int(rng.choice([1, 3, 63, 64, 65, 255, 256, 257, 300, 511, 513, 600]))
+    n_blocks = int(rng.integers(1, 17))
+    split = int(rng.choice([1, 1, 2, 3, 4, 8]))
+    k = 32 * split * int(rng.integers(1, 9))
+    n = 128 * n_blocks
+    cuts = sorted(set(int(c) for c in rng.integers(1, n_blocks, size=int(rng.integers(0, 4)))) if n_blocks > 1 else [])[:3]
+    bounds = [0] + [128 * c for c in cuts] + [n]
+    widths = [b - a for a, b in zip(bounds, bounds[1:])]
+    with_bias = bool(rng.integers(0, 2))
+    a = W.normal_bf16_bits(rng, (m, k), 1.0)
+    w = W.normal_bf16_bits(rng, (n, k), k ** -0.5)
+    b = W.normal_bf16_bits(rng, (n,), 0.5) if with_bias else None
+    f64 = lambda x: O.bf16_bits_to_f32(x).astype(np.float64)
+    ref = f64(a) @ f64(w).T + (f64(b) if with_bias else 0.0)
+    outs = [torch.full((m, wd), float("nan"), dtype=torch.bfloat16, device="cuda") for wd in widths]
+    need = M.ms_gemm_workspace_bytes(m, n, k, split)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+    M.ms_gemm_bf16(S.to_device(a, M.MS_BF16), S.to_device(w, M.MS_BF16), None if b is None else S.to_device(b, M.MS_BF16),
+                   outs, split, ws)
+    torch.cuda.synchronize()
+    got = np.concatenate([o.float().cpu().numpy() for o in outs], axis=1).astype(np.float64)
+    assert np.isfinite(got).all(), f"m {m} n {n} k {k} split {split} widths {widths}"
+    err = np.abs(got - ref)
+    bound = 2.0 ** -8 * np.abs(ref) + 1e-5 * np.abs(ref).max()
+    assert (err <= bound).all(), f"m {m} n {n} k {k} split {split} widths {widths}: max excess {np.max(err - bound):.3e}"
+
+
 def test_gemm_last_round_split_is_optional():
     """Without workspace the same shape runs whole tiles throughout; both ways give the product."""
     from paper_2604_14889_amd import binding as M
