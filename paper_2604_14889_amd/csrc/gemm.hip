@@ -81,7 +81,7 @@ __device__ __forceinline__ void gemm_lds_barrier() {
 }
 
 template <int kMode>
-__global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
+__global__ __launch_bounds__(kGemmThreads, 4) void gemm_tn_bf16(GemmArgs g) {
     constexpr bool kSplit = kMode == kGemmAllPartial;
     __shared__ __attribute__((aligned(16))) char smem[2 * kGemmStageBytes];
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
@@ -109,9 +109,13 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_tn_bf16(GemmArgs g) {
 
     // global -> LDS staging.  Four consecutive threads bring the 64 bytes one row contributes to a
     // step, so a load instruction of a wave covers 16 rows x 64 contiguous bytes; thread t handles
-    // chunk t % 4 of activation rows t / 4 and t / 4 + 128 and of weight row t / 4.
+    // chunk t % 4 of activation rows r and r + 128 and of weight row r, r = t / 4 up to the order below.
     // Rows past M are clamped (read again, never stored).
-    const int sr = tid >> 2, sc = tid & 3;
+    // Within each block of 16 rows the 4 x 4 (lane group, row) order is transposed: the 16 lanes that
+    // store together then hold rows r, r + 4, r + 8, r + 12, whose 80-byte strides put their four
+    // 16-byte chunks on 16 different groups of 4 banks (rows r .. r + 3 would collide two ways).
+    const int sr_lin = tid >> 2, sc = tid & 3;
+    const int sr = (sr_lin & ~15) | ((sr_lin & 3) << 2) | ((sr_lin >> 2) & 3);
     const uint16_t* a_src[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
