@@ -251,7 +251,10 @@ int ms_argmax_rows(const void* logits, int n, int vocab, long ld, int* out, void
  * aligned workspace.  With split_k == 1 that function returns what the call can use to split the
  * tiles of a partly filled last round over K (0 if the shape has none on the current device);
  * without that much workspace the call computes whole tiles throughout, with the same result up to
- * the order of the fp32 additions. */
+ * the order of the fp32 additions.  With M <= 8 and K % 512 == 0 (the step of a single sequence)
+ * the product is bound by reading W once and runs on a kernel that streams whole weight rows
+ * (no tiles, no matrix cores); it divides K by what fits its LDS share (ms_gemm_workspace_bytes
+ * covers the partial sums) and ignores split_k unless the workspace is too small for that. */
 size_t ms_gemm_workspace_bytes(int M, int N, int K, int split_k);
 int ms_gemm_bf16(const void* a, const void* w, const void* bias, int M, int N, int K, int n_out,
                  void* const* out, const int* out_col, int split_k, void* workspace, size_t ws_bytes,

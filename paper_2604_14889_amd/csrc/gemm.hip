@@ -313,6 +313,127 @@ __global__ __launch_bounds__(256) void gemm_reduce(GemmArgs g, int parts, int co
     *reinterpret_cast<uint2*>(dst + (size_t)m * ld + (n - dcol0)) = pk;
 }
 
+typedef __attribute__((ext_vector_type(4))) uint32_t g_u32x4_t;
+
+// ---------------------------------------------------------------------------------------------
+// At most 8 rows (the step of a single sequence).  The product is bound by reading W once; tiles
+// and matrix cores buy nothing.  A wave owns kR weight rows; per K step of 512 a lane takes 16
+// bytes of each of them, so that one load instruction reads 1 KB of one row, and multiplies them
+// with the activations' same 8 elements (from LDS, where the workgroup keeps its K range of all
+// rows of A; read and widened once per step for all kR rows) with fp32 FMAs into sums per lane
+// (v_dot2c_f32_bf16 was slower: the kernel became bound by it at 8 rows).
+// The 64 lanes' sums are added at the end (DPP), lane 63 writes.  A workgroup's K range is what fits
+// 64 KB of LDS with all rows of A (at most 16 steps): deeper K is divided over `parts` workgroups
+// (fp32 partials, summed by gemm_reduce).
+// ---------------------------------------------------------------------------------------------
+constexpr int kGemvStepK = 512;            // 64 lanes x 8 elements
+constexpr int kGemvThreads = 512;          // 8 waves share the staged activations
+constexpr int kGemvLdsBytes = 64 * 1024;
+
+// the 8 bf16 of a 16-byte chunk as fp32 (a shift or a mask each)
+__device__ __forceinline__ void unpack8_bf16(uint4 v, float (&f)[8]) {
+    f[0] = __uint_as_float(v.x << 16);
+    f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16);
+    f[3] = __uint_as_float(v.y & 0xffff0000u);
+    f[4] = __uint_as_float(v.z << 16);
+    f[5] = __uint_as_float(v.z & 0xffff0000u);
+    f[6] = __uint_as_float(v.w << 16);
+    f[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+
+// Sum over the wave; the total arrives in lane 63.  Within rows of 16 lanes: the other lane of a
+// pair, the other pair of a quad, the mirrored half row, the mirrored row; then lane 15 of rows 0
+// and 2 into rows 1 and 3, lane 31 into rows 2 and 3.
+__device__ __forceinline__ float wave_sum_to_last_lane(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xA, 0xF, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false));
+    return v;
+}
+
+template <int kM, int kR>   // rows of A (1 .. 8), weight rows per wave
+__global__ __launch_bounds__(kGemvThreads) void gemv_rows_bf16(GemmArgs g, int parts) {
+    extern __shared__ __attribute__((aligned(16))) char a_lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int steps_total = g.K / kGemvStepK;
+    const int part = blockIdx.y;
+    const int s_lo = (int)((long)steps_total * part / parts), s_hi = (int)((long)steps_total * (part + 1) / parts);
+    const int steps = s_hi - s_lo, kp = steps * kGemvStepK;
+    // the workgroup's K range of A: [kM][kp] bf16 (kM = M)
+    for (int c = tid; c < kM * (kp / 8); c += kGemvThreads) {
+        const int m = c / (kp / 8), kc = c % (kp / 8);
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (m < g.M) v = *reinterpret_cast<const uint4*>(g.a + (size_t)m * g.K + (size_t)s_lo * kGemvStepK + 8 * kc);
+        *reinterpret_cast<uint4*>(a_lds + ((size_t)m * kp + 8 * kc) * 2) = v;
+    }
+    const int n0 = (blockIdx.x * (kGemvThreads / 64) + w) * kR;
+    const uint16_t* wp = g.w + (size_t)n0 * g.K + (size_t)s_lo * kGemvStepK + 8 * lane;
+    uint4 w0[kR], w1[kR];
+    const int last = steps - 1;
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        w0[r] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const g_u32x4_t*>(wp + (size_t)r * g.K)));
+        w1[r] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(
+            reinterpret_cast<const g_u32x4_t*>(wp + (size_t)r * g.K + (1 < last ? 1 : last) * kGemvStepK)));
+    }
+    float acc[kR][kM];
+#pragma unroll
+    for (int r = 0; r < kR; ++r)
+#pragma unroll
+        for (int m = 0; m < kM; ++m) acc[r][m] = 0.f;
+    __syncthreads();
+#define MS_GEMV_STEP(WV, s_)                                                                                  \
+    do {                                                                                                      \
+        float af[kM][8];                                                                                      \
+        _Pragma("unroll") for (int m = 0; m < kM; ++m) unpack8_bf16(                                          \
+            *reinterpret_cast<const uint4*>(a_lds + ((size_t)m * kp + (s_) * kGemvStepK + 8 * lane) * 2), af[m]); \
+        _Pragma("unroll") for (int r = 0; r < kR; ++r) {                                                      \
+            float wf[8];                                                                                      \
+            unpack8_bf16(WV[r], wf);                                                                          \
+            _Pragma("unroll") for (int m = 0; m < kM; ++m)                                                    \
+                _Pragma("unroll") for (int e = 0; e < 8; ++e) acc[r][m] = fmaf(wf[e], af[m][e], acc[r][m]);   \
+        }                                                                                                     \
+    } while (0)
+#define MS_GEMV_LOAD(WV, s_)                                                                                  \
+    do {                                                                                                      \
+        const int sc_ = (s_) < last ? (s_) : last; /* past the end: the last step again, unused */            \
+        _Pragma("unroll") for (int r = 0; r < kR; ++r) WV[r] = __builtin_bit_cast(uint4, __builtin_nontemporal_load( \
+            reinterpret_cast<const g_u32x4_t*>(wp + (size_t)r * g.K + sc_ * kGemvStepK)));                    \
+    } while (0)
+    for (int s = 0; s < steps; s += 2) {
+        MS_GEMV_STEP(w0, s);
+        MS_GEMV_LOAD(w0, s + 2);
+        if (s + 1 < steps) MS_GEMV_STEP(w1, s + 1);
+        MS_GEMV_LOAD(w1, s + 3);
+    }
+#undef MS_GEMV_STEP
+#undef MS_GEMV_LOAD
+#pragma unroll
+    for (int r = 0; r < kR; ++r)
+#pragma unroll
+        for (int m = 0; m < kM; ++m) acc[r][m] = wave_sum_to_last_lane(acc[r][m]);
+    if (lane != 63) return;
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        const int n = n0 + r;
+        uint16_t* dst = nullptr;
+        int col0 = 0, ld = 0;
+        if (parts == 1) pick_destination(g, n, dst, col0, ld);
+        const float b = parts == 1 && g.bias ? bf16_bits_to_float(g.bias[n]) : 0.f;
+#pragma unroll
+        for (int m = 0; m < kM; ++m) {
+            if (m >= g.M) continue;
+            if (parts > 1) g.partial[((size_t)part * g.M + m) * g.N + n] = acc[r][m];
+            else dst[(size_t)m * ld + (n - col0)] = float_to_bf16_bits(acc[r][m] + b);
+        }
+    }
+}
+
 static bool g_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Workgroups the chip holds at once (two per compute unit), for the current device.
@@ -365,6 +486,27 @@ static GemmPlan gemm_plan(int M, int N, int K, int split_k) {
     return p;
 }
 
+// At most 8 rows: the row-streaming kernel's launch shape (0 parts: shape not eligible).
+constexpr int kGemvMaxRows = 8;
+struct GemvPlan {
+    int parts, km, kr, lds_bytes;
+    size_t workspace_bytes;
+};
+static GemvPlan gemv_plan(int M, int N, int K) {
+    GemvPlan p = {0, 0, 0, 0, 0};
+    if (M > kGemvMaxRows || K % kGemvStepK) return p;
+    p.km = M;
+    int max_steps = kGemvLdsBytes / (p.km * kGemvStepK * 2);         // K steps whose rows of A fit the LDS share
+    if (max_steps > 16) max_steps = 16;
+    const int steps = K / kGemvStepK;
+    p.parts = (steps + max_steps - 1) / max_steps;
+    p.lds_bytes = p.km * ((steps + p.parts - 1) / p.parts) * kGemvStepK * 2;
+    const int want = gemm_slots();                                   // workgroups the chip holds two of per CU
+    p.kr = N / 64 >= want ? 8 : N / 32 >= want ? 4 : 2;              // weight rows per wave, 8 waves per workgroup
+    p.workspace_bytes = p.parts > 1 ? (size_t)p.parts * M * N * sizeof(float) : 0;
+    return p;
+}
+
 static int gemm_check_shape(const char* what, int M, int N, int K, int split_k) {
     if (M < 0 || N < 1 || K < 1 || split_k < 1) MS_FAIL(MS_ERR_INVALID, "%s: bad size", what);
     if (N % kGemmBN || K % (kGemmBK * split_k))
@@ -376,7 +518,42 @@ static int gemm_check_shape(const char* what, int M, int N, int K, int split_k) 
 }
 
 // Launches the tiles (and the reduction of the parts, if any).  g holds operands and destinations.
+template <int kM>
+static void gemv_dispatch(const GemmArgs& g, const GemvPlan& v, hipStream_t stream) {
+    const dim3 grid((unsigned)(g.N / (kGemvThreads / 64 * v.kr)), (unsigned)v.parts);
+    if (v.kr == 8)
+        hipLaunchKernelGGL((gemv_rows_bf16<kM, 8>), grid, dim3(kGemvThreads), v.lds_bytes, stream, g, v.parts);
+    else if (v.kr == 4)
+        hipLaunchKernelGGL((gemv_rows_bf16<kM, 4>), grid, dim3(kGemvThreads), v.lds_bytes, stream, g, v.parts);
+    else
+        hipLaunchKernelGGL((gemv_rows_bf16<kM, 2>), grid, dim3(kGemvThreads), v.lds_bytes, stream, g, v.parts);
+}
+
 static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, size_t ws_bytes, hipStream_t stream) {
+    if (!swiglu) {
+        const GemvPlan v = gemv_plan(g.M, g.N, g.K);
+        if (v.parts == 1 || (v.parts > 1 && workspace && ws_bytes >= v.workspace_bytes && g_aligned16(workspace))) {
+            g.k_per_split = g.K;
+            g.partial = v.parts > 1 ? (float*)workspace : nullptr;
+            g.tail_first = g.tail_blocks = g.tail_k = g.tail_col0 = 0;
+            switch (v.km) {
+                case 1: gemv_dispatch<1>(g, v, stream); break;
+                case 2: gemv_dispatch<2>(g, v, stream); break;
+                case 3: gemv_dispatch<3>(g, v, stream); break;
+                case 4: gemv_dispatch<4>(g, v, stream); break;
+                case 5: gemv_dispatch<5>(g, v, stream); break;
+                case 6: gemv_dispatch<6>(g, v, stream); break;
+                case 7: gemv_dispatch<7>(g, v, stream); break;
+                default: gemv_dispatch<8>(g, v, stream); break;
+            }
+            if (v.parts > 1) {
+                const size_t quads = (size_t)g.M * g.N / 4;
+                hipLaunchKernelGGL((gemm_reduce<false>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, g, v.parts, 0);
+            }
+            MS_HIP_TRY(hipGetLastError());
+            return MS_OK;
+        }
+    }
     GemmPlan p = gemm_plan(g.M, g.N, g.K, split_k);
     if (split_k == 1 && p.tail_groups && (!workspace || ws_bytes < p.workspace_bytes || !g_aligned16(workspace))) {
         p.main_groups = p.n_groups;   // no room for the parts: whole tiles throughout
@@ -422,7 +599,9 @@ static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, s
 
 extern "C" size_t ms_gemm_workspace_bytes(int M, int N, int K, int split_k) {
     if (M < 1 || N < 1 || K < 1 || split_k < 1 || N % ms::kGemmBN || K % (ms::kGemmBK * split_k)) return 0;
-    return ms::gemm_plan(M, N, K, split_k).workspace_bytes;
+    const size_t tiled = ms::gemm_plan(M, N, K, split_k).workspace_bytes;
+    const size_t rows = ms::gemv_plan(M, N, K).workspace_bytes;   // enough for either kernel
+    return tiled > rows ? tiled : rows;
 }
 
 extern "C" int ms_gemm_bf16(const void* a, const void* w, const void* bias, int M, int N, int K, int n_out, void* const* out,

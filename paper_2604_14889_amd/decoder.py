@@ -13,6 +13,7 @@ Nothing here computes on the CPU; every call fails if the HIP library is missing
 """
 from __future__ import annotations
 
+import ctypes as C
 from dataclasses import dataclass
 from typing import List, Optional, Sequence
 
@@ -115,6 +116,7 @@ class Decoder:
         self.x = buf(max_rows, cfg.hidden)
         self.q = buf(max_rows, qd)
         self._kv = {}             # rows -> (k_new, v_new), each [L, rows, Hkv*D] contiguous for the commit
+        self._prepared = {}       # rows -> prepared argument tuples of the library calls
         self.attn = buf(max_rows, qd)
         self.proj = buf(max_rows, cfg.hidden)
         self.gate_up = buf(max_rows, 2 * cfg.inter)
@@ -133,6 +135,8 @@ class Decoder:
         if self.hand_gemm:
             need = max(M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, cfg.hidden, self.splits_few[0]),
                        M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[1]),
+                       M.ms_gemm_workspace_bytes(min(max_rows, 8), qd + 2 * kd, cfg.hidden, 1),
+                       M.ms_gemm_workspace_bytes(min(max_rows, 8), cfg.hidden, cfg.inter, 1),
                        M.ms_gemm_workspace_bytes(max_rows, 2 * cfg.inter, cfg.hidden, 1) if self.fused_mlp else 0)
             self.gemm_ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
@@ -155,6 +159,8 @@ class Decoder:
             self._kv[rows] = (torch.empty(cfg.n_layers, rows, kd, dtype=torch.bfloat16, device=h.device),
                               torch.empty(cfg.n_layers, rows, kd, dtype=torch.bfloat16, device=h.device))
         self.k_new, self.v_new = self._kv[rows]
+        if self.hand_gemm and not self.fused_mlp:
+            return self._step_prepared(seq_ids, tokens, pos, n_verify, n_foresight, ctx_new, rows)
         qkv_split, down_split = self.splits_few if rows <= 256 else self.splits_many
         M.ms_embed_rows(w.embed, tokens, h)
         delta = None
@@ -167,14 +173,8 @@ class Decoder:
                 torch.addmm(lw.bq, x, lw.wq.t(), out=q)
                 torch.addmm(lw.bk, x, lw.wk.t(), out=k)
                 torch.addmm(lw.bv, x, lw.wv.t(), out=v)
-            if self.attn_events is not None:
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
             self.ses.attention(li, seq_ids, n_verify, n_foresight, q.view(B, n_q, hq, d), k.view(B, n_q, hkv, d),
                                v.view(B, n_q, hkv, d), pos, ctx_new, 0.0, attn.view(B, n_q, hq, d))
-            if self.attn_events is not None:
-                e1.record()
-                self.attn_events.append((e0, e1))
             torch.mm(attn, lw.wo.t(), out=proj)
             M.ms_add_rmsnorm(h, proj, lw.ln2, cfg.eps, x)
             if self.fused_mlp:
@@ -190,6 +190,79 @@ class Decoder:
         M.ms_add_rmsnorm(h, delta, w.norm, cfg.eps, x)
         logits = self.logits[:rows]
         torch.mm(x, w.lm_head.t(), out=logits)
+        M.ms_argmax_rows(logits, cfg.vocab, self.targets[:rows])
+        return logits, self.targets[:rows]
+
+    # ---- the same step with the library calls' arguments prepared once -------------------------------
+    def _prepare(self, rows: int):
+        """Argument tuples of every per-layer library call of a step of `rows` rows.  All buffers are
+        this object's and all weights are fixed, so the addresses never change; a step with a single
+        sequence is otherwise bound by re-deriving them in Python for its ~200 calls."""
+        cfg, w = self.cfg, self.w
+        ptr = lambda t: t.data_ptr()
+        qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+        h, x, q, attn, proj, gate_up, act = (ptr(t) for t in (self.h, self.x, self.q, self.attn, self.proj, self.gate_up, self.act))
+        k_all, v_all = self._kv[rows]
+        ws, ws_bytes = ptr(self.gemm_ws), self.gemm_ws.numel()
+        qkv_split, down_split = self.splits_few if rows <= 256 else self.splits_many
+        cols_qkv = M.int_array([0, qd, qd + kd, qd + 2 * kd])
+        cols_h = M.int_array([0, cfg.hidden])
+        outs_proj = (C.c_void_p * 1)(proj)
+        layers = []
+        for li, lw in enumerate(w.layers):
+            k, v = ptr(k_all[li]), ptr(v_all[li])
+            layers.append(dict(
+                keep=(outs_proj, cols_qkv, cols_h),
+                norm1=(h, proj if li else None, ptr(lw.ln1), cfg.eps, x, rows, cfg.hidden),
+                qkv=(x, ptr(lw.wqkv), ptr(lw.bqkv), rows, qd + 2 * kd, cfg.hidden, 3, (C.c_void_p * 3)(q, k, v), cols_qkv,
+                     qkv_split, ws, ws_bytes),
+                k=k, v=v,
+                o=(attn, ptr(lw.wo), None, rows, cfg.hidden, qd, 1, outs_proj, cols_h, 1, ws, ws_bytes),
+                wo_t=lw.wo.t(), w_gate_up_t=lw.w_gate_up.t(),
+                norm2=(h, proj, ptr(lw.ln2), cfg.eps, x, rows, cfg.hidden),
+                swiglu=(gate_up, act, rows, cfg.inter),
+                down=(act, ptr(lw.w_down), None, rows, cfg.hidden, cfg.inter, 1, outs_proj, cols_h, down_split, ws, ws_bytes)))
+        return dict(layers=layers, final=(h, proj, ptr(w.norm), cfg.eps, x, rows, cfg.hidden), q=q, attn=attn)
+
+    def _step_prepared(self, seq_ids, tokens, pos, n_verify, n_foresight, ctx_new, rows):
+        cfg, w, lib, check = self.cfg, self.w, M.lib, M._check
+        if rows not in self._prepared:
+            self._prepared[rows] = self._prepare(rows)
+        prep = self._prepared[rows]
+        B, n_q = len(seq_ids), n_verify + n_foresight
+        if tokens.numel() != rows or pos.numel() != rows or (ctx_new is not None and ctx_new.numel() != rows):
+            raise M.MsError(M.MS_ERR_INVALID, "tokens / pos / ctx_new do not have one entry per row")
+        st = M._stream(None)
+        ids = M.int_array(seq_ids)
+        att_ws = self.ses.ensure_workspace(B, n_q)
+        att_ws_ptr, att_ws_bytes = att_ws.data_ptr(), att_ws.numel() * att_ws.element_size()
+        pos_ptr, ctx_ptr = M._dev(pos), M._dev(ctx_new)
+        cache, q, attn = self.ses.cache, prep["q"], prep["attn"]
+        x_t, attn_t, proj_t, gate_up_t = self.x[:rows], self.attn[:rows], self.proj[:rows], self.gate_up[:rows]
+        few = rows <= 8     # few rows: the row-streaming kernel is ahead of the library on the output projection too
+        M.ms_embed_rows(w.embed, tokens, self.h[:rows])
+        for li, c in enumerate(prep["layers"]):
+            check(lib.ms_add_rmsnorm(*c["norm1"], st))
+            check(lib.ms_gemm_bf16(*c["qkv"], st))
+            if self.attn_events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            check(lib.ms_predict_verify_attention(cache, li, B, ids, n_verify, n_foresight, q, c["k"], c["v"], pos_ptr, ctx_ptr, 0.0,
+                                                  attn, att_ws_ptr, att_ws_bytes, st))
+            if self.attn_events is not None:
+                e1.record()
+                self.attn_events.append((e0, e1))
+            if few:
+                check(lib.ms_gemm_bf16(*c["o"], st))
+            else:
+                torch.mm(attn_t, c["wo_t"], out=proj_t)
+            check(lib.ms_add_rmsnorm(*c["norm2"], st))
+            torch.mm(x_t, c["w_gate_up_t"], out=gate_up_t)
+            check(lib.ms_swiglu(*c["swiglu"], st))
+            check(lib.ms_gemm_bf16(*c["down"], st))
+        check(lib.ms_add_rmsnorm(*prep["final"], st))
+        logits = self.logits[:rows]
+        torch.mm(x_t, w.lm_head.t(), out=logits)
         M.ms_argmax_rows(logits, cfg.vocab, self.targets[:rows])
         return logits, self.targets[:rows]
 
