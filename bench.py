@@ -52,6 +52,8 @@ def parse():
     ap.add_argument("--deterministic", action="store_true",
                     help="fixed tile-to-wave assignment in the attention kernel (bit-reproducible results, about 1.5 %% slower)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fused-lm-head", action="store_true",
+                    help="decode_step: LM head and greedy token in one kernel of the library (fp32 sums, no logits)")
     ap.add_argument("--no-gemm-tuning", action="store_true",
                     help="decode_step: take torch's default pick for the library GEMMs instead of timing the candidates once")
     ap.add_argument("--cpu-seqs", type=int, default=32, help="sequences the CPU oracle is timed on")
@@ -296,7 +298,7 @@ def decode_step_bench(args):
         ses.pool[layer].normal_(0.0, 0.5, generator=gen)
     ids = [M.ms_seq_import(ses.cache, n, pt) for n, pt in zip(lengths, page_tables)]
     weights = D.DecoderTensors.random(cfg, W.BASE_SEED + 6, dev)
-    dec = D.Decoder(cfg, weights, ses, B * nq, tune_library_gemms=not args.no_gemm_tuning)
+    dec = D.Decoder(cfg, weights, ses, B * nq, tune_library_gemms=not args.no_gemm_tuning, fused_lm_head=args.fused_lm_head)
     ses.ensure_workspace(B, nq)
 
     foresight_id = cfg.vocab - 1                           # stands for the <f> token

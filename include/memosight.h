@@ -269,6 +269,15 @@ int ms_gemm_bf16(const void* a, const void* w, const void* bias, int M, int N, i
 int ms_gemm_swiglu_bf16(const void* a, const void* w_gate_up, int M, int inter, int K, void* out,
                         void* workspace, size_t ws_bytes, void* stream);
 
+/* The LM head and the greedy token in one: out[m] = argmax over n of A[m] . W[n] (device int32 [M]),
+ * taken on the fp32 sums, the lowest column among equal maxima, NaN never wins (a row of NaN gives
+ * 0); the [M][vocab] logits are not written.  Operands as for ms_gemm_bf16 (vocab % 128 == 0,
+ * K % 32 == 0); workspace: ms_lm_head_argmax_workspace_bytes(M, vocab, K) bytes, 16-byte aligned,
+ * MS_ERR_WORKSPACE without it.  (The greedy token of Algorithm 1's SpeculativeStep.) */
+size_t ms_lm_head_argmax_workspace_bytes(int M, int vocab, int K);
+int ms_lm_head_argmax_bf16(const void* a, const void* w, int M, int vocab, int K, int* out,
+                           void* workspace, size_t ws_bytes, void* stream);
+
 /* ---- profiling ------------------------------------------------------------------------------- */
 
 /* From now on, every stride-th ms_predict_verify_attention call on this cache that runs the

@@ -77,6 +77,8 @@ _SIGS = {
     "ms_argmax_rows": (_I, [_P, _I, _I, C.c_long, _P, _P]),
     "ms_gemm_workspace_bytes": (_SZ, [_I, _I, _I, _I]),
     "ms_gemm_swiglu_bf16": (_I, [_P, _P, _I, _I, _I, _P, _P, _SZ, _P]),
+    "ms_lm_head_argmax_workspace_bytes": (_SZ, [_I, _I, _I]),
+    "ms_lm_head_argmax_bf16": (_I, [_P, _P, _I, _I, _I, _P, _P, _SZ, _P]),
     "ms_gemm_bf16": (_I, [_P, _P, _P, _I, _I, _I, _I, C.POINTER(_P), _IP, _I, _P, _SZ, _P]),
     "ms_profile_attention": (_I, [_P, _I, _I]),
     "ms_profile_read": (_I, [_P, C.POINTER(C.c_float), _I, _IP]),
@@ -306,6 +308,21 @@ def ms_gemm_swiglu_bf16(a, w_gate_up, out, workspace=None, stream=None) -> None:
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.ms_gemm_swiglu_bf16(_sized(None, a, "a", M_ * K, 2), _sized(None, w_gate_up, "w_gate_up", 2 * inter * K, 2), M_, inter, K,
                                    _sized(None, out, "out", M_ * inter, 2), _dev(workspace), ws_bytes, _stream(stream)))
+
+
+def ms_lm_head_argmax_workspace_bytes(M: int, vocab: int, K: int) -> int:
+    return lib.ms_lm_head_argmax_workspace_bytes(M, vocab, K)
+
+
+def ms_lm_head_argmax_bf16(a, w, out, workspace, stream=None) -> None:
+    """out[m] (int32) = greedy token of row m: argmax of a[m] . w[n] over n on the fp32 sums."""
+    M_, K = a.shape
+    vocab = w.shape[0]
+    if w.shape[1] != K:
+        raise MsError(MS_ERR_INVALID, "ms_lm_head_argmax_bf16: shapes do not match")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.ms_lm_head_argmax_bf16(_sized(None, a, "a", M_ * K, 2), _sized(None, w, "w", vocab * K, 2), M_, vocab, K,
+                                      _sized(None, out, "out", M_, 4), _dev(workspace), ws_bytes, _stream(stream)))
 
 
 def interleave_gate_up(w_gate, w_up):

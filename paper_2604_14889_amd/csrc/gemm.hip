@@ -45,9 +45,12 @@ struct GemmArgs {
     // K-split last round (split_k == 1 only): blocks from tail_first on compute K part
     // (block - tail_first) / tail_blocks of tile tail_first + (block - tail_first) % tail_blocks
     int tail_first, tail_blocks, tail_k, tail_col0;
+    // greedy-token mode: no C is written; every group of columns leaves its best (value, column) per
+    // row as a 64-bit key in keys[group][M], and argmax_finish picks the best key of each row
+    unsigned long long* keys;
 };
 
-enum GemmMode { kGemmPlain = 0, kGemmAllPartial = 1, kGemmSwiglu = 2 };
+enum GemmMode { kGemmPlain = 0, kGemmAllPartial = 1, kGemmSwiglu = 2, kGemmArgmax = 3 };
 
 // Destination of column n: base pointer, first column and width.  Written as a chain of selects
 // over constant indices (a run-time index into the argument arrays would move them to memory).
@@ -71,6 +74,16 @@ __device__ __forceinline__ uint32_t g_pack_bf16x2(float a, float b) {
 
 // silu(gate) * up in fp32 (SwiGLU of the models' MLP)
 __device__ __forceinline__ float swiglu_value(float gate, float up) { return gate / (1.f + __expf(-gate)) * up; }
+
+// Greedy token over fp32 sums: a 64-bit key orders by value first, then by lower column; NaN never
+// wins (key 0).  max over keys = the largest value, the lowest column among equals.
+__device__ __forceinline__ unsigned long long argmax_key(float v, int n) {
+    if (v != v) return 0ull;
+    uint32_t u = __float_as_uint(v);
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return ((unsigned long long)u << 32) | (0xffffffffu - (uint32_t)n);
+}
+__device__ __forceinline__ unsigned long long key_max(unsigned long long a, unsigned long long b) { return a > b ? a : b; }
 
 // Workgroup barrier that orders LDS traffic only (a plain __syncthreads() would also wait for the
 // global loads of the steps ahead).
@@ -220,6 +233,24 @@ __global__ __launch_bounds__(kGemmThreads, 4) void gemm_tn_bf16(GemmArgs g) {
         }
         return;
     }
+    if (kMode == kGemmArgmax) {
+        // group = (column tile, wave column): 64 columns; a lane first folds its 32 of them, then the
+        // two half-waves (same row m, the other 4-column pieces) are folded through a lane exchange
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+            unsigned long long best = 0ull;
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    best = key_max(best, argmax_key(acc[ni][mi][i], n0 + 64 * wn + 32 * ni + 8 * (i >> 2) + 4 * hf + (i & 3)));
+            const uint32_t lo = __shfl_xor((int)(uint32_t)best, 32, 64), hi = __shfl_xor((int)(uint32_t)(best >> 32), 32, 64);
+            best = key_max(best, ((unsigned long long)hi << 32) | lo);
+            const int m = m0 + 64 * wm + 32 * mi + l32;
+            if (m < g.M && hf == 0) g.keys[(size_t)(n_tile * 2 + wn) * g.M + m] = best;
+        }
+        return;
+    }
     if (kMode == kGemmSwiglu) {
         // weight rows 64 wn .. + 32 of the tile are gate rows, the next 32 the matching up rows:
         // accumulators [0][mi] and [1][mi] hold gate and up of output column n0 / 2 + 32 wn + ...
@@ -311,6 +342,21 @@ __global__ __launch_bounds__(256) void gemm_reduce(GemmArgs g, int parts, int co
     pk.x = g_pack_bf16x2(s.x, s.y);
     pk.y = g_pack_bf16x2(s.z, s.w);
     *reinterpret_cast<uint2*>(dst + (size_t)m * ld + (n - dcol0)) = pk;
+}
+
+// out[m] = column of the best key among keys[0 .. groups)[m]; a row without any key (all NaN) gives 0.
+__global__ __launch_bounds__(256) void argmax_finish(const unsigned long long* keys, int groups, int M, int* out) {
+    __shared__ unsigned long long red[256];
+    const int m = blockIdx.x;
+    unsigned long long best = 0ull;
+    for (int gI = threadIdx.x; gI < groups; gI += 256) best = key_max(best, keys[(size_t)gI * M + m]);
+    red[threadIdx.x] = best;
+    __syncthreads();
+    for (int s_ = 128; s_ > 0; s_ >>= 1) {
+        if ((int)threadIdx.x < s_) red[threadIdx.x] = key_max(red[threadIdx.x], red[threadIdx.x + s_]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[m] = red[0] ? (int)(0xffffffffu - (uint32_t)red[0]) : 0;
 }
 
 typedef __attribute__((ext_vector_type(4))) uint32_t g_u32x4_t;
@@ -418,6 +464,16 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_rows_bf16(GemmArgs g, int p
 #pragma unroll
         for (int m = 0; m < kM; ++m) acc[r][m] = wave_sum_to_last_lane(acc[r][m]);
     if (lane != 63) return;
+    if (g.keys) {   // greedy-token mode (parts == 1): the best of this wave's rows per row of A
+#pragma unroll
+        for (int m = 0; m < kM; ++m) {
+            unsigned long long best = 0ull;
+#pragma unroll
+            for (int r = 0; r < kR; ++r) best = key_max(best, argmax_key(acc[r][m], n0 + r));
+            g.keys[(size_t)(n0 / kR) * g.M + m] = best;
+        }
+        return;
+    }
 #pragma unroll
     for (int r = 0; r < kR; ++r) {
         const int n = n0 + r;
@@ -621,6 +677,7 @@ extern "C" int ms_gemm_bf16(const void* a, const void* w, const void* bias, int 
     g.N = N;
     g.K = K;
     g.n_out = n_out;
+    g.keys = nullptr;
     if (out_col[0] != 0 || out_col[n_out] != N) MS_FAIL(MS_ERR_INVALID, "ms_gemm_bf16: destinations must cover columns 0 .. N");
     for (int i = 0; i < n_out; ++i) {
         if (out_col[i + 1] <= out_col[i] || out_col[i] % kGemmBN || !out[i] || (reinterpret_cast<uintptr_t>(out[i]) & 7u) ||
@@ -652,6 +709,7 @@ extern "C" int ms_gemm_swiglu_bf16(const void* a, const void* w_gate_up, int M, 
     g.a = (const uint16_t*)a;
     g.w = (const uint16_t*)w_gate_up;
     g.bias = nullptr;
+    g.keys = nullptr;
     g.M = M;
     g.N = N;
     g.K = K;
@@ -661,4 +719,68 @@ extern "C" int ms_gemm_swiglu_bf16(const void* a, const void* w_gate_up, int M, 
     for (int i = 1; i < kGemmMaxOut; ++i) g.out[i] = nullptr;
     for (int i = 1; i <= kGemmMaxOut; ++i) g.out_col[i] = N;
     return gemm_launch(g, 1, true, workspace, ws_bytes, (hipStream_t)stream);
+}
+
+// Column groups that leave a key per row in greedy-token mode, for the kernel the shape runs on.
+static int argmax_groups(int M, int N, int K) {
+    const ms::GemvPlan v = ms::gemv_plan(M, N, K);
+    return v.parts == 1 ? N / v.kr : N / ms::kGemmBN * 2;
+}
+
+extern "C" size_t ms_lm_head_argmax_workspace_bytes(int M, int vocab, int K) {
+    if (M < 1 || vocab < 1 || K < 1 || vocab % ms::kGemmBN || K % ms::kGemmBK) return 0;
+    return (size_t)argmax_groups(M, vocab, K) * M * sizeof(unsigned long long);
+}
+
+extern "C" int ms_lm_head_argmax_bf16(const void* a, const void* w, int M, int vocab, int K, int* out, void* workspace,
+                                      size_t ws_bytes, void* stream_) {
+    using namespace ms;
+    hipStream_t stream = (hipStream_t)stream_;
+    int rc = gemm_check_shape("ms_lm_head_argmax_bf16", M, vocab, K, 1);
+    if (rc != MS_OK) return rc;
+    if (M == 0) return MS_OK;
+    if (!a || !w || !out || !g_aligned16(a) || !g_aligned16(w)) MS_FAIL(MS_ERR_INVALID, "ms_lm_head_argmax_bf16: null or misaligned operand");
+    const size_t need = ms_lm_head_argmax_workspace_bytes(M, vocab, K);
+    if (!workspace || ws_bytes < need || !g_aligned16(workspace))
+        MS_FAIL(MS_ERR_WORKSPACE, "ms_lm_head_argmax_bf16: workspace of %zu bytes needed", need);
+    GemmArgs g;
+    g.a = (const uint16_t*)a;
+    g.w = (const uint16_t*)w;
+    g.bias = nullptr;
+    g.M = M;
+    g.N = vocab;
+    g.K = K;
+    g.k_per_split = K;
+    g.n_out = 1;
+    for (int i = 0; i < kGemmMaxOut; ++i) g.out[i] = nullptr;
+    g.out_col[0] = 0;
+    for (int i = 1; i <= kGemmMaxOut; ++i) g.out_col[i] = vocab;
+    g.partial = nullptr;
+    g.keys = (unsigned long long*)workspace;
+    const int groups = argmax_groups(M, vocab, K);
+    const GemvPlan v = gemv_plan(M, vocab, K);
+    if (v.parts == 1) {
+        g.tail_first = g.tail_blocks = g.tail_k = g.tail_col0 = 0;
+        switch (v.km) {
+            case 1: gemv_dispatch<1>(g, v, stream); break;
+            case 2: gemv_dispatch<2>(g, v, stream); break;
+            case 3: gemv_dispatch<3>(g, v, stream); break;
+            case 4: gemv_dispatch<4>(g, v, stream); break;
+            case 5: gemv_dispatch<5>(g, v, stream); break;
+            case 6: gemv_dispatch<6>(g, v, stream); break;
+            case 7: gemv_dispatch<7>(g, v, stream); break;
+            default: gemv_dispatch<8>(g, v, stream); break;
+        }
+    } else {
+        const GemmPlan p = gemm_plan(M, vocab, K, 1);
+        const int blocks = p.n_groups * p.group_blocks;   // whole tiles throughout
+        g.tail_first = blocks;
+        g.tail_blocks = 0;
+        g.tail_k = K;
+        g.tail_col0 = vocab;
+        hipLaunchKernelGGL((gemm_tn_bf16<kGemmArgmax>), dim3((unsigned)blocks), dim3(kGemmThreads), 0, stream, g);
+    }
+    hipLaunchKernelGGL(argmax_finish, dim3((unsigned)M), dim3(256), 0, stream, (const unsigned long long*)workspace, groups, M, out);
+    MS_HIP_TRY(hipGetLastError());
+    return MS_OK;
 }

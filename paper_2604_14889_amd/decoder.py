@@ -90,7 +90,8 @@ class Decoder:
     """Buffers and the step driver for up to max_rows = B * n_q tokens per step."""
 
     def __init__(self, cfg: DecoderConfig, weights: DecoderTensors, session: Session, max_rows: int,
-                 hand_gemm: bool = True, fused_mlp: bool = False, tune_library_gemms: bool = False):
+                 hand_gemm: bool = True, fused_mlp: bool = False, tune_library_gemms: bool = False,
+                 fused_lm_head: bool = False):
         """hand_gemm: run the Q/K/V and down projections on this library's GEMM (needs widths that
         are multiples of 128 and depths that are multiples of 128); otherwise everything dense goes
         through torch."""
@@ -131,6 +132,12 @@ class Decoder:
                           cfg.hidden % (32 * 4) == 0 and cfg.inter % (32 * 8) == 0)
         # gate/up + SwiGLU in one GEMM: keeps a second, row-interleaved copy of the gate/up weights
         self.fused_mlp = fused_mlp and self.hand_gemm and cfg.inter % 64 == 0
+        # LM head and greedy token in one kernel of the library (fp32 sums, no logits): step() then
+        # returns None for the logits
+        self.fused_lm_head = fused_lm_head and cfg.vocab % 128 == 0 and cfg.hidden % 32 == 0
+        self.lm_ws = None
+        if self.fused_lm_head:
+            self.lm_ws = torch.empty(M.ms_lm_head_argmax_workspace_bytes(max_rows, cfg.vocab, cfg.hidden), dtype=torch.uint8, device=dev)
         self.gemm_ws = None
         if self.hand_gemm:
             need = max(M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, cfg.hidden, self.splits_few[0]),
@@ -143,8 +150,8 @@ class Decoder:
     def step(self, seq_ids: Sequence[int], tokens: torch.Tensor, pos: torch.Tensor, n_verify: int, n_foresight: int,
              ctx_new: Optional[torch.Tensor] = None):
         """tokens, pos: int32 device [B, n_q].  Returns (logits [B*n_q, vocab] bf16, greedy tokens
-        [B*n_q] int32), both views of this object's buffers; step_kv() gives the step's keys and
-        values for ms_commit_accepted."""
+        [B*n_q] int32), both views of this object's buffers (logits is None with fused_lm_head);
+        step_kv() gives the step's keys and values for ms_commit_accepted."""
         cfg, w = self.cfg, self.w
         B = len(seq_ids)
         n_q = n_verify + n_foresight
@@ -188,10 +195,7 @@ class Decoder:
                 torch.mm(act, lw.w_down.t(), out=proj)
             delta = proj
         M.ms_add_rmsnorm(h, delta, w.norm, cfg.eps, x)
-        logits = self.logits[:rows]
-        torch.mm(x, w.lm_head.t(), out=logits)
-        M.ms_argmax_rows(logits, cfg.vocab, self.targets[:rows])
-        return logits, self.targets[:rows]
+        return self._greedy_tokens(x, rows)
 
     # ---- the same step with the library calls' arguments prepared once -------------------------------
     def _prepare(self, rows: int):
@@ -261,10 +265,21 @@ class Decoder:
             check(lib.ms_swiglu(*c["swiglu"], st))
             check(lib.ms_gemm_bf16(*c["down"], st))
         check(lib.ms_add_rmsnorm(*prep["final"], st))
+        return self._greedy_tokens(x_t, rows)
+
+    def _greedy_tokens(self, x, rows):
+        targets = self.targets[:rows]
+        if self.fused_lm_head:
+            # the workspace was sized for max_rows; fewer rows may run on another kernel with more column groups
+            need = M.ms_lm_head_argmax_workspace_bytes(rows, self.cfg.vocab, self.cfg.hidden)
+            if need > self.lm_ws.numel():
+                self.lm_ws = torch.empty(need, dtype=torch.uint8, device=self.lm_ws.device)
+            M.ms_lm_head_argmax_bf16(x, self.w.lm_head, targets, self.lm_ws)
+            return None, targets
         logits = self.logits[:rows]
-        torch.mm(x_t, w.lm_head.t(), out=logits)
-        M.ms_argmax_rows(logits, cfg.vocab, self.targets[:rows])
-        return logits, self.targets[:rows]
+        torch.mm(x, self.w.lm_head.t(), out=logits)
+        M.ms_argmax_rows(logits, self.cfg.vocab, targets)
+        return logits, targets
 
     def step_kv(self):
         """The last step's K / V as contiguous [L, rows, Hkv, D] tensors (input of ms_commit_accepted)."""

@@ -48,7 +48,7 @@ def make_weights(rng, cfg):
 
 def test_decode_step_matches_oracle_and_commits_accepted_rows():
     M, S, D = _mods()
-    cfg = D.DecoderConfig(n_layers=2, hidden=512, inter=1024, vocab=1000, n_q_heads=8, n_kv_heads=2, head_dim=128)
+    cfg = D.DecoderConfig(n_layers=2, hidden=512, inter=1024, vocab=1024, n_q_heads=8, n_kv_heads=2, head_dim=128)
     rng = W.make_rng(700)
     layers, top = make_weights(rng, cfg)
     f64 = lambda b: O.bf16_bits_to_f32(b).astype(np.float64)
@@ -125,6 +125,15 @@ def test_decode_step_matches_oracle_and_commits_accepted_rows():
         err_f = np.abs(logits_f.float().cpu().numpy().reshape(B, nq, cfg.vocab).astype(np.float64) - ref.logits)
         print(f"logits (fused MLP): max-abs {err_f.max():.3e}, mean-rel {err_f.mean() / np.abs(ref.logits).mean():.3e}")
         assert err_f.max() <= 4e-2 * scale and err_f.mean() / np.abs(ref.logits).mean() <= 2e-2
+        # LM head and greedy token in one kernel (fp32 sums, no logits): same tokens wherever the decision is clear
+        dec_g = D.Decoder(cfg, gw, ses, B * nq, fused_lm_head=True)
+        assert dec_g.fused_lm_head
+        none_logits, targets_g = dec_g.step(ids, S.ints_dev(tokens).view(B, nq), S.ints_dev(pos).view(B, nq), nv, nf)
+        torch.cuda.synchronize()
+        assert none_logits is None
+        srt_g = np.sort(ref.logits, axis=-1)
+        clear_g = (srt_g[..., -1] - srt_g[..., -2]) > 2 * max_abs
+        assert (targets_g.cpu().numpy().reshape(B, nq)[clear_g] == ref.targets[clear_g]).all()
         # greedy tokens wherever the oracle's decision has a margin
         srt = np.sort(ref.logits, axis=-1)
         margin = srt[..., -1] - srt[..., -2]

@@ -151,6 +151,51 @@ def test_gate_up_gemm_with_swiglu_epilogue(m, inter, k):
     assert (err <= bound).all(), f"max excess {np.max(err - bound):.3e} at {np.unravel_index(np.argmax(err - bound), err.shape)}"
 
 
+ARGMAX_CASES = [(7, 16384, 1536), (5, 2048, 512), (1, 128, 512), (8, 37888, 1024), (9, 1024, 512), (300, 4096, 256), (448, 2048, 3584)]
+
+
+@pytest.mark.parametrize("m,vocab,k", ARGMAX_CASES)
+def test_lm_head_with_greedy_token(m, vocab, k):
+    """Greedy token straight from the fp32 sums of the LM-head product (Algorithm 1, SpeculativeStep:
+    the model's own next token): against the argmax of the fp64 product wherever that one is clear;
+    equal maxima resolve to the lowest column and NaN never wins."""
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import session as S
+    rng = W.make_rng(906, m, vocab, k)
+    a = W.normal_bf16_bits(rng, (m, k), 1.0)
+    w = W.normal_bf16_bits(rng, (vocab, k), k ** -0.5)
+    # planted cases: row 0's best column duplicated further down (a tie: the lower one must win) ...
+    f64 = lambda x: O.bf16_bits_to_f32(x).astype(np.float64)
+    ref = f64(a) @ f64(w).T
+    top0 = int(np.argmax(ref[0]))
+    dup = (top0 + vocab // 2) % vocab
+    w[dup] = w[top0]
+    # ... and a weight row of NaN (0x7fc0), which must never be chosen
+    nan_col = (top0 + 7) % vocab
+    if nan_col == dup:
+        nan_col = (nan_col + 1) % vocab
+    w[nan_col] = 0x7FC0
+    ref = f64(a) @ f64(w).T
+    ref_valid = np.where(np.isnan(ref), -np.inf, ref)
+    want = np.argmax(ref_valid, axis=1)                      # numpy: first among equal maxima
+    srt = np.sort(ref_valid, axis=1)
+    margin = srt[:, -1] - srt[:, -2]
+    out = torch.full((m,), -1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(M.ms_lm_head_argmax_workspace_bytes(m, vocab, k), dtype=torch.uint8, device="cuda")
+    M.ms_lm_head_argmax_bf16(S.to_device(a, M.MS_BF16), S.to_device(w, M.MS_BF16), out, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert got[0] == min(top0, dup), f"tie between columns {top0} and {dup} went to {got[0]}"
+    assert (got != nan_col).all()
+    clear = margin > 1e-4 * np.abs(ref[np.isfinite(ref)]).max()
+    clear[0] = False                                          # row 0 is the planted tie (margin 0)
+    assert clear.sum() >= (m - 1) * 0.8
+    assert (got[clear] == want[clear]).all(), f"rows {np.nonzero(clear & (got != want))[0]}"
+    with pytest.raises(M.MsError) as e:
+        M.ms_lm_head_argmax_bf16(S.to_device(a, M.MS_BF16), S.to_device(w, M.MS_BF16), out, None)
+    assert e.value.code == M.MS_ERR_WORKSPACE
+
+
 def test_gemm_rejects_what_it_is_not_built_for():
     from paper_2604_14889_amd import binding as M
     a = torch.zeros(4, 64, dtype=torch.bfloat16, device="cuda")
