@@ -201,7 +201,8 @@ class Decoder:
     def _prepare(self, rows: int):
         """Argument tuples of every per-layer library call of a step of `rows` rows.  All buffers are
         this object's and all weights are fixed, so the addresses never change; a step with a single
-        sequence is otherwise bound by re-deriving them in Python for its ~200 calls."""
+        sequence is otherwise bound by re-deriving them in Python for its ~200 calls.  Whoever swaps
+        a weight tensor for another one afterwards calls forget_prepared()."""
         cfg, w = self.cfg, self.w
         ptr = lambda t: t.data_ptr()
         qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
@@ -227,6 +228,10 @@ class Decoder:
                 swiglu=(gate_up, act, rows, cfg.inter),
                 down=(act, ptr(lw.w_down), None, rows, cfg.hidden, cfg.inter, 1, outs_proj, cols_h, down_split, ws, ws_bytes)))
         return dict(layers=layers, final=(h, proj, ptr(w.norm), cfg.eps, x, rows, cfg.hidden), q=q, attn=attn)
+
+    def forget_prepared(self) -> None:
+        """Drops the prepared argument tuples (they hold device addresses of the weights)."""
+        self._prepared.clear()
 
     def _step_prepared(self, seq_ids, tokens, pos, n_verify, n_foresight, ctx_new, rows):
         cfg, w, lib, check = self.cfg, self.w, M.lib, M._check
