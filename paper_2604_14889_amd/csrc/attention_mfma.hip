@@ -402,6 +402,7 @@ __device__ __forceinline__ void close_pair(const MfmaArgs& a, int q0, int n_rows
         }
 #pragma unroll
         for (int k = 0; k < kBatch; ++k) {
+            if (p0 + k >= p_end) continue;                          // (uniform) nothing in this slot
             const float mn = fmaxf(m, pm[k]);                       // the first partial exists and is finite
             const float fo = __builtin_amdgcn_exp2f(m - mn);
             const float fp = __builtin_amdgcn_exp2f(pm[k] - mn);
