@@ -43,7 +43,7 @@ def parse():
     ap.add_argument("--ragged", action="store_true", help="lengths uniform in [1k, 16k] instead of --kv")
     ap.add_argument("--q-heads", type=int, default=28, help="query heads (28 / 4: Qwen2.5-7B, 32 / 8: Llama-3.1-8B)")
     ap.add_argument("--kv-heads", type=int, default=4)
-    ap.add_argument("--event-stride", type=int, default=13,
+    ap.add_argument("--event-stride", type=int, default=29,
                     help="time every n-th attention launch with HIP events (an event pair costs the stream a few microseconds)")
     ap.add_argument("--workload", choices=["attention", "decode_step"], default="attention",
                     help="attention: the metric's workload (default); decode_step: the whole model step "
