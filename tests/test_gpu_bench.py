@@ -1,0 +1,54 @@
+"""bench.py end to end at reduced sizes: one JSON line with the contract's fields, for both workloads."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def run_bench(*flags):
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), *flags], capture_output=True, text=True, timeout=300, cwd=ROOT)
+    assert res.returncode == 0, res.stderr[-2000:]
+    lines = [l for l in res.stdout.splitlines() if l.startswith("{")]
+    assert len(lines) == 1, res.stdout[-2000:]
+    return json.loads(lines[0])
+
+
+def check_contract(r):
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline"):
+        assert key in r, key
+    assert r["n_gpus"] == 1 and r["value"] > 0 and r["ms_per_step"] > 0 and "workload" in r["config"]
+    rf = r["roofline"]
+    assert rf["bound"] == "hbm" and rf["peak"] == 8000.0 and rf["unit"] == "GB/s"
+    assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
+
+
+def test_attention_bench_small():
+    r = run_bench("--layers", "2", "--batch", "3", "--kv", "512", "--steps", "3", "--warmup", "1", "--event-stride", "1", "--cpu-seqs", "1")
+    check_contract(r)
+    assert r["metric"] == "predict_verify_attn_hbm_gbps_b32_kv8k"
+    cb = r["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1
+    assert cb["gpu_vs_oracle_max_abs"] <= 2e-2 and cb["gpu_vs_oracle_mean_rel"] <= 1e-2
+
+
+def test_decode_step_bench_small():
+    r = run_bench("--workload", "decode_step", "--layers", "1", "--batch", "2", "--kv", "128", "--steps", "2", "--warmup", "1",
+                  "--no-gemm-tuning")
+    check_contract(r)
+    assert r["attention_share_of_step"] > 0
+    r = run_bench("--workload", "decode_step", "--layers", "1", "--batch", "1", "--kv", "128", "--steps", "2", "--warmup", "1",
+                  "--no-gemm-tuning", "--fused-lm-head")
+    check_contract(r)
+
+
+def test_more_than_one_gpu_is_refused():
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120, cwd=ROOT)
+    assert res.returncode != 0
+    assert "one GPU" in (res.stdout + res.stderr) or "single" in (res.stdout + res.stderr).lower()
