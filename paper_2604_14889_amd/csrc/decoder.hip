@@ -142,7 +142,36 @@ __global__ __launch_bounds__(kRowThreads) void argmax_rows(const uint16_t* __res
     float bv = -INFINITY;
     int bi = 0x7fffffff;
     const int vec_end = vocab & ~7;
-    for (int i = threadIdx.x * 8; i < vec_end; i += kRowThreads * 8) {
+    // four chunks per turn, each with a candidate of its own: four loads in flight and four
+    // independent compare chains instead of one (take_better keeps the lower index among equals,
+    // so the order in which candidates are folded does not matter)
+    constexpr int kWays = 4;
+    float cv[kWays];
+    int ci[kWays];
+#pragma unroll
+    for (int u = 0; u < kWays; ++u) {
+        cv[u] = -INFINITY;
+        ci[u] = 0x7fffffff;
+    }
+    int i = threadIdx.x * 8;
+    for (; i + (kWays - 1) * kRowThreads * 8 < vec_end; i += kWays * kRowThreads * 8) {
+        uint4 v[kWays];
+#pragma unroll
+        for (int u = 0; u < kWays; ++u) v[u] = *reinterpret_cast<const uint4*>(row + i + u * kRowThreads * 8);
+#pragma unroll
+        for (int u = 0; u < kWays; ++u) {
+            const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+            const int at = i + u * kRowThreads * 8;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                take_better(cv[u], ci[u], bf16_bits_to_float(w[e] & 0xffffu), at + 2 * e);
+                take_better(cv[u], ci[u], bf16_bits_to_float(w[e] >> 16), at + 2 * e + 1);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kWays; ++u) take_better(bv, bi, cv[u], ci[u]);
+    for (; i < vec_end; i += kRowThreads * 8) {
         const uint4 v = *reinterpret_cast<const uint4*>(row + i);
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
