@@ -43,8 +43,12 @@ def parse():
     ap.add_argument("--ragged", action="store_true", help="lengths uniform in [1k, 16k] instead of --kv")
     ap.add_argument("--q-heads", type=int, default=28, help="query heads (28 / 4: Qwen2.5-7B, 32 / 8: Llama-3.1-8B)")
     ap.add_argument("--kv-heads", type=int, default=4)
-    ap.add_argument("--event-stride", type=int, default=29,
-                    help="time every n-th attention launch with HIP events (an event pair costs the stream a few microseconds)")
+    ap.add_argument("--event-stride", type=int, default=None,
+                    help="every n-th attention launch opens a span timed by one pair of HIP events (a pair costs the "
+                         "stream a few microseconds); default: --layers for the attention workload, 29 for decode_step")
+    ap.add_argument("--event-span", type=int, default=None,
+                    help="attention launches one event pair covers (default: --layers for the attention workload, whose "
+                         "layers launch back to back; 1 for decode_step, where other kernels run between them)")
     ap.add_argument("--workload", choices=["attention", "decode_step"], default="attention",
                     help="attention: the metric's workload (default); decode_step: the whole model step "
                          "(Qwen2.5-7B shapes, batch 64, 8k cached tokens, 4 verify + 3 foresight) with torch GEMMs around "
@@ -183,7 +187,11 @@ def main():
         step()
     torch.cuda.synchronize()
     state.update(kv_bytes=0.0, accepted=0, attn_calls=0)
-    M.ms_profile_attention(ses.cache, args.steps * NL, args.event_stride)
+    # one event pair per step around its NL back-to-back attention launches: nothing else runs on the
+    # stream between them, so span time / NL is the kernel's duration plus the gap to the next launch
+    ev_stride = args.event_stride or NL
+    ev_span = min(args.event_span or NL, ev_stride)
+    M.ms_profile_attention(ses.cache, args.steps * NL, ev_stride, ev_span)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -191,14 +199,14 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kern_ms = M.ms_profile_read(ses.cache, args.steps * NL)
-    M.ms_profile_attention(ses.cache, 0, 1)
+    M.ms_profile_attention(ses.cache, 0, 1, 1)
     M.ms_check_integrity(ses.cache)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     gbps = state["kv_bytes"] / (t1 - t0) / 1e9
     lengths = np.asarray(ses.lengths(ids), dtype=np.int64)
     assert np.array_equal(lengths, cur_len), "host copy of the lengths drifted from the cache's"
-    per_launch_bytes = algorithmic_bytes(lengths)
+    per_launch_bytes = int(round(state["kv_bytes"] / state["attn_calls"]))   # mean over the timed launches
     kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else float("nan")
     achieved = per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9 if kern_ms else float("nan")
 
@@ -245,7 +253,8 @@ def main():
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "traffic": traffic,
             "avg_kernel_ms": round(kern_avg_ms, 5),
-            "launches": len(kern_ms),
+            "launches": len(kern_ms) * ev_span,
+            "launches_per_event_pair": ev_span,
             "algorithmic_bytes_per_launch": per_launch_bytes,
         },
     }
@@ -339,7 +348,8 @@ def decode_step_bench(args):
     torch.cuda.synchronize()
     state.update(committed=0, kv_bytes=0.0)
     dec.attn_events = []
-    M.ms_profile_attention(ses.cache, args.steps * NL, args.event_stride)
+    # other kernels run between the layers' attention launches here: one launch per event pair
+    M.ms_profile_attention(ses.cache, args.steps * NL, args.event_stride or 29, 1)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -347,7 +357,7 @@ def decode_step_bench(args):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kern_ms = M.ms_profile_read(ses.cache, args.steps * NL)
-    M.ms_profile_attention(ses.cache, 0, 1)
+    M.ms_profile_attention(ses.cache, 0, 1, 1)
     attn_ms = sum(a.elapsed_time(b) for a, b in dec.attn_events) / args.steps
     M.ms_check_integrity(ses.cache)
     assert np.array_equal(np.asarray(ses.lengths(ids)), cur_len)

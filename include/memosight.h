@@ -281,12 +281,16 @@ int ms_lm_head_argmax_bf16(const void* a, const void* w, int M, int vocab, int K
 /* ---- profiling ------------------------------------------------------------------------------- */
 
 /* From now on, every stride-th ms_predict_verify_attention call on this cache that runs the
- * streaming kernel (the first such call included) records a pair of HIP events around that kernel's
- * launch(es), for up to `capacity` recorded calls; capacity 0 switches profiling off.  An event
- * pair costs the stream a few microseconds, hence the stride.  Creates the events (synchronous). */
-int ms_profile_attention(ms_cache* cache, int capacity, int stride);
-/* Synchronises the recorded events and stores the kernel durations in milliseconds, in call order,
- * in ms_out (host, up to cap entries); *n receives how many were recorded.  Resets the count. */
+ * streaming kernel (the first such call included) opens a timed span: one pair of HIP events
+ * around the launches of that call and of the span - 1 eligible calls after it (1 <= span <=
+ * stride), for up to `capacity` spans; capacity 0 switches profiling off.  An event pair costs the
+ * stream a few microseconds, which a span of back-to-back calls shares out and a stride keeps rare;
+ * the caller keeps other work on the stream out of a span it wants to read as kernel time (a span
+ * of 1 always is).  Creates the events (synchronous). */
+int ms_profile_attention(ms_cache* cache, int capacity, int stride, int span);
+/* Synchronises the recorded events and stores, per span in call order, its duration divided by the
+ * span (milliseconds per call) in ms_out (host, up to cap entries); *n receives how many spans were
+ * recorded (complete ones only: a span still open is dropped).  Resets the count. */
 int ms_profile_read(ms_cache* cache, float* ms_out, int cap, int* n);
 
 /* ---- position layout helpers (pure host integer functions) --------------------------------- */

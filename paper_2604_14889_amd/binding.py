@@ -80,7 +80,7 @@ _SIGS = {
     "ms_lm_head_argmax_workspace_bytes": (_SZ, [_I, _I, _I]),
     "ms_lm_head_argmax_bf16": (_I, [_P, _P, _I, _I, _I, _P, _P, _SZ, _P]),
     "ms_gemm_bf16": (_I, [_P, _P, _P, _I, _I, _I, _I, C.POINTER(_P), _IP, _I, _P, _SZ, _P]),
-    "ms_profile_attention": (_I, [_P, _I, _I]),
+    "ms_profile_attention": (_I, [_P, _I, _I, _I]),
     "ms_profile_read": (_I, [_P, C.POINTER(C.c_float), _I, _IP]),
     "ms_ama_count": (_I, [_I, _I]),
     "ms_upl_positions": (_I, [_I, _I, _I, _IP, _I]),
@@ -375,8 +375,8 @@ def ms_check_integrity(cache, stream=None) -> None:
     _check(lib.ms_check_integrity(cache, _stream(stream)))
 
 
-def ms_profile_attention(cache, capacity: int, stride: int = 1) -> None:
-    _check(lib.ms_profile_attention(cache, capacity, stride))
+def ms_profile_attention(cache, capacity: int, stride: int = 1, span: int = 1) -> None:
+    _check(lib.ms_profile_attention(cache, capacity, stride, span))
 
 
 def ms_profile_read(cache, cap: int):

@@ -974,8 +974,12 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     a.dbg = (long long*)((char*)ga.ws + (size_t)(mfma_items(c) + B) * c->d.n_kv_heads * kPartFloats * sizeof(float));
 #endif
     {
-        const bool prof = c->prof_count < (int)c->prof_start.size() && c->prof_seen++ % c->prof_stride == 0;
-        if (prof) MS_HIP_TRY(hipEventRecord(c->prof_start[c->prof_count], stream));
+        // every prof_stride-th call opens a timed span of prof_span consecutive calls
+        if (c->prof_open == 0 && c->prof_count < (int)c->prof_start.size() && c->prof_seen % c->prof_stride == 0) {
+            MS_HIP_TRY(hipEventRecord(c->prof_start[c->prof_count], stream));
+            c->prof_open = c->prof_span;
+        }
+        c->prof_seen++;
         const dim3 grid(c->plan_items, a.n_kv_heads);
         if (a.n_q <= kDecodeQueries && a.n_q * a.group <= kRows) {
             a.q0 = 0;
@@ -995,17 +999,20 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
             }
         }
         MS_HIP_TRY(hipGetLastError());
-        if (prof) MS_HIP_TRY(hipEventRecord(c->prof_stop[c->prof_count++], stream));
+        if (c->prof_open > 0 && --c->prof_open == 0) MS_HIP_TRY(hipEventRecord(c->prof_stop[c->prof_count++], stream));
     }
     return MS_OK;
 }
 
 }  // namespace ms
 
-extern "C" int ms_profile_attention(ms_cache* c, int capacity, int stride) {
-    if (!c || capacity < 0 || stride < 1) MS_FAIL(MS_ERR_INVALID, "ms_profile_attention: bad argument");
+extern "C" int ms_profile_attention(ms_cache* c, int capacity, int stride, int span) {
+    if (!c || capacity < 0 || stride < 1 || span < 1 || span > stride)
+        MS_FAIL(MS_ERR_INVALID, "ms_profile_attention: bad argument");
     c->prof_stride = stride;
+    c->prof_span = span;
     c->prof_seen = 0;
+    c->prof_open = 0;
     for (hipEvent_t e : c->prof_start) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->prof_stop) (void)hipEventDestroy(e);
     c->prof_start.clear();
@@ -1027,7 +1034,9 @@ extern "C" int ms_profile_read(ms_cache* c, float* ms_out, int cap, int* n) {
     for (int i = 0; i < c->prof_count && i < cap; ++i) {
         MS_HIP_TRY(hipEventSynchronize(c->prof_stop[i]));
         MS_HIP_TRY(hipEventElapsedTime(&ms_out[i], c->prof_start[i], c->prof_stop[i]));
+        ms_out[i] /= (float)c->prof_span;
     }
     c->prof_count = 0;
+    c->prof_open = 0;   // a span still open is dropped
     return MS_OK;
 }

@@ -83,7 +83,9 @@ struct ms_cache {
     std::vector<hipEvent_t> prof_start, prof_stop;  // event pairs around the streaming kernel
     bool deterministic = false;   // attention: fixed tile-to-wave assignment (bitwise reproducible)
     int prof_count = 0;
-    int prof_stride = 1;   // every prof_stride-th eligible launch is timed
+    int prof_stride = 1;   // every prof_stride-th eligible call opens a timed span
+    int prof_span = 1;     // consecutive calls one event pair covers
+    int prof_open = 0;     // calls the open span still waits for
     int prof_seen = 0;
 };
 

@@ -318,6 +318,38 @@ def test_repeated_launches_agree_with_many_partials_per_pair():
             check_out(again, want, "bf16", f"default assignment, launch {i}")
 
 
+def test_profiling_spans_count_calls_and_leave_results_alone():
+    """The event pairs of ms_profile_attention: every stride-th call opens a span of `span` calls, an
+    unfinished span is not reported, a read resets the count, the outputs do not change."""
+    M, S = _mods()
+    sh = W.AttnShape("prof", "bf16", 3, 28, 4, 128, 4, 3, [700, 2100, 50], 0.5, 1000000.0, n_layers=2)
+    inp = W.attention_inputs(sh, 404)
+    ses, ora, ids = setup_pair(inp)
+    with ses:
+        pos = pids_for(inp, M)
+        M.ms_attention_set_deterministic(ses.cache, True)
+        base = run_gpu_attention(ses, inp, ids, pos, 0)
+        check_out(base, oracle_attention(ora, inp, ids, pos, 0), "bf16", "before profiling")
+        for bad in ((4, 0, 1), (4, 2, 3), (4, 2, 0), (-1, 1, 1)):
+            with pytest.raises(M.MsError):
+                M.ms_profile_attention(ses.cache, *bad)
+        M.ms_profile_attention(ses.cache, 8, 3, 2)
+        for i in range(7):      # spans open at calls 0, 3, 6; the last one stays open
+            assert np.array_equal(run_gpu_attention(ses, inp, ids, pos, 0), base), f"call {i}"
+        ms = M.ms_profile_read(ses.cache, 8)
+        assert len(ms) == 2 and all(0.0 < t < 50.0 for t in ms), ms
+        assert M.ms_profile_read(ses.cache, 8) == []
+        run_gpu_attention(ses, inp, ids, pos, 0)      # the read dropped the open span: nothing to close
+        assert M.ms_profile_read(ses.cache, 8) == []
+        M.ms_profile_attention(ses.cache, 2, 1, 1)
+        for i in range(5):      # capacity 2: only the first two calls are recorded
+            run_gpu_attention(ses, inp, ids, pos, 0)
+        assert len(M.ms_profile_read(ses.cache, 8)) == 2
+        M.ms_profile_attention(ses.cache, 0, 1, 1)
+        assert np.array_equal(run_gpu_attention(ses, inp, ids, pos, 0), base)
+        assert M.ms_profile_read(ses.cache, 8) == []
+
+
 # ------------------------------------------------------------------ the named configurations ---
 
 def test_config1_fp32_built_through_append_and_compact():
