@@ -19,6 +19,7 @@ resident in HBM; `roofline` prices the streaming attention kernel alone against 
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -193,11 +194,14 @@ def main():
     ev_span = min(args.event_span or NL, ev_stride)
     M.ms_profile_attention(ses.cache, args.steps * NL, ev_stride, ev_span)
     torch.cuda.synchronize()
+    gc.collect()
+    gc.disable()    # a full collection in the middle of a step stalls the launch thread for tens of milliseconds
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    gc.enable()
     kern_ms = M.ms_profile_read(ses.cache, args.steps * NL)
     M.ms_profile_attention(ses.cache, 0, 1, 1)
     M.ms_check_integrity(ses.cache)
@@ -347,29 +351,31 @@ def decode_step_bench(args):
         step()
     torch.cuda.synchronize()
     state.update(committed=0, kv_bytes=0.0)
-    dec.attn_events = []
     # other kernels run between the layers' attention launches here: one launch per event pair
     M.ms_profile_attention(ses.cache, args.steps * NL, args.event_stride or 29, 1)
     torch.cuda.synchronize()
+    gc.collect()
+    gc.disable()    # a full collection in the middle of a step stalls the launch thread for tens of milliseconds
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    gc.enable()
     kern_ms = M.ms_profile_read(ses.cache, args.steps * NL)
     M.ms_profile_attention(ses.cache, 0, 1, 1)
-    attn_ms = sum(a.elapsed_time(b) for a, b in dec.attn_events) / args.steps
     M.ms_check_integrity(ses.cache)
     assert np.array_equal(np.asarray(ses.lengths(ids)), cur_len)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     per_launch_bytes = int(np.sum(2 * cur_len * Hkv * Dh * 2 + 4 * (-(-cur_len // 16)))) + B * nq * (2 * Hq + 2 * Hkv) * Dh * 2
     kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else float("nan")
     achieved = per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9
+    attn_ms = kern_avg_ms * NL      # from the sampled launches (an event pair around every launch would stall the stream)
     n_params = (sum(t.numel() for lw in weights.layers for name, t in vars(lw).items()
                      if name not in ("wqkv", "bqkv", "w_gate_up_blocked")) +
                 weights.lm_head.numel() + weights.norm.numel())
     result = {
-        "metric": "full_decode_step_tokens_per_s_b64_kv8k",
+        "metric": f"full_decode_step_tokens_per_s_b{B}_kv{L0 // 1024}k",
         "value": round(state["committed"] / (t1 - t0), 1),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -377,9 +383,12 @@ def decode_step_bench(args):
         "config": {
             "workload": f"decode_step_qwen2.5-7b_shapes_batch{B}_kv{L0}_layers{NL}_verify{nv}_foresight{nf}",
             "batch": B, "mean_kv_len": round(float(cur_len.mean()), 1), "layers": NL,
-            "step": "embedding, 28 blocks (hand-written norm / attention / SwiGLU kernels, hand-written GEMM for the fused "
-                    "Q/K/V and the down projection, torch GEMMs for the output, gate/up and LM-head projections), greedy "
-                    "tokens, accept, commit; random weights, so about one token per sequence is accepted per step",
+            "step": "embedding, 28 blocks (hand-written norm / attention / SwiGLU kernels, " +
+                    ("every projection on this library's few-row matrix-core kernel, gate/up with SwiGLU in its epilogue"
+                     if dec._few(B * nq) else
+                     "hand-written GEMM for the fused Q/K/V and the down projection, torch GEMMs for the output, gate/up "
+                     "and LM-head projections") +
+                    "), greedy tokens, accept, commit; random weights, so about one token per sequence is accepted per step",
             "library_gemms": "default pick" if args.no_gemm_tuning else "candidates timed once per shape (torch.cuda.tunable), in the warm-up",
         },
         "query_tokens_per_s": round(B * nq * args.steps / (t1 - t0), 1),

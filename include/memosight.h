@@ -251,10 +251,11 @@ int ms_argmax_rows(const void* logits, int n, int vocab, long ld, int* out, void
  * aligned workspace.  With split_k == 1 that function returns what the call can use to split the
  * tiles of a partly filled last round over K (0 if the shape has none on the current device);
  * without that much workspace the call computes whole tiles throughout, with the same result up to
- * the order of the fp32 additions.  With M <= 8 and K % 512 == 0 (the step of a single sequence)
- * the product is bound by reading W once and runs on a kernel that streams whole weight rows
- * (no tiles, no matrix cores); it divides K by what fits its LDS share (ms_gemm_workspace_bytes
- * covers the partial sums) and ignores split_k unless the workspace is too small for that. */
+ * the order of the fp32 additions.  With M <= 16 and K % 128 == 0 (the step of one or two
+ * sequences) the product is bound by reading W once and runs on a kernel that streams 16 weight
+ * rows per wave through the matrix cores with all rows of A as the other operand; it divides K by
+ * what fits its LDS share (ms_gemm_workspace_bytes covers the partial sums) and ignores split_k
+ * unless the workspace is too small for that. */
 size_t ms_gemm_workspace_bytes(int M, int N, int K, int split_k);
 int ms_gemm_bf16(const void* a, const void* w, const void* bias, int M, int N, int K, int n_out,
                  void* const* out, const int* out_col, int split_k, void* workspace, size_t ws_bytes,
@@ -265,7 +266,8 @@ int ms_gemm_bf16(const void* a, const void* w, const void* bias, int M, int N, i
  * [2 * inter][K] weight with the rows of both projections interleaved in blocks of 32: rows
  * 64 b .. 64 b + 32 are gate rows 32 b .. 32 b + 32, rows 64 b + 32 .. 64 b + 64 the up rows of the
  * same outputs.  inter % 64 == 0, K % 32 == 0; workspace as for ms_gemm_bf16 with N = 2 * inter and
- * split_k = 1 (optional). */
+ * split_k = 1 (optional).  M <= 16 with inter % 128 == 0 and K % 128 == 0 runs on the few-row
+ * kernel of ms_gemm_bf16 when all rows of A fit its LDS share (M <= 8 at K = 3584). */
 int ms_gemm_swiglu_bf16(const void* a, const void* w_gate_up, int M, int inter, int K, void* out,
                         void* workspace, size_t ws_bytes, void* stream);
 

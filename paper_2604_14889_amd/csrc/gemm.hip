@@ -362,131 +362,177 @@ __global__ __launch_bounds__(256) void argmax_finish(const unsigned long long* k
 typedef __attribute__((ext_vector_type(4))) uint32_t g_u32x4_t;
 
 // ---------------------------------------------------------------------------------------------
-// At most 8 rows (the step of a single sequence).  The product is bound by reading W once; tiles
-// and matrix cores buy nothing.  A wave owns kR weight rows; per K step of 512 a lane takes 16
-// bytes of each of them, so that one load instruction reads 1 KB of one row, and multiplies them
-// with the activations' same 8 elements (from LDS, where the workgroup keeps its K range of all
-// rows of A; read and widened once per step for all kR rows) with fp32 FMAs into sums per lane
-// (v_dot2c_f32_bf16 was slower: the kernel became bound by it at 8 rows).
-// The 64 lanes' sums are added at the end (DPP), lane 63 writes.  A workgroup's K range is what fits
-// 64 KB of LDS with all rows of A (at most 16 steps): deeper K is divided over `parts` workgroups
-// (fp32 partials, summed by gemm_reduce).
+// At most 16 rows on the matrix cores (the step of one or two sequences).  The product is bound by
+// reading W once, and the vector ALUs cannot keep up with 7 or more FMAs per weight (a kernel with
+// fp32 FMAs per lane and a wave reduction at the end reached 2.2 to 3.9 TB/s at 7 rows), so W goes
+// through v_mfma_f32_16x16x32_bf16: 16 weight rows are the A operand, the activations the B
+// operand (columns = rows of A, padded to 16 by repeating the last one; from LDS, where the
+// workgroup keeps its K range of A).  A tile of 16 weight rows x 128 K is loaded with four 16-byte
+// loads per lane, each covering 256 contiguous bytes of four rows (loading the operand layout
+// directly - one row per lane - ran at half the rate: every lane of a load then touches another
+// cache line), passes through a wave-private LDS tile (row stride 272 bytes) and is read back in
+// the operand layout (row = lane % 16, k = 8 (lane / 16) + 32 j for the j-th MFMA).  Per tile: four
+// loads, four LDS writes, four (+ four for the activations) LDS reads, four MFMAs.  A workgroup is
+// 4 waves: kWK of them split the K range of the same weight rows (summed through LDS at the end),
+// 4 / kWK take different rows; a wave owns kNT tiles of 16 rows and keeps 16 loads (16 KB) in
+// flight.  K ranges too long for the LDS are divided over `parts` workgroups (fp32 partials, summed
+// by gemm_reduce).  kSwiglu (four tiles per wave = one gate block and one up block of the
+// interleaved gate/up weight): the wave writes silu(gate) * up.
 // ---------------------------------------------------------------------------------------------
-constexpr int kGemvStepK = 512;            // 64 lanes x 8 elements
-constexpr int kGemvThreads = 512;          // 8 waves share the staged activations
-constexpr int kGemvLdsBytes = 64 * 1024;
+constexpr int kSkinnyMaxRows = 16;
+constexpr int kSkinnyStepK = 128;
+constexpr int kSkinnyThreads = 256;
+constexpr int kSkinnyTileRowBytes = kSkinnyStepK * 2 + 16;        // 272
+constexpr int kSkinnyTileBytes = 16 * kSkinnyTileRowBytes;        // 4352 per wave
+constexpr int kSkinnyLdsBytes = 76 * 1024;                        // two workgroups per compute unit
+constexpr int kSkinnyLdsForA = kSkinnyLdsBytes - 4 * kSkinnyTileBytes;
+typedef __attribute__((ext_vector_type(4))) float g_f32x4_t;
 
-// the 8 bf16 of a 16-byte chunk as fp32 (a shift or a mask each)
-__device__ __forceinline__ void unpack8_bf16(uint4 v, float (&f)[8]) {
-    f[0] = __uint_as_float(v.x << 16);
-    f[1] = __uint_as_float(v.x & 0xffff0000u);
-    f[2] = __uint_as_float(v.y << 16);
-    f[3] = __uint_as_float(v.y & 0xffff0000u);
-    f[4] = __uint_as_float(v.z << 16);
-    f[5] = __uint_as_float(v.z & 0xffff0000u);
-    f[6] = __uint_as_float(v.w << 16);
-    f[7] = __uint_as_float(v.w & 0xffff0000u);
-}
-
-// Sum over the wave; the total arrives in lane 63.  Within rows of 16 lanes: the other lane of a
-// pair, the other pair of a quad, the mirrored half row, the mirrored row; then lane 15 of rows 0
-// and 2 into rows 1 and 3, lane 31 into rows 2 and 3.
-__device__ __forceinline__ float wave_sum_to_last_lane(float v) {
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xA, 0xF, false));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false));
-    return v;
-}
-
-template <int kM, int kR>   // rows of A (1 .. 8), weight rows per wave
-__global__ __launch_bounds__(kGemvThreads) void gemv_rows_bf16(GemmArgs g, int parts) {
+template <int kNT, int kWK, bool kSwiglu = false>
+__global__ __launch_bounds__(kSkinnyThreads) void skinny_mfma_bf16(GemmArgs g, int parts) {
+    static_assert(!kSwiglu || (kNT == 4 && kWK == 1), "SwiGLU: a wave owns 64 consecutive weight rows");
+    constexpr int kDepth = 4 / kNT;            // K steps in flight: 16 loads per wave
+    constexpr int kWN = 4 / kWK;
     extern __shared__ __attribute__((aligned(16))) char a_lds[];
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, q = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int steps_total = g.K / kGemvStepK;
+    const int wn = w / kWK, wk = w % kWK;
+    const int steps_total = g.K / kSkinnyStepK;
     const int part = blockIdx.y;
-    const int s_lo = (int)((long)steps_total * part / parts), s_hi = (int)((long)steps_total * (part + 1) / parts);
-    const int steps = s_hi - s_lo, kp = steps * kGemvStepK;
-    // the workgroup's K range of A: [kM][kp] bf16 (kM = M)
-    for (int c = tid; c < kM * (kp / 8); c += kGemvThreads) {
-        const int m = c / (kp / 8), kc = c % (kp / 8);
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (m < g.M) v = *reinterpret_cast<const uint4*>(g.a + (size_t)m * g.K + (size_t)s_lo * kGemvStepK + 8 * kc);
-        *reinterpret_cast<uint4*>(a_lds + ((size_t)m * kp + 8 * kc) * 2) = v;
+    const int p_lo = (int)((long)steps_total * part / parts), p_hi = (int)((long)steps_total * (part + 1) / parts);
+    const int p_steps = p_hi - p_lo, kp = p_steps * kSkinnyStepK;
+    // this wave's steps of the part
+    const int s_lo = p_steps * wk / kWK, s_hi = p_steps * (wk + 1) / kWK;
+    const int steps = s_hi - s_lo, last = steps > 0 ? steps - 1 : 0;
+    const int n0 = ((int)blockIdx.x * kWN + wn) * (16 * kNT);
+    // (a wave without steps, which the launch shapes in use never leave, would load the part's first step)
+    // load i of a tile: row 4 i + lane / 16, 16 bytes at k = 8 (lane % 16)
+    const uint16_t* wp = g.w + (size_t)(n0 + q) * g.K + (size_t)(p_lo + (steps > 0 ? s_lo : 0)) * kSkinnyStepK + 8 * r;
+    const size_t tile_stride = (size_t)16 * g.K, quad_stride = (size_t)4 * g.K;
+    // The workgroup's K range of A goes to LDS: [M][kp] bf16, rows 16 bytes further apart than their
+    // length.  Its loads are issued first and the weight loads right behind them, so that waiting
+    // for A (loads return in order) leaves the weights in flight.
+    const int row_bytes = kp * 2 + 16;
+    const int lds_a_bytes = (g.M * row_bytes + 15) & ~15;
+    const int chunks = g.M * (kp / 8), row_chunks = kp / 8;
+    constexpr int kStage = 16;                 // 16-byte chunks per thread in the first round (all of A at the sizes in use)
+    uint4 sv[kStage];
+#pragma unroll
+    for (int u = 0; u < kStage; ++u) {
+        const int c = tid + u * kSkinnyThreads < chunks ? tid + u * kSkinnyThreads : 0;
+        sv[u] = *reinterpret_cast<const uint4*>(g.a + (size_t)(c / row_chunks) * g.K + (size_t)p_lo * kSkinnyStepK + 8 * (c % row_chunks));
     }
-    const int n0 = (blockIdx.x * (kGemvThreads / 64) + w) * kR;
-    const uint16_t* wp = g.w + (size_t)n0 * g.K + (size_t)s_lo * kGemvStepK + 8 * lane;
-    uint4 w0[kR], w1[kR];
-    const int last = steps - 1;
+    uint4 wv[kDepth][kNT][4];
+#define MS_SKINNY_LOAD(d_, s_)                                                                                 \
+    do {                                                                                                       \
+        const int sc_ = (s_) < last ? (s_) : last; /* past the end: the last step again, unused */             \
+        _Pragma("unroll") for (int t = 0; t < kNT; ++t) _Pragma("unroll") for (int j = 0; j < 4; ++j)          \
+            wv[d_][t][j] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const g_u32x4_t*>( \
+                wp + t * tile_stride + j * quad_stride + (size_t)sc_ * kSkinnyStepK)));                        \
+    } while (0)
 #pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        w0[r] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const g_u32x4_t*>(wp + (size_t)r * g.K)));
-        w1[r] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(
-            reinterpret_cast<const g_u32x4_t*>(wp + (size_t)r * g.K + (1 < last ? 1 : last) * kGemvStepK)));
+    for (int d = 0; d < kDepth; ++d) MS_SKINNY_LOAD(d, d);
+#pragma unroll
+    for (int u = 0; u < kStage; ++u) {
+        const int c = tid + u * kSkinnyThreads;
+        if (c < chunks) *reinterpret_cast<uint4*>(a_lds + (size_t)(c / row_chunks) * row_bytes + 16 * (c % row_chunks)) = sv[u];
     }
-    float acc[kR][kM];
+    for (int c = tid + kStage * kSkinnyThreads; c < chunks; c += kSkinnyThreads)   // longer ranges: the rest, one chunk a time
+        *reinterpret_cast<uint4*>(a_lds + (size_t)(c / row_chunks) * row_bytes + 16 * (c % row_chunks)) =
+            *reinterpret_cast<const uint4*>(g.a + (size_t)(c / row_chunks) * g.K + (size_t)p_lo * kSkinnyStepK + 8 * (c % row_chunks));
+    g_f32x4_t acc[kNT];
 #pragma unroll
-    for (int r = 0; r < kR; ++r)
-#pragma unroll
-        for (int m = 0; m < kM; ++m) acc[r][m] = 0.f;
+    for (int t = 0; t < kNT; ++t) acc[t] = g_f32x4_t{0.f, 0.f, 0.f, 0.f};
     __syncthreads();
-#define MS_GEMV_STEP(WV, s_)                                                                                  \
-    do {                                                                                                      \
-        float af[kM][8];                                                                                      \
-        _Pragma("unroll") for (int m = 0; m < kM; ++m) unpack8_bf16(                                          \
-            *reinterpret_cast<const uint4*>(a_lds + ((size_t)m * kp + (s_) * kGemvStepK + 8 * lane) * 2), af[m]); \
-        _Pragma("unroll") for (int r = 0; r < kR; ++r) {                                                      \
-            float wf[8];                                                                                      \
-            unpack8_bf16(WV[r], wf);                                                                          \
-            _Pragma("unroll") for (int m = 0; m < kM; ++m)                                                    \
-                _Pragma("unroll") for (int e = 0; e < 8; ++e) acc[r][m] = fmaf(wf[e], af[m][e], acc[r][m]);   \
-        }                                                                                                     \
+    const char* ap = a_lds + (size_t)(r < g.M ? r : g.M - 1) * row_bytes + ((size_t)s_lo * kSkinnyStepK + 8 * q) * 2;
+    char* tile = a_lds + lds_a_bytes + w * kSkinnyTileBytes;       // this wave's own
+    char* tile_in = tile + q * kSkinnyTileRowBytes + 16 * r;       // as loaded: + 4 i rows
+    const char* tile_out = tile + r * kSkinnyTileRowBytes + 16 * q;  // as multiplied: + 64 j bytes
+#define MS_SKINNY_STEP(d_, s_)                                                                                 \
+    do {                                                                                                       \
+        g_bf16x8_t af[4];                                                                                      \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                          \
+            af[j] = *reinterpret_cast<const g_bf16x8_t*>(ap + ((size_t)(s_) * kSkinnyStepK + 32 * j) * 2);     \
+        _Pragma("unroll") for (int t = 0; t < kNT; ++t) {                                                      \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                      \
+                *reinterpret_cast<uint4*>(tile_in + 4 * i * kSkinnyTileRowBytes) = wv[d_][t][i];               \
+            g_bf16x8_t wf[4];                                                                                  \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) wf[j] = *reinterpret_cast<const g_bf16x8_t*>(tile_out + 64 * j); \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                      \
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[j], af[j], acc[t], 0, 0, 0);               \
+        }                                                                                                      \
     } while (0)
-#define MS_GEMV_LOAD(WV, s_)                                                                                  \
-    do {                                                                                                      \
-        const int sc_ = (s_) < last ? (s_) : last; /* past the end: the last step again, unused */            \
-        _Pragma("unroll") for (int r = 0; r < kR; ++r) WV[r] = __builtin_bit_cast(uint4, __builtin_nontemporal_load( \
-            reinterpret_cast<const g_u32x4_t*>(wp + (size_t)r * g.K + sc_ * kGemvStepK)));                    \
-    } while (0)
-    for (int s = 0; s < steps; s += 2) {
-        MS_GEMV_STEP(w0, s);
-        MS_GEMV_LOAD(w0, s + 2);
-        if (s + 1 < steps) MS_GEMV_STEP(w1, s + 1);
-        MS_GEMV_LOAD(w1, s + 3);
+    for (int s = 0; s < steps; s += kDepth) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            if (s + d < steps) MS_SKINNY_STEP(d, s + d);
+            MS_SKINNY_LOAD(d, s + d + kDepth);
+        }
     }
-#undef MS_GEMV_STEP
-#undef MS_GEMV_LOAD
+#undef MS_SKINNY_STEP
+#undef MS_SKINNY_LOAD
+    if (kWK > 1) {   // the waves that split K: sums to the first of them, through the LDS
+        __syncthreads();
+        float* red = reinterpret_cast<float*>(a_lds);
+        if (wk > 0) {
 #pragma unroll
-    for (int r = 0; r < kR; ++r)
+            for (int t = 0; t < kNT; ++t)
+                *reinterpret_cast<g_f32x4_t*>(red + ((size_t)((wn * (kWK - 1) + wk - 1) * kNT + t) * 64 + lane) * 4) = acc[t];
+        }
+        __syncthreads();
+        if (wk > 0) return;
 #pragma unroll
-        for (int m = 0; m < kM; ++m) acc[r][m] = wave_sum_to_last_lane(acc[r][m]);
-    if (lane != 63) return;
-    if (g.keys) {   // greedy-token mode (parts == 1): the best of this wave's rows per row of A
+        for (int o = 0; o < kWK - 1; ++o)
 #pragma unroll
-        for (int m = 0; m < kM; ++m) {
-            unsigned long long best = 0ull;
+            for (int t = 0; t < kNT; ++t)
+                acc[t] += *reinterpret_cast<const g_f32x4_t*>(red + ((size_t)((wn * (kWK - 1) + o) * kNT + t) * 64 + lane) * 4);
+    }
+    // lane: row m = r of A, columns n0 + 16 t + 4 q .. + 3
+    const int m = r;
+    if (g.keys) {   // greedy-token mode (parts == 1): the best of this wave's columns per row of A
+        unsigned long long best = 0ull;
 #pragma unroll
-            for (int r = 0; r < kR; ++r) best = key_max(best, argmax_key(acc[r][m], n0 + r));
-            g.keys[(size_t)(n0 / kR) * g.M + m] = best;
+        for (int t = 0; t < kNT; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) best = key_max(best, argmax_key(acc[t][i], n0 + 16 * t + 4 * q + i));
+        best = key_max(best, __shfl_xor(best, 16));
+        best = key_max(best, __shfl_xor(best, 32));
+        if (q == 0 && m < g.M) g.keys[(size_t)(n0 / (16 * kNT)) * g.M + m] = best;
+        return;
+    }
+    if (m >= g.M) return;
+    if (kSwiglu) {   // rows n0 .. n0 + 31: gate of output columns n0 / 2 .. + 31, rows n0 + 32 .. + 63: up of the same
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            uint2 pk;
+            pk.x = g_pack_bf16x2(swiglu_value(acc[t][0], acc[t + 2][0]), swiglu_value(acc[t][1], acc[t + 2][1]));
+            pk.y = g_pack_bf16x2(swiglu_value(acc[t][2], acc[t + 2][2]), swiglu_value(acc[t][3], acc[t + 2][3]));
+            *reinterpret_cast<uint2*>(g.out[0] + (size_t)m * (g.N / 2) + n0 / 2 + 16 * t + 4 * q) = pk;
         }
         return;
     }
 #pragma unroll
-    for (int r = 0; r < kR; ++r) {
-        const int n = n0 + r;
+    for (int t = 0; t < kNT; ++t) {
+        const int n = n0 + 16 * t + 4 * q;
+        if (parts > 1) {
+            *reinterpret_cast<g_f32x4_t*>(g.partial + ((size_t)part * g.M + m) * g.N + n) = acc[t];
+            continue;
+        }
         uint16_t* dst = nullptr;
         int col0 = 0, ld = 0;
-        if (parts == 1) pick_destination(g, n, dst, col0, ld);
-        const float b = parts == 1 && g.bias ? bf16_bits_to_float(g.bias[n]) : 0.f;
-#pragma unroll
-        for (int m = 0; m < kM; ++m) {
-            if (m >= g.M) continue;
-            if (parts > 1) g.partial[((size_t)part * g.M + m) * g.N + n] = acc[r][m];
-            else dst[(size_t)m * ld + (n - col0)] = float_to_bf16_bits(acc[r][m] + b);
+        pick_destination(g, n, dst, col0, ld);
+        float4 v = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+        if (g.bias) {
+            const uint2 b = *reinterpret_cast<const uint2*>(g.bias + n);
+            v.x += bf16_bits_to_float(b.x & 0xffffu);
+            v.y += bf16_bits_to_float(b.x >> 16);
+            v.z += bf16_bits_to_float(b.y & 0xffffu);
+            v.w += bf16_bits_to_float(b.y >> 16);
         }
+        uint2 pk;
+        pk.x = g_pack_bf16x2(v.x, v.y);
+        pk.y = g_pack_bf16x2(v.z, v.w);
+        *reinterpret_cast<uint2*>(dst + (size_t)m * ld + (n - col0)) = pk;
     }
 }
 
@@ -542,25 +588,67 @@ static GemmPlan gemm_plan(int M, int N, int K, int split_k) {
     return p;
 }
 
-// At most 8 rows: the row-streaming kernel's launch shape (0 parts: shape not eligible).
-constexpr int kGemvMaxRows = 8;
-struct GemvPlan {
-    int parts, km, kr, lds_bytes;
+// At most 16 rows: the matrix-core row-streaming kernel's launch shape (0 parts: shape not eligible).
+struct SkinnyPlan {
+    int parts, nt, wk, lds_bytes;
     size_t workspace_bytes;
 };
-static GemvPlan gemv_plan(int M, int N, int K) {
-    GemvPlan p = {0, 0, 0, 0, 0};
-    if (M > kGemvMaxRows || K % kGemvStepK) return p;
-    p.km = M;
-    int max_steps = kGemvLdsBytes / (p.km * kGemvStepK * 2);         // K steps whose rows of A fit the LDS share
-    if (max_steps > 16) max_steps = 16;
-    const int steps = K / kGemvStepK;
-    p.parts = (steps + max_steps - 1) / max_steps;
-    p.lds_bytes = p.km * ((steps + p.parts - 1) / p.parts) * kGemvStepK * 2;
-    const int want = gemm_slots();                                   // workgroups the chip holds two of per CU
-    p.kr = N / 64 >= want ? 8 : N / 32 >= want ? 4 : 2;              // weight rows per wave, 8 waves per workgroup
-    p.workspace_bytes = p.parts > 1 ? (size_t)p.parts * M * N * sizeof(float) : 0;
+static SkinnyPlan skinny_plan(int M, int N, int K) {
+    SkinnyPlan p = {0, 0, 0, 0, 0};
+    if (M < 1 || M > kSkinnyMaxRows || K % kSkinnyStepK || N % 64) return p;
+    const int steps = K / kSkinnyStepK;
+    // fewest K parts whose rows of A fit the LDS share
+    int parts = 1;
+    while (parts < steps && (long)M * (((steps + parts - 1) / parts) * kSkinnyStepK * 2 + 16) > kSkinnyLdsForA) ++parts;
+    const int want = 2 * gemm_slots();   // waves that fill the memory pipeline with 16 KB in flight each
+    const int n_tiles = N / 16;
+    int nt = 1, wk = 1;
+    if (parts > 1) {   // partials and a second kernel anyway: enough parts for about 1.75 x want waves (measured)
+        const int more = (int)((7L * want / 4 + n_tiles - 1) / n_tiles);
+        if (more > parts) parts = more < steps / 4 ? more : (steps / 4 > parts ? steps / 4 : parts);
+    }
+    if (N % 128 == 0 && (long)n_tiles / 2 * parts >= 4 * want) nt = 2;
+    else if ((long)n_tiles * parts < want) wk = (long)n_tiles * parts * 2 >= want ? 2 : 4;
+    while (wk > 1 && steps / parts < wk) wk /= 2;   // every wave gets a step
+#ifdef MS_TIMING
+    if (const char* e = getenv("MS_SKINNY")) {   // "nt,wk,parts", or "off" (experiments)
+        if (e[0] == 'o') return p;
+        int a = 0, b = 0, c = 0;
+        if (sscanf(e, "%d,%d,%d", &a, &b, &c) == 3 && (a == 1 || ((a == 2 || a == 4) && b == 1)) && (b == 1 || b == 2 || b == 4) &&
+            c >= parts && steps / c >= b && N % (64 / b * a) == 0) { nt = a; wk = b; parts = c; }
+    }
+#endif
+    p.parts = parts;
+    p.nt = nt;
+    p.wk = wk;
+    const int a_bytes = ((M * (((steps + parts - 1) / parts) * kSkinnyStepK * 2 + 16) + 15) & ~15) + 4 * kSkinnyTileBytes;
+    const int red_bytes = (4 / wk) * (wk - 1) * nt * 64 * 16;
+    p.lds_bytes = a_bytes > red_bytes ? a_bytes : red_bytes;
+    p.workspace_bytes = parts > 1 ? (size_t)parts * M * N * sizeof(float) : 0;
     return p;
+}
+
+static int skinny_dispatch(const GemmArgs& g, const SkinnyPlan& v, hipStream_t stream, bool swiglu = false) {
+    static bool lds_allowed[64] = {};   // per device: the builds may use more than the default 64 KB of dynamic LDS
+    int dev = 0;
+    MS_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) MS_FAIL(MS_ERR_UNSUPPORTED, "ms_gemm_bf16: device index %d", dev);
+    if (!lds_allowed[dev]) {
+        const void* builds[] = {(const void*)skinny_mfma_bf16<4, 1>, (const void*)skinny_mfma_bf16<2, 1>, (const void*)skinny_mfma_bf16<1, 4>,
+                                (const void*)skinny_mfma_bf16<1, 2>, (const void*)skinny_mfma_bf16<1, 1>,
+                                (const void*)skinny_mfma_bf16<4, 1, true>};
+        for (const void* f : builds) MS_HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kSkinnyLdsBytes));
+        lds_allowed[dev] = true;
+    }
+    const dim3 grid((unsigned)(g.N / (4 / v.wk * 16 * v.nt)), (unsigned)v.parts);
+    const dim3 block(kSkinnyThreads);
+    if (swiglu) hipLaunchKernelGGL((skinny_mfma_bf16<4, 1, true>), grid, block, v.lds_bytes, stream, g, v.parts);
+    else if (v.nt == 4) hipLaunchKernelGGL((skinny_mfma_bf16<4, 1>), grid, block, v.lds_bytes, stream, g, v.parts);
+    else if (v.nt == 2) hipLaunchKernelGGL((skinny_mfma_bf16<2, 1>), grid, block, v.lds_bytes, stream, g, v.parts);
+    else if (v.wk == 4) hipLaunchKernelGGL((skinny_mfma_bf16<1, 4>), grid, block, v.lds_bytes, stream, g, v.parts);
+    else if (v.wk == 2) hipLaunchKernelGGL((skinny_mfma_bf16<1, 2>), grid, block, v.lds_bytes, stream, g, v.parts);
+    else hipLaunchKernelGGL((skinny_mfma_bf16<1, 1>), grid, block, v.lds_bytes, stream, g, v.parts);
+    return MS_OK;
 }
 
 static int gemm_check_shape(const char* what, int M, int N, int K, int split_k) {
@@ -574,37 +662,29 @@ static int gemm_check_shape(const char* what, int M, int N, int K, int split_k) 
 }
 
 // Launches the tiles (and the reduction of the parts, if any).  g holds operands and destinations.
-template <int kM>
-static void gemv_dispatch(const GemmArgs& g, const GemvPlan& v, hipStream_t stream) {
-    const dim3 grid((unsigned)(g.N / (kGemvThreads / 64 * v.kr)), (unsigned)v.parts);
-    if (v.kr == 8)
-        hipLaunchKernelGGL((gemv_rows_bf16<kM, 8>), grid, dim3(kGemvThreads), v.lds_bytes, stream, g, v.parts);
-    else if (v.kr == 4)
-        hipLaunchKernelGGL((gemv_rows_bf16<kM, 4>), grid, dim3(kGemvThreads), v.lds_bytes, stream, g, v.parts);
-    else
-        hipLaunchKernelGGL((gemv_rows_bf16<kM, 2>), grid, dim3(kGemvThreads), v.lds_bytes, stream, g, v.parts);
-}
-
 static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, size_t ws_bytes, hipStream_t stream) {
-    if (!swiglu) {
-        const GemvPlan v = gemv_plan(g.M, g.N, g.K);
-        if (v.parts == 1 || (v.parts > 1 && workspace && ws_bytes >= v.workspace_bytes && g_aligned16(workspace))) {
+    if (swiglu) {   // few rows: four tiles per wave, the whole K in one part
+        SkinnyPlan sk = skinny_plan(g.M, g.N, g.K);
+        if (sk.parts == 1 && g.N % 256 == 0) {
+            sk.nt = 4;
+            sk.wk = 1;
             g.k_per_split = g.K;
-            g.partial = v.parts > 1 ? (float*)workspace : nullptr;
+            g.partial = nullptr;
             g.tail_first = g.tail_blocks = g.tail_k = g.tail_col0 = 0;
-            switch (v.km) {
-                case 1: gemv_dispatch<1>(g, v, stream); break;
-                case 2: gemv_dispatch<2>(g, v, stream); break;
-                case 3: gemv_dispatch<3>(g, v, stream); break;
-                case 4: gemv_dispatch<4>(g, v, stream); break;
-                case 5: gemv_dispatch<5>(g, v, stream); break;
-                case 6: gemv_dispatch<6>(g, v, stream); break;
-                case 7: gemv_dispatch<7>(g, v, stream); break;
-                default: gemv_dispatch<8>(g, v, stream); break;
-            }
-            if (v.parts > 1) {
+            if (int rc = skinny_dispatch(g, sk, stream, true)) return rc;
+            MS_HIP_TRY(hipGetLastError());
+            return MS_OK;
+        }
+    } else {
+        const SkinnyPlan sk = skinny_plan(g.M, g.N, g.K);
+        if (sk.parts == 1 || (sk.parts > 1 && workspace && ws_bytes >= sk.workspace_bytes && g_aligned16(workspace))) {
+            g.k_per_split = g.K;
+            g.partial = sk.parts > 1 ? (float*)workspace : nullptr;
+            g.tail_first = g.tail_blocks = g.tail_k = g.tail_col0 = 0;
+            if (int rc = skinny_dispatch(g, sk, stream)) return rc;
+            if (sk.parts > 1) {
                 const size_t quads = (size_t)g.M * g.N / 4;
-                hipLaunchKernelGGL((gemm_reduce<false>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, g, v.parts, 0);
+                hipLaunchKernelGGL((gemm_reduce<false>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, g, sk.parts, 0);
             }
             MS_HIP_TRY(hipGetLastError());
             return MS_OK;
@@ -656,8 +736,8 @@ static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, s
 extern "C" size_t ms_gemm_workspace_bytes(int M, int N, int K, int split_k) {
     if (M < 1 || N < 1 || K < 1 || split_k < 1 || N % ms::kGemmBN || K % (ms::kGemmBK * split_k)) return 0;
     const size_t tiled = ms::gemm_plan(M, N, K, split_k).workspace_bytes;
-    const size_t rows = ms::gemv_plan(M, N, K).workspace_bytes;   // enough for either kernel
-    return tiled > rows ? tiled : rows;
+    const size_t few = ms::skinny_plan(M, N, K).workspace_bytes;   // enough for either kernel
+    return tiled > few ? tiled : few;
 }
 
 extern "C" int ms_gemm_bf16(const void* a, const void* w, const void* bias, int M, int N, int K, int n_out, void* const* out,
@@ -723,8 +803,8 @@ extern "C" int ms_gemm_swiglu_bf16(const void* a, const void* w_gate_up, int M, 
 
 // Column groups that leave a key per row in greedy-token mode, for the kernel the shape runs on.
 static int argmax_groups(int M, int N, int K) {
-    const ms::GemvPlan v = ms::gemv_plan(M, N, K);
-    return v.parts == 1 ? N / v.kr : N / ms::kGemmBN * 2;
+    const ms::SkinnyPlan sk = ms::skinny_plan(M, N, K);
+    return sk.parts == 1 ? N / (16 * sk.nt) : N / ms::kGemmBN * 2;
 }
 
 extern "C" size_t ms_lm_head_argmax_workspace_bytes(int M, int vocab, int K) {
@@ -758,19 +838,11 @@ extern "C" int ms_lm_head_argmax_bf16(const void* a, const void* w, int M, int v
     g.partial = nullptr;
     g.keys = (unsigned long long*)workspace;
     const int groups = argmax_groups(M, vocab, K);
-    const GemvPlan v = gemv_plan(M, vocab, K);
-    if (v.parts == 1) {
+    const SkinnyPlan sk = skinny_plan(M, vocab, K);
+    if (sk.parts == 1) {
         g.tail_first = g.tail_blocks = g.tail_k = g.tail_col0 = 0;
-        switch (v.km) {
-            case 1: gemv_dispatch<1>(g, v, stream); break;
-            case 2: gemv_dispatch<2>(g, v, stream); break;
-            case 3: gemv_dispatch<3>(g, v, stream); break;
-            case 4: gemv_dispatch<4>(g, v, stream); break;
-            case 5: gemv_dispatch<5>(g, v, stream); break;
-            case 6: gemv_dispatch<6>(g, v, stream); break;
-            case 7: gemv_dispatch<7>(g, v, stream); break;
-            default: gemv_dispatch<8>(g, v, stream); break;
-        }
+        rc = skinny_dispatch(g, sk, stream);
+        if (rc != MS_OK) return rc;
     } else {
         const GemmPlan p = gemm_plan(M, vocab, K, 1);
         const int blocks = p.n_groups * p.group_blocks;   // whole tiles throughout

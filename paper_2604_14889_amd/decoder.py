@@ -226,8 +226,16 @@ class Decoder:
                 wo_t=lw.wo.t(), w_gate_up_t=lw.w_gate_up.t(),
                 norm2=(h, proj, ptr(lw.ln2), cfg.eps, x, rows, cfg.hidden),
                 swiglu=(gate_up, act, rows, cfg.inter),
+                # few rows: gate/up with SwiGLU in the product's epilogue, from the row-interleaved copy of the weight
+                mlp_few=(x, ptr(lw.gate_up_blocked()), rows, cfg.inter, cfg.hidden, act, ws, ws_bytes) if self._few(rows) else None,
                 down=(act, ptr(lw.w_down), None, rows, cfg.hidden, cfg.inter, 1, outs_proj, cols_h, down_split, ws, ws_bytes)))
         return dict(layers=layers, final=(h, proj, ptr(w.norm), cfg.eps, x, rows, cfg.hidden), q=q, attn=attn)
+
+    def _few(self, rows: int) -> bool:
+        """Steps of at most 8 rows (a single sequence) run every projection on this library's
+        row-streaming kernel, gate/up fused with SwiGLU (which keeps a row-interleaved second copy
+        of that weight, made at the first such step)."""
+        return rows <= 8 and self.cfg.inter % 128 == 0
 
     def forget_prepared(self) -> None:
         """Drops the prepared argument tuples (they hold device addresses of the weights)."""
@@ -248,7 +256,7 @@ class Decoder:
         pos_ptr, ctx_ptr = M._dev(pos), M._dev(ctx_new)
         cache, q, attn = self.ses.cache, prep["q"], prep["attn"]
         x_t, attn_t, proj_t, gate_up_t = self.x[:rows], self.attn[:rows], self.proj[:rows], self.gate_up[:rows]
-        few = rows <= 8     # few rows: the row-streaming kernel is ahead of the library on the output projection too
+        few = self._few(rows)
         M.ms_embed_rows(w.embed, tokens, self.h[:rows])
         for li, c in enumerate(prep["layers"]):
             check(lib.ms_add_rmsnorm(*c["norm1"], st))
@@ -266,8 +274,11 @@ class Decoder:
             else:
                 torch.mm(attn_t, c["wo_t"], out=proj_t)
             check(lib.ms_add_rmsnorm(*c["norm2"], st))
-            torch.mm(x_t, c["w_gate_up_t"], out=gate_up_t)
-            check(lib.ms_swiglu(*c["swiglu"], st))
+            if few:
+                check(lib.ms_gemm_swiglu_bf16(*c["mlp_few"], st))
+            else:
+                torch.mm(x_t, c["w_gate_up_t"], out=gate_up_t)
+                check(lib.ms_swiglu(*c["swiglu"], st))
             check(lib.ms_gemm_bf16(*c["down"], st))
         check(lib.ms_add_rmsnorm(*prep["final"], st))
         return self._greedy_tokens(x_t, rows)
@@ -282,7 +293,10 @@ class Decoder:
             M.ms_lm_head_argmax_bf16(x, self.w.lm_head, targets, self.lm_ws)
             return None, targets
         logits = self.logits[:rows]
-        torch.mm(x, self.w.lm_head.t(), out=logits)
+        if self.hand_gemm and self._few(rows) and self.cfg.vocab % 128 == 0:
+            M.ms_gemm_bf16(x, self.w.lm_head, None, [logits], 1, self.gemm_ws)
+        else:
+            torch.mm(x, self.w.lm_head.t(), out=logits)
         M.ms_argmax_rows(logits, self.cfg.vocab, targets)
         return logits, targets
 

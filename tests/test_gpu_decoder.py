@@ -134,6 +134,24 @@ def test_decode_step_matches_oracle_and_commits_accepted_rows():
         srt_g = np.sort(ref.logits, axis=-1)
         clear_g = (srt_g[..., -1] - srt_g[..., -2]) > 2 * max_abs
         assert (targets_g.cpu().numpy().reshape(B, nq)[clear_g] == ref.targets[clear_g]).all()
+        # a single sequence (7 rows): every projection on the few-row kernel, gate/up with SwiGLU in
+        # its epilogue, the LM head with and without the greedy token; rows of a step do not depend
+        # on the other sequences, so the batch's reference serves
+        for b in (0, 2):
+            dec_1 = D.Decoder(cfg, gw, ses, nq, fused_lm_head=(b == 2))
+            assert dec_1._few(nq)
+            logits_1, targets_1 = dec_1.step(ids[b:b + 1], S.ints_dev(tokens[b:b + 1]).view(1, nq), S.ints_dev(pos[b:b + 1]).view(1, nq), nv, nf)
+            torch.cuda.synchronize()
+            if b == 0:
+                err_1 = np.abs(logits_1.float().cpu().numpy().astype(np.float64) - ref.logits[b])
+                print(f"logits (single sequence): max-abs {err_1.max():.3e}, mean-rel {err_1.mean() / np.abs(ref.logits[b]).mean():.3e}")
+                assert err_1.max() <= 4e-2 * scale and err_1.mean() / np.abs(ref.logits[b]).mean() <= 2e-2
+            else:
+                assert logits_1 is None
+            assert (targets_1.cpu().numpy()[clear_g[b]] == ref.targets[b][clear_g[b]]).all()
+            k_1, _ = dec_1.step_kv()
+            assert np.abs(k_1.float().cpu().numpy().reshape(cfg.n_layers, nq, cfg.n_kv_heads, cfg.head_dim) - ref.k_new[:, b]).max() \
+                <= 4e-2 * np.abs(ref.k_new).max()
         # greedy tokens wherever the oracle's decision has a margin
         srt = np.sort(ref.logits, axis=-1)
         margin = srt[..., -1] - srt[..., -2]

@@ -30,6 +30,15 @@ CASES = [
     (3, 3584, 18944, [3584], 1, True),            # 4 rows of A kept: K in 3 parts
     (4, 37888, 512, [37888], 1, True),            # 8 weight rows per wave
     (7, 16384, 1536, [16384], 1, False),          # 4 weight rows per wave, 3 steps
+    # at most 16 rows and K a multiple of 128: the matrix-core row-streaming kernel
+    (16, 256, 128, [128, 128], 1, True),          # a single K step
+    (9, 4608, 3584, [3584, 512, 512], 1, True),   # four waves split K over the same weight rows
+    (7, 3584, 3584, [3584], 1, False),            # output projection of a single sequence
+    (14, 3584, 18944, [3584], 1, False),          # two sequences' down projection: K in parts, fp32 partials
+    (16, 37888, 384, [37888], 1, True),           # two 16-row tiles per wave, 3 steps (odd against 2 in flight)
+    (2, 152064, 256, [152064], 1, False),         # four tiles per wave (LM-head width)
+    (12, 1024, 640, [512, 512], 1, False),        # 5 steps over 4 waves (1, 1, 1, 2)
+    (11, 128, 2176, [128], 1, True),              # 17 steps over 4 waves, one workgroup column block of two
 ]
 
 
@@ -48,7 +57,7 @@ def test_gemm_matches_fp64_definition(m, n, k, widths, split, with_bias):
     need = M.ms_gemm_workspace_bytes(m, n, k, split)
     if split > 1:
         assert need == split * m * n * 4
-    elif n >= 37888 and m > 8:
+    elif n >= 37888 and m > 16:
         assert need > 0, "this shape is meant to exercise the K-split last round"
     if need:
         ws = torch.empty(need, dtype=torch.uint8, device="cuda")
@@ -118,7 +127,8 @@ def test_gemm_last_round_split_is_optional():
     assert float(d.max()) <= 2.0 ** -7 * float(o2.float().abs().max())   # other order of fp32 additions: one bf16 step at most
 
 
-SWIGLU_CASES = [(7, 64, 32), (300, 1088, 256), (448, 18944, 512)]
+SWIGLU_CASES = [(7, 64, 32), (300, 1088, 256), (448, 18944, 512),
+                (7, 18944, 512), (16, 128, 128), (5, 1152, 384), (1, 2048, 3584)]   # few rows: the row-streaming kernel
 
 
 @pytest.mark.parametrize("m,inter,k", SWIGLU_CASES)
@@ -138,8 +148,8 @@ def test_gate_up_gemm_with_swiglu_epilogue(m, inter, k):
     blocked = M.interleave_gate_up(S.to_device(wg, M.MS_BF16), S.to_device(wu, M.MS_BF16))
     out = torch.full((m, inter), float("nan"), dtype=torch.bfloat16, device="cuda")
     need = M.ms_gemm_workspace_bytes(m, 2 * inter, k, 1)
-    if inter == 18944:
-        assert need > 0
+    if inter == 18944 and m > 16:
+        assert need > 0      # the tiled kernel's K-split last round
     ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
     M.ms_gemm_swiglu_bf16(S.to_device(a, M.MS_BF16), blocked, out, ws)
     torch.cuda.synchronize()
@@ -151,7 +161,8 @@ def test_gate_up_gemm_with_swiglu_epilogue(m, inter, k):
     assert (err <= bound).all(), f"max excess {np.max(err - bound):.3e} at {np.unravel_index(np.argmax(err - bound), err.shape)}"
 
 
-ARGMAX_CASES = [(7, 16384, 1536), (5, 2048, 512), (1, 128, 512), (8, 37888, 1024), (9, 1024, 512), (300, 4096, 256), (448, 2048, 3584)]
+ARGMAX_CASES = [(7, 16384, 1536), (5, 2048, 512), (1, 128, 512), (8, 37888, 1024), (9, 1024, 512), (300, 4096, 256), (448, 2048, 3584),
+                (16, 152064, 256), (12, 37888, 384), (3, 1024, 128), (7, 152064, 256)]
 
 
 @pytest.mark.parametrize("m,vocab,k", ARGMAX_CASES)
