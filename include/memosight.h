@@ -271,6 +271,20 @@ int ms_gemm_bf16(const void* a, const void* w, const void* bias, int M, int N, i
 int ms_gemm_swiglu_bf16(const void* a, const void* w_gate_up, int M, int inter, int K, void* out,
                         void* workspace, size_t ws_bytes, void* stream);
 
+/* A projection together with the residual add and RMSNorm that follow it in the decoder block (the
+ * MLP's down projection and the next block's input norm): delta = A[M][K] . W[N][K]^T rounded to
+ * bf16, h[m] += delta[m] (device fp32 [M][N], in place), out[m] = h[m] / sqrt(mean(h[m]^2) + eps) *
+ * norm_weight (bf16 [N]; out bf16 [M][N]) -- ms_gemm_bf16 without bias followed by ms_add_rmsnorm,
+ * with the same bits, one launch less and no [M][N] intermediate.  K is always divided (the sum of
+ * the parts and the norm share a kernel): split_k >= 2 above 16 rows, any split_k (ignored) up to
+ * 16 rows with K % 128 == 0.  N % 128 == 0, N <= 8192, K % (32 * split_k) == 0; operands 16-byte
+ * aligned; workspace: ms_gemm_add_rmsnorm_workspace_bytes(M, N, K, split_k) bytes, 16-byte aligned
+ * (0: the shape needs split_k >= 2), MS_ERR_WORKSPACE without it. */
+size_t ms_gemm_add_rmsnorm_workspace_bytes(int M, int N, int K, int split_k);
+int ms_gemm_add_rmsnorm_bf16(const void* a, const void* w, int M, int N, int K, int split_k, float* h,
+                             const void* norm_weight, float eps, void* out, void* workspace,
+                             size_t ws_bytes, void* stream);
+
 /* The LM head and the greedy token in one: out[m] = argmax over n of A[m] . W[n] (device int32 [M]),
  * taken on the fp32 sums, the lowest column among equal maxima, NaN never wins (a row of NaN gives
  * 0); the [M][vocab] logits are not written.  Operands as for ms_gemm_bf16 (vocab % 128 == 0,

@@ -77,6 +77,8 @@ _SIGS = {
     "ms_argmax_rows": (_I, [_P, _I, _I, C.c_long, _P, _P]),
     "ms_gemm_workspace_bytes": (_SZ, [_I, _I, _I, _I]),
     "ms_gemm_swiglu_bf16": (_I, [_P, _P, _I, _I, _I, _P, _P, _SZ, _P]),
+    "ms_gemm_add_rmsnorm_workspace_bytes": (_SZ, [_I, _I, _I, _I]),
+    "ms_gemm_add_rmsnorm_bf16": (_I, [_P, _P, _I, _I, _I, _I, _P, _P, _F, _P, _P, _SZ, _P]),
     "ms_lm_head_argmax_workspace_bytes": (_SZ, [_I, _I, _I]),
     "ms_lm_head_argmax_bf16": (_I, [_P, _P, _I, _I, _I, _P, _P, _SZ, _P]),
     "ms_gemm_bf16": (_I, [_P, _P, _P, _I, _I, _I, _I, C.POINTER(_P), _IP, _I, _P, _SZ, _P]),
@@ -308,6 +310,22 @@ def ms_gemm_swiglu_bf16(a, w_gate_up, out, workspace=None, stream=None) -> None:
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.ms_gemm_swiglu_bf16(_sized(None, a, "a", M_ * K, 2), _sized(None, w_gate_up, "w_gate_up", 2 * inter * K, 2), M_, inter, K,
                                    _sized(None, out, "out", M_ * inter, 2), _dev(workspace), ws_bytes, _stream(stream)))
+
+
+def ms_gemm_add_rmsnorm_workspace_bytes(M: int, N: int, K: int, split_k: int) -> int:
+    return lib.ms_gemm_add_rmsnorm_workspace_bytes(M, N, K, split_k)
+
+
+def ms_gemm_add_rmsnorm_bf16(a, w, h, norm_weight, eps: float, out, split_k: int = 1, workspace=None, stream=None) -> None:
+    """h[M, N] (fp32, in place) += bf16(a . w^T); out = rmsnorm(h) * norm_weight (bf16)."""
+    M_, K = a.shape
+    N = w.shape[0]
+    if w.shape[1] != K or tuple(h.shape) != (M_, N) or tuple(out.shape) != (M_, N) or norm_weight.numel() != N:
+        raise MsError(MS_ERR_INVALID, "ms_gemm_add_rmsnorm_bf16: shapes do not match")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.ms_gemm_add_rmsnorm_bf16(_sized(None, a, "a", M_ * K, 2), _sized(None, w, "w", N * K, 2), M_, N, K, split_k,
+                                        _sized(None, h, "h", M_ * N, 4), _sized(None, norm_weight, "norm_weight", N, 2), eps,
+                                        _sized(None, out, "out", M_ * N, 2), _dev(workspace), ws_bytes, _stream(stream)))
 
 
 def ms_lm_head_argmax_workspace_bytes(M: int, vocab: int, K: int) -> int:

@@ -14,18 +14,6 @@ namespace ms {
 
 constexpr int kRowThreads = 256;
 
-__device__ __forceinline__ float block_sum(float x, float* red) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
-    const int w = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) red[w] = x;
-    __syncthreads();
-    float t = 0.f;
-#pragma unroll
-    for (int i = 0; i < kRowThreads / 64; ++i) t += red[i];
-    return t;
-}
-
 // h[row] = table[tokens[row]] widened to fp32.  One workgroup per row, 8 elements per thread and turn.
 __global__ __launch_bounds__(kRowThreads) void embed_rows(const uint16_t* __restrict__ table, int vocab, int hidden,
                                                            const int* __restrict__ tokens, float* __restrict__ h) {
@@ -52,26 +40,34 @@ __global__ __launch_bounds__(kRowThreads) void embed_rows(const uint16_t* __rest
 }
 
 // h[row] += delta[row] (if given); out[row] = h[row] / sqrt(mean(h[row]^2) + eps) * weight.
-// One workgroup per row; the row is read once (kept in registers between the two passes).
-constexpr int kMaxPerThread = 4;   // x 8 elements x 256 threads: hidden up to 8192
-__global__ __launch_bounds__(kRowThreads) void add_rmsnorm(float* __restrict__ h, const uint16_t* __restrict__ delta,
-                                                            const uint16_t* __restrict__ weight, float eps,
-                                                            uint16_t* __restrict__ out, int hidden) {
-    __shared__ float red[kRowThreads / 64];
+// One workgroup per row; the row is read once (kept in registers between the two passes); all loads
+// are issued before the first wait (with a few rows the kernel is one memory round trip long).
+__global__ __launch_bounds__(kNormThreads) void add_rmsnorm(float* __restrict__ h, const uint16_t* __restrict__ delta,
+                                                             const uint16_t* __restrict__ weight, float eps,
+                                                             uint16_t* __restrict__ out, int hidden) {
+    __shared__ float red[kNormThreads / 64];
     const int row = blockIdx.x;
     float* hr = h + (size_t)row * hidden;
-    float x[kMaxPerThread][8];
-    float ss = 0.f;
+    float x[kNormMaxPerThread][8];
+    uint4 wv[kNormMaxPerThread], dv[kNormMaxPerThread];
 #pragma unroll
-    for (int t = 0; t < kMaxPerThread; ++t) {
-        const int i = (t * kRowThreads + threadIdx.x) * 8;
+    for (int t = 0; t < kNormMaxPerThread; ++t) {
+        const int i = (t * kNormThreads + (int)threadIdx.x) * 8;
         if (i < hidden) {
             const float4 a = *reinterpret_cast<const float4*>(hr + i), b = *reinterpret_cast<const float4*>(hr + i + 4);
             x[t][0] = a.x; x[t][1] = a.y; x[t][2] = a.z; x[t][3] = a.w;
             x[t][4] = b.x; x[t][5] = b.y; x[t][6] = b.z; x[t][7] = b.w;
+            wv[t] = *reinterpret_cast<const uint4*>(weight + i);
+            if (delta) dv[t] = *reinterpret_cast<const uint4*>(delta + (size_t)row * hidden + i);
+        }
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int t = 0; t < kNormMaxPerThread; ++t) {
+        const int i = (t * kNormThreads + (int)threadIdx.x) * 8;
+        if (i < hidden) {
             if (delta) {
-                const uint4 dv = *reinterpret_cast<const uint4*>(delta + (size_t)row * hidden + i);
-                const uint32_t w[4] = {dv.x, dv.y, dv.z, dv.w};
+                const uint32_t w[4] = {dv[t].x, dv[t].y, dv[t].z, dv[t].w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     x[t][2 * e] += bf16_bits_to_float(w[e] & 0xffffu);
@@ -84,13 +80,12 @@ __global__ __launch_bounds__(kRowThreads) void add_rmsnorm(float* __restrict__ h
             for (int e = 0; e < 8; ++e) ss += x[t][e] * x[t][e];
         }
     }
-    const float rs = 1.0f / sqrtf(block_sum(ss, red) / (float)hidden + eps);
+    const float rs = 1.0f / sqrtf(block_sum<kNormThreads>(ss, red) / (float)hidden + eps);
 #pragma unroll
-    for (int t = 0; t < kMaxPerThread; ++t) {
-        const int i = (t * kRowThreads + threadIdx.x) * 8;
+    for (int t = 0; t < kNormMaxPerThread; ++t) {
+        const int i = (t * kNormThreads + (int)threadIdx.x) * 8;
         if (i < hidden) {
-            const uint4 wv = *reinterpret_cast<const uint4*>(weight + i);
-            const uint32_t w[4] = {wv.x, wv.y, wv.z, wv.w};
+            const uint32_t w[4] = {wv[t].x, wv[t].y, wv[t].z, wv[t].w};
             uint32_t o[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -213,13 +208,13 @@ extern "C" int ms_embed_rows(const void* table, int vocab, int hidden, const int
 
 extern "C" int ms_add_rmsnorm(float* h, const void* delta, const void* weight, float eps, void* out, int n, int hidden,
                               void* stream) {
-    if (n < 0 || hidden < 8 || hidden % 8 || hidden > ms::kMaxPerThread * ms::kRowThreads * 8 || !(eps >= 0.f))
+    if (n < 0 || hidden < 8 || hidden % 8 || hidden > ms::kNormMaxPerThread * ms::kNormThreads * 8 || !(eps >= 0.f))
         MS_FAIL(MS_ERR_INVALID, "ms_add_rmsnorm: need hidden a multiple of 8 up to %d and eps >= 0",
-                ms::kMaxPerThread * ms::kRowThreads * 8);
+                ms::kNormMaxPerThread * ms::kNormThreads * 8);
     if (n == 0) return MS_OK;
     if (!h || !weight || !out || !ms::aligned16(h) || !ms::aligned16(weight) || !ms::aligned16(out) || !ms::aligned16(delta))
         MS_FAIL(MS_ERR_INVALID, "ms_add_rmsnorm: null or misaligned (16 bytes) argument");
-    hipLaunchKernelGGL(ms::add_rmsnorm, dim3(n), dim3(ms::kRowThreads), 0, (hipStream_t)stream, h, (const uint16_t*)delta,
+    hipLaunchKernelGGL(ms::add_rmsnorm, dim3(n), dim3(ms::kNormThreads), 0, (hipStream_t)stream, h, (const uint16_t*)delta,
                        (const uint16_t*)weight, eps, (uint16_t*)out, hidden);
     MS_HIP_TRY(hipGetLastError());
     return MS_OK;

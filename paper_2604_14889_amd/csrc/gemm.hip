@@ -344,6 +344,75 @@ __global__ __launch_bounds__(256) void gemm_reduce(GemmArgs g, int parts, int co
     *reinterpret_cast<uint2*>(dst + (size_t)m * ld + (n - dcol0)) = pk;
 }
 
+// gemm_reduce over whole rows (no bias) and the decoder block's residual add + RMSNorm in one pass:
+// delta = the K parts' sum rounded to bf16, h[row] += delta, out[row] = h[row] / sqrt(mean(h[row]^2)
+// + eps) * weight.  One workgroup per row; same arithmetic in the same order as the two kernels it
+// replaces (the same bits).  N a multiple of 8, at most 8192.
+__global__ __launch_bounds__(kNormThreads) void reduce_add_rmsnorm(const float* __restrict__ partial, int parts, int M, int N,
+                                                                    float* __restrict__ h, const uint16_t* __restrict__ weight,
+                                                                    float eps, uint16_t* __restrict__ out) {
+    __shared__ float red[kNormThreads / 64];
+    const int row = blockIdx.x;
+    float* hr = h + (size_t)row * N;
+    float x[kNormMaxPerThread][8];
+    uint4 wv[kNormMaxPerThread];
+    float ss = 0.f;
+#pragma unroll
+    for (int t = 0; t < kNormMaxPerThread; ++t) {
+        const int i = (t * kNormThreads + (int)threadIdx.x) * 8;
+        if (i < N) {
+            const float4 ha = *reinterpret_cast<const float4*>(hr + i), hb = *reinterpret_cast<const float4*>(hr + i + 4);
+            wv[t] = *reinterpret_cast<const uint4*>(weight + i);
+            float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            const float* p = partial + (size_t)row * N + i;
+            const size_t part_stride = (size_t)M * N;
+            int z = 0;
+            for (; z + 8 <= parts; z += 8) {   // eight parts per memory round trip, added in their order
+                float4 a[8], b[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    a[u] = *reinterpret_cast<const float4*>(p + (z + u) * part_stride);
+                    b[u] = *reinterpret_cast<const float4*>(p + (z + u) * part_stride + 4);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    s[0] += a[u].x; s[1] += a[u].y; s[2] += a[u].z; s[3] += a[u].w;
+                    s[4] += b[u].x; s[5] += b[u].y; s[6] += b[u].z; s[7] += b[u].w;
+                }
+            }
+            for (; z < parts; ++z) {
+                const float4 a = *reinterpret_cast<const float4*>(p + z * part_stride), b = *reinterpret_cast<const float4*>(p + z * part_stride + 4);
+                s[0] += a.x; s[1] += a.y; s[2] += a.z; s[3] += a.w;
+                s[4] += b.x; s[5] += b.y; s[6] += b.z; s[7] += b.w;
+            }
+            x[t][0] = ha.x; x[t][1] = ha.y; x[t][2] = ha.z; x[t][3] = ha.w;
+            x[t][4] = hb.x; x[t][5] = hb.y; x[t][6] = hb.z; x[t][7] = hb.w;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[t][e] += bf16_bits_to_float(float_to_bf16_bits(s[e]));
+            *reinterpret_cast<float4*>(hr + i) = make_float4(x[t][0], x[t][1], x[t][2], x[t][3]);
+            *reinterpret_cast<float4*>(hr + i + 4) = make_float4(x[t][4], x[t][5], x[t][6], x[t][7]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += x[t][e] * x[t][e];
+        }
+    }
+    const float rs = 1.0f / sqrtf(block_sum<kNormThreads>(ss, red) / (float)N + eps);
+#pragma unroll
+    for (int t = 0; t < kNormMaxPerThread; ++t) {
+        const int i = (t * kNormThreads + (int)threadIdx.x) * 8;
+        if (i < N) {
+            const uint32_t w[4] = {wv[t].x, wv[t].y, wv[t].z, wv[t].w};
+            uint32_t o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = x[t][2 * e] * rs * bf16_bits_to_float(w[e] & 0xffffu);
+                const float hi = x[t][2 * e + 1] * rs * bf16_bits_to_float(w[e] >> 16);
+                o[e] = (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+            }
+            *reinterpret_cast<uint4*>(out + (size_t)row * N + i) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
+}
+
 // out[m] = column of the best key among keys[0 .. groups)[m]; a row without any key (all NaN) gives 0.
 __global__ __launch_bounds__(256) void argmax_finish(const unsigned long long* keys, int groups, int M, int* out) {
     __shared__ unsigned long long red[256];
@@ -593,12 +662,13 @@ struct SkinnyPlan {
     int parts, nt, wk, lds_bytes;
     size_t workspace_bytes;
 };
-static SkinnyPlan skinny_plan(int M, int N, int K) {
+static SkinnyPlan skinny_plan(int M, int N, int K, int min_parts = 1) {
     SkinnyPlan p = {0, 0, 0, 0, 0};
     if (M < 1 || M > kSkinnyMaxRows || K % kSkinnyStepK || N % 64) return p;
     const int steps = K / kSkinnyStepK;
-    // fewest K parts whose rows of A fit the LDS share
-    int parts = 1;
+    if (steps < min_parts) return p;
+    // fewest K parts (from min_parts up) whose rows of A fit the LDS share
+    int parts = min_parts;
     while (parts < steps && (long)M * (((steps + parts - 1) / parts) * kSkinnyStepK * 2 + 16) > kSkinnyLdsForA) ++parts;
     const int want = 2 * gemm_slots();   // waves that fill the memory pipeline with 16 KB in flight each
     const int n_tiles = N / 16;
@@ -661,8 +731,18 @@ static int gemm_check_shape(const char* what, int M, int N, int K, int split_k) 
     return MS_OK;
 }
 
+// What follows the down projection in a decoder block: with it, the product always goes through fp32
+// partials and reduce_add_rmsnorm takes the place of gemm_reduce.
+struct NormTail {
+    float* h;
+    const uint16_t* weight;
+    float eps;
+    uint16_t* out;
+};
+
 // Launches the tiles (and the reduction of the parts, if any).  g holds operands and destinations.
-static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, size_t ws_bytes, hipStream_t stream) {
+static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, size_t ws_bytes, hipStream_t stream,
+                       const NormTail* norm = nullptr) {
     if (swiglu) {   // few rows: four tiles per wave, the whole K in one part
         SkinnyPlan sk = skinny_plan(g.M, g.N, g.K);
         if (sk.parts == 1 && g.N % 256 == 0) {
@@ -676,13 +756,16 @@ static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, s
             return MS_OK;
         }
     } else {
-        const SkinnyPlan sk = skinny_plan(g.M, g.N, g.K);
+        const SkinnyPlan sk = skinny_plan(g.M, g.N, g.K, norm ? 2 : 1);
         if (sk.parts == 1 || (sk.parts > 1 && workspace && ws_bytes >= sk.workspace_bytes && g_aligned16(workspace))) {
             g.k_per_split = g.K;
             g.partial = sk.parts > 1 ? (float*)workspace : nullptr;
             g.tail_first = g.tail_blocks = g.tail_k = g.tail_col0 = 0;
             if (int rc = skinny_dispatch(g, sk, stream)) return rc;
-            if (sk.parts > 1) {
+            if (norm) {
+                hipLaunchKernelGGL(reduce_add_rmsnorm, dim3((unsigned)g.M), dim3(kNormThreads), 0, stream, (const float*)g.partial,
+                                   sk.parts, g.M, g.N, norm->h, norm->weight, norm->eps, norm->out);
+            } else if (sk.parts > 1) {
                 const size_t quads = (size_t)g.M * g.N / 4;
                 hipLaunchKernelGGL((gemm_reduce<false>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, g, sk.parts, 0);
             }
@@ -710,9 +793,15 @@ static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, s
         g.partial = (float*)workspace;
         g.tail_first = (int)grid.x;   // unused by this build of the kernel
         hipLaunchKernelGGL((gemm_tn_bf16<kGemmAllPartial>), grid, dim3(kGemmThreads), 0, stream, g);
-        const size_t quads = (size_t)g.M * g.N / 4;
-        hipLaunchKernelGGL((gemm_reduce<false>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, g, split_k, 0);
+        if (norm) {
+            hipLaunchKernelGGL(reduce_add_rmsnorm, dim3((unsigned)g.M), dim3(kNormThreads), 0, stream, (const float*)g.partial, split_k,
+                               g.M, g.N, norm->h, norm->weight, norm->eps, norm->out);
+        } else {
+            const size_t quads = (size_t)g.M * g.N / 4;
+            hipLaunchKernelGGL((gemm_reduce<false>), dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, g, split_k, 0);
+        }
     } else {
+        if (norm) MS_FAIL(MS_ERR_INVALID, "ms_gemm_add_rmsnorm_bf16: split_k >= 2 needed above %d rows", kSkinnyMaxRows);
         if (p.tail_groups) g.partial = (float*)workspace;
         if (swiglu)
             hipLaunchKernelGGL((gemm_tn_bf16<kGemmSwiglu>), grid, dim3(kGemmThreads), 0, stream, g);
@@ -772,6 +861,46 @@ extern "C" int ms_gemm_bf16(const void* a, const void* w, const void* bias, int 
         g.out_col[i + 1] = N;
     }
     return gemm_launch(g, split_k, false, workspace, ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" size_t ms_gemm_add_rmsnorm_workspace_bytes(int M, int N, int K, int split_k) {
+    if (M < 1 || N < 1 || K < 1 || split_k < 1 || N % ms::kGemmBN || K % (ms::kGemmBK * split_k)) return 0;
+    const size_t tiled = split_k > 1 ? ms::gemm_plan(M, N, K, split_k).workspace_bytes : 0;
+    const size_t few = ms::skinny_plan(M, N, K, 2).workspace_bytes;
+    return tiled > few ? tiled : few;
+}
+
+extern "C" int ms_gemm_add_rmsnorm_bf16(const void* a, const void* w, int M, int N, int K, int split_k, float* h,
+                                        const void* norm_weight, float eps, void* out, void* workspace, size_t ws_bytes,
+                                        void* stream) {
+    using namespace ms;
+    int rc = gemm_check_shape("ms_gemm_add_rmsnorm_bf16", M, N, K, split_k);
+    if (rc != MS_OK) return rc;
+    if (N > kNormMaxPerThread * kNormThreads * 8 || !(eps >= 0.f))
+        MS_FAIL(MS_ERR_INVALID, "ms_gemm_add_rmsnorm_bf16: need N up to %d and eps >= 0", kNormMaxPerThread * kNormThreads * 8);
+    if (M == 0) return MS_OK;
+    if (!a || !w || !h || !norm_weight || !out || !g_aligned16(a) || !g_aligned16(w) || !g_aligned16(h) ||
+        !g_aligned16(norm_weight) || !g_aligned16(out))
+        MS_FAIL(MS_ERR_INVALID, "ms_gemm_add_rmsnorm_bf16: null or misaligned (16 bytes) argument");
+    const size_t need = ms_gemm_add_rmsnorm_workspace_bytes(M, N, K, split_k);
+    if (!need) MS_FAIL(MS_ERR_INVALID, "ms_gemm_add_rmsnorm_bf16: split_k >= 2 needed for this shape");
+    if (!workspace || ws_bytes < need || !g_aligned16(workspace))
+        MS_FAIL(MS_ERR_WORKSPACE, "ms_gemm_add_rmsnorm_bf16: workspace of %zu bytes needed", need);
+    GemmArgs g;
+    g.a = (const uint16_t*)a;
+    g.w = (const uint16_t*)w;
+    g.bias = nullptr;
+    g.keys = nullptr;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.n_out = 1;
+    g.out[0] = (uint16_t*)out;   // not written by the product itself
+    g.out_col[0] = 0;
+    for (int i = 1; i < kGemmMaxOut; ++i) g.out[i] = nullptr;
+    for (int i = 1; i <= kGemmMaxOut; ++i) g.out_col[i] = N;
+    const NormTail tail = {h, (const uint16_t*)norm_weight, eps, (uint16_t*)out};
+    return gemm_launch(g, split_k, false, workspace, ws_bytes, (hipStream_t)stream, &tail);
 }
 
 extern "C" int ms_gemm_swiglu_bf16(const void* a, const void* w_gate_up, int M, int inter, int K, void* out, void* workspace,

@@ -21,6 +21,25 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
     return (uint16_t)(u >> 16);
 }
 
+// Sum over a workgroup of kThreads threads; every thread gets the total.  red: kThreads / 64 floats of LDS.
+template <int kThreads>
+__device__ __forceinline__ float block_sum(float x, float* red) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) red[w] = x;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < kThreads / 64; ++i) t += red[i];
+    return t;
+}
+
+// Row kernels with a norm (one workgroup per row, the row held in registers between the two passes):
+// threads per row and 8-element chunks per thread; rows of up to 8192 elements.
+constexpr int kNormThreads = 512;
+constexpr int kNormMaxPerThread = 2;
+
 __device__ __forceinline__ float to_float(float x) { return x; }
 __device__ __forceinline__ float to_float(bf16_t x) { return bf16_bits_to_float(x.bits); }
 

@@ -144,6 +144,9 @@ class Decoder:
                        M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[1]),
                        M.ms_gemm_workspace_bytes(min(max_rows, 8), qd + 2 * kd, cfg.hidden, 1),
                        M.ms_gemm_workspace_bytes(min(max_rows, 8), cfg.hidden, cfg.inter, 1),
+                       M.ms_gemm_add_rmsnorm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[1]),
+                       max(M.ms_gemm_add_rmsnorm_workspace_bytes(r, cfg.hidden, cfg.inter, self.splits_few[1])
+                           for r in range(1, min(max_rows, 16) + 1)),
                        M.ms_gemm_workspace_bytes(max_rows, 2 * cfg.inter, cfg.hidden, 1) if self.fused_mlp else 0)
             self.gemm_ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
@@ -228,8 +231,10 @@ class Decoder:
                 swiglu=(gate_up, act, rows, cfg.inter),
                 # few rows: gate/up with SwiGLU in the product's epilogue, from the row-interleaved copy of the weight
                 mlp_few=(x, ptr(lw.gate_up_blocked()), rows, cfg.inter, cfg.hidden, act, ws, ws_bytes) if self._few(rows) else None,
-                down=(act, ptr(lw.w_down), None, rows, cfg.hidden, cfg.inter, 1, outs_proj, cols_h, down_split, ws, ws_bytes)))
-        return dict(layers=layers, final=(h, proj, ptr(w.norm), cfg.eps, x, rows, cfg.hidden), q=q, attn=attn)
+                # the down projection with the residual add and the norm that follow it (the next block's, or the final one)
+                down_norm=(act, ptr(lw.w_down), rows, cfg.hidden, cfg.inter, down_split, h,
+                           ptr(w.layers[li + 1].ln1 if li + 1 < len(w.layers) else w.norm), cfg.eps, x, ws, ws_bytes)))
+        return dict(layers=layers, q=q, attn=attn)
 
     def _few(self, rows: int) -> bool:
         """Steps of at most 8 rows (a single sequence) run every projection on this library's
@@ -259,7 +264,8 @@ class Decoder:
         few = self._few(rows)
         M.ms_embed_rows(w.embed, tokens, self.h[:rows])
         for li, c in enumerate(prep["layers"]):
-            check(lib.ms_add_rmsnorm(*c["norm1"], st))
+            if li == 0:     # the later blocks' input norm is applied by the block before, with its down projection
+                check(lib.ms_add_rmsnorm(*c["norm1"], st))
             check(lib.ms_gemm_bf16(*c["qkv"], st))
             if self.attn_events is not None:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -279,8 +285,7 @@ class Decoder:
             else:
                 torch.mm(x_t, c["w_gate_up_t"], out=gate_up_t)
                 check(lib.ms_swiglu(*c["swiglu"], st))
-            check(lib.ms_gemm_bf16(*c["down"], st))
-        check(lib.ms_add_rmsnorm(*prep["final"], st))
+            check(lib.ms_gemm_add_rmsnorm_bf16(*c["down_norm"], st))
         return self._greedy_tokens(x_t, rows)
 
     def _greedy_tokens(self, x, rows):

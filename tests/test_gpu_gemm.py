@@ -207,6 +207,68 @@ def test_lm_head_with_greedy_token(m, vocab, k):
     assert e.value.code == M.MS_ERR_WORKSPACE
 
 
+NORM_CASES = [
+    # M, N, K, split_k, same K parts as the two-call path (then the bits must agree)
+    (7, 3584, 18944, 1, True),      # a single sequence's down projection: 8 K parts either way
+    (448, 3584, 18944, 4, True),    # a batch's down projection on the tiled kernel
+    (300, 1024, 2048, 8, True),
+    (16, 128, 256, 1, False),       # few rows, short K: one part in the two-call path, two here
+    (14, 512, 1024, 1, False),
+    (257, 8192, 64, 2, True),       # the widest row the norm takes
+]
+
+
+@pytest.mark.parametrize("m,n,k,split,same_parts", NORM_CASES)
+def test_projection_with_residual_add_and_rmsnorm(m, n, k, split, same_parts):
+    """h += bf16(A W^T), out = rmsnorm(h) * g in one call: against the fp64 definition, and against
+    ms_gemm_bf16 followed by ms_add_rmsnorm (the same bits where both divide K alike)."""
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import session as S
+    rng = W.make_rng(907, m, n, k)
+    a = W.normal_bf16_bits(rng, (m, k), 1.0)
+    w = W.normal_bf16_bits(rng, (n, k), k ** -0.5)
+    gam = W.normal_bf16_bits(rng, (n,), 0.3) 
+    h0 = rng.standard_normal((m, n)).astype(np.float32)
+    eps = 1e-6
+    f64 = lambda x: O.bf16_bits_to_f32(x).astype(np.float64)
+    delta = f64(a) @ f64(w).T
+    h_ref = h0.astype(np.float64) + delta
+    out_ref = h_ref / np.sqrt((h_ref ** 2).mean(axis=1, keepdims=True) + eps) * f64(gam)
+    ad, wd, gd = S.to_device(a, M.MS_BF16), S.to_device(w, M.MS_BF16), S.to_device(gam, M.MS_BF16)
+    need = M.ms_gemm_add_rmsnorm_workspace_bytes(m, n, k, split)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    h1 = torch.from_numpy(h0).cuda()
+    out1 = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device="cuda")
+    M.ms_gemm_add_rmsnorm_bf16(ad, wd, h1, gd, eps, out1, split, ws)
+    torch.cuda.synchronize()
+    got_h, got = h1.cpu().numpy().astype(np.float64), out1.float().cpu().numpy().astype(np.float64)
+    # delta is rounded to bf16 before it is added (2^-9 relative), the output once more
+    assert (np.abs(got_h - h_ref) <= 2.0 ** -8 * np.abs(delta) + 1e-5 * np.abs(delta).max() + 1e-6 * np.abs(h_ref)).all()
+    tol = 2.0 ** -8 * np.abs(out_ref) + 2.0 ** -7 * np.abs(f64(gam)) * (np.abs(delta) / np.sqrt((h_ref ** 2).mean(axis=1, keepdims=True))) + 1e-4
+    assert np.isfinite(got).all() and (np.abs(got - out_ref) <= tol).all(), f"max excess {np.max(np.abs(got - out_ref) - tol):.3e}"
+    # the two-call path
+    d2 = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+    need2 = M.ms_gemm_workspace_bytes(m, n, k, split)
+    ws2 = torch.empty(max(need2, 16), dtype=torch.uint8, device="cuda")
+    M.ms_gemm_bf16(ad, wd, None, [d2], split, ws2)
+    h2 = torch.from_numpy(h0).cuda()
+    out2 = torch.empty_like(out1)
+    M.ms_add_rmsnorm(h2, d2, gd, eps, out2)
+    torch.cuda.synchronize()
+    if same_parts:
+        assert torch.equal(h1, h2) and torch.equal(out1.view(torch.int16), out2.view(torch.int16))
+    else:
+        assert float((h1 - h2).abs().max()) <= 2.0 ** -7 * float(d2.float().abs().max())
+    with pytest.raises(M.MsError) as e:
+        M.ms_gemm_add_rmsnorm_bf16(ad, wd, h1, gd, eps, out1, split, None)
+    assert e.value.code == M.MS_ERR_WORKSPACE
+    if m > 16:
+        with pytest.raises(M.MsError) as e:
+            M.ms_gemm_add_rmsnorm_bf16(ad, wd, h1, gd, eps, out1, 1, ws)     # above 16 rows the caller divides K
+        assert e.value.code == M.MS_ERR_INVALID
+
+
 def test_gemm_rejects_what_it_is_not_built_for():
     from paper_2604_14889_amd import binding as M
     a = torch.zeros(4, 64, dtype=torch.bfloat16, device="cuda")
