@@ -17,7 +17,11 @@
 // whole tile's time.  The gate/up projection of the MLP can apply SwiGLU in the epilogue: with the
 // weight rows interleaved in blocks of 32 (gate block, up block), a lane holds gate and up of the
 // same output element in two accumulators and writes silu(gate) * up directly.
+// Steps of at most 16 rows (one or two sequences) are bound by reading W once and run on a second
+// kernel, further down, that streams 16 weight rows per wave through the matrix cores.
 #include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
 
 #include "ms_device.h"
 #include "ms_internal.h"
@@ -657,7 +661,7 @@ static GemmPlan gemm_plan(int M, int N, int K, int split_k) {
     return p;
 }
 
-// At most 16 rows: the matrix-core row-streaming kernel's launch shape (0 parts: shape not eligible).
+// At most 16 rows: the few-row kernel's launch shape (0 parts: shape not eligible).
 struct SkinnyPlan {
     int parts, nt, wk, lds_bytes;
     size_t workspace_bytes;

@@ -238,7 +238,7 @@ class Decoder:
 
     def _few(self, rows: int) -> bool:
         """Steps of at most 8 rows (a single sequence) run every projection on this library's
-        row-streaming kernel, gate/up fused with SwiGLU (which keeps a row-interleaved second copy
+        few-row kernel, gate/up fused with SwiGLU (which keeps a row-interleaved second copy
         of that weight, made at the first such step)."""
         return rows <= 8 and self.cfg.inter % 128 == 0
 

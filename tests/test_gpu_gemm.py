@@ -22,23 +22,23 @@ CASES = [
     (300, 1024, 2048, [128, 512, 256, 128], 8, True),
     (448, 37888, 512, [37888], 1, True),          # gate/up width: 592 tiles, the last 80 split over K
     (100, 67584, 512, [67584], 1, False),         # one row tile: 528 tiles, the last 16 split over K
-    # at most 8 rows and K a multiple of 512: the row-streaming kernel (split_k is not used there)
+    # at most 16 rows and K a multiple of 128: the few-row kernel that streams the weight once (split_k is not used there)
     (1, 128, 512, [128], 1, False),
     (7, 4608, 3584, [3584, 512, 512], 1, True),   # a single sequence's fused Q / K / V projection
     (5, 256, 1024, [128, 128], 1, True),
-    (8, 3584, 18944, [3584], 1, False),           # down projection: K in 5 parts (8, 7, 7, 8, 7 steps), fp32 partials
-    (3, 3584, 18944, [3584], 1, True),            # 4 rows of A kept: K in 3 parts
-    (4, 37888, 512, [37888], 1, True),            # 8 weight rows per wave
-    (7, 16384, 1536, [16384], 1, False),          # 4 weight rows per wave, 3 steps
-    # at most 16 rows and K a multiple of 128: the matrix-core row-streaming kernel
+    (8, 3584, 18944, [3584], 1, False),           # down projection: K in parts, fp32 partials
+    (3, 3584, 18944, [3584], 1, True),            # fewer rows: fewer, longer K parts
+    (4, 37888, 512, [37888], 1, True),            # gate/up width
+    (7, 16384, 1536, [16384], 1, False),          # 12 K steps against 4 in flight
+    # the same kernel's launch shapes: waves that split K, several tiles per wave, K in parts
     (16, 256, 128, [128, 128], 1, True),          # a single K step
     (9, 4608, 3584, [3584, 512, 512], 1, True),   # four waves split K over the same weight rows
     (7, 3584, 3584, [3584], 1, False),            # output projection of a single sequence
     (14, 3584, 18944, [3584], 1, False),          # two sequences' down projection: K in parts, fp32 partials
-    (16, 37888, 384, [37888], 1, True),           # two 16-row tiles per wave, 3 steps (odd against 2 in flight)
-    (2, 152064, 256, [152064], 1, False),         # four tiles per wave (LM-head width)
+    (16, 37888, 384, [37888], 1, True),           # gate/up width, 3 steps against 4 in flight
+    (2, 152064, 256, [152064], 1, False),         # LM-head width: two 16-row tiles per wave, 2 steps
     (12, 1024, 640, [512, 512], 1, False),        # 5 steps over 4 waves (1, 1, 1, 2)
-    (11, 128, 2176, [128], 1, True),              # 17 steps over 4 waves, one workgroup column block of two
+    (11, 128, 2176, [128], 1, True),              # 17 steps over 4 waves
 ]
 
 
