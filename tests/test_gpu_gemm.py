@@ -105,6 +105,62 @@ def test_gemm_random_shapes(case):
     assert (err <= bound).all(), f"m {m} n {n} k {k} split {split} widths {widths}: max excess {np.max(err - bound):.3e}"
 
 
+@pytest.mark.parametrize("case", range(12))
+def test_few_row_gemm_random_shapes(case):
+    """Seeded random shapes of the few-row kernel: 1 to 16 rows, K a multiple of 128 (one step to
+    dozens, also more than one K part), several destinations, bias or none; every third case the
+    SwiGLU product, every fourth the greedy token as well."""
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import session as S
+    from oracle import decoder_oracle as DO
+    rng = W.make_rng(908, case)
+    m = int(rng.integers(1, 17))
+    n_blocks = int(rng.choice([1, 2, 3, 8, 20, 37]))
+    k = 128 * int(rng.choice([1, 2, 3, 5, 8, 13, 28, 40]))
+    n = 128 * n_blocks
+    cuts = sorted(set(int(c) for c in rng.integers(1, n_blocks, size=int(rng.integers(0, 3)))) if n_blocks > 1 else [])[:3]
+    bounds = [0] + [128 * c for c in cuts] + [n]
+    widths = [b - a for a, b in zip(bounds, bounds[1:])]
+    with_bias = bool(rng.integers(0, 2))
+    a = W.normal_bf16_bits(rng, (m, k), 1.0)
+    w = W.normal_bf16_bits(rng, (n, k), k ** -0.5)
+    b = W.normal_bf16_bits(rng, (n,), 0.5) if with_bias else None
+    f64 = lambda x: O.bf16_bits_to_f32(x).astype(np.float64)
+    prod = f64(a) @ f64(w).T
+    ref = prod + (f64(b) if with_bias else 0.0)
+    what = f"m {m} n {n} k {k} widths {widths} bias {with_bias}"
+    ad, wd = S.to_device(a, M.MS_BF16), S.to_device(w, M.MS_BF16)
+    outs = [torch.full((m, wd_), float("nan"), dtype=torch.bfloat16, device="cuda") for wd_ in widths]
+    need = M.ms_gemm_workspace_bytes(m, n, k, 1)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    M.ms_gemm_bf16(ad, wd, None if b is None else S.to_device(b, M.MS_BF16), outs, 1, ws)
+    torch.cuda.synchronize()
+    got = np.concatenate([o.float().cpu().numpy() for o in outs], axis=1).astype(np.float64)
+    assert np.isfinite(got).all(), what
+    err = np.abs(got - ref)
+    bound = 2.0 ** -8 * np.abs(ref) + 1e-5 * np.abs(ref).max()
+    assert (err <= bound).all(), f"{what}: max excess {np.max(err - bound):.3e}"
+    if case % 3 == 0 and n % 256 == 0:      # the same weight read as interleaved gate / up blocks
+        inter = n // 2
+        wv = f64(w).reshape(inter // 32, 2, 32, k)
+        gate, up = f64(a) @ wv[:, 0].reshape(inter, k).T, f64(a) @ wv[:, 1].reshape(inter, k).T
+        want = DO.silu(gate) * up
+        act = torch.full((m, inter), float("nan"), dtype=torch.bfloat16, device="cuda")
+        M.ms_gemm_swiglu_bf16(ad, wd, act, ws)
+        torch.cuda.synchronize()
+        ga = act.float().cpu().numpy().astype(np.float64)
+        tol = 2.0 ** -8 * np.abs(want) + 2e-5 * (np.abs(gate) + 1.0) * (np.abs(up) + 1.0)
+        assert np.isfinite(ga).all() and (np.abs(ga - want) <= tol).all(), what
+    if case % 4 == 0:
+        tok = torch.full((m,), -1, dtype=torch.int32, device="cuda")
+        kws = torch.empty(M.ms_lm_head_argmax_workspace_bytes(m, n, k), dtype=torch.uint8, device="cuda")
+        M.ms_lm_head_argmax_bf16(ad, wd, tok, kws)
+        torch.cuda.synchronize()
+        srt = np.sort(prod, axis=1)
+        clear = (srt[:, -1] - srt[:, -2]) > 1e-4 * np.abs(prod).max() if n > 1 else np.ones(m, bool)
+        assert (tok.cpu().numpy()[clear] == np.argmax(prod, axis=1)[clear]).all(), what
+
+
 def test_gemm_last_round_split_is_optional():
     """Without workspace the same shape runs whole tiles throughout; both ways give the product."""
     from paper_2604_14889_amd import binding as M
