@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--layers", type=int, default=28)
-    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--batch", type=int, default=None, help="sequences (default: 32 for the attention workload, 64 for decode_step)")
     ap.add_argument("--kv", type=int, default=8192)
     ap.add_argument("--ragged", action="store_true", help="lengths uniform in [1k, 16k] instead of --kv")
     ap.add_argument("--q-heads", type=int, default=28, help="query heads (28 / 4: Qwen2.5-7B, 32 / 8: Llama-3.1-8B)")
@@ -74,6 +74,7 @@ def main():
         sys.exit(2)
     if args.workload == "decode_step":
         return decode_step_bench(args)
+    args.batch = args.batch or 32
     import numpy as np
     import torch
 
@@ -295,7 +296,7 @@ def decode_step_bench(args):
     cfg = D.DecoderConfig.qwen2_5_7b()
     if args.layers != 28:
         cfg.n_layers = args.layers
-    B = 64 if args.batch == 32 else args.batch           # this workload's default batch is 64
+    B = args.batch or 64
     L0, nv, nf = args.kv, 4, 3
     nq = nv + nf
     NL, Hq, Hkv, Dh = cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
