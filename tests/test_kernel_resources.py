@@ -1,4 +1,4 @@
-"""The streaming attention kernel's decode builds must compile without register spills.
+"""The streaming attention kernel's decode builds and the projection kernels must compile without register spills.
 
 A spilled value inside the stream loop is reloaded through scratch memory, which shares the load
 counter with the tile prefetches: every reload then waits for all loads in flight and the loop
@@ -13,8 +13,9 @@ import tempfile
 from paper_2604_14889_amd import build as B
 
 
-def test_decode_builds_of_the_stream_kernel_do_not_spill_in_the_stream_loop():
-    src = os.path.join(B.CSRC, "attention_mfma.hip")
+def compiled_kernels(source: str):
+    """(assembly text, {kernel: resource usage}) of one source file compiled for gfx950."""
+    src = os.path.join(B.CSRC, source)
     flags = [f for f in B.FLAGS if f not in ("-shared", "-fPIC")]
     with tempfile.TemporaryDirectory() as tmp:
         cmd = [B.hipcc(), *flags, f"-I{B.INCLUDE}", f"-I{B.CSRC}", "-c", src, "-o", os.path.join(tmp, "k.o"), "-save-temps=obj"]
@@ -28,6 +29,28 @@ def test_decode_builds_of_the_stream_kernel_do_not_spill_in_the_stream_loop():
         name = re.search(r"\.name:\s+(\S+)", block).group(1)
         kernels[name] = {k: int(re.search(rf"\.{k}:\s+(\d+)", block).group(1))
                          for k in ("vgpr_count", "vgpr_spill_count", "sgpr_spill_count", "private_segment_fixed_size")}
+    return text, kernels
+
+
+def test_projection_kernels_do_not_spill():
+    """The few-row kernel keeps 16 loads in flight per wave and the tiled one sits at its 128-register
+    budget (two workgroups per CU): a spilled value would put a wait for all loads into their loops."""
+    _, kernels = compiled_kernels("gemm.hip")
+    few = {n: r for n, r in kernels.items() if "skinny_mfma_bf16" in n}
+    assert len(few) == 6, sorted(kernels)
+    for name, r in few.items():
+        assert r["vgpr_spill_count"] == 0 and r["private_segment_fixed_size"] == 0 and r["vgpr_count"] <= 128, (name, r)
+    tiled = {n: r for n, r in kernels.items() if "gemm_tn_bf16" in n}
+    assert len(tiled) == 4, sorted(kernels)
+    for name, r in tiled.items():
+        greedy = "ILi3E" in name      # the greedy-token build parks two registers across its loop (stored before, reloaded after)
+        assert r["vgpr_spill_count"] <= (2 if greedy else 0) and r["vgpr_count"] <= 128, (name, r)
+    norm = [r for n, r in kernels.items() if "reduce_add_rmsnorm" in n]
+    assert len(norm) == 1 and norm[0]["vgpr_spill_count"] == 0 and norm[0]["vgpr_count"] <= 128, norm
+
+
+def test_decode_builds_of_the_stream_kernel_do_not_spill_in_the_stream_loop():
+    text, kernels = compiled_kernels("attention_mfma.hip")
     decode = {n: r for n, r in kernels.items() if "pv_attn_mfma_streamILb0E" in n}
     assert len(decode) == 4, sorted(kernels)           # fixed / first-come tile assignment x small / large layer pool
     lines = text.split("\n")
