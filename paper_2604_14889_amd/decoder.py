@@ -144,6 +144,7 @@ class Decoder:
                        M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[1]),
                        M.ms_gemm_workspace_bytes(min(max_rows, 8), qd + 2 * kd, cfg.hidden, 1),
                        M.ms_gemm_workspace_bytes(min(max_rows, 8), cfg.hidden, cfg.inter, 1),
+                       max(M.ms_gemm_workspace_bytes(r, cfg.hidden, qd, 1) for r in range(1, min(max_rows, 16) + 1)),
                        M.ms_gemm_add_rmsnorm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[1]),
                        max(M.ms_gemm_add_rmsnorm_workspace_bytes(r, cfg.hidden, cfg.inter, self.splits_few[1])
                            for r in range(1, min(max_rows, 16) + 1)),
@@ -275,7 +276,7 @@ class Decoder:
             if self.attn_events is not None:
                 e1.record()
                 self.attn_events.append((e0, e1))
-            if few:
+            if few or rows <= 16:     # up to 16 rows the few-row kernel is ahead of the library on the output projection
                 check(lib.ms_gemm_bf16(*c["o"], st))
             else:
                 torch.mm(attn_t, c["wo_t"], out=proj_t)
