@@ -84,3 +84,23 @@ def test_bad_arguments_return_errors_not_crashes():
     assert e.value.code == M.MS_ERR_INVALID and "pool" in str(e.value)
     with pytest.raises(M.MsError):
         M.ms_accept(-1, 4, None, None, None, None, None)
+
+
+def test_projection_workspace_sizes_follow_the_launch_shapes():
+    """Host-only sizing functions of the projections (256 compute units assumed without a device).
+    Up to 16 rows the few-row kernel divides K only where all rows of A do not fit its LDS share."""
+    f = 4   # bytes per fp32 partial sum
+    assert M.ms_gemm_workspace_bytes(7, 4608, 3584, 1) == 0                     # a single sequence's Q/K/V: one K part
+    assert M.ms_gemm_workspace_bytes(14, 4608, 3584, 1) == 7 * 14 * 4608 * f    # two sequences: A needs two parts, seven fill the chip
+    assert M.ms_gemm_workspace_bytes(7, 3584, 18944, 1) == 8 * 7 * 3584 * f     # down projection: eight parts
+    assert M.ms_gemm_workspace_bytes(448, 3584, 18944, 4) == 4 * 448 * 3584 * f  # tiled kernel, caller's split
+    assert M.ms_gemm_workspace_bytes(448, 4608, 3584, 1) == 0                   # tiled, one round of tiles
+    assert M.ms_gemm_workspace_bytes(7, 4600, 3584, 1) == 0                     # unsupported width
+    # with the residual add and the norm the K parts are summed by the norm's kernel: at least two
+    assert M.ms_gemm_add_rmsnorm_workspace_bytes(7, 3584, 18944, 1) == 8 * 7 * 3584 * f
+    assert M.ms_gemm_add_rmsnorm_workspace_bytes(7, 3584, 3584, 1) == 7 * 7 * 3584 * f
+    assert M.ms_gemm_add_rmsnorm_workspace_bytes(448, 3584, 18944, 4) == 4 * 448 * 3584 * f
+    assert M.ms_gemm_add_rmsnorm_workspace_bytes(448, 3584, 18944, 1) == 0      # above 16 rows the caller must divide K
+    # the greedy-token LM head leaves one 8-byte key per row and column group
+    assert M.ms_lm_head_argmax_workspace_bytes(7, 152064, 3584) == 152064 // 32 * 7 * 8     # two 16-row tiles per wave
+    assert M.ms_lm_head_argmax_workspace_bytes(448, 152064, 3584) == 152064 // 128 * 2 * 448 * 8
