@@ -267,7 +267,8 @@ int ms_gemm_bf16(const void* a, const void* w, const void* bias, int M, int N, i
  * 64 b .. 64 b + 32 are gate rows 32 b .. 32 b + 32, rows 64 b + 32 .. 64 b + 64 the up rows of the
  * same outputs.  inter % 64 == 0, K % 32 == 0; workspace as for ms_gemm_bf16 with N = 2 * inter and
  * split_k = 1 (optional).  M <= 16 with inter % 128 == 0 and K % 128 == 0 runs on the few-row
- * kernel of ms_gemm_bf16 when all rows of A fit its LDS share (M <= 8 at K = 3584). */
+ * kernel of ms_gemm_bf16 when all rows of A over the whole K fit its LDS share (at K = 3584: up to
+ * 8 rows, and up to 16 rows for 2 * inter >= 32768, where a workgroup takes a whole compute unit). */
 int ms_gemm_swiglu_bf16(const void* a, const void* w_gate_up, int M, int inter, int K, void* out,
                         void* workspace, size_t ws_bytes, void* stream);
 

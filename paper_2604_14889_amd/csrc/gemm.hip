@@ -459,6 +459,10 @@ constexpr int kSkinnyTileRowBytes = kSkinnyStepK * 2 + 16;        // 272
 constexpr int kSkinnyTileBytes = 16 * kSkinnyTileRowBytes;        // 4352 per wave
 constexpr int kSkinnyLdsBytes = 76 * 1024;                        // two workgroups per compute unit
 constexpr int kSkinnyLdsForA = kSkinnyLdsBytes - 4 * kSkinnyTileBytes;
+// One workgroup per compute unit: room for all rows of A over the whole K of a wide projection at 9 to
+// 16 rows (K = 3584: 115 KB), which then needs no K parts (and can apply SwiGLU in its epilogue).
+constexpr int kSkinnyLdsBytesWide = 152 * 1024;
+constexpr int kSkinnyLdsForAWide = kSkinnyLdsBytesWide - 4 * kSkinnyTileBytes;
 typedef __attribute__((ext_vector_type(4))) float g_f32x4_t;
 
 template <int kNT, int kWK, bool kSwiglu = false>
@@ -510,9 +514,19 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_mfma_bf16(GemmArgs g, i
         const int c = tid + u * kSkinnyThreads;
         if (c < chunks) *reinterpret_cast<uint4*>(a_lds + (size_t)(c / row_chunks) * row_bytes + 16 * (c % row_chunks)) = sv[u];
     }
-    for (int c = tid + kStage * kSkinnyThreads; c < chunks; c += kSkinnyThreads)   // longer ranges: the rest, one chunk a time
-        *reinterpret_cast<uint4*>(a_lds + (size_t)(c / row_chunks) * row_bytes + 16 * (c % row_chunks)) =
-            *reinterpret_cast<const uint4*>(g.a + (size_t)(c / row_chunks) * g.K + (size_t)p_lo * kSkinnyStepK + 8 * (c % row_chunks));
+    for (int c0 = tid + kStage * kSkinnyThreads; c0 < chunks; c0 += 8 * kSkinnyThreads) {   // longer ranges: the rest, eight chunks a round
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int c = c0 + u * kSkinnyThreads < chunks ? c0 + u * kSkinnyThreads : c0;
+            v[u] = *reinterpret_cast<const uint4*>(g.a + (size_t)(c / row_chunks) * g.K + (size_t)p_lo * kSkinnyStepK + 8 * (c % row_chunks));
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int c = c0 + u * kSkinnyThreads;
+            if (c < chunks) *reinterpret_cast<uint4*>(a_lds + (size_t)(c / row_chunks) * row_bytes + 16 * (c % row_chunks)) = v[u];
+        }
+    }
     g_f32x4_t acc[kNT];
 #pragma unroll
     for (int t = 0; t < kNT; ++t) acc[t] = g_f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -677,11 +691,26 @@ static SkinnyPlan skinny_plan(int M, int N, int K, int min_parts = 1) {
     const int want = 2 * gemm_slots();   // waves that fill the memory pipeline with 16 KB in flight each
     const int n_tiles = N / 16;
     int nt = 1, wk = 1;
-    if (parts > 1) {   // partials and a second kernel anyway: enough parts for about 1.75 x want waves (measured)
+    // wide outputs whose rows of A fit a whole compute unit's LDS: one K part, one workgroup per compute unit
+    const bool wide = parts > 1 && min_parts == 1 && N % 256 == 0 && N / 16 >= 2048 &&
+                      (long)M * (K * 2 + 16) <= kSkinnyLdsForAWide;
+    if (wide) {
+        parts = 1;
+        const int cus = gemm_slots() / 2;
+        // workgroups of 64 nt rows: all at once if four tiles per wave allow it, else the split with the fullest last round
+        double best = 0.0;
+        for (int cand = 4; cand >= 1; cand /= 2) {
+            const int wgs = N / (64 * cand);
+            if (cand == 4 && wgs <= cus) { nt = 4; break; }
+            const double fill = (double)wgs / ((wgs + cus - 1) / cus * cus);
+            if (fill > best + 1e-9) { best = fill; nt = cand; }
+        }
+    } else if (parts > 1) {   // partials and a second kernel anyway: enough parts for about 1.75 x want waves (measured)
         const int more = (int)((7L * want / 4 + n_tiles - 1) / n_tiles);
         if (more > parts) parts = more < steps / 4 ? more : (steps / 4 > parts ? steps / 4 : parts);
     }
-    if (N % 128 == 0 && (long)n_tiles / 2 * parts >= 4 * want) nt = 2;
+    if (wide) {
+    } else if (N % 128 == 0 && (long)n_tiles / 2 * parts >= 4 * want) nt = 2;
     else if ((long)n_tiles * parts < want) wk = (long)n_tiles * parts * 2 >= want ? 2 : 4;
     while (wk > 1 && steps / parts < wk) wk /= 2;   // every wave gets a step
 #ifdef MS_TIMING
@@ -711,7 +740,7 @@ static int skinny_dispatch(const GemmArgs& g, const SkinnyPlan& v, hipStream_t s
         const void* builds[] = {(const void*)skinny_mfma_bf16<4, 1>, (const void*)skinny_mfma_bf16<2, 1>, (const void*)skinny_mfma_bf16<1, 4>,
                                 (const void*)skinny_mfma_bf16<1, 2>, (const void*)skinny_mfma_bf16<1, 1>,
                                 (const void*)skinny_mfma_bf16<4, 1, true>};
-        for (const void* f : builds) MS_HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kSkinnyLdsBytes));
+        for (const void* f : builds) MS_HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kSkinnyLdsBytesWide));
         lds_allowed[dev] = true;
     }
     const dim3 grid((unsigned)(g.N / (4 / v.wk * 16 * v.nt)), (unsigned)v.parts);

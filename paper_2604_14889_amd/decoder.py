@@ -142,8 +142,10 @@ class Decoder:
         if self.hand_gemm:
             need = max(M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, cfg.hidden, self.splits_few[0]),
                        M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[1]),
-                       M.ms_gemm_workspace_bytes(min(max_rows, 8), qd + 2 * kd, cfg.hidden, 1),
-                       M.ms_gemm_workspace_bytes(min(max_rows, 8), cfg.hidden, cfg.inter, 1),
+                       max(M.ms_gemm_workspace_bytes(r, qd + 2 * kd, cfg.hidden, 1) for r in range(1, min(max_rows, 16) + 1)),
+                       max(M.ms_gemm_workspace_bytes(r, 2 * cfg.inter, cfg.hidden, 1) for r in range(1, min(max_rows, 16) + 1)),
+                       max(M.ms_gemm_workspace_bytes(r, cfg.vocab, cfg.hidden, 1) for r in range(1, min(max_rows, 16) + 1))
+                       if cfg.vocab % 128 == 0 else 0,
                        max(M.ms_gemm_workspace_bytes(r, cfg.hidden, qd, 1) for r in range(1, min(max_rows, 16) + 1)),
                        M.ms_gemm_add_rmsnorm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[1]),
                        max(M.ms_gemm_add_rmsnorm_workspace_bytes(r, cfg.hidden, cfg.inter, self.splits_few[1])
@@ -238,10 +240,10 @@ class Decoder:
         return dict(layers=layers, q=q, attn=attn)
 
     def _few(self, rows: int) -> bool:
-        """Steps of at most 8 rows (a single sequence) run every projection on this library's
+        """Steps of at most 16 rows (one or two sequences) run every projection on this library's
         few-row kernel, gate/up fused with SwiGLU (which keeps a row-interleaved second copy
         of that weight, made at the first such step)."""
-        return rows <= 8 and self.cfg.inter % 128 == 0
+        return rows <= 16 and self.cfg.inter % 128 == 0
 
     def forget_prepared(self) -> None:
         """Drops the prepared argument tuples (they hold device addresses of the weights)."""
@@ -276,7 +278,7 @@ class Decoder:
             if self.attn_events is not None:
                 e1.record()
                 self.attn_events.append((e0, e1))
-            if few or rows <= 16:     # up to 16 rows the few-row kernel is ahead of the library on the output projection
+            if few:
                 check(lib.ms_gemm_bf16(*c["o"], st))
             else:
                 torch.mm(attn_t, c["wo_t"], out=proj_t)

@@ -39,6 +39,7 @@ CASES = [
     (2, 152064, 256, [152064], 1, False),         # LM-head width: two 16-row tiles per wave, 2 steps
     (12, 1024, 640, [512, 512], 1, False),        # 5 steps over 4 waves (1, 1, 1, 2)
     (11, 128, 2176, [128], 1, True),              # 17 steps over 4 waves
+    (14, 37888, 3584, [37888], 1, True),          # two sequences' gate/up width: all of A (100 KB) in one compute unit's LDS
 ]
 
 
@@ -184,7 +185,8 @@ def test_gemm_last_round_split_is_optional():
 
 
 SWIGLU_CASES = [(7, 64, 32), (300, 1088, 256), (448, 18944, 512),
-                (7, 18944, 512), (16, 128, 128), (5, 1152, 384), (1, 2048, 3584)]   # few rows: the row-streaming kernel
+                (7, 18944, 512), (16, 128, 128), (5, 1152, 384), (1, 2048, 3584),   # few rows: the few-row kernel
+                (14, 18944, 3584), (16, 16384, 3584)]                               # ... with a whole compute unit's LDS for A
 
 
 @pytest.mark.parametrize("m,inter,k", SWIGLU_CASES)
@@ -218,7 +220,7 @@ def test_gate_up_gemm_with_swiglu_epilogue(m, inter, k):
 
 
 ARGMAX_CASES = [(7, 16384, 1536), (5, 2048, 512), (1, 128, 512), (8, 37888, 1024), (9, 1024, 512), (300, 4096, 256), (448, 2048, 3584),
-                (16, 152064, 256), (12, 37888, 384), (3, 1024, 128), (7, 152064, 256)]
+                (16, 152064, 256), (12, 37888, 384), (3, 1024, 128), (7, 152064, 256), (12, 32768, 3584)]
 
 
 @pytest.mark.parametrize("m,vocab,k", ARGMAX_CASES)
