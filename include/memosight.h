@@ -182,6 +182,22 @@ int ms_predict_verify_attention(ms_cache* cache, int layer, int B, const int* se
 
 size_t ms_attention_workspace_bytes(ms_cache* cache, int B, int n_q);
 
+/* ms_predict_verify_attention for callers that cannot allocate device memory or carry a workspace
+ * around: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors, without the workspace: the split-KV partial results go to a fixed
+ * array of MS_STATIC_SCRATCH_BYTES of device memory inside the library, which every GPU the library
+ * runs on holds until the process ends.  The call allocates and frees nothing on the device.
+ * A call whose ms_attention_workspace_bytes(cache, B, n_q) exceeds MS_STATIC_SCRATCH_BYTES fails
+ * with MS_ERR_WORKSPACE and launches nothing (at 4 KV heads on a 256-CU part: up to 188 sequences
+ * per call).  All calls on one GPU -- from any cache, stream or thread -- share the one array, which
+ * keeps the last call's partials: calls that overlap in time on one GPU race; order them on one
+ * stream or with events.  Nothing in the array has to start at zero. */
+#define MS_STATIC_SCRATCH_BYTES (32u << 20)
+int ms_predict_verify_attention_static(ms_cache* cache, int layer, int B, const int* seq_ids,
+                                       int n_verify, int n_foresight, const void* q,
+                                       const void* k_new, const void* v_new, const int* pos_ids,
+                                       const int* ctx_new, float scale, void* out, void* stream);
+
 /* By default attention results are reproducible to rounding only: the streaming kernel (bf16,
  * head_dim 128) lets the waves of a workgroup take KV tiles first come, first served, so the
  * order in which a row's partial sums are added varies from call to call.  on != 0 fixes the

@@ -64,6 +64,7 @@ _SIGS = {
     "ms_compact_workspace_bytes": (_SZ, [_P, _I, _IP, _IP, _IP]),
     "ms_predict_verify_attention": (_I, [_P, _I, _I, _IP, _I, _I, _P, _P, _P, _P, _P, _F, _P, _P, _SZ, _P]),
     "ms_attention_workspace_bytes": (_SZ, [_P, _I, _I]),
+    "ms_predict_verify_attention_static": (_I, [_P, _I, _I, _IP, _I, _I, _P, _P, _P, _P, _P, _F, _P, _P]),
     "ms_accept": (_I, [_I, _I, _P, _P, _P, _I, _P, _P, _P]),
     "ms_seq_len": (_I, [_P, _I, _IP]),
     "ms_seq_page_table": (_I, [_P, _I, _IP, _I, _IP]),
@@ -251,6 +252,21 @@ def ms_predict_verify_attention(cache, layer, seq_ids, n_verify, n_foresight, q,
                                            _sized(cache, ctx_new, "ctx_new", rows, 4), float(scale),
                                            _sized(cache, out, "out", rows * hq * d), _dev(workspace), ws_bytes,
                                            _stream(stream)))
+
+
+MS_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def ms_predict_verify_attention_static(cache, layer, seq_ids, n_verify, n_foresight, q, k_new, v_new, pos_ids,
+                                       ctx_new, scale, out, stream=None) -> None:
+    """ms_predict_verify_attention on the library's fixed workspace (no device allocation anywhere)."""
+    _, hq, hkv, d, _ = _DESC[cache]
+    rows = len(seq_ids) * (n_verify + n_foresight)
+    _check(lib.ms_predict_verify_attention_static(cache, layer, len(seq_ids), _ints(seq_ids), n_verify, n_foresight,
+                                                  _sized(cache, q, "q", rows * hq * d), _sized(cache, k_new, "k_new", rows * hkv * d),
+                                                  _sized(cache, v_new, "v_new", rows * hkv * d), _sized(cache, pos_ids, "pos_ids", rows, 4),
+                                                  _sized(cache, ctx_new, "ctx_new", rows, 4), float(scale),
+                                                  _sized(cache, out, "out", rows * hq * d), _stream(stream)))
 
 
 def ms_embed_rows(table, tokens, h_out, stream=None) -> None:

@@ -40,6 +40,9 @@ struct ms_cache;
 
 namespace ms {
 
+// attention.hip
+int static_scratch(int device, void** ptr);
+
 // attention_mfma.hip
 bool mfma_eligible(const ms_cache* c, int n_q);
 size_t mfma_workspace_bytes(const ms_cache* c, int B);

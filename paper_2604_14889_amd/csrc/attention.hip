@@ -8,6 +8,8 @@
 // a foresight token itself ever attends to a foresight token.
 #include <math.h>
 
+#include <mutex>
+
 #include "attention.h"
 #include "ms_device.h"
 #include "ms_internal.h"
@@ -219,6 +221,37 @@ size_t rowwave_workspace_bytes(const ms_cache* c, int B, int n_q) {
     return (size_t)B * n_q * c->d.n_q_heads * kMaxRowwaveSplits * (c->d.head_dim + 2) * sizeof(float);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Library-owned workspace for callers that cannot allocate (ms_predict_verify_attention_static):
+// the split-KV partials live in a fixed array of device memory that every GPU the library runs on
+// holds until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: the address the kernels get is resolved once per device, with that device
+// current, and kept in g_scratch_ptr.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[MS_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on `device`, which must be the current device.  Resolved on the first call
+// per device (ms_cache_create makes that call).
+int static_scratch(int device, void** ptr) {
+    if (device < 0 || device >= kMaxDevices) MS_FAIL(MS_ERR_UNSUPPORTED, "device index %d outside [0, %d)", device, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        int cur = -1;
+        MS_HIP_TRY(hipGetDevice(&cur));
+        if (cur != device) MS_FAIL(MS_ERR_INVALID, "static workspace: device %d is not the current device (%d)", device, cur);
+        void* p = nullptr;
+        MS_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || ((uintptr_t)p & 255) != 0) MS_FAIL(MS_ERR_HIP, "static workspace: bad symbol address %p", p);
+        g_scratch_ptr[device] = p;
+    }
+    *ptr = g_scratch_ptr[device];
+    return MS_OK;
+}
+
 }  // namespace ms
 
 using namespace ms;
@@ -292,4 +325,28 @@ extern "C" int ms_predict_verify_attention(ms_cache* c, int layer, int B, const 
     if (c->d.dtype == MS_F32)
         return D == 64 ? launch_rowwave<float, 64>(a, bm, B, max_len, stream) : launch_rowwave<float, 128>(a, bm, B, max_len, stream);
     return D == 64 ? launch_rowwave<bf16_t, 64>(a, bm, B, max_len, stream) : launch_rowwave<bf16_t, 128>(a, bm, B, max_len, stream);
+}
+
+extern "C" int ms_predict_verify_attention_static(ms_cache* c, int layer, int B, const int* seq_ids, int n_verify,
+                                                  int n_foresight, const void* q, const void* k_new, const void* v_new,
+                                                  const int* pos_ids, const int* ctx_new, float scale, void* out,
+                                                  void* stream) {
+    if (!c) MS_FAIL(MS_ERR_INVALID, "ms_predict_verify_attention_static: null cache");
+    if (B == 0) return MS_OK;
+    const int n_q = n_verify + n_foresight;
+    if (B < 0 || B > MS_MAX_BATCH || n_verify < 0 || n_foresight < 0 || n_q < 1 || n_q > MS_MAX_QUERIES)
+        MS_FAIL(MS_ERR_INVALID, "ms_predict_verify_attention_static: B %d, n_verify %d, n_foresight %d out of range", B, n_verify,
+                n_foresight);
+    const size_t need = ms_attention_workspace_bytes(c, B, n_q);
+    if (need > (size_t)MS_STATIC_SCRATCH_BYTES)
+        MS_FAIL(MS_ERR_WORKSPACE,
+                "ms_predict_verify_attention_static: this call needs %zu bytes of workspace, the library's fixed one has %zu; "
+                "use ms_predict_verify_attention with a workspace of the caller's",
+                need, (size_t)MS_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    const int rc = static_scratch(c->device, &ws);   // resolved in ms_cache_create: a table look-up here
+    if (rc != MS_OK) return rc;
+    // nothing in the workspace has to start at zero: every partial is written before it is read
+    return ms_predict_verify_attention(c, layer, B, seq_ids, n_verify, n_foresight, q, k_new, v_new, pos_ids, ctx_new, scale,
+                                       out, ws, (size_t)MS_STATIC_SCRATCH_BYTES, stream);
 }

@@ -432,6 +432,9 @@ int ms_cache_create(const ms_cache_desc* desc, ms_cache** out) {
     }
     rc = c->stage.init();
     if (rc != MS_OK) return fail(rc);
+    void* fixed_ws = nullptr;   // this device's copy of the library's fixed attention workspace
+    rc = static_scratch(c->device, &fixed_ws);
+    if (rc != MS_OK) return fail(rc);
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0) c->n_cus = cus;
     if (hipMalloc((void**)&c->d_plan, (size_t)mfma_plan_ints(MS_MAX_BATCH) * sizeof(int)) != hipSuccess) {
