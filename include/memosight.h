@@ -135,7 +135,7 @@ int ms_commit_accepted(ms_cache* cache, int B, const int* seq_ids, const int* ac
 /* For b = 0..B-1 in order: logical rows [seg_begin[b], seg_begin[b] + seg_len[b]) of sequence
  * seq_ids[b] are dropped and n_mem[b] memory-token rows take their place; rows after the segment
  * (none when the segment is the cache suffix, as in Algorithm 1) keep their stored values and
- * follow.  All layers at once.  (Section 2.1.2; Algorithm 1 "Evict verbose and insert memory".)
+ * follow.  All layers at once.  (Section 2.1.2; Algorithm 1, UpdateCache.)
  *   seq_ids, seg_begin, seg_len, n_mem : host [B]
  *   mem_k, mem_v : device [n_layers][sum n_mem][n_kv_heads][head_dim]
  *   mem_pos      : device [sum n_mem] (the memory tokens' UPL position ids; see ms_upl_positions)
@@ -205,6 +205,18 @@ int ms_predict_verify_attention_static(ms_cache* cache, int layer, int B, const 
  * same bits, a few percent slower.  The general kernel is always reproducible. */
 int ms_attention_set_deterministic(ms_cache* cache, int on);
 
+/* Test hook for the failure path of the streaming kernel's split-KV combine.  In one launch the
+ * shares of a (sequence, KV head) pair count themselves in two counters; the share that finishes
+ * last waits (a few microseconds) until the others have published their partial results and folds
+ * them.  If the counters are ever in a bad state the wait gives up after a bounded number of polls:
+ * the pair's output rows are left unwritten, nothing faults, and the next
+ * ms_predict_verify_attention call on the cache (and ms_check_integrity) returns MS_ERR_HIP and
+ * puts the counters back to zero.  This call forces that condition from the host: poll_limit > 0
+ * replaces the bound (0 restores the default, about a second), and every pair's "published"
+ * counter is set to published_bias (0 = the healthy state) behind the work already queued on
+ * `stream`. */
+int ms_attention_fault_injection(ms_cache* cache, int poll_limit, int published_bias, void* stream);
+
 /* ---- greedy longest-prefix acceptance (footnote of Section 2.1.1) -------------------------- */
 
 /* accept_len[b] = number of leading j with draft[b][j] == target[b][j] (target[b][j] being the
@@ -223,6 +235,9 @@ int ms_seq_len(ms_cache* cache, int seq_id, int* len);
 int ms_seq_page_table(ms_cache* cache, int seq_id, int* out, int cap, int* n);
 int ms_free_page_count(ms_cache* cache, int* n);
 int ms_peak_pages(ms_cache* cache, int* n);
+/* Kernels launched so far by calls on this cache (attention, append, commit, compaction, page-table
+ * patches): lets a caller see how many launches a call cost. */
+int ms_launch_count(ms_cache* cache, long long* n);
 /* Checks: every page is free or owned exactly once, page counts match lengths, and (after
  * synchronising `stream`) the device mirror equals the host tables.  MS_OK or MS_ERR_INVALID. */
 int ms_check_integrity(ms_cache* cache, void* stream);
@@ -230,7 +245,7 @@ int ms_check_integrity(ms_cache* cache, void* stream);
 /* ---- the decoder block around the attention (full decode step) ------------------------------
  *
  * Algorithm 1 (Appendix A) runs the whole model once per speculative step.  Around the attention
- * the block of the paper's models (Section 4.1) is: RMSNorm, Q/K/V projections, output projection,
+ * the block of the paper's models (Section 3.1) is: RMSNorm, Q/K/V projections, output projection,
  * residual, RMSNorm, SwiGLU MLP, residual; then the final norm, the LM head and the greedy token.
  * The projections are dense GEMMs the caller runs; these are the memory-bound pieces between them.
  * All tensors are device pointers, 16-byte aligned, rows contiguous; activations and weights are
@@ -255,7 +270,7 @@ int ms_argmax_rows(const void* logits, int n, int vocab, long ld, int* out, void
 
 /* Dense projection of a step's rows: C[M][N] = A[M][K] . W[N][K]^T (+ bias[N]), bf16 operands and
  * results, fp32 accumulation on the matrix cores (the model's projections inside Algorithm 1's
- * SpeculativeStep; Section 4.1 names the models).  A, W, bias, the destinations and the workspace
+ * SpeculativeStep; Section 3.1 names the models).  A, W, bias, the destinations and the workspace
  * are device pointers; out and out_col are host arrays.  The N columns may go to up to 4
  * destinations: columns out_col[i] .. out_col[i + 1] are written to out[i], a row-major
  * [M][out_col[i + 1] - out_col[i]] bf16 tensor (out_col[0] = 0, out_col[n_out] = N, boundaries
@@ -336,13 +351,18 @@ int ms_ama_count(int n_tokens, int c);
 int ms_upl_positions(int first_pid, int n_tokens, int c, int* out, int cap);
 /* PID of <o> after a step whose last token has PID last_pid (Section 2.2): last_pid + 1. */
 int ms_output_token_pid(int last_pid);
-/* PIDs of d foresight tokens after a prefix ending at last_prefix_pid: last + 1 .. last + d. */
+/* PIDs of d foresight tokens after a prefix ending at last_prefix_pid: last + 1 .. last + d
+ * (Section 2.1.1: foresight token j stands at the position of the j-th token after the prefix and
+ * predicts the token one position further). */
 int ms_foresight_pids(int last_prefix_pid, int d, int* out, int cap);
 /* Position ids of a whole batch's step, out[B][n_verify + n_foresight] (host): sequence b's verify
- * tokens hold first_pid[b] .. and its foresight tokens follow by the rule of ms_foresight_pids.
+ * tokens hold first_pid[b] .. and its foresight tokens follow by the rule of ms_foresight_pids
+ * (Section 2.1.1; the position rule of Section 2.2 with the verify block as the prefix).
  * Returns the number of entries written, negative on bad input. */
 int ms_step_positions(int B, const int* first_pid, int n_verify, int n_foresight, int* out);
-/* Default ctx_new row for n_verify + n_foresight queries. */
+/* Default ctx_new row for n_verify + n_foresight queries: verify token i sees the i verify tokens
+ * before it, every foresight token sees the whole verify block and, like every query, itself
+ * (Section 2.1.1; Section 2.3 "MTP Attention"). */
 int ms_default_ctx_new(int n_verify, int n_foresight, int* out, int cap);
 /* Per-position foresight step (Section 2.2 "CoT Augmentation", Section 2.3 "MTP Attention": the
  * layout the model is trained on, used at inference so that drafts survive a partial acceptance):

@@ -1,7 +1,7 @@
 """CPU oracle of one full MemoSight decode step (test infrastructure only -- never imported by the
 product path).
 
-Scope: Algorithm 1's SpeculativeStep (Appendix A) on the models the paper fine-tunes (Section 4.1:
+Scope: Algorithm 1's SpeculativeStep (Appendix A) on the models the paper fine-tunes (Section 3.1:
 Qwen2.5-7B, Llama-3.1-8B).  The paper does not restate the decoder block; it is the public
 pre-norm architecture of those models -- RMSNorm, Q/K/V projections (with bias in Qwen2.5), rotary
 attention with grouped KV heads, output projection, SwiGLU MLP, final norm and LM head -- and this

@@ -70,8 +70,10 @@ _SIGS = {
     "ms_seq_page_table": (_I, [_P, _I, _IP, _I, _IP]),
     "ms_free_page_count": (_I, [_P, _IP]),
     "ms_peak_pages": (_I, [_P, _IP]),
+    "ms_launch_count": (_I, [_P, C.POINTER(C.c_longlong)]),
     "ms_check_integrity": (_I, [_P, _P]),
     "ms_attention_set_deterministic": (_I, [_P, _I]),
+    "ms_attention_fault_injection": (_I, [_P, _I, _I, _P]),
     "ms_embed_rows": (_I, [_P, _I, _I, _P, _I, _P, _P]),
     "ms_add_rmsnorm": (_I, [_P, _P, _P, _F, _P, _I, _I, _P]),
     "ms_swiglu": (_I, [_P, _P, _I, _I, _P]),
@@ -372,6 +374,10 @@ def ms_attention_set_deterministic(cache, on: bool) -> None:
     _check(lib.ms_attention_set_deterministic(cache, 1 if on else 0))
 
 
+def ms_attention_fault_injection(cache, poll_limit: int, published_bias: int, stream=None) -> None:
+    _check(lib.ms_attention_fault_injection(cache, poll_limit, published_bias, _stream(stream)))
+
+
 def ms_accept(B, n, draft, target, stop_ids, accept_len, next_token, stream=None) -> None:
     n_stop = 0 if stop_ids is None else stop_ids.numel()
     _check(lib.ms_accept(B, n, _sized(None, draft, "draft", B * n, 4), _sized(None, target, "target", B * n, 4),
@@ -402,6 +408,12 @@ def ms_free_page_count(cache) -> int:
 def ms_peak_pages(cache) -> int:
     n = C.c_int(0)
     _check(lib.ms_peak_pages(cache, C.byref(n)))
+    return n.value
+
+
+def ms_launch_count(cache) -> int:
+    n = C.c_longlong(0)
+    _check(lib.ms_launch_count(cache, C.byref(n)))
     return n.value
 
 

@@ -47,6 +47,7 @@ int static_scratch(int device, void** ptr);
 bool mfma_eligible(const ms_cache* c, int n_q);
 size_t mfma_workspace_bytes(const ms_cache* c, int B);
 int mfma_plan_ints(int B);
+int reset_arrival_counters(ms_cache* c, int published, hipStream_t stream);
 int launch_mfma(ms_cache* c, const AttnArgs& a, const BatchMeta& bm, int B, hipStream_t stream);
 
 }  // namespace ms

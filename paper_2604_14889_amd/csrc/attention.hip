@@ -204,9 +204,10 @@ static int rowwave_splits(int rows, int max_len, int* chunk) {
 }
 
 template <typename T, int D>
-static int launch_rowwave(AttnArgs& a, const BatchMeta& bm, int B, int max_len, hipStream_t stream) {
+static int launch_rowwave(ms_cache* c, AttnArgs& a, const BatchMeta& bm, int B, int max_len, hipStream_t stream) {
     const int rows = a.n_q * a.n_q_heads;
     a.n_splits = rowwave_splits(B * rows, max_len, &a.chunk);
+    c->launches += a.n_splits > 1 ? 2 : 1;
     hipLaunchKernelGGL((pv_attn_rowwave<T, D>), dim3(a.n_splits, rows, B), dim3(64), 0, stream, a, bm);
     MS_HIP_TRY(hipGetLastError());
     if (a.n_splits > 1) {
@@ -323,8 +324,8 @@ extern "C" int ms_predict_verify_attention(ms_cache* c, int layer, int B, const 
     if (mfma_eligible(c, n_q)) return launch_mfma(c, a, bm, B, stream);
     const int D = c->d.head_dim;
     if (c->d.dtype == MS_F32)
-        return D == 64 ? launch_rowwave<float, 64>(a, bm, B, max_len, stream) : launch_rowwave<float, 128>(a, bm, B, max_len, stream);
-    return D == 64 ? launch_rowwave<bf16_t, 64>(a, bm, B, max_len, stream) : launch_rowwave<bf16_t, 128>(a, bm, B, max_len, stream);
+        return D == 64 ? launch_rowwave<float, 64>(c, a, bm, B, max_len, stream) : launch_rowwave<float, 128>(c, a, bm, B, max_len, stream);
+    return D == 64 ? launch_rowwave<bf16_t, 64>(c, a, bm, B, max_len, stream) : launch_rowwave<bf16_t, 128>(c, a, bm, B, max_len, stream);
 }
 
 extern "C" int ms_predict_verify_attention_static(ms_cache* c, int layer, int B, const int* seq_ids, int n_verify,

@@ -26,6 +26,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "attention.h"
@@ -109,13 +110,12 @@ struct MfmaArgs {
     const Seg* segs;        // all segments in item order
     const int* part_begin;  // [B + 1]
     int* arrive;            // [B][n_kv_heads][2] counters (shares finished, partials published), zero between calls
+    int* error_word;        // host memory the device can write: set when a closing workgroup gave up waiting
+    int poll_limit;         // polls of the published counter before a closing workgroup gives up
     int n_q, n_verify, n_q_heads, n_kv_heads, group, max_pages;
     int q0, n_qc;           // this launch computes queries q0 .. q0 + n_qc (decode build: all of them)
     long page_elems;
     float scale_log2;       // softmax scale * log2(e)
-#ifdef MS_TIMING
-    long long* dbg;         // [workgroup][8] wall-clock stamps (100 MHz)
-#endif
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
@@ -474,10 +474,6 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
     const uint32_t page_bytes = (uint32_t)a.page_elems * 2;
     const uint32_t lane_off_k = ((uint32_t)g * 2 * MS_PAGE_SIZE * kD + (lane & 15) * kD + 8 * hf) * 2;
     const uint32_t lane_off_v = (((uint32_t)g * 2 + 1) * MS_PAGE_SIZE * kD + (lane >> 4) * kD + 8 * l16) * 2;
-#ifdef MS_TIMING
-    long long* dbg = a.dbg + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8;
-    if (tid == 0) dbg[0] = wall_clock64();
-#endif
     // The item's first segment record also holds the item's segment range and the page ids of the
     // first tiles, so the first loads depend on this one record only.
     const float inv_f = a.inv_freq[lane];   // rotation pair `lane`; issued before anything else
@@ -491,9 +487,6 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         const int n_tiles = (n_tok + kTile - 1) / kTile;
         const bool first_seg = sg_t0 == 0;   // this workgroup also runs the sequence's in-flight tile
         int pa = uniform_load(&sp->pages[2 * w]), pb = uniform_load(&sp->pages[2 * w + 1]);
-#ifdef MS_TIMING
-        if (tid == 0 && si == seg_begin) dbg[4] = wall_clock64() + (pa & 0) + (n_tok & 0);
-#endif
 
         // ---- set-up loads.  Order matters: waiting for a load also waits for every load issued
         // before it, so the small loads the Q rotation needs go first and this wave's first tile
@@ -535,10 +528,6 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
                 cs_tab[(w + 8 * k) * 64 + (tid_p & 63)] = make_float2(cs, sn);
             }
         lds_barrier();
-#ifdef MS_TIMING
-        if (tid == 0 && si == seg_begin) dbg[5] = wall_clock64();
-        if (tid == 0 && si == seg_begin) dbg[6] = wall_clock64() + (x0v.x & 0) + (k1v.w & 0);
-#endif
         {
             const uint32_t w0[4] = {x0v.x, x0v.y, x0v.z, x0v.w}, w1[4] = {x1v.x, x1v.y, x1v.z, x1v.w};
             const uint32_t u0[4] = {k0v.x, k0v.y, k0v.z, k0v.w}, u1[4] = {k1v.x, k1v.y, k1v.z, k1v.w};
@@ -574,9 +563,6 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
             }
         }
         lds_barrier();
-#ifdef MS_TIMING
-        if (tid == 0 && si == seg_begin) dbg[1] = wall_clock64();
-#endif
         WaveState st;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
@@ -675,9 +661,6 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         int* ctr = a.arrive + 2 * (sg_b * a.n_kv_heads + g);   // [0] shares finished, [1] partials published
         int lane_m = lane;
         asm volatile("" : "+v"(lane_m));
-#ifdef MS_TIMING
-        if (tid == 0 && si == seg_begin) dbg[2] = wall_clock64();
-#endif
         int ticket = 0;
         float4 own[2][2];
         float own_m = 0.f, own_l = 0.f;
@@ -768,21 +751,32 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         } else {
             if (tid == 0) {
                 const int others = p_end - p_begin - 1;
-                // (the bound only guards against a corrupted counter: about a second of polling)
-                for (int spin = 0; spin < (1 << 22) && __hip_atomic_load(ctr + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != others; ++spin)
+                // The wait ends when the shares that took their tickets earlier have published; they
+                // wait for nothing, so this takes a few microseconds.  The bound (about a second by
+                // default) only guards against counters left in a bad state: then nothing is folded
+                // from the workspace, the output rows of the pair stay unwritten, and the host is
+                // told through the error word -- the next call on the cache fails and resets them.
+                int seen = __hip_atomic_load(ctr + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int spin = 0; spin < a.poll_limit && seen != others; ++spin) {
                     __builtin_amdgcn_s_sleep(2);
-                __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);       // ready for the next call
-                __hip_atomic_store(ctr + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    seen = __hip_atomic_load(ctr + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                const bool complete = seen == others;
+                if (complete) {
+                    __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);       // ready for the next call
+                    __hip_atomic_store(ctr + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    __hip_atomic_store(a.error_word, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                }
+                *reinterpret_cast<volatile int*>(smem + L::kFlag + 8) = complete ? 1 : 0;
             }
             lds_barrier();
             asm volatile("" ::: "memory");   // the partials are read after the wait, also in the compiler's order
-            close_pair(a, q0, n_rows, sg_b, g, p_begin, p_end, sg_part, own, own_m, own_l, w, lane_m);
+            if (*reinterpret_cast<volatile int*>(smem + L::kFlag + 8))
+                close_pair(a, q0, n_rows, sg_b, g, p_begin, p_end, sg_part, own, own_m, own_l, w, lane_m);
         }
         lds_barrier();  // the next segment reuses the LDS
     }
-#ifdef MS_TIMING
-    if (tid == 0) dbg[3] = wall_clock64();
-#endif
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -802,19 +796,33 @@ static bool big_pool(const ms_cache* c) { return (unsigned long long)c->layer_el
 static int mfma_items(const ms_cache* c) {
     int target = c->n_cus / c->d.n_kv_heads;
     if (target < 1) target = 1;
-#ifdef MS_TIMING
-    if (const char* e = getenv("MS_ITEMS")) target = atoi(e);
-#endif
     return target > kMaxMfmaItems ? kMaxMfmaItems : target;
 }
 
 // every share contributes one partial plus one per sequence boundary inside it
 size_t mfma_workspace_bytes(const ms_cache* c, int B) {
     size_t n = (size_t)(mfma_items(c) + B) * c->d.n_kv_heads * kPartFloats * sizeof(float);
-#ifdef MS_TIMING
-    n += 1 << 20;
-#endif
     return n;
+}
+
+constexpr int kMaxAttrDevices = 64;
+constexpr int kDefaultPollLimit = 1 << 22;   // about a second
+
+__global__ void fill_arrival_counters(int* ctr, int n_pairs, int finished, int published) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_pairs) {
+        ctr[2 * i] = finished;
+        ctr[2 * i + 1] = published;
+    }
+}
+
+// Sets every pair's counters (a fill kernel: safe under stream capture, ordered behind earlier launches).
+int reset_arrival_counters(ms_cache* c, int published, hipStream_t stream) {
+    const int n_pairs = MS_MAX_BATCH * c->d.n_kv_heads;
+    c->launches++;
+    hipLaunchKernelGGL(fill_arrival_counters, dim3((n_pairs + 255) / 256), dim3(256), 0, stream, c->d_arrive, n_pairs, 0, published);
+    MS_HIP_TRY(hipGetLastError());
+    return MS_OK;
 }
 
 constexpr int kSegInts = (int)(sizeof(Seg) / sizeof(int));
@@ -920,16 +928,32 @@ static void build_plan(const ms_cache* c, const BatchMeta& bm, int B, int n_item
 }
 
 int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
+    // the kernels' LDS size is a per-device attribute: set once for every device the library meets
+    static std::once_flag attr_once[kMaxAttrDevices];
+    static hipError_t attr_result[kMaxAttrDevices];
+    if (c->device < 0 || c->device >= kMaxAttrDevices) MS_FAIL(MS_ERR_UNSUPPORTED, "device index %d outside [0, %d)", c->device, kMaxAttrDevices);
+    std::call_once(attr_once[c->device], [&] {
+        hipError_t e = hipSuccess;
         const void* decode_builds[] = {(const void*)pv_attn_mfma_stream<false, false, false>, (const void*)pv_attn_mfma_stream<false, true, false>,
                                        (const void*)pv_attn_mfma_stream<false, false, true>, (const void*)pv_attn_mfma_stream<false, true, true>};
         for (const void* f : decode_builds)
-            MS_HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Lds<false>::kBytes));
+            if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Lds<false>::kBytes);
         const void* wide_builds[] = {(const void*)pv_attn_mfma_stream<true, false, false>, (const void*)pv_attn_mfma_stream<true, false, true>};
         for (const void* f : wide_builds)
-            MS_HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Lds<true>::kBytes));
-        attr_set = true;
+            if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Lds<true>::kBytes);
+        attr_result[c->device] = e;
+    });
+    if (attr_result[c->device] != hipSuccess)
+        MS_FAIL(MS_ERR_HIP, "hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed: %s", hipGetErrorString(attr_result[c->device]));
+    // A closing workgroup of an earlier launch on this cache gave up waiting for partial results
+    // (arrival counters in a bad state): that launch left output rows unwritten.  Report it once,
+    // and put the counters back to zero behind everything queued so far.
+    if (__atomic_load_n(c->h_error, __ATOMIC_RELAXED) != 0) {
+        __atomic_store_n(c->h_error, 0, __ATOMIC_RELAXED);
+        int rc = reset_arrival_counters(c, 0, stream);
+        if (rc != MS_OK) return rc;
+        MS_FAIL(MS_ERR_HIP, "an earlier attention launch on this cache timed out waiting for split-KV partial results and left "
+                            "output rows unwritten; the arrival counters have been reset, repeat the step");
     }
     // plan: rebuilt only when the batch (ids, lengths) changed since the last call on this cache
     std::vector<int> key;
@@ -962,6 +986,8 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     a.segs = reinterpret_cast<const Seg*>(c->d_plan + (size_t)c->plan_items * kSegInts);
     a.part_begin = c->d_plan + (size_t)(c->plan_items + c->plan_parts) * kSegInts;
     a.arrive = c->d_arrive;
+    a.error_word = c->d_error;
+    a.poll_limit = c->poll_limit > 0 ? c->poll_limit : kDefaultPollLimit;
     a.n_q = ga.n_q;
     a.n_verify = ga.n_verify;
     a.n_q_heads = ga.n_q_heads;
@@ -970,9 +996,6 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     a.max_pages = ga.max_pages;
     a.page_elems = ga.page_elems;
     a.scale_log2 = ga.scale * 1.44269504088896340736f;
-#ifdef MS_TIMING
-    a.dbg = (long long*)((char*)ga.ws + (size_t)(mfma_items(c) + B) * c->d.n_kv_heads * kPartFloats * sizeof(float));
-#endif
     {
         // every prof_stride-th call opens a timed span of prof_span consecutive calls
         if (c->prof_open == 0 && c->prof_count < (int)c->prof_start.size() && c->prof_seen % c->prof_stride == 0) {
@@ -987,6 +1010,7 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
             const bool big = big_pool(c);
             auto kern = c->deterministic ? (big ? pv_attn_mfma_stream<false, false, true> : pv_attn_mfma_stream<false, false, false>)
                                          : (big ? pv_attn_mfma_stream<false, true, true> : pv_attn_mfma_stream<false, true, false>);
+            c->launches++;
             hipLaunchKernelGGL(kern, grid, dim3(kThreads), Lds<false>::kBytes, stream, a);
         } else {
             // wide steps: one launch per chunk of queries; launches on one stream run in order, so
@@ -995,6 +1019,7 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
             for (a.q0 = 0; a.q0 < a.n_q; a.q0 += per_launch) {
                 a.n_qc = a.n_q - a.q0 < per_launch ? a.n_q - a.q0 : per_launch;
                 auto kern = big_pool(c) ? pv_attn_mfma_stream<true, false, true> : pv_attn_mfma_stream<true, false, false>;
+                c->launches++;
                 hipLaunchKernelGGL(kern, grid, dim3(kThreads), Lds<true>::kBytes, stream, a);
             }
         }
@@ -1039,4 +1064,10 @@ extern "C" int ms_profile_read(ms_cache* c, float* ms_out, int cap, int* n) {
     c->prof_count = 0;
     c->prof_open = 0;   // a span still open is dropped
     return MS_OK;
+}
+
+extern "C" int ms_attention_fault_injection(ms_cache* c, int poll_limit, int published_bias, void* stream) {
+    if (!c || poll_limit < 0) MS_FAIL(MS_ERR_INVALID, "ms_attention_fault_injection: bad argument");
+    c->poll_limit = poll_limit;
+    return ms::reset_arrival_counters(c, published_bias, (hipStream_t)stream);
 }

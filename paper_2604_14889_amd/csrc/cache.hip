@@ -241,6 +241,7 @@ int flush_page_table_patches(ms_cache* c, hipStream_t stream) {
         void* dev = nullptr;
         int rc = c->stage.upload(c->pending_pt.data() + 3 * done, cnt * 3 * sizeof(int), stream, &dev);
         if (rc != MS_OK) return rc;
+        c->launches++;
         hipLaunchKernelGGL(patch_page_table, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, stream,
                            c->d_pt, (const int*)dev, (int)cnt, c->d.max_pages_per_seq);
         MS_HIP_TRY(hipGetLastError());
@@ -308,6 +309,7 @@ static int launch_rows(ms_cache* c, bool gather, const std::vector<RowDesc>& des
     return dispatch(c, [&](auto* tp, auto dc) -> int {
         using T = std::remove_pointer_t<decltype(tp)>;
         constexpr int D = decltype(dc)::value;
+        c->launches++;
         if (gather)
             hipLaunchKernelGGL((kv_gather<T, D>), grid, dim3(256), 0, stream, a);
         else
@@ -353,6 +355,7 @@ static int patch_and_scatter(ms_cache* c, const std::vector<RowDesc>& desc, int 
     return dispatch(c, [&](auto* tp, auto dc) -> int {
         using T = std::remove_pointer_t<decltype(tp)>;
         constexpr int D = decltype(dc)::value;
+        c->launches++;
         hipLaunchKernelGGL((kv_scatter_inline<T, D>), grid, dim3(256), 0, stream, a, tb);
         MS_HIP_TRY(hipGetLastError());
         return (int)MS_OK;
@@ -446,6 +449,12 @@ int ms_cache_create(const ms_cache_desc* desc, ms_cache** out) {
         set_error("allocating the arrival counters failed");
         return fail(MS_ERR_HIP);
     }
+    if (hipHostMalloc((void**)&c->h_error, sizeof(int), hipHostMallocMapped) != hipSuccess ||
+        hipHostGetDevicePointer((void**)&c->d_error, c->h_error, 0) != hipSuccess) {
+        set_error("allocating the error word failed");
+        return fail(MS_ERR_HIP);
+    }
+    *c->h_error = 0;
     *out = c;
     return MS_OK;
 }
@@ -458,6 +467,7 @@ int ms_cache_destroy(ms_cache* c) {
     if (c->d_inv_freq) (void)hipFree(c->d_inv_freq);
     if (c->d_plan) (void)hipFree(c->d_plan);
     if (c->d_arrive) (void)hipFree(c->d_arrive);
+    if (c->h_error) (void)hipHostFree(c->h_error);
     for (hipEvent_t e : c->prof_start) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->prof_stop) (void)hipEventDestroy(e);
     delete c;
@@ -730,6 +740,12 @@ int ms_peak_pages(ms_cache* c, int* n) {
     return MS_OK;
 }
 
+int ms_launch_count(ms_cache* c, long long* n) {
+    if (!c || !n) MS_FAIL(MS_ERR_INVALID, "ms_launch_count: null argument");
+    *n = c->launches;
+    return MS_OK;
+}
+
 int ms_check_integrity(ms_cache* c, void* stream) {
     if (!c) MS_FAIL(MS_ERR_INVALID, "ms_check_integrity: null cache");
     std::vector<char> owner(c->d.n_pages, 0);
@@ -751,6 +767,8 @@ int ms_check_integrity(ms_cache* c, void* stream) {
         if (!owner[p]) MS_FAIL(MS_ERR_INVALID, "integrity: page %d leaked", p);
     if (!c->pending_pt.empty()) MS_FAIL(MS_ERR_INVALID, "integrity: page-table patches not flushed");
     MS_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    if (__atomic_load_n(c->h_error, __ATOMIC_RELAXED) != 0)   // left set: the next attention call reports and clears it too
+        MS_FAIL(MS_ERR_HIP, "integrity: an attention launch timed out waiting for split-KV partial results");
     std::vector<int> row(c->d.max_pages_per_seq);
     for (int s = 0; s < c->d.max_seqs; ++s) {
         if (!c->live[s] || c->pt[s].empty()) continue;

@@ -1,6 +1,6 @@
 // Memory-bound pieces of the decoder block around the attention, for the full decode step
 // (MemoSight paper, Appendix A, Algorithm 1: SpeculativeStep runs the model once over the verify
-// and foresight tokens; Section 4.1 names the models, whose block is pre-norm RMSNorm, attention,
+// and foresight tokens; Section 3.1 names the models, whose block is pre-norm RMSNorm, attention,
 // SwiGLU MLP): embedding rows, residual add + RMSNorm, SiLU(gate) * up, and the greedy token of
 // every logits row.  The dense projections are GEMMs and live outside this file.
 //

@@ -1,6 +1,6 @@
 // bf16 GEMM for the decode step's dense projections: C[M][N] = A[M][K] . W[N][K]^T (+ bias),
 // fp32 accumulation on the matrix cores (MemoSight paper, Appendix A, Algorithm 1: SpeculativeStep
-// runs the model's projections over the few hundred tokens of a step; Section 4.1 names the models).
+// runs the model's projections over the few hundred tokens of a step; Section 3.1 names the models).
 //
 // Shape of the problem: M is small (batch x queries, a few hundred rows), N and K are the model's
 // widths, both operands are K-contiguous.  One workgroup of 8 waves computes a 256 (M) x 128 (N)
@@ -713,14 +713,6 @@ static SkinnyPlan skinny_plan(int M, int N, int K, int min_parts = 1) {
     } else if (N % 128 == 0 && (long)n_tiles / 2 * parts >= 4 * want) nt = 2;
     else if ((long)n_tiles * parts < want) wk = (long)n_tiles * parts * 2 >= want ? 2 : 4;
     while (wk > 1 && steps / parts < wk) wk /= 2;   // every wave gets a step
-#ifdef MS_TIMING
-    if (const char* e = getenv("MS_SKINNY")) {   // "nt,wk,parts", or "off" (experiments)
-        if (e[0] == 'o') return p;
-        int a = 0, b = 0, c = 0;
-        if (sscanf(e, "%d,%d,%d", &a, &b, &c) == 3 && (a == 1 || ((a == 2 || a == 4) && b == 1)) && (b == 1 || b == 2 || b == 4) &&
-            c >= parts && steps / c >= b && N % (64 / b * a) == 0) { nt = a; wk = b; parts = c; }
-    }
-#endif
     p.parts = parts;
     p.nt = nt;
     p.wk = wk;

@@ -78,6 +78,9 @@ struct ms_cache {
     int n_cus = 256;             // compute units of the device
     int* d_plan = nullptr;       // device copy of the streaming kernel's work plan
     int* d_arrive = nullptr;     // [MS_MAX_BATCH][n_kv_heads][2] counters of the streaming kernel: shares finished, partials published
+    int* h_error = nullptr;      // pinned host word the streaming kernel sets when a closing workgroup times out
+    int* d_error = nullptr;      // the same word as the device sees it
+    int poll_limit = 0;          // polls before a closing workgroup gives up; 0 = the default (about a second)
     std::vector<int> plan_key;   // batch (ids, lengths) the plan was built for
     int plan_items = 0, plan_parts = 0, plan_B = 0;
     std::vector<hipEvent_t> prof_start, prof_stop;  // event pairs around the streaming kernel
@@ -87,6 +90,7 @@ struct ms_cache {
     int prof_span = 1;     // consecutive calls one event pair covers
     int prof_open = 0;     // calls the open span still waits for
     int prof_seen = 0;
+    long long launches = 0;   // kernels launched by calls on this cache so far
 };
 
 namespace ms {

@@ -1,10 +1,14 @@
 """MemoSight's iterative inference (Appendix A, Algorithm 1 of the paper) on the GPU step by step.
 
-Phase 1, foresight-based acceleration: one fused pass per step over the verify block
-[next token, drafts] and d foresight tokens (Section 2.1.1); the drafts that match the model's own
-greedy tokens are accepted, the accepted tokens' K/V enter the paged cache, the foresight rows'
-greedy tokens are the next drafts.  Phase 2, compression: when a step delimiter is among the
-accepted tokens, l = ceil(|R| / c) memory tokens and the output token <o> are run through the model
+Phase 1, foresight-based acceleration (Section 2.1.1).  A sequence that holds drafts runs the fused
+pass: the verify block [next token, d drafts] and d foresight tokens behind it; the drafts that match
+the model's own greedy tokens are accepted and the accepted tokens' K/V enter the paged cache.  Only
+when the whole block was kept do the foresight rows stand at the position ids of the tokens that
+follow it, and only then are their greedy tokens the next drafts.  A sequence without valid drafts
+(a new step, or a block that was cut short) runs the Predict pass alone: its next token and d
+foresight tokens right behind it, which yields the next token's successor and d drafts.  Both kinds
+share one forward pass of the batch: every query carries its own position id and visibility bound.
+Phase 2, compression: when a step delimiter is among the accepted tokens, l = ceil(|R| / c) memory tokens and the output token <o> are run through the model
 (causal among themselves, position ids from the uniform position layout, Section 2.1.2 / 2.2), and
 the step's tokens are replaced in the cache by those l + 1 rows; generation continues from <o>'s
 greedy token.
@@ -46,6 +50,7 @@ class SeqState:
     generated: List[int] = field(default_factory=list)
     finished: bool = False
     steps_closed: int = 0
+    drafts_valid: bool = False  # False: `drafts` are placeholders, the next pass is a Predict pass for this sequence
 
 
 class Observer:
@@ -61,8 +66,11 @@ class Observer:
 
 class MemoSightDriver:
     def __init__(self, decoder: Decoder, d: int, c: int, special: SpecialTokens, observer: Optional[Observer] = None,
-                 per_position: bool = False):
-        """per_position: put d foresight tokens behind EVERY verify token (the layout the model is
+                 per_position: bool = False, upl: bool = True, fixed_memory: Optional[int] = None):
+        """upl=False and fixed_memory=n select the ablation layouts of Appendix B: memory tokens on the
+        consecutive position ids after the step ("w/o UPL"), n memory tokens for every step whatever
+        its length ("w/o AMA").
+        per_position: put d foresight tokens behind EVERY verify token (the layout the model is
         trained on, Section 2.2) instead of behind the block only, so that the drafts for the next
         pass are valid whatever number of verify tokens was kept; costs (d + 1) d instead of d extra
         queries per pass."""
@@ -70,11 +78,15 @@ class MemoSightDriver:
             raise ValueError("need d >= 0 and c >= 1")
         if per_position and (d + 1) * (d + 1) > M.MS_MAX_QUERIES:
             raise ValueError("too many queries per pass")
-        self.per_position = per_position
+        if fixed_memory is not None and not 1 <= fixed_memory < M.MS_MAX_QUERIES:
+            raise ValueError("fixed_memory out of range")
+        self.per_position, self.upl, self.fixed_memory = per_position, upl, fixed_memory
         self.dec, self.ses, self.d, self.c, self.sp = decoder, decoder.ses, d, c, special
         self.obs = observer or Observer()
         self.state: Dict[int, SeqState] = {}
         self.passes = {"speculative": 0, "memory": 0, "prefill": 0}
+        self.blocks = {"verify": 0, "predict": 0}   # per sequence and pass: which kind it ran
+        self.committed = 0         # tokens committed by speculative passes
         self.raw_tokens = 0        # tokens that would be cached without compression
 
     # ---- helpers --------------------------------------------------------------------------------
@@ -116,28 +128,52 @@ class MemoSightDriver:
         act = [s for s in self.state.values() if not s.finished]
         if not act:
             return []
-        d, nv = self.d, self.d + 1
+        d = self.d
         ids = [s.seq_id for s in act]
-        nf = nv * d if self.per_position else d
-        tokens = np.asarray([[s.next_token] + s.drafts + [self.sp.foresight] * nf for s in act], np.int32)
+        B = len(act)
+        F = self.sp.foresight
         ctx_d = None
         if self.per_position:
+            # d foresight tokens behind every verify token: whatever is kept, drafts follow it
+            nv, nf = d + 1, (d + 1) * d
+            tokens = np.asarray([[s.next_token] + s.drafts + [F] * nf for s in act], np.int32)
             lay = [M.ms_per_position_layout(s.next_pid, nv, d) for s in act]
             pos = np.asarray([p for p, _ in lay], np.int32)
             ctx_d = torch.tensor([c_ for _, c_ in lay], dtype=torch.int32, device="cuda")
+            verifying = [True] * B
         else:
-            pos = M.ms_step_positions(np.asarray([s.next_pid for s in act], np.int32), nv, d)
+            verifying = [s.drafts_valid and d > 0 for s in act]
+            first = np.asarray([s.next_pid for s in act], np.int32)
+            if not any(verifying):
+                # Predict pass for everyone: the next token and d foresight tokens behind it
+                nv, nf = 1, d
+                tokens = np.asarray([[s.next_token] + [F] * d for s in act], np.int32)
+                pos = M.ms_step_positions(first, 1, d)
+            else:
+                # fused pass; a sequence without drafts runs its Predict pass inside it: its d
+                # foresight tokens take the place of the drafts (each sees the next token and
+                # itself) and the block's last d rows are padding that sees, and is seen by, nothing
+                nv, nf = d + 1, d
+                tokens = np.asarray([[s.next_token] + (s.drafts if v else [F] * d) + [F] * d for s, v in zip(act, verifying)], np.int32)
+                pos = M.ms_step_positions(first, nv, d)
+                if not all(verifying):
+                    pred = M.ms_step_positions(first, 1, d)
+                    fused_ctx, pred_ctx = M.ms_default_ctx_new(nv, d), M.ms_default_ctx_new(1, d) + [0] * d
+                    for b, v in enumerate(verifying):
+                        if not v:
+                            pos[b, :1 + d] = pred[b]
+                    ctx_d = torch.tensor([fused_ctx if v else pred_ctx for v in verifying], dtype=torch.int32, device="cuda")
         pos_d, targets = self._forward("speculative", ids, tokens, pos, nv, nf, ctx_d)
-        B, nq = len(act), nv + nf
+        nq = nv + nf
         tg = targets.view(B, nq)
         n_commit = [1] * B
-        if d > 0:
+        if nv > 1:
             acc_d = torch.empty(B, dtype=torch.int32, device="cuda")
             nxt_d = torch.empty(B, dtype=torch.int32, device="cuda")
             stops = torch.tensor(list(self.sp.delimiters) + [self.sp.eos], dtype=torch.int32, device="cuda")
             draft_d = torch.from_numpy(np.ascontiguousarray(tokens[:, 1:nv])).cuda()
             M.ms_accept(B, d, draft_d, tg[:, :d].contiguous(), stops, acc_d, nxt_d)
-            n_commit = [1 + int(a) for a in acc_d.cpu().numpy()]
+            n_commit = [1 + int(a) if v else 1 for a, v in zip(acc_d.cpu().numpy(), verifying)]
         tg_h = tg.cpu().numpy()
         boundary = set(self.sp.delimiters) | {self.sp.eos}
         for b, s in enumerate(act):
@@ -151,14 +187,24 @@ class MemoSightDriver:
             kept = [int(t) for t in tokens[b, :n_commit[b]]]
             s.generated += kept
             self.raw_tokens += len(kept)
+            self.committed += len(kept)
+            self.blocks["verify" if verifying[b] else "predict"] += 1
             last = kept[-1]
             s.next_pid += len(kept)
             s.next_token = int(tg_h[b, len(kept) - 1])          # the greedy token after the last kept one
-            # drafts for the next pass: the greedy tokens of the foresight rows behind the last kept
-            # verify token; with foresight tokens behind the block only, those are conditioned on the
-            # whole block and only have a chance when all of it was kept
-            f0 = nv + (len(kept) - 1) * d if self.per_position else nv
-            s.drafts = [int(t) for t in tg_h[b, f0:f0 + d]]
+            # drafts for the next pass: the greedy tokens of the foresight rows that stand right
+            # behind the last kept token.  Per-position layout: the d rows of that verify token.
+            # Otherwise the foresight rows follow the whole block (or, in a Predict pass, the next
+            # token): their position ids and what they saw fit only if all of it was kept.
+            if self.per_position:
+                f0 = nv + (len(kept) - 1) * d
+                s.drafts, s.drafts_valid = [int(t) for t in tg_h[b, f0:f0 + d]], True
+            elif not verifying[b]:
+                s.drafts, s.drafts_valid = [int(t) for t in tg_h[b, 1:1 + d]], True
+            elif len(kept) == nv:
+                s.drafts, s.drafts_valid = [int(t) for t in tg_h[b, nv:nv + d]], True
+            else:
+                s.drafts, s.drafts_valid = [F] * d, False
             if last == self.sp.eos:
                 s.finished = True
             elif last in self.sp.delimiters:
@@ -170,11 +216,23 @@ class MemoSightDriver:
         s = self.state[sid]
         cur = M.ms_seq_len(self.ses.cache, sid)
         seg_len = cur - s.step_begin
-        l = M.ms_ama_count(seg_len, self.c)
+        last_pid = s.step_first_pid + seg_len - 1
+        # how many memory tokens: one per c tokens of the step (adaptive memory allocation), or a
+        # fixed budget (Appendix B, "w/o AMA")
+        l = M.ms_ama_count(seg_len, self.c) if self.fixed_memory is None else self.fixed_memory
         if l + 1 > M.MS_MAX_QUERIES:
             raise M.MsError(M.MS_ERR_UNSUPPORTED, f"step of {seg_len} tokens needs {l + 1} queries in one pass")
-        mem_pids = M.ms_upl_positions(s.step_first_pid, seg_len, self.c)
-        o_pid = M.ms_output_token_pid(s.step_first_pid + seg_len - 1)
+        # where they stand: spread over the step's position span (uniform position layout), or on
+        # the consecutive positions after the step (Appendix B, "w/o UPL")
+        if not self.upl:
+            mem_pids = M.ms_consecutive_memory_positions(last_pid, l)
+            o_pid = M.ms_output_token_pid(last_pid + l)
+        elif self.fixed_memory is None:
+            mem_pids = M.ms_upl_positions(s.step_first_pid, seg_len, self.c)
+            o_pid = M.ms_output_token_pid(last_pid)
+        else:
+            mem_pids = M.ms_upl_positions_fixed(s.step_first_pid, seg_len, l)
+            o_pid = M.ms_output_token_pid(last_pid)
         tokens = np.asarray([[self.sp.memory] * l + [self.sp.output]], np.int32)
         pos = np.asarray([mem_pids + [o_pid]], np.int32)
         pos_d, targets = self._forward("memory", [sid], tokens, pos, l + 1, 0)
@@ -186,7 +244,7 @@ class MemoSightDriver:
         s.steps_closed += 1
         s.next_token = int(targets[l].item())      # generation continues from <o>'s greedy token
         s.next_pid = o_pid + 1
-        s.drafts = [self.sp.foresight] * self.d    # no drafts yet for the new step
+        s.drafts, s.drafts_valid = [self.sp.foresight] * self.d, False    # no drafts yet for the new step
         s.step_begin = M.ms_seq_len(self.ses.cache, sid)
         s.step_first_pid = s.next_pid
 
@@ -209,4 +267,7 @@ class MemoSightDriver:
                                              for s in self.state.values()),
             "cached_tokens": {sid: M.ms_seq_len(self.ses.cache, sid) for sid in self.state},
             "raw_tokens": self.raw_tokens,
+            "blocks": dict(self.blocks),
+            # tokens committed per sequence and speculative pass (1 = no gain over plain decoding)
+            "mean_committed": self.committed / max(1, sum(self.blocks.values())),
         }

@@ -32,10 +32,21 @@ def check_contract(r):
 def test_attention_bench_small():
     r = run_bench("--layers", "2", "--batch", "3", "--kv", "512", "--steps", "3", "--warmup", "1", "--event-stride", "1", "--cpu-seqs", "1")
     check_contract(r)
-    assert r["metric"] == "predict_verify_attn_hbm_gbps_b32_kv8k"
+    assert r["metric"] == "predict_verify_attn_hbm_gbps_b3_kv512"        # the label follows the configuration
+    assert r["config"]["workload"].startswith("batch3_kv512_layers2") and "also" not in r
     cb = r["cpu_baseline"]
-    assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1
-    assert cb["gpu_vs_oracle_max_abs"] <= 2e-2 and cb["gpu_vs_oracle_mean_rel"] <= 1e-2
+    assert cb["kind"] == "oracle" and cb["value"] > 0 and 1 <= cb["cores"] <= cb["cores_usable"] <= cb["nproc"]
+    assert cb["gpu_vs_oracle_max_abs"] <= 2e-2 and cb["gpu_vs_oracle_mean_rel"] <= 1e-2 and cb["within_tolerance"] is True
+    r = run_bench("--layers", "2", "--batch", "32", "--kv", "8192", "--steps", "2", "--warmup", "1", "--no-cpu-baseline", "--no-also")
+    assert r["metric"] == "predict_verify_attn_hbm_gbps_b32_kv8k" and r["roofline"]["traffic"] is not None
+
+
+def test_compaction_bench_small():
+    r = run_bench("--workload", "compaction", "--layers", "3", "--batch", "4", "--steps", "3", "--warmup", "1")
+    check_contract(r)
+    cp = r["compaction"]
+    assert cp["calls"] == 3 and cp["device_us_per_call"] > 0 and cp["kernel_launches_per_call"] >= 1
+    assert cp["kv_row_bytes_written_per_call"] == 4 * 8 * 3 * 4 * 128 * 2 * 2
 
 
 def test_decode_step_bench_small():

@@ -243,3 +243,74 @@ def test_decoder_helper_kernels_against_closed_forms():
         want = vals.argmax(axis=1)
         assert res.cpu().numpy().tolist() == want.tolist()
         assert res[0].item() == 3 and res[1].item() == v - 1
+
+
+def test_config5_full_widths_one_block_final_norm_and_lm_head():
+    """Config 5 at its real widths (hidden 3584, FFN 18944, vocabulary 152064, 28/4 heads x 128) and
+    row count (batch 64 x (4 verify + 3 foresight) = 448 rows): one decoder block, the final norm and
+    the LM head against the fp64 oracle (0.7 TFLOP of numpy).  One sequence holds 8192 cached tokens,
+    the others 16 to 300.  Same tolerances and margin rule as the reduced-model test above."""
+    M, S, D = _mods()
+    cfg = D.DecoderConfig(n_layers=1, hidden=3584, inter=18944, vocab=152064, n_q_heads=28, n_kv_heads=4, head_dim=128)
+    rng = W.make_rng(710)
+
+    def bits(shape, std, mean=0.0):
+        x = rng.standard_normal(shape, dtype=np.float32) * np.float32(std)
+        if mean:
+            x += np.float32(mean)
+        return (x.view(np.uint32) >> 16).astype(np.uint16)
+
+    qd, kd, H, I, V = 28 * 128, 4 * 128, cfg.hidden, cfg.inter, cfg.vocab
+    l = dict(ln1=bits(H, 0.2, 1.0), wq=bits((qd, H), H ** -0.5), bq=bits(qd, 0.1), wk=bits((kd, H), H ** -0.5), bk=bits(kd, 0.1),
+             wv=bits((kd, H), H ** -0.5), bv=bits(kd, 0.1), wo=bits((H, qd), qd ** -0.5), ln2=bits(H, 0.2, 1.0),
+             w_gate=bits((I, H), H ** -0.5), w_up=bits((I, H), H ** -0.5), w_down=bits((H, I), I ** -0.5))
+    top = dict(embed=bits((V, H), 1.0), norm=bits(H, 0.2, 1.0), lm_head=bits((V, H), H ** -0.5))
+    f32 = O.bf16_bits_to_f32                                   # the oracle widens to fp64 where it computes
+    wts = DO.DecoderWeights(
+        embed=f32(top["embed"]), norm=f32(top["norm"]).astype(np.float64), lm_head=f32(top["lm_head"]),
+        layers=[DO.LayerWeights(**{k: f32(v).astype(np.float64) for k, v in l.items()})],
+        n_q_heads=28, n_kv_heads=4, head_dim=128, eps=cfg.eps)
+    dev = lambda b: S.to_device(b, M.MS_BF16)
+    gw = D.DecoderTensors(
+        dev(top["embed"]),
+        [D.LayerTensors(dev(l["ln1"]), dev(l["wq"]), dev(l["bq"]), dev(l["wk"]), dev(l["bk"]), dev(l["wv"]), dev(l["bv"]),
+                        dev(l["wo"]), dev(l["ln2"]), dev(np.concatenate([l["w_gate"], l["w_up"]], axis=0)), dev(l["w_down"]))],
+        dev(top["norm"]), dev(top["lm_head"]))
+
+    B, nv, nf = 64, 4, 3
+    nq = nv + nf
+    lengths = [8192] + [int(x) for x in rng.integers(16, 301, size=B - 1)]
+    sh = W.AttnShape("c5", "bf16", B, 28, 4, 128, nv, nf, lengths, 0.5, cfg.rope_base, n_layers=1)
+    inp = W.attention_inputs(sh, 711)
+    ses, ora, ids = None, None, None
+    from tests.test_gpu_parity import setup_pair
+    ses, ora, ids = setup_pair(inp)
+    with ses:
+        pos = M.ms_step_positions(np.asarray([3 * n + 1 for n in lengths], np.int32), nv, nf)
+        tokens = rng.integers(0, V, size=(B, nq)).astype(np.int32)
+        dec = D.Decoder(cfg, gw, ses, B * nq)
+        logits, targets = dec.step(ids, S.ints_dev(tokens).view(B, nq), S.ints_dev(pos).view(B, nq), nv, nf)
+        torch.cuda.synchronize()
+        got = logits.float().cpu().numpy().reshape(B, nq, V)
+        tg = targets.cpu().numpy().reshape(B, nq)
+        ref = DO.speculative_step(wts, ora, ids, tokens, pos, nv, nf)
+        err = np.abs(got - ref.logits)
+        scale = np.abs(ref.logits).max()
+        max_abs, mean_rel = err.max(), err.mean() / np.abs(ref.logits).mean()
+        print(f"config 5 widths, 448 rows: logits max-abs {max_abs:.3e} (scale {scale:.2f}), mean-rel {mean_rel:.3e}")
+        assert max_abs <= 4e-2 * scale and mean_rel <= 2e-2
+        part = np.partition(ref.logits, V - 2, axis=-1)
+        clear = (part[..., -1] - part[..., -2]) > 2 * max_abs
+        assert clear.mean() > 0.3, clear.mean()
+        assert np.array_equal(tg[clear], ref.targets[clear])
+        k_new, v_new = dec.step_kv()
+        kg = k_new.float().cpu().numpy().reshape(1, B, nq, 4, 128)
+        vg = v_new.float().cpu().numpy().reshape(1, B, nq, 4, 128)
+        assert np.abs(kg - ref.k_new).max() <= 4e-2 * np.abs(ref.k_new).max()
+        assert np.abs(vg - ref.v_new).max() <= 4e-2 * np.abs(ref.v_new).max()
+        # the greedy token straight from the fp32 sums (no logits) at the same widths
+        dec_g = D.Decoder(cfg, gw, ses, B * nq, fused_lm_head=True)
+        none_logits, targets_g = dec_g.step(ids, S.ints_dev(tokens).view(B, nq), S.ints_dev(pos).view(B, nq), nv, nf)
+        torch.cuda.synchronize()
+        assert none_logits is None
+        assert np.array_equal(targets_g.cpu().numpy().reshape(B, nq)[clear], ref.targets[clear])

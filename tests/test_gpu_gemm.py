@@ -191,7 +191,7 @@ SWIGLU_CASES = [(7, 64, 32), (300, 1088, 256), (448, 18944, 512),
 
 @pytest.mark.parametrize("m,inter,k", SWIGLU_CASES)
 def test_gate_up_gemm_with_swiglu_epilogue(m, inter, k):
-    """silu(A Wg^T) * (A Wu^T) (the models' MLP, Section 4.1) in fp64 against the fused GEMM, which
+    """silu(A Wg^T) * (A Wu^T) (the models' MLP, Section 3.1) in fp64 against the fused GEMM, which
     applies SwiGLU to its fp32 sums and rounds once."""
     from paper_2604_14889_amd import binding as M
     from paper_2604_14889_amd import session as S
