@@ -66,6 +66,8 @@ def parse():
                          "the hand-written kernels")
     ap.add_argument("--deterministic", action="store_true",
                     help="fixed tile-to-wave assignment in the attention kernel (bit-reproducible results, about 1.5 %% slower)")
+    ap.add_argument("--host-commit", action="store_true",
+                    help="attention workload: read the accept lengths back and commit from the host (synchronises the stream every step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fused-lm-head", action="store_true",
                     help="decode_step: LM head and greedy token in one kernel of the library (fp32 sums, no logits)")
@@ -169,16 +171,21 @@ def attention_workload(args, sh, steps, warmup, want_cpu, ragged):
     pos_np, mpos_np = pos_h.numpy(), mpos_h.numpy()     # views of the pinned buffers
     ses.ensure_workspace(B, nq)
 
-    # raw position of each sequence's next token (about 3x the compressed length) and the open segment;
-    # the host keeps its own copy of the lengths (it knows every append and compaction it asks for)
+    # raw position of each sequence's next token (about 3x the compressed length) and the open segment.
+    # With the commit on the device the host learns the accepted counts only when it asks (for a
+    # compaction, which needs exact segment ranges): `known` is what it knew at the last such point.
     next_pid = np.asarray([sh.first_query_pid(b) for b in range(B)], dtype=np.int32)
     seg_len = np.zeros(B, dtype=np.int64)
     cur_len = np.asarray(ses.lengths(ids), dtype=np.int64)
     acc_np = acc_h.numpy()
-    state = {"kv_bytes": 0.0, "accepted": 0, "attn_calls": 0}
+    total_steps = warmup + steps
+    acc_log = torch.zeros(total_steps, B, dtype=torch.int32, device=dev)     # the device's accept lengths, step by step
+    first_pid_d = S.ints_dev(next_pid)
+    state = {"step": 0, "known": 0, "compacted_after": []}
     layer_args = [(k_new[layer], v_new[layer]) for layer in range(NL)]
     stream = torch.cuda.current_stream()
     sh_ = stream.cuda_stream    # raw handle for the library calls
+    host_commit = args.host_commit
 
     def algorithmic_bytes(lengths):
         es = 2
@@ -186,48 +193,76 @@ def attention_workload(args, sh, steps, warmup, want_cpu, ragged):
         per_call += B * nq * (2 * Hq + 2 * Hkv) * D * es
         return per_call
 
+    def catch_up():
+        """The host learns the accept lengths of the steps since it last asked (synchronises)."""
+        i0, i1 = state["known"], state["step"]
+        if i1 > i0:
+            got = acc_log[i0:i1].cpu().numpy().astype(np.int64).sum(axis=0)
+            next_pid[:] += got.astype(np.int32)
+            seg_len[:] += got
+            cur_len[:] += got
+            state["known"] = i1
+
+    def compact_if_due():
+        # a8: close and compact the segment once it holds 56 tokens
+        if seg_len.min() < SEG_TOKENS:
+            return
+        begin = cur_len - seg_len
+        cnt = [M.ms_ama_count(int(n), RATIO) for n in seg_len]
+        assert all(c == n_mem for c in cnt)
+        off = 0
+        for b in range(B):
+            first = int(next_pid[b] - seg_len[b])
+            mp = M.ms_upl_positions(first, int(seg_len[b]), RATIO)
+            mpos_np[off:off + len(mp)] = mp
+            off += len(mp)
+        mpos_d.copy_(mpos_h, non_blocking=True)
+        M.ms_compact_segment(ses.cache, ids, begin, seg_len, cnt, mem_k, mem_v, mpos_d)
+        next_pid[:] = [M.ms_output_token_pid(int(p) - 1) + 1 for p in next_pid]   # <o> takes one position
+        cur_len[:] += np.asarray(cnt) - seg_len
+        seg_len_before = seg_len.copy()
+        seg_len[:] = 0
+        state["compacted_after"].append((state["step"], np.asarray(cnt, dtype=np.int64) - seg_len_before))
+        if not host_commit:
+            first_pid_d.copy_(torch.from_numpy(next_pid), non_blocking=False)
+
     def step():
-        # a1: position layout (verify block, then foresight tokens right after it)
-        M.ms_step_positions(next_pid, nv, nf, pos_np)
-        pos_d.copy_(pos_h, non_blocking=True)
+        acc_d = acc_log[state["step"]]
+        if host_commit:
+            # a1: position layout on the host (verify block, then foresight tokens right after it)
+            M.ms_step_positions(next_pid, nv, nf, pos_np)
+            pos_d.copy_(pos_h, non_blocking=True)
+        else:
+            M.ms_step_positions_device(first_pid_d, nv, nf, pos_d, sh_)
         # a2-a5: attention in every layer
         for layer in range(NL):
             kl, vl = layer_args[layer]
             ses.attention(layer, ids, nv, nf, q, kl, vl, pos_d, None, 0.0, out, sh_)
-        state["kv_bytes"] += NL * algorithmic_bytes(cur_len)
-        state["attn_calls"] += NL
-        # a6: acceptance on the device, lengths back to the host
+        # a6: acceptance on the device
         M.ms_accept(B, nv, draft, target, None, acc_d, nxt_d, sh_)
-        acc_h.copy_(acc_d, non_blocking=True)
-        stream.synchronize()
-        # a7: commit accepted verify rows in every layer
-        M.ms_commit_accepted(ses.cache, ids, acc_np, nq, k_new, v_new, pos_d, sh_)
-        next_pid[:] += acc_np
-        seg_len[:] += acc_np
-        cur_len[:] += acc_np
-        state["accepted"] += int(acc_np.sum())
-        # a8: close and compact the segment once it holds 56 tokens
-        if seg_len.min() >= SEG_TOKENS:
-            begin = cur_len - seg_len
-            cnt = [M.ms_ama_count(int(n), RATIO) for n in seg_len]
-            assert all(c == n_mem for c in cnt)
-            off = 0
-            for b in range(B):
-                first = int(next_pid[b] - seg_len[b])
-                mp = M.ms_upl_positions(first, int(seg_len[b]), RATIO)
-                mpos_np[off:off + len(mp)] = mp
-                off += len(mp)
-            mpos_d.copy_(mpos_h, non_blocking=True)
-            M.ms_compact_segment(ses.cache, ids, begin, seg_len, cnt, mem_k, mem_v, mpos_d)
-            next_pid[:] = [M.ms_output_token_pid(int(p) - 1) + 1 for p in next_pid]   # <o> takes one position
-            cur_len[:] += np.asarray(cnt) - seg_len
-            seg_len[:] = 0
-
+        state["step"] += 1
+        if host_commit:
+            # accept lengths back to the host, a7: commit of the accepted verify rows in every layer
+            acc_h.copy_(acc_d, non_blocking=True)
+            stream.synchronize()
+            M.ms_commit_accepted(ses.cache, ids, acc_np, nq, k_new, v_new, pos_d, sh_)
+            next_pid[:] += acc_np
+            seg_len[:] += acc_np
+            cur_len[:] += acc_np
+            state["known"] = state["step"]
+            compact_if_due()
+            return
+        # a7 on the device: the kernel reads the accept lengths, takes pages in the host's order and
+        # advances the lengths and the next position ids; the stream is not synchronised
+        M.ms_commit_accepted_device(ses.cache, ids, acc_d, nq, nv, k_new, v_new, pos_d, first_pid_d, sh_)
+        # the host asks only when the open segment could have reached 56 tokens by now
+        if (seg_len + nv * (state["step"] - state["known"])).min() >= SEG_TOKENS:
+            catch_up()
+            compact_if_due()
 
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    state.update(kv_bytes=0.0, accepted=0, attn_calls=0)
     # one event pair per step around its NL back-to-back attention launches: nothing else runs on the
     # stream between them, so span time / NL is the kernel's duration plus the gap to the next launch
     ev_stride = args.event_stride or NL
@@ -247,10 +282,24 @@ def attention_workload(args, sh, steps, warmup, want_cpu, ragged):
     M.ms_check_integrity(ses.cache)
 
     ms_per_step = (t1 - t0) * 1e3 / steps
-    gbps = state["kv_bytes"] / (t1 - t0) / 1e9
+    catch_up()
     lengths = np.asarray(ses.lengths(ids), dtype=np.int64)
     assert np.array_equal(lengths, cur_len), "host copy of the lengths drifted from the cache's"
-    per_launch_bytes = int(round(state["kv_bytes"] / state["attn_calls"]))   # mean over the timed launches
+    # the bytes every timed launch had to move, from the lengths step by step (replayed from the device's accept log)
+    log = acc_log.cpu().numpy().astype(np.int64)
+    lens = np.asarray(sh.lengths, dtype=np.int64)
+    kv_bytes, accepted = 0.0, 0
+    for i in range(total_steps):
+        if i >= warmup:
+            kv_bytes += NL * algorithmic_bytes(lens)
+            accepted += int(log[i].sum())
+        lens = lens + log[i]
+        for after, delta in state["compacted_after"]:
+            if after == i + 1:
+                lens = lens + delta
+    assert np.array_equal(lens, cur_len), "replayed lengths differ from the cache's"
+    gbps = kv_bytes / (t1 - t0) / 1e9
+    per_launch_bytes = int(round(kv_bytes / (steps * NL)))   # mean over the timed launches
     kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else float("nan")
     achieved = per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9 if kern_ms else float("nan")
 
@@ -285,13 +334,15 @@ def attention_workload(args, sh, steps, warmup, want_cpu, ragged):
                         f"_layers{NL}_q{Hq}_kv{Hkv}_d{D}_verify{nv}_foresight{nf}",
             "batch": B, "mean_kv_len": round(float(np.mean(lengths)), 1), "layers": NL,
             "step": f"{NL}-layer attention + accept + commit, compaction 56->8 every 14 steps",
+            "commit": "host-side: accept lengths read back, the stream synchronised every step" if host_commit else
+                      "device-side: the kernel reads the accept lengths; the host synchronises only for a compaction",
             "attention_tile_assignment": "fixed (bit-reproducible)" if args.deterministic else
                                          "first come, first served (reproducible to rounding)",
         },
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "query_tokens_per_s": round(B * nq * steps / (t1 - t0), 1),
-        "decode_tokens_per_s": round(state["accepted"] / (t1 - t0), 1),
-        "accepted_per_step_per_seq": round(state["accepted"] / steps / B, 3),
+        "decode_tokens_per_s": round(accepted / (t1 - t0), 1),
+        "accepted_per_step_per_seq": round(accepted / steps / B, 3),
         "roofline": {
             "kernel": "pv_attn_mfma_stream",
             "bound": "hbm",

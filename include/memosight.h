@@ -130,6 +130,30 @@ int ms_append_kv(ms_cache* cache, int B, const int* seq_ids, const int* n_tok, c
 int ms_commit_accepted(ms_cache* cache, int B, const int* seq_ids, const int* accept_len, int n_q,
                        const void* k_new, const void* v_new, const int* pos_ids, void* stream);
 
+/* ms_commit_accepted with the accept lengths read on the device (Algorithm 1, "S <- S (+) A", without
+ * the host learning how many tokens were accepted): the step's stream never has to be synchronised.
+ *   accept_len : DEVICE [B] int32 (e.g. what ms_accept wrote); values are clamped to [0, n_max]
+ *   n_max      : the most rows a sequence can keep (the verify block's size), 1 <= n_max <= min(n_q, 16)
+ *   first_pid  : DEVICE [B] int32 or NULL; first_pid[b] += accept_len[b] (the next step's first
+ *                position id, see ms_step_positions_device)
+ * Same rows, same pages and same page order as ms_commit_accepted with the same accept lengths: the
+ * kernel takes pages from an ascending list of the free pages in the order the host would (sequences
+ * in argument order, the lowest free page whenever a row's index is a multiple of 16).  Afterwards
+ * the host's lengths and page tables lag behind the device's: ms_predict_verify_attention and further
+ * device-side commits go by the device's and need no catching up; every other call that reads or
+ * changes lengths, page tables or the free set (ms_seq_len, ms_seq_page_table, ms_append_kv,
+ * ms_compact_segment, ms_seq_free, ...) first synchronises the stream of the outstanding commits and
+ * brings the host up to date (ms_cache_sync does only that).  The call needs room for the worst case
+ * (n_max rows for every sequence: one page each): MS_ERR_OOM_PAGES otherwise, nothing changes.  A
+ * sequence id may appear once per call; all outstanding device-side commits must be on one stream. */
+int ms_commit_accepted_device(ms_cache* cache, int B, const int* seq_ids, const int* accept_len,
+                              int n_q, int n_max, const void* k_new, const void* v_new,
+                              const int* pos_ids, int* first_pid, void* stream);
+
+/* Brings the host's lengths and page tables up to date with outstanding device-side commits
+ * (synchronises their stream).  A no-op when there are none. */
+int ms_cache_sync(ms_cache* cache);
+
 /* ---- UpdateCache : evict a finished step, keep its memory tokens -------------------------- */
 
 /* For b = 0..B-1 in order: logical rows [seg_begin[b], seg_begin[b] + seg_len[b]) of sequence
@@ -360,6 +384,11 @@ int ms_foresight_pids(int last_prefix_pid, int d, int* out, int cap);
  * (Section 2.1.1; the position rule of Section 2.2 with the verify block as the prefix).
  * Returns the number of entries written, negative on bad input. */
 int ms_step_positions(int B, const int* first_pid, int n_verify, int n_foresight, int* out);
+/* ms_step_positions from a DEVICE array of first position ids into a DEVICE array out[B][n_verify +
+ * n_foresight]: with ms_commit_accepted_device advancing first_pid, a decode loop needs no host
+ * round trip for its position ids.  Asynchronous on `stream`. */
+int ms_step_positions_device(int B, const int* first_pid, int n_verify, int n_foresight, int* out,
+                             void* stream);
 /* Default ctx_new row for n_verify + n_foresight queries: verify token i sees the i verify tokens
  * before it, every foresight token sees the whole verify block and, like every query, itself
  * (Section 2.1.1; Section 2.3 "MTP Attention"). */

@@ -60,6 +60,9 @@ _SIGS = {
     "ms_seq_free": (_I, [_P, _I]),
     "ms_append_kv": (_I, [_P, _I, _IP, _IP, _P, _P, _P, _I, _P]),
     "ms_commit_accepted": (_I, [_P, _I, _IP, _IP, _I, _P, _P, _P, _P]),
+    "ms_commit_accepted_device": (_I, [_P, _I, _IP, _P, _I, _I, _P, _P, _P, _P, _P]),
+    "ms_cache_sync": (_I, [_P]),
+    "ms_step_positions_device": (_I, [_I, _P, _I, _I, _P, _P]),
     "ms_compact_segment": (_I, [_P, _I, _IP, _IP, _IP, _IP, _P, _P, _P, _I, _P, _SZ, _P]),
     "ms_compact_workspace_bytes": (_SZ, [_P, _I, _IP, _IP, _IP]),
     "ms_predict_verify_attention": (_I, [_P, _I, _I, _IP, _I, _I, _P, _P, _P, _P, _P, _F, _P, _P, _SZ, _P]),
@@ -221,6 +224,28 @@ def ms_commit_accepted(cache, seq_ids, accept_len, n_q, k_new, v_new, pos_ids, s
     _check(lib.ms_commit_accepted(cache, len(seq_ids), _ints(seq_ids), _ints(accept_len), n_q,
                                   _sized(cache, k_new, "k_new", n), _sized(cache, v_new, "v_new", n),
                                   _sized(cache, pos_ids, "pos_ids", len(seq_ids) * n_q, 4), _stream(stream)))
+
+
+def ms_commit_accepted_device(cache, seq_ids, accept_len, n_q, n_max, k_new, v_new, pos_ids, first_pid=None, stream=None) -> None:
+    """accept_len (and first_pid, if given): int32 device tensors [B]."""
+    L, _, hkv, d, _ = _DESC[cache]
+    B = len(seq_ids)
+    n = L * B * n_q * hkv * d
+    _check(lib.ms_commit_accepted_device(cache, B, _ints(seq_ids), _sized(cache, accept_len, "accept_len", B, 4), n_q, n_max,
+                                         _sized(cache, k_new, "k_new", n), _sized(cache, v_new, "v_new", n),
+                                         _sized(cache, pos_ids, "pos_ids", B * n_q, 4), _sized(cache, first_pid, "first_pid", B, 4),
+                                         _stream(stream)))
+
+
+def ms_cache_sync(cache) -> None:
+    _check(lib.ms_cache_sync(cache))
+
+
+def ms_step_positions_device(first_pid, n_verify: int, n_foresight: int, out, stream=None) -> None:
+    """first_pid: int32 device tensor [B]; out: int32 device tensor [B, n_verify + n_foresight]."""
+    B = first_pid.numel()
+    _check(lib.ms_step_positions_device(B, _sized(None, first_pid, "first_pid", B, 4), n_verify, n_foresight,
+                                        _sized(None, out, "out", B * (n_verify + n_foresight), 4), _stream(stream)))
 
 
 def ms_compact_workspace_bytes(cache, seq_ids, seg_begin, seg_len) -> int:

@@ -10,8 +10,8 @@ namespace ms {
 constexpr int kMaxRowwaveSplits = 16;
 constexpr int kMaxMfmaItems = 256;   // stream-kernel workgroups per KV head
 
-// Per-call sequence ids and cache lengths, passed by value in the kernel argument block so that a
-// launch sees exactly the host state of the moment it was issued.
+// Per-call sequence ids and the cache lengths the host knows (lower bounds while device-side commits
+// are outstanding), passed by value in the kernel argument block.
 struct BatchMeta {
     int seq[MS_MAX_BATCH];
     int len[MS_MAX_BATCH];
@@ -20,6 +20,7 @@ struct BatchMeta {
 struct AttnArgs {
     const void* pool_layer;  // first element of this layer's pages
     const int* d_pt;         // device page tables [max_seqs][max_pages]
+    const int* d_len;        // device lengths [max_seqs]: what the kernels go by (the host's may lag behind device-side commits)
     const float* inv_freq;   // [head_dim / 2]
     const void* q;
     const void* k_new;

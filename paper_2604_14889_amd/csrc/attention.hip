@@ -59,7 +59,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(64) void pv_attn_rowwave(AttnArgs a, BatchMeta bm) {
     const int sp = blockIdx.x, row = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
     const int i = row / a.n_q_heads, h = row % a.n_q_heads, g = h / a.group;
-    const int seq = bm.seq[b], L = bm.len[b];
+    const int seq = bm.seq[b], L = a.d_len[seq];
     const int* pt = a.d_pt + (size_t)seq * a.max_pages;
     const T* pool = (const T*)a.pool_layer;
     constexpr int H2 = D / 2;
@@ -83,7 +83,9 @@ __global__ __launch_bounds__(64) void pv_attn_rowwave(AttnArgs a, BatchMeta bm) 
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
     const int t_begin = sp * a.chunk;
-    const int t_end = min(L, t_begin + a.chunk);
+    // (the chunks were cut from the lengths the host knew; rows committed on the device since then
+    // fall to the last split)
+    const int t_end = sp == a.n_splits - 1 ? L : min(L, t_begin + a.chunk);
     for (int t0 = t_begin; t0 < t_end; t0 += 64) {
         const int t = t0 + lane;
         const bool valid = t < t_end;
@@ -289,6 +291,10 @@ extern "C" int ms_predict_verify_attention(ms_cache* c, int layer, int B, const 
         MS_FAIL(MS_ERR_WORKSPACE, "ms_predict_verify_attention: workspace needs %zu bytes, has %zu", need,
                 workspace ? ws_bytes : (size_t)0);
     if (((uintptr_t)workspace & 255) != 0) MS_FAIL(MS_ERR_WORKSPACE, "ms_predict_verify_attention: workspace not 256-byte aligned");
+    if (!c->pending_pt.empty()) {   // lengths of sequences created or freed since the last call with a stream
+        int rc = flush_page_table_patches(c, stream);
+        if (rc != MS_OK) return rc;
+    }
     BatchMeta bm;
     int max_len = 0;
     for (int b = 0; b < B; ++b) {
@@ -301,6 +307,7 @@ extern "C" int ms_predict_verify_attention(ms_cache* c, int layer, int B, const 
     AttnArgs a;
     a.pool_layer = (const char*)c->d.pool + (size_t)layer * c->layer_elems * c->esize;
     a.d_pt = c->d_pt;
+    a.d_len = c->d_len;
     a.inv_freq = c->d_inv_freq;
     a.q = q;
     a.k_new = k_new;

@@ -98,6 +98,7 @@ struct Seg {
 struct MfmaArgs {
     const uint16_t* pool_layer;
     const int* d_pt;
+    const int* d_len;       // [max_seqs] lengths on the device: what the kernel goes by
     const float* inv_freq;
     const uint16_t* q;
     const uint16_t* k_new;
@@ -481,12 +482,21 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
     for (int si = seg_begin; si < seg_end; ++si) {
         const Seg* sp = si == seg_begin ? a.item_first + item : a.segs + si;
         const int sg_b = uniform_load(&sp->b), sg_t0 = uniform_load(&sp->t0), sg_part = uniform_load(&sp->part);
-        const int* pt = a.d_pt + (size_t)uniform_load(&sp->seq) * a.max_pages;
-        const int last_page = (uniform_load(&sp->len) - 1) >> 4;
-        const int n_tok = uniform_load(&sp->t1) - sg_t0;
+        const int sg_seq = uniform_load(&sp->seq);
+        const int* pt = a.d_pt + (size_t)sg_seq * a.max_pages;
+        // The plan was cut from the lengths the host knew.  Rows committed on the device since then
+        // (the host has not been told how many) belong to the sequence's last segment, the one that
+        // ended at the length the plan knew: it runs to the length the device holds.
+        const int len_plan = uniform_load(&sp->len), t1_plan = uniform_load(&sp->t1);
+        const int len_dev = uniform_load(a.d_len + sg_seq);
+        const int last_page = (len_dev - 1) >> 4;
+        const int n_tok = (t1_plan == len_plan ? len_dev : t1_plan) - sg_t0;
         const int n_tiles = (n_tok + kTile - 1) / kTile;
         const bool first_seg = sg_t0 == 0;   // this workgroup also runs the sequence's in-flight tile
         int pa = uniform_load(&sp->pages[2 * w]), pb = uniform_load(&sp->pages[2 * w + 1]);
+        // the record's page ids hold for tiles below the last page the plan knew; a first tile that
+        // reaches past it is looked up in the page table (written by the device-side commit)
+        if (len_dev != len_plan && (sg_t0 >> 4) + 2 * w + 1 > ((len_plan - 1) >> 4)) tile_pages(pt, w, n_tiles, sg_t0, last_page, pa, pb);
 
         // ---- set-up loads.  Order matters: waiting for a load also waits for every load issued
         // before it, so the small loads the Q rotation needs go first and this wave's first tile
@@ -974,6 +984,7 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     MfmaArgs a;
     a.pool_layer = (const uint16_t*)ga.pool_layer;
     a.d_pt = ga.d_pt;
+    a.d_len = ga.d_len;
     a.inv_freq = ga.inv_freq;
     a.q = (const uint16_t*)ga.q;
     a.k_new = (const uint16_t*)ga.k_new;

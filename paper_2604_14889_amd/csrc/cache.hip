@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <iterator>
 #include <new>
 
 #include "attention.h"
@@ -80,16 +81,21 @@ int StageRing::upload_to(void* dst, const void* src, size_t bytes, hipStream_t s
 // kernels
 // ---------------------------------------------------------------------------------------------
 
-// Writes (seq, index, page) triples into the device page-table mirror.
-__global__ void patch_page_table(int* __restrict__ d_pt, const int* __restrict__ triples, int n,
+// Writes (seq, index, page) triples into the device page-table mirror; a triple with index -1
+// carries the sequence's new length instead.
+__global__ void patch_page_table(int* __restrict__ d_pt, int* __restrict__ d_len, const int* __restrict__ triples, int n,
                                  int max_pages) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) d_pt[(size_t)triples[3 * i] * max_pages + triples[3 * i + 1]] = triples[3 * i + 2];
+    if (i >= n) return;
+    const int seq = triples[3 * i], idx = triples[3 * i + 1], val = triples[3 * i + 2];
+    if (idx < 0) d_len[seq] = val;
+    else d_pt[(size_t)seq * max_pages + idx] = val;
 }
 
 struct ScatterArgs {
     void* pool;
     const int* d_pt;
+    int* d_len;
     const float* inv_freq;
     const RowDesc* desc;
     int n_seq;
@@ -155,7 +161,7 @@ __global__ __launch_bounds__(256) void kv_scatter(ScatterArgs a) {
 // call's patches first (the mirror does not hold them yet) and in the mirror otherwise; workgroup
 // (0, 0) writes the patches into the mirror for the launches that follow.
 constexpr int kInlineSeqs = 64;
-constexpr int kInlinePatches = 128;
+constexpr int kInlinePatches = 160;
 struct InlineTables {
     RowDesc desc[kInlineSeqs];
     int patch[3 * kInlinePatches];
@@ -175,8 +181,10 @@ __global__ __launch_bounds__(256) void kv_scatter_inline(ScatterArgs a, InlineTa
         if (tb.patch[3 * i] == de.seq && tb.patch[3 * i + 1] == t / MS_PAGE_SIZE) page = tb.patch[3 * i + 2];
     if (page < 0) page = a.d_pt[(size_t)de.seq * a.max_pages + t / MS_PAGE_SIZE];
     if (r == 0 && layer == 0)
-        for (int i = threadIdx.x; i < tb.n_patch; i += blockDim.x)
-            const_cast<int*>(a.d_pt)[(size_t)tb.patch[3 * i] * a.max_pages + tb.patch[3 * i + 1]] = tb.patch[3 * i + 2];
+        for (int i = threadIdx.x; i < tb.n_patch; i += blockDim.x) {
+            if (tb.patch[3 * i + 1] < 0) a.d_len[tb.patch[3 * i]] = tb.patch[3 * i + 2];     // a sequence's new length
+            else const_cast<int*>(a.d_pt)[(size_t)tb.patch[3 * i] * a.max_pages + tb.patch[3 * i + 1]] = tb.patch[3 * i + 2];
+        }
     const int slot = t % MS_PAGE_SIZE;
     T* pool = (T*)a.pool + (size_t)layer * a.layer_elems + (size_t)page * a.page_elems;
     const T* ks = (const T*)a.k + src_row * a.n_kv_heads * D;
@@ -223,6 +231,132 @@ __global__ __launch_bounds__(256) void kv_gather(ScatterArgs a) {
     }
 }
 
+// ---- commit with the accept lengths read on the device ------------------------------------------
+//
+// The host does not know how many rows each sequence keeps, so it cannot name pages: it hands over
+// an ascending list of free pages, and the kernel gives them out in the order the host would (the
+// sequences in argument order, a page whenever a row's index is a multiple of 16, always the lowest
+// free one).  state[0] counts the list entries used so far; arrival counters tell when every
+// workgroup has read the lengths, and the last one to arrive writes the new lengths, the new
+// page-table entries and, per page taken, the sequence that took it (for the host to catch up later).
+struct CommitArgs {
+    void* pool;
+    int* d_pt;
+    int* d_len;
+    const float* inv_freq;
+    const int* d_free;
+    int* state;
+    const int* accept_len;   // device [B]
+    int* first_pid;          // device [B] or null: advanced by the accepted count
+    const void* k;
+    const void* v;
+    const int* pos;
+    int B, n_q, n_max, n_kv_heads, max_pages;
+    long page_elems, layer_elems, buf_layer_rows;
+};
+struct SeqIds {
+    int seq[MS_MAX_BATCH];
+};
+
+__device__ __forceinline__ int clamp_accept(int a, int n_max) { return a < 0 ? 0 : (a > n_max ? n_max : a); }
+// pages a sequence of length len takes when it grows by acc rows
+__device__ __forceinline__ int pages_taken(int len, int acc) { return ((len + acc + MS_PAGE_SIZE - 1) >> 4) - ((len + MS_PAGE_SIZE - 1) >> 4); }
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void kv_commit_device(CommitArgs a, SeqIds ids) {
+    __shared__ int red[8];
+    const int r = blockIdx.x, layer = blockIdx.y, tid = threadIdx.x;
+    const int b = r / a.n_max, j = r % a.n_max;
+    // pages taken by the sequences listed before this one
+    int mine = 0;
+    for (int bb = tid; bb < b; bb += 256) mine += pages_taken(a.d_len[ids.seq[bb]], clamp_accept(a.accept_len[bb], a.n_max));
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o, 64);
+    if ((tid & 63) == 0) red[tid >> 6] = mine;
+    const int seq = ids.seq[b];
+    const int len0 = a.d_len[seq], acc = clamp_accept(a.accept_len[b], a.n_max), cursor = a.state[0];
+    __syncthreads();
+    const int rank = red[0] + red[1] + red[2] + red[3];
+    if (j < acc) {
+        const int t = len0 + j, pi = t >> 4, had = (len0 + MS_PAGE_SIZE - 1) >> 4;
+        const int page = pi < had ? a.d_pt[(size_t)seq * a.max_pages + pi] : a.d_free[cursor + rank + (pi - had)];
+        const int slot = t & (MS_PAGE_SIZE - 1);
+        const long src_row = (long)layer * a.buf_layer_rows + (long)b * a.n_q + j;
+        T* pool = (T*)a.pool + (size_t)layer * a.layer_elems + (size_t)page * a.page_elems;
+        const T* ks = (const T*)a.k + src_row * a.n_kv_heads * D;
+        const T* vs = (const T*)a.v + src_row * a.n_kv_heads * D;
+        const float posf = (float)a.pos[b * a.n_q + j];
+        constexpr int H2 = D / 2;
+        for (int e = tid; e < a.n_kv_heads * H2; e += 256) {
+            const int g = e / H2, i = e % H2;
+            const float x0 = to_float(ks[g * D + i]), x1 = to_float(ks[g * D + i + H2]);
+            float sn, cs;
+            sincosf(posf * a.inv_freq[i], &sn, &cs);
+            T* kd = pool + ((size_t)g * 2 + 0) * MS_PAGE_SIZE * D + slot * D;
+            T* vd = pool + ((size_t)g * 2 + 1) * MS_PAGE_SIZE * D + slot * D;
+            kd[i] = from_float<T>(x0 * cs - x1 * sn);
+            kd[i + H2] = from_float<T>(x1 * cs + x0 * sn);
+            vd[i] = vs[g * D + i];
+            vd[i + H2] = vs[g * D + i + H2];
+        }
+    }
+    // every thread has used the lengths and the list position it read: count this workgroup in.
+    // Two levels (a counter per layer, 256 bytes apart, then one over the layers): thousands of
+    // arrivals at a single address would take tens of microseconds.
+    __syncthreads();
+    if (tid == 0) {
+        int* layer_ctr = a.state + 2 + kFreeListCap + 64 * layer;
+        int last = 0;
+        if (__hip_atomic_fetch_add(layer_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1) {
+            __hip_atomic_store(layer_ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            last = __hip_atomic_fetch_add(a.state + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.y - 1;
+        }
+        red[4] = last;
+    }
+    __syncthreads();
+    if (!red[4]) return;
+    // ---- the last workgroup: thread bb brings sequence bb of the call up to date ----
+    int len_b = 0, acc_b = 0, take = 0, seq_b = 0;
+    if (tid < a.B) {
+        seq_b = ids.seq[tid];
+        len_b = a.d_len[seq_b];
+        acc_b = clamp_accept(a.accept_len[tid], a.n_max);
+        take = pages_taken(len_b, acc_b);
+    }
+    int incl = take;   // inclusive scan over the 256 threads: within waves, then over the waves' totals
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o, 64);
+        if ((tid & 63) >= o) incl += up;
+    }
+    __syncthreads();
+    if ((tid & 63) == 63) red[tid >> 6] = incl;
+    __syncthreads();
+    int before = incl - take;
+    for (int w = 0; w < (tid >> 6); ++w) before += red[w];
+    if (tid < a.B) {
+        const int had = (len_b + MS_PAGE_SIZE - 1) >> 4;
+        for (int k = 0; k < take; ++k) {
+            const int at = cursor + before + k;
+            a.d_pt[(size_t)seq_b * a.max_pages + had + k] = a.d_free[at];
+            a.state[2 + at] = seq_b;
+        }
+        a.d_len[seq_b] = len_b + acc_b;
+        if (a.first_pid) a.first_pid[tid] += acc_b;
+    }
+    if (tid == 255) {   // holds the grand total
+        a.state[0] = cursor + before + take;
+        __hip_atomic_store(a.state + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// pos[b][i] = first_pid[b] + i: the verify block's consecutive position ids followed by the
+// foresight tokens' (Section 2.1.1), from a device array of first position ids.
+__global__ void step_positions_device(int B, const int* __restrict__ first_pid, int n_q, int* __restrict__ out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < B * n_q) out[i] = first_pid[i / n_q] + i % n_q;
+}
+
 // ---------------------------------------------------------------------------------------------
 // host helpers
 // ---------------------------------------------------------------------------------------------
@@ -243,13 +377,48 @@ int flush_page_table_patches(ms_cache* c, hipStream_t stream) {
         if (rc != MS_OK) return rc;
         c->launches++;
         hipLaunchKernelGGL(patch_page_table, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, stream,
-                           c->d_pt, (const int*)dev, (int)cnt, c->d.max_pages_per_seq);
+                           c->d_pt, c->d_len, (const int*)dev, (int)cnt, c->d.max_pages_per_seq);
         MS_HIP_TRY(hipGetLastError());
         done += cnt;
     }
     c->pending_pt.clear();
     return MS_OK;
 }
+
+int reconcile(ms_cache* c) {
+    if (!c->deferred) return MS_OK;
+    MS_HIP_TRY(hipStreamSynchronize(c->deferred_stream));
+    int used = 0;
+    MS_HIP_TRY(hipMemcpy(&used, c->d_commit_state, sizeof(int), hipMemcpyDeviceToHost));
+    if (used < 0 || used > (int)c->free_list.size()) MS_FAIL(MS_ERR_HIP, "device-side commit state is corrupt (%d pages taken of %zu listed)", used, c->free_list.size());
+    std::vector<int> who(used), lens(c->d.max_seqs);
+    if (used > 0) MS_HIP_TRY(hipMemcpy(who.data(), c->d_commit_state + 2, used * sizeof(int), hipMemcpyDeviceToHost));
+    MS_HIP_TRY(hipMemcpy(lens.data(), c->d_len, lens.size() * sizeof(int), hipMemcpyDeviceToHost));
+    for (int k = 0; k < used; ++k) {
+        const int seq = who[k], page = c->free_list[k];
+        if (seq < 0 || seq >= c->d.max_seqs || !c->live[seq] || !c->free_pages.count(page))
+            MS_FAIL(MS_ERR_HIP, "device-side commit state is corrupt (page %d to sequence %d)", page, seq);
+        c->free_pages.erase(page);
+        c->pt[seq].push_back(page);
+    }
+    for (int s = 0; s < c->d.max_seqs; ++s)
+        if (c->live[s]) c->len[s] = lens[s];
+    const int in_use = c->d.n_pages - (int)c->free_pages.size();
+    if (in_use > c->peak_pages) c->peak_pages = in_use;
+    c->pending_growth.assign(c->d.max_seqs, 0);
+    c->reserved_pages = 0;
+    c->free_list_valid = false;
+    c->deferred = false;
+    c->version++;
+    return MS_OK;
+}
+
+#define MS_RECONCILE(c)                      \
+    do {                                     \
+        int rc_ = ::ms::reconcile(c);        \
+        if (rc_ != MS_OK) return rc_;        \
+        (c)->free_list_valid = false;        \
+    } while (0)
 
 static int take_page(ms_cache* c, int seq) {
     c->version++;
@@ -264,6 +433,19 @@ static int take_page(ms_cache* c, int seq) {
     return page;
 }
 
+// Queues the sequence's current length for the device copy of the lengths.
+static void note_len(ms_cache* c, int seq) {
+    // one entry per sequence: the patch kernel writes the entries of a batch in no particular order
+    for (size_t i = 0; i + 2 < c->pending_pt.size(); i += 3)
+        if (c->pending_pt[i] == seq && c->pending_pt[i + 1] == -1) {
+            c->pending_pt[i + 2] = c->len[seq];
+            return;
+        }
+    c->pending_pt.push_back(seq);
+    c->pending_pt.push_back(-1);
+    c->pending_pt.push_back(c->len[seq]);
+}
+
 // Grows `seq` by n rows (pages first-fit lowest); the caller has verified capacity.
 static void grow(ms_cache* c, int seq, int n) {
     c->version++;
@@ -271,6 +453,7 @@ static void grow(ms_cache* c, int seq, int n) {
         if (c->len[seq] % MS_PAGE_SIZE == 0) take_page(c, seq);
         c->len[seq]++;
     }
+    if (n > 0) note_len(c, seq);
 }
 
 static inline int pages_for(long n) { return (int)((n + MS_PAGE_SIZE - 1) / MS_PAGE_SIZE); }
@@ -292,6 +475,7 @@ static int launch_rows(ms_cache* c, bool gather, const std::vector<RowDesc>& des
     ScatterArgs a;
     a.pool = c->d.pool;
     a.d_pt = c->d_pt;
+    a.d_len = c->d_len;
     a.inv_freq = c->d_inv_freq;
     a.desc = (const RowDesc*)dev;
     a.n_seq = (int)desc.size();
@@ -338,6 +522,7 @@ static int patch_and_scatter(ms_cache* c, const std::vector<RowDesc>& desc, int 
     ScatterArgs a;
     a.pool = c->d.pool;
     a.d_pt = c->d_pt;
+    a.d_len = c->d_len;
     a.inv_freq = c->d_inv_freq;
     a.desc = nullptr;
     a.n_seq = (int)desc.size();
@@ -424,6 +609,14 @@ int ms_cache_create(const ms_cache_desc* desc, ms_cache** out) {
         set_error("allocating the page-table mirror (%zu bytes) failed", pt_bytes);
         return fail(MS_ERR_HIP);
     }
+    const size_t len_bytes = (size_t)desc->max_seqs * sizeof(int), state_bytes = (size_t)(2 + kFreeListCap + 64 * desc->n_layers) * sizeof(int);
+    if (hipMalloc((void**)&c->d_len, len_bytes) != hipSuccess || hipMemset(c->d_len, 0, len_bytes) != hipSuccess ||
+        hipMalloc((void**)&c->d_free, (size_t)kFreeListCap * sizeof(int)) != hipSuccess ||
+        hipMalloc((void**)&c->d_commit_state, state_bytes) != hipSuccess || hipMemset(c->d_commit_state, 0, state_bytes) != hipSuccess) {
+        set_error("allocating the device-side lengths and free-page list failed");
+        return fail(MS_ERR_HIP);
+    }
+    c->pending_growth.assign(desc->max_seqs, 0);
     // inv_freq_i = float(base^(-2i/D)), evaluated in double and rounded once
     std::vector<float> inv(desc->head_dim / 2);
     for (int i = 0; i < desc->head_dim / 2; ++i)
@@ -464,6 +657,9 @@ int ms_cache_destroy(ms_cache* c) {
     (void)hipDeviceSynchronize();
     c->stage.destroy();
     if (c->d_pt) (void)hipFree(c->d_pt);
+    if (c->d_len) (void)hipFree(c->d_len);
+    if (c->d_free) (void)hipFree(c->d_free);
+    if (c->d_commit_state) (void)hipFree(c->d_commit_state);
     if (c->d_inv_freq) (void)hipFree(c->d_inv_freq);
     if (c->d_plan) (void)hipFree(c->d_plan);
     if (c->d_arrive) (void)hipFree(c->d_arrive);
@@ -476,12 +672,14 @@ int ms_cache_destroy(ms_cache* c) {
 
 int ms_seq_create(ms_cache* c, int* seq_id) {
     if (!c || !seq_id) MS_FAIL(MS_ERR_INVALID, "ms_seq_create: null argument");
+    MS_RECONCILE(c);
     for (int s = 0; s < c->d.max_seqs; ++s)
         if (!c->live[s]) {
             c->version++;
             c->live[s] = 1;
             c->len[s] = 0;
             c->pt[s].clear();
+            note_len(c, s);
             *seq_id = s;
             return MS_OK;
         }
@@ -492,6 +690,7 @@ int ms_seq_import(ms_cache* c, int length, const int* pages, int n_pages, int* s
     if (!c || !seq_id || (n_pages > 0 && !pages)) MS_FAIL(MS_ERR_INVALID, "ms_seq_import: null argument");
     if (length < 0 || n_pages != pages_for(length))
         MS_FAIL(MS_ERR_INVALID, "ms_seq_import: %d pages do not match length %d", n_pages, length);
+    MS_RECONCILE(c);
     if (n_pages > c->d.max_pages_per_seq)
         MS_FAIL(MS_ERR_OOM_PAGES, "ms_seq_import: %d pages exceed max_pages_per_seq %d", n_pages, c->d.max_pages_per_seq);
     std::set<int> seen;
@@ -510,6 +709,7 @@ int ms_seq_import(ms_cache* c, int length, const int* pages, int n_pages, int* s
         c->pt[s].push_back(pages[i]);
     }
     c->len[s] = length;
+    note_len(c, s);
     c->version++;
     int in_use = c->d.n_pages - (int)c->free_pages.size();
     if (in_use > c->peak_pages) c->peak_pages = in_use;
@@ -521,10 +721,12 @@ int ms_seq_free(ms_cache* c, int seq_id) {
     if (!c) MS_FAIL(MS_ERR_INVALID, "ms_seq_free: null cache");
     int rc = check_seq(c, seq_id, "ms_seq_free");
     if (rc != MS_OK) return rc;
+    MS_RECONCILE(c);
     c->version++;
     for (int p : c->pt[seq_id]) c->free_pages.insert(p);
     c->pt[seq_id].clear();
     c->len[seq_id] = 0;
+    note_len(c, seq_id);
     c->live[seq_id] = 0;
     return MS_OK;
 }
@@ -534,6 +736,7 @@ int ms_seq_free(ms_cache* c, int seq_id) {
 static int append_rows(ms_cache* c, const char* what, int B, const int* seq_ids, const int* counts,
                        const std::vector<int>& src_first, long buf_layer_rows, const void* k,
                        const void* v, const int* pos, int rope, hipStream_t stream) {
+    MS_RECONCILE(c);
     long need = 0;
     std::vector<int> extra(c->d.max_seqs, 0);  // a sequence may appear more than once in a call
     for (int b = 0; b < B; ++b) {
@@ -599,8 +802,120 @@ int ms_commit_accepted(ms_cache* c, int B, const int* seq_ids, const int* accept
                        (hipStream_t)stream);
 }
 
+int ms_commit_accepted_device(ms_cache* c, int B, const int* seq_ids, const int* accept_len, int n_q, int n_max,
+                              const void* k_new, const void* v_new, const int* pos_ids, int* first_pid, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!c || B < 0 || (B > 0 && (!seq_ids || !accept_len || !k_new || !v_new || !pos_ids)))
+        MS_FAIL(MS_ERR_INVALID, "ms_commit_accepted_device: null argument");
+    if (B == 0) return MS_OK;
+    if (B > MS_MAX_BATCH) MS_FAIL(MS_ERR_INVALID, "ms_commit_accepted_device: B %d exceeds %d", B, MS_MAX_BATCH);
+    if (n_q < 1 || n_q > MS_MAX_QUERIES || n_max < 1 || n_max > n_q || n_max > MS_PAGE_SIZE)
+        MS_FAIL(MS_ERR_INVALID, "ms_commit_accepted_device: need 1 <= n_max <= min(n_q, %d), n_q <= %d", MS_PAGE_SIZE, MS_MAX_QUERIES);
+    std::vector<char> seen(c->d.max_seqs, 0);
+    for (int b = 0; b < B; ++b) {
+        int rc = check_seq(c, seq_ids[b], "ms_commit_accepted_device");
+        if (rc != MS_OK) return rc;
+        if (seen[seq_ids[b]]) MS_FAIL(MS_ERR_INVALID, "ms_commit_accepted_device: sequence %d is listed twice", seq_ids[b]);
+        seen[seq_ids[b]] = 1;
+    }
+    if (c->deferred && c->deferred_stream != stream) {   // the device-side state is ordered by one stream at a time
+        int rc = reconcile(c);
+        if (rc != MS_OK) return rc;
+    }
+    // Room for the worst case (every sequence keeps n_max rows: at most one more page each).  First
+    // against the bounds the host has; if those do not suffice, against the exact state.
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        bool fits = c->free_list_valid && c->reserved_pages + B <= (int)c->free_list.size();
+        for (int b = 0; b < B && fits; ++b) {
+            const int s = seq_ids[b];
+            fits = pages_for((long)c->len[s] + c->pending_growth[s] + n_max) <= c->d.max_pages_per_seq;
+        }
+        if (fits) break;
+        if (attempt == 1) {
+            for (int b = 0; b < B; ++b)
+                if (pages_for((long)c->len[seq_ids[b]] + n_max) > c->d.max_pages_per_seq)
+                    MS_FAIL(MS_ERR_OOM_PAGES, "ms_commit_accepted_device: sequence %d could need more than max_pages_per_seq %d pages",
+                            seq_ids[b], c->d.max_pages_per_seq);
+            MS_FAIL(MS_ERR_OOM_PAGES, "ms_commit_accepted_device: needs room for %d pages, %zu free", B, c->free_pages.size());
+        }
+        int rc = reconcile(c);
+        if (rc != MS_OK) return rc;
+        rc = flush_page_table_patches(c, stream);
+        if (rc != MS_OK) return rc;
+        // hand the device the lowest free pages in ascending order and start counting from zero
+        c->free_list.assign(c->free_pages.begin(), c->free_pages.size() > (size_t)kFreeListCap
+                                                        ? std::next(c->free_pages.begin(), kFreeListCap) : c->free_pages.end());
+        if (!c->free_list.empty()) {
+            rc = c->stage.upload_to(c->d_free, c->free_list.data(), c->free_list.size() * sizeof(int), stream);
+            if (rc != MS_OK) return rc;
+        }
+        const int zero[2] = {0, 0};
+        rc = c->stage.upload_to(c->d_commit_state, zero, sizeof(zero), stream);
+        if (rc != MS_OK) return rc;
+        c->free_list_valid = true;
+        c->reserved_pages = 0;
+    }
+    int rc = flush_page_table_patches(c, stream);
+    if (rc != MS_OK) return rc;
+    CommitArgs a;
+    a.pool = c->d.pool;
+    a.d_pt = c->d_pt;
+    a.d_len = c->d_len;
+    a.inv_freq = c->d_inv_freq;
+    a.d_free = c->d_free;
+    a.state = c->d_commit_state;
+    a.accept_len = accept_len;
+    a.first_pid = first_pid;
+    a.k = k_new;
+    a.v = v_new;
+    a.pos = pos_ids;
+    a.B = B;
+    a.n_q = n_q;
+    a.n_max = n_max;
+    a.n_kv_heads = c->d.n_kv_heads;
+    a.max_pages = c->d.max_pages_per_seq;
+    a.page_elems = (long)c->page_elems;
+    a.layer_elems = (long)c->layer_elems;
+    a.buf_layer_rows = (long)B * n_q;
+    SeqIds ids;
+    memset(&ids, 0, sizeof(ids));
+    for (int b = 0; b < B; ++b) {
+        ids.seq[b] = seq_ids[b];
+        c->pending_growth[seq_ids[b]] += n_max;
+    }
+    c->reserved_pages += B;
+    c->deferred = true;
+    c->deferred_stream = stream;
+    c->launches++;
+    const dim3 grid((unsigned)(B * n_max), (unsigned)c->d.n_layers);
+    return dispatch(c, [&](auto* tp, auto dc) -> int {
+        using T = std::remove_pointer_t<decltype(tp)>;
+        constexpr int D = decltype(dc)::value;
+        hipLaunchKernelGGL((kv_commit_device<T, D>), grid, dim3(256), 0, stream, a, ids);
+        MS_HIP_TRY(hipGetLastError());
+        return (int)MS_OK;
+    });
+}
+
+int ms_cache_sync(ms_cache* c) {
+    if (!c) MS_FAIL(MS_ERR_INVALID, "ms_cache_sync: null cache");
+    return reconcile(c);
+}
+
+int ms_step_positions_device(int B, const int* first_pid, int n_verify, int n_foresight, int* out, void* stream) {
+    const int n_q = n_verify + n_foresight;
+    if (B < 0 || n_verify < 0 || n_foresight < 0 || n_q < 1) MS_FAIL(MS_ERR_INVALID, "ms_step_positions_device: bad size");
+    if (B == 0) return MS_OK;
+    if (!first_pid || !out) MS_FAIL(MS_ERR_INVALID, "ms_step_positions_device: null argument");
+    hipLaunchKernelGGL(step_positions_device, dim3((unsigned)((B * n_q + 255) / 256)), dim3(256), 0, (hipStream_t)stream, B, first_pid,
+                       n_q, out);
+    MS_HIP_TRY(hipGetLastError());
+    return MS_OK;
+}
+
 size_t ms_compact_workspace_bytes(ms_cache* c, int B, const int* seq_ids, const int* seg_begin, const int* seg_len) {
     if (!c || B < 0 || (B > 0 && (!seq_ids || !seg_begin || !seg_len))) return 0;
+    if (reconcile(c) != MS_OK) return 0;
     std::vector<int> cur(c->len);
     long tail = 0;
     for (int b = 0; b < B; ++b) {
@@ -620,6 +935,7 @@ int ms_compact_segment(ms_cache* c, int B, const int* seq_ids, const int* seg_be
         MS_FAIL(MS_ERR_INVALID, "ms_compact_segment: null argument");
     if (B > MS_MAX_BATCH) MS_FAIL(MS_ERR_INVALID, "ms_compact_segment: B %d exceeds %d", B, MS_MAX_BATCH);
     if (flags != MS_PRE_ROTATED && flags != MS_ROPE_APPLY) MS_FAIL(MS_ERR_INVALID, "ms_compact_segment: bad flags %d", flags);
+    MS_RECONCILE(c);
     // ---- validate everything on a simulated copy of the lengths / page counts ----
     std::vector<int> sim_len(c->len);
     std::vector<int> sim_pages(c->d.max_seqs);
@@ -700,6 +1016,7 @@ int ms_compact_segment(ms_cache* c, int B, const int* seq_ids, const int* seg_be
             tp2 += t;
         }
         grow(c, s, t);
+        note_len(c, s);
     }
     // ---- 3. scatter memory rows (rotated at their UPL position ids), then the saved tails ----
     if (total_tail == 0 && total_mem > 0)
@@ -715,6 +1032,8 @@ int ms_seq_len(ms_cache* c, int seq_id, int* len) {
     if (!c || !len) MS_FAIL(MS_ERR_INVALID, "ms_seq_len: null argument");
     int rc = check_seq(c, seq_id, "ms_seq_len");
     if (rc != MS_OK) return rc;
+    rc = reconcile(c);
+    if (rc != MS_OK) return rc;
     *len = c->len[seq_id];
     return MS_OK;
 }
@@ -723,6 +1042,8 @@ int ms_seq_page_table(ms_cache* c, int seq_id, int* out, int cap, int* n) {
     if (!c || !n || (cap > 0 && !out)) MS_FAIL(MS_ERR_INVALID, "ms_seq_page_table: null argument");
     int rc = check_seq(c, seq_id, "ms_seq_page_table");
     if (rc != MS_OK) return rc;
+    rc = reconcile(c);
+    if (rc != MS_OK) return rc;
     *n = (int)c->pt[seq_id].size();
     for (int i = 0; i < *n && i < cap; ++i) out[i] = c->pt[seq_id][i];
     return MS_OK;
@@ -730,12 +1051,14 @@ int ms_seq_page_table(ms_cache* c, int seq_id, int* out, int cap, int* n) {
 
 int ms_free_page_count(ms_cache* c, int* n) {
     if (!c || !n) MS_FAIL(MS_ERR_INVALID, "ms_free_page_count: null argument");
+    if (int rc = reconcile(c)) return rc;
     *n = (int)c->free_pages.size();
     return MS_OK;
 }
 
 int ms_peak_pages(ms_cache* c, int* n) {
     if (!c || !n) MS_FAIL(MS_ERR_INVALID, "ms_peak_pages: null argument");
+    if (int rc = reconcile(c)) return rc;
     *n = c->peak_pages;
     return MS_OK;
 }
@@ -748,6 +1071,8 @@ int ms_launch_count(ms_cache* c, long long* n) {
 
 int ms_check_integrity(ms_cache* c, void* stream) {
     if (!c) MS_FAIL(MS_ERR_INVALID, "ms_check_integrity: null cache");
+    if (int rc = reconcile(c)) return rc;
+    if (int rc = flush_page_table_patches(c, (hipStream_t)stream)) return rc;   // lengths of sequences created or freed since
     std::vector<char> owner(c->d.n_pages, 0);
     for (int s = 0; s < c->d.max_seqs; ++s) {
         if (!c->live[s]) {
@@ -769,6 +1094,11 @@ int ms_check_integrity(ms_cache* c, void* stream) {
     MS_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
     if (__atomic_load_n(c->h_error, __ATOMIC_RELAXED) != 0)   // left set: the next attention call reports and clears it too
         MS_FAIL(MS_ERR_HIP, "integrity: an attention launch timed out waiting for split-KV partial results");
+    std::vector<int> dev_len(c->d.max_seqs);
+    MS_HIP_TRY(hipMemcpy(dev_len.data(), c->d_len, dev_len.size() * sizeof(int), hipMemcpyDeviceToHost));
+    for (int s = 0; s < c->d.max_seqs; ++s)
+        if (c->live[s] && dev_len[s] != c->len[s])
+            MS_FAIL(MS_ERR_INVALID, "integrity: device copy of sequence %d's length is %d, host has %d", s, dev_len[s], c->len[s]);
     std::vector<int> row(c->d.max_pages_per_seq);
     for (int s = 0; s < c->d.max_seqs; ++s) {
         if (!c->live[s] || c->pt[s].empty()) continue;

@@ -71,6 +71,18 @@ struct ms_cache {
     std::vector<char> live;
     int peak_pages = 0;
     int* d_pt = nullptr;         // device mirror [max_seqs][max_pages_per_seq]
+    int* d_len = nullptr;        // device [max_seqs]: the sequences' lengths as the kernels see them
+    // ---- device-side commits (ms_commit_accepted_device): the kernels take pages from an ordered
+    // list of free pages and advance d_len; the host tables below are stale until reconciled
+    int* d_free = nullptr;       // device [kFreeListCap]: free pages in ascending order, as uploaded at the last reconcile
+    int* d_commit_state = nullptr;  // device: {pages taken from d_free so far, layers arrived}, then [kFreeListCap] the sequence
+                                 // that took each page, in order, then one arrival counter per layer (64 ints apart)
+    std::vector<int> free_list;  // host copy of what d_free holds
+    bool free_list_valid = false;
+    int reserved_pages = 0;      // upper bound of the pages device-side commits may have taken since the last reconcile
+    std::vector<int> pending_growth;   // per sequence: upper bound of the rows added on the device since the last reconcile
+    bool deferred = false;       // device-side commits are outstanding: host lengths / page tables are stale
+    hipStream_t deferred_stream = nullptr;
     float* d_inv_freq = nullptr; // device [head_dim / 2]
     ms::StageRing stage;
     std::vector<int> pending_pt; // (seq, index, page) triples not yet sent to the mirror
@@ -95,8 +107,12 @@ struct ms_cache {
 
 namespace ms {
 
+constexpr int kFreeListCap = 16384;   // entries of the device-side free-page list
+
 // cache.hip
 int flush_page_table_patches(ms_cache* c, hipStream_t stream);
+// Brings the host tables up to date with device-side commits (synchronises their stream); a no-op otherwise.
+int reconcile(ms_cache* c);
 int check_seq(const ms_cache* c, int seq, const char* what);
 
 }  // namespace ms

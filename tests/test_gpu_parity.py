@@ -559,6 +559,141 @@ def test_commit_accepted_appends_only_accepted_verify_rows():
         M.ms_check_integrity(ses.cache)
 
 
+def test_device_side_commit_keeps_pace_with_host_commit_and_oracle():
+    """ms_commit_accepted_device over several steps with no host synchronisation in between: the
+    attention that follows goes by the device's lengths (the host's lag behind), and once the host
+    has caught up its page tables, lengths and free set are the oracle's, and the pool holds the same
+    bits as a twin cache driven through the host-side ms_commit_accepted."""
+    M, S = _mods()
+    rng = W.make_rng(415)
+    L, Hq, Hkv, D, NP, nv, nf = 2, 28, 4, 128, 80, 4, 3
+    nq = nv + nf
+    start = [14, 15, 16, 30, 0, 250, 31]
+    B = len(start)
+    order = [3, 0, 6, 1, 5, 2, 4]                 # argument order differs from id order
+    bf = O.bf16_bits_to_f32
+    dev = S.Session(L, Hq, Hkv, D, NP, M.MS_BF16, 1000000.0, max_seqs=8, max_pages_per_seq=24)
+    host = S.Session(L, Hq, Hkv, D, NP, M.MS_BF16, 1000000.0, max_seqs=8, max_pages_per_seq=24)
+    ora = O.PagedCache(L, Hkv, D, NP, dtype=O.BF16, rope_base=1000000.0, max_seqs=8)
+    with dev, host:
+        ids = [M.ms_seq_create(dev.cache) for _ in range(B)]
+        assert ids == [M.ms_seq_create(host.cache) for _ in range(B)] == [ora.seq_create() for _ in range(B)]
+        n = sum(start)
+        k, v = W.normal_bf16_bits(rng, (L, n, Hkv, D)), W.normal_bf16_bits(rng, (L, n, Hkv, D))
+        pos = np.concatenate([np.arange(1, c + 1) for c in start]).astype(np.int32)
+        for ses in (dev, host):
+            M.ms_append_kv(ses.cache, ids, start, S.to_device(k, M.MS_BF16), S.to_device(v, M.MS_BF16), S.ints_dev(pos))
+        ora.append(ids, start, bf(k), bf(v), pos)
+        sid = [ids[i] for i in order]
+        first_pid = np.asarray([start[i] + 1 for i in order], np.int32)
+        first_d = S.ints_dev(first_pid)
+        pos_d = torch.empty(B, nq, dtype=torch.int32, device="cuda")
+        accepts = [[4, 0, 1, 3, 2, 4, 1], [1, 1, 4, 4, 4, 2, 1], [0, 0, 0, 0, 0, 0, 0], [4, 4, 4, 4, 4, 4, 4], [2, 3, 4, 1, 0, 4, 4],
+                   [4, 4, 4, 4, 4, 4, 4], [3, 4, 4, 2, 4, 4, 4]]
+        for step, acc in enumerate(accepts):
+            kn, vn = W.normal_bf16_bits(rng, (L, B, nq, Hkv, D)), W.normal_bf16_bits(rng, (L, B, nq, Hkv, D))
+            M.ms_step_positions_device(first_d, nv, nf, pos_d)
+            pq = M.ms_step_positions(first_pid, nv, nf)
+            # attention first: it reads the cache as the commits so far left it, the host none the wiser
+            q = W.normal_bf16_bits(rng, (B, nq, Hq, D))
+            got = dev.attention(1, sid, nv, nf, S.to_device(q, M.MS_BF16), S.to_device(kn[1], M.MS_BF16), S.to_device(vn[1], M.MS_BF16), pos_d)
+            want = O.attention(ora, 1, sid, nv, nf, bf(q), bf(kn[1]), bf(vn[1]), pq)
+            check_out(S.to_host_f32(got), want, "bf16", f"step {step}")
+            assert np.array_equal(pos_d.cpu().numpy(), pq)
+            acc_d = S.ints_dev(acc)
+            M.ms_commit_accepted_device(dev.cache, sid, acc_d, nq, nv, S.to_device(kn, M.MS_BF16), S.to_device(vn, M.MS_BF16), pos_d, first_d)
+            M.ms_commit_accepted(host.cache, sid, acc, nq, S.to_device(kn, M.MS_BF16), S.to_device(vn, M.MS_BF16), S.ints_dev(pq).view(B, nq))
+            for b in range(B):
+                ora.append([sid[b]], [acc[b]], bf(kn)[:, b, :acc[b]], bf(vn)[:, b, :acc[b]], pq[b, :acc[b]])
+            first_pid = first_pid + np.asarray(acc, np.int32)
+            if step == 3:        # the host catches up in the middle (any call that needs its tables does)
+                for s_ in ids:
+                    assert M.ms_seq_len(dev.cache, s_) == ora.seq_len[s_]
+        assert np.array_equal(first_d.cpu().numpy(), first_pid)
+        M.ms_cache_sync(dev.cache)
+        for s_ in ids:
+            assert M.ms_seq_page_table(dev.cache, s_) == M.ms_seq_page_table(host.cache, s_) == ora.page_table[s_]
+            assert M.ms_seq_len(dev.cache, s_) == ora.seq_len[s_]
+        assert M.ms_free_page_count(dev.cache) == ora.free_page_count()
+        assert M.ms_peak_pages(dev.cache) == M.ms_peak_pages(host.cache) == ora.peak_pages
+        M.ms_check_integrity(dev.cache)
+        torch.cuda.synchronize()
+        assert torch.equal(dev.pool.view(torch.int16), host.pool.view(torch.int16))     # the same bits as the host-side commit
+        # compaction after device-side commits, then device-side commits again
+        seg = [5, 3]
+        cids = [ids[5], ids[0]]
+        begin = [M.ms_seq_len(dev.cache, s_) - n_ for s_, n_ in zip(cids, seg)]
+        mk, mv = W.normal_bf16_bits(rng, (L, 2, Hkv, D)), W.normal_bf16_bits(rng, (L, 2, Hkv, D))
+        M.ms_compact_segment(dev.cache, cids, begin, seg, [1, 1], S.to_device(mk, M.MS_BF16), S.to_device(mv, M.MS_BF16), S.ints_dev([400, 50]))
+        ora.compact(cids, begin, seg, [1, 1], bf(mk), bf(mv), [400, 50])
+        kn, vn = W.normal_bf16_bits(rng, (L, B, nq, Hkv, D)), W.normal_bf16_bits(rng, (L, B, nq, Hkv, D))
+        acc = [4, 4, 1, 0, 4, 4, 2]
+        M.ms_step_positions_device(first_d, nv, nf, pos_d)
+        M.ms_commit_accepted_device(dev.cache, sid, S.ints_dev(acc), nq, nv, S.to_device(kn, M.MS_BF16), S.to_device(vn, M.MS_BF16), pos_d, first_d)
+        pq = M.ms_step_positions(first_pid, nv, nf)
+        for b in range(B):
+            ora.append([sid[b]], [acc[b]], bf(kn)[:, b, :acc[b]], bf(vn)[:, b, :acc[b]], pq[b, :acc[b]])
+        for s_ in ids:
+            assert M.ms_seq_page_table(dev.cache, s_) == ora.page_table[s_]
+        M.ms_check_integrity(dev.cache)
+
+
+def test_device_side_commit_general_kernel_and_errors():
+    M, S = _mods()
+    rng = W.make_rng(416)
+    L, Hq, Hkv, D, NP, nv, nf = 1, 4, 2, 64, 6, 3, 2
+    nq = nv + nf
+    ses = S.Session(L, Hq, Hkv, D, NP, M.MS_F32, 10000.0, max_seqs=3, max_pages_per_seq=3)
+    ora = O.PagedCache(L, Hkv, D, NP, dtype=O.F32, rope_base=10000.0, max_seqs=3)
+    with ses:
+        ids = [M.ms_seq_create(ses.cache) for _ in range(2)]
+        [ora.seq_create() for _ in range(2)]
+        start = [15, 2]
+        k, v = W.normal_f32(rng, (L, 17, Hkv, D)), W.normal_f32(rng, (L, 17, Hkv, D))
+        pos = np.concatenate([np.arange(1, c + 1) for c in start]).astype(np.int32)
+        M.ms_append_kv(ses.cache, ids, start, S.to_device(k, M.MS_F32), S.to_device(v, M.MS_F32), S.ints_dev(pos))
+        ora.append(ids, start, k, v, pos)
+        first_pid = np.asarray([16, 3], np.int32)
+        first_d = S.ints_dev(first_pid)
+        pos_d = torch.empty(2, nq, dtype=torch.int32, device="cuda")
+        for acc in ([3, 1], [2, 3], [3, 3]):
+            kn, vn = W.normal_f32(rng, (L, 2, nq, Hkv, D)), W.normal_f32(rng, (L, 2, nq, Hkv, D))
+            q = W.normal_f32(rng, (2, nq, Hq, D))
+            M.ms_step_positions_device(first_d, nv, nf, pos_d)
+            pq = M.ms_step_positions(first_pid, nv, nf)
+            got = ses.attention(0, ids, nv, nf, S.to_device(q, M.MS_F32), S.to_device(kn[0], M.MS_F32), S.to_device(vn[0], M.MS_F32), pos_d)
+            check_out(S.to_host_f32(got), O.attention(ora, 0, ids, nv, nf, q, kn[0], vn[0], pq), "f32", "general kernel, lengths on the device")
+            M.ms_commit_accepted_device(ses.cache, ids, S.ints_dev(acc), nq, nv, S.to_device(kn, M.MS_F32), S.to_device(vn, M.MS_F32), pos_d, first_d)
+            for b in range(2):
+                ora.append([ids[b]], [acc[b]], kn[:, b, :acc[b]], vn[:, b, :acc[b]], pq[b, :acc[b]])
+            first_pid = first_pid + np.asarray(acc, np.int32)
+        for s_ in ids:
+            assert M.ms_seq_page_table(ses.cache, s_) == ora.page_table[s_] and M.ms_seq_len(ses.cache, s_) == ora.seq_len[s_]
+        torch.cuda.synchronize()
+        gp = ses.pool_host_f32()
+        for s_ in ids:
+            for t in range(ora.seq_len[s_]):
+                p_, sl = ora.page_table[s_][t // 16], t % 16
+                assert np.abs(gp[0, p_, :, :, sl] - ora.pool[0, p_, :, :, sl]).max() < 3e-6
+        # 23 and 9 rows in 2 + 1 of 6 pages; a third sequence and four more steps use up the worst-case room
+        kn, vn = S.to_device(W.normal_f32(rng, (L, 2, nq, Hkv, D)), M.MS_F32), S.to_device(W.normal_f32(rng, (L, 2, nq, Hkv, D)), M.MS_F32)
+        with pytest.raises(M.MsError) as e:
+            M.ms_commit_accepted_device(ses.cache, [ids[0], ids[0]], S.ints_dev([1, 1]), nq, nv, kn, vn, pos_d)
+        assert e.value.code == M.MS_ERR_INVALID                                        # listed twice
+        with pytest.raises(M.MsError) as e:
+            M.ms_commit_accepted_device(ses.cache, ids, S.ints_dev([1, 1]), nq, nq + 1, kn, vn, pos_d)
+        assert e.value.code == M.MS_ERR_INVALID                                        # n_max above n_q
+        third = M.ms_seq_create(ses.cache)
+        ora.seq_create()
+        k3 = S.to_device(W.normal_f32(rng, (L, 40, Hkv, D)), M.MS_F32)
+        M.ms_append_kv(ses.cache, [third], [40], k3, k3, S.ints_dev(np.arange(40)))    # 3 pages: the pool is full
+        with pytest.raises(M.MsError) as e:
+            M.ms_commit_accepted_device(ses.cache, ids, S.ints_dev([0, 0]), nq, nv, kn, vn, pos_d)
+        assert e.value.code == M.MS_ERR_OOM_PAGES                                      # no room for the worst case
+        assert M.ms_seq_len(ses.cache, ids[0]) == 23 and M.ms_free_page_count(ses.cache) == 0
+        M.ms_check_integrity(ses.cache)
+
+
 # ------------------------------------------------------------------ compaction ---------------
 
 def test_config4_page_tables_batch16_28_layers():
