@@ -59,7 +59,8 @@ def parse():
                     help="attention launches one event pair covers (default: --layers for the attention workload, whose "
                          "layers launch back to back; 1 for decode_step, where other kernels run between them)")
     ap.add_argument("--no-also", action="store_true", help="skip the two extra points (batch 32 x 4096 tokens, ragged batch)")
-    ap.add_argument("--workload", choices=["attention", "decode_step", "compaction"], default="attention",
+    ap.add_argument("--queries", type=int, default=41, help="wide_step: causal queries per sequence (the memory tokens and <o>, or a prompt chunk)")
+    ap.add_argument("--workload", choices=["attention", "decode_step", "compaction", "wide_step"], default="attention",
                     help="attention: the metric's workload (default); compaction: configuration 4 (batch 16, 28 layers, "
                          "256 -> 8 tokens per sequence, then attention over the result); decode_step: the whole model step "
                          "(Qwen2.5-7B shapes, batch 64, 8k cached tokens, 4 verify + 3 foresight) with torch GEMMs around "
@@ -79,6 +80,16 @@ def parse():
     return ap.parse_args()
 
 
+def calibrate_copy(torch, dev, gen):
+    """Plain 1 GiB device copies: what rocprofv3's byte counters read for a known size scales them."""
+    src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0, generator=gen)   # 1 GiB
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -88,6 +99,8 @@ def main():
         return decode_step_bench(args)
     if args.workload == "compaction":
         return compaction_bench(args)
+    if args.workload == "wide_step":
+        return wide_step_bench(args)
     args.batch = args.batch or 32
     import torch
 
@@ -360,18 +373,91 @@ def attention_workload(args, sh, steps, warmup, want_cpu, ragged):
     }
 
     if args.calibrate_copy:
-        src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0, generator=gen)   # 1 GiB
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        calibrate_copy(torch, dev, gen)
     if want_cpu:
         result["cpu_baseline"] = cpu_baseline(args, ses, sh, ids, lengths, q, k_new, v_new, pos_d, out, M, S, W)
     ses.close()
     del ses, q, k_new, v_new, mem_k, mem_v, layer_args
     torch.cuda.empty_cache()
     return result
+
+
+def wide_step_bench(args):
+    """A pass of many causal queries and no foresight tokens over the cache: the memory-token pass that
+    closes a reasoning step (l + 1 queries, Algorithm 1) or a chunk of a prompt.  --queries queries
+    per sequence (up to 64), --batch sequences of --kv cached tokens, one attention call per layer."""
+    import numpy as np
+    import torch
+
+    import workloads as W
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import session as S
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    B, NL, Hq, Hkv, D, nq = args.batch or 8, args.layers, args.q_heads, args.kv_heads, 128, args.queries
+    sh = W.AttnShape("wide", "bf16", B, Hq, Hkv, D, nq, 0, [args.kv] * B, 0.5, 1000000.0, n_layers=NL)
+    rng = W.make_rng(1006, B, NL)
+    page_tables = W.shuffled_page_tables(rng, sh.n_pages, sh.lengths)
+    ses = S.Session(NL, Hq, Hkv, D, sh.n_pages, M.MS_BF16, sh.rope_base, max_seqs=B, max_pages_per_seq=max(len(p) for p in page_tables) + 4)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(W.BASE_SEED + 6)
+    for layer in range(NL):
+        ses.pool[layer].normal_(0.0, sh.sigma, generator=gen)
+    ids = M.int_array([M.ms_seq_import(ses.cache, n, pt) for n, pt in zip(sh.lengths, page_tables)])
+
+    def dev_normal(*shape):
+        return torch.empty(*shape, dtype=torch.bfloat16, device=dev).normal_(0.0, sh.sigma, generator=gen)
+
+    q, k_new, v_new = dev_normal(B, nq, Hq, D), dev_normal(NL, B, nq, Hkv, D), dev_normal(NL, B, nq, Hkv, D)
+    out = torch.empty_like(q)
+    pos_d = S.ints_dev(M.ms_step_positions(np.asarray([3 * n + 1 for n in sh.lengths], np.int32), nq, 0)).view(B, nq)
+    ses.ensure_workspace(B, nq)
+    sh_ = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        for layer in range(NL):
+            ses.attention(layer, ids, nq, 0, q, k_new[layer], v_new[layer], pos_d, None, 0.0, out, sh_)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    n0 = M.ms_launch_count(ses.cache)
+    M.ms_profile_attention(ses.cache, args.steps, NL, NL)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    launches = (M.ms_launch_count(ses.cache) - n0) / (args.steps * NL)
+    if args.calibrate_copy:
+        calibrate_copy(torch, dev, gen)
+    kern_ms = M.ms_profile_read(ses.cache, args.steps)
+    M.ms_profile_attention(ses.cache, 0, 1, 1)
+    lens = np.asarray(sh.lengths, dtype=np.int64)
+    per_call_bytes = int(np.sum(2 * lens * Hkv * D * 2 + 4 * (-(-lens // 16)))) + B * nq * (2 * Hq + 2 * Hkv) * D * 2
+    per_call_flops = 4.0 * float(lens.sum() + B * nq / 2) * Hq * nq * D
+    call_ms = float(np.mean(kern_ms))
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    result = {
+        "metric": f"wide_step_attn_hbm_gbps_b{B}_kv{args.kv}_q{nq}",
+        "value": round(NL * per_call_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"wide_step_batch{B}_kv{args.kv}_layers{NL}_q{Hq}_kv{Hkv}_d{D}_causal_queries{nq}", "batch": B, "layers": NL,
+                   "step": f"{NL} attention calls of {nq} causal queries per sequence"},
+        "kernel_launches_per_call": launches,
+        "call_us": round(call_ms * 1e3, 2),
+        "matrix_core_tflops": round(per_call_flops / (call_ms * 1e-3) / 1e12, 1),
+        "roofline": {"kernel": "pv_attn_mfma_wide" if launches >= 1 and (nq > 16 or nq * (Hq // Hkv) > 64) else "pv_attn_mfma_stream",
+                     "bound": "hbm", "achieved": round(per_call_bytes / (call_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(per_call_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "avg_kernel_ms": round(call_ms, 5), "launches": len(kern_ms) * NL, "launches_per_event_pair": NL,
+                     "algorithmic_bytes_per_launch": per_call_bytes},
+        "cpu_baseline": None,
+    }
+    ses.close()
+    print(json.dumps(result))
 
 
 def compaction_bench(args):

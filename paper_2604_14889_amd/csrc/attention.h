@@ -46,7 +46,7 @@ int static_scratch(int device, void** ptr);
 
 // attention_mfma.hip
 bool mfma_eligible(const ms_cache* c, int n_q);
-size_t mfma_workspace_bytes(const ms_cache* c, int B);
+size_t mfma_workspace_bytes(const ms_cache* c, int B, int n_q);
 int mfma_plan_ints(int B);
 int reset_arrival_counters(ms_cache* c, int published, hipStream_t stream);
 int launch_mfma(ms_cache* c, const AttnArgs& a, const BatchMeta& bm, int B, hipStream_t stream);

@@ -267,7 +267,7 @@ extern "C" int ms_attention_set_deterministic(ms_cache* c, int on) {
 
 extern "C" size_t ms_attention_workspace_bytes(ms_cache* c, int B, int n_q) {
     if (!c || B < 1 || B > MS_MAX_BATCH || n_q < 1 || n_q > MS_MAX_QUERIES) return 0;
-    size_t need = mfma_eligible(c, n_q) ? mfma_workspace_bytes(c, B) : rowwave_workspace_bytes(c, B, n_q);
+    size_t need = mfma_eligible(c, n_q) ? mfma_workspace_bytes(c, B, n_q) : rowwave_workspace_bytes(c, B, n_q);
     return (need + 255) & ~(size_t)255;
 }
 

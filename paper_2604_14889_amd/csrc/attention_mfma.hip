@@ -26,6 +26,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
@@ -59,22 +60,20 @@ constexpr int kPartFloats = 2 * kRows + kRows * kD;  // m[64], l[64], O[128 regs
 // phase (overlays it): per wave 64 accumulator registers (two d blocks of both row blocks) + 4
 // softmax scalars per lane.
 //
-// The kernel comes in two builds.  The decode build takes all of a step's queries in one launch
-// (at most 16 queries, 64 rows).  The wide build (memory-token pass, per-position foresight: up to
-// 64 queries) is launched once per chunk of 64 / group queries; every launch sees all of the
-// step's in-flight keys, in up to two 32-token tiles.
+// This is the decode kernel: all of a step's queries in one launch, at most 16 queries and 64 rows.
+// Wider steps (memory-token pass, prompt chunks, per-position foresight: up to 64 queries) run
+// pv_attn_mfma_wide further down.
 constexpr int kDecodeQueries = 16;
 constexpr int kMergeRegionBytes = (64 + 4) * 64 * 4;                     // 17408
 constexpr int kLdsMerge = kWaves * kMergeRegionBytes;                    // 139264
-template <bool kWide>
 struct Lds {
-    static constexpr int kQueries = kWide ? MS_MAX_QUERIES : kDecodeQueries;   // rows of the cos/sin table
-    static constexpr int kNewTiles = kWide ? (MS_MAX_QUERIES + kTile - 1) / kTile : 1;
+    static constexpr int kQueries = kDecodeQueries;   // rows of the cos/sin table
+    static constexpr int kNewTiles = 1;
     static constexpr int kQ = 0;
     static constexpr int kCs = kQ + kRows * kQRowBytes;                  // 17408
-    static constexpr int kKn = kCs + kQueries * 64 * 8;                  // + 8192 (wide: 32768)
-    static constexpr int kV = kKn + kNewTiles * kTile * kQRowBytes;      // + 8704 (wide: 17408)
-    static constexpr int kStream = kV + kWaves * kVTileBytes;            // + 73728 = 108032 (wide: 141312)
+    static constexpr int kKn = kCs + kQueries * 64 * 8;                  // + 8192
+    static constexpr int kV = kKn + kNewTiles * kTile * kQRowBytes;      // + 8704
+    static constexpr int kStream = kV + kWaves * kVTileBytes;            // + 73728 = 108032
     static constexpr int kFlag = kLdsMerge > kStream ? kLdsMerge : kStream;  // one word: "last arriver"
     static constexpr int kBytes = kFlag + 16;
     static_assert(kBytes <= 160 * 1024, "LDS budget of one compute unit");
@@ -114,7 +113,7 @@ struct MfmaArgs {
     int* error_word;        // host memory the device can write: set when a closing workgroup gave up waiting
     int poll_limit;         // polls of the published counter before a closing workgroup gives up
     int n_q, n_verify, n_q_heads, n_kv_heads, group, max_pages;
-    int q0, n_qc;           // this launch computes queries q0 .. q0 + n_qc (decode build: all of them)
+    int q0, n_qc;           // wide kernel: this launch computes queries q0 .. q0 + n_qc
     long page_elems;
     float scale_log2;       // softmax scale * log2(e)
 };
@@ -448,11 +447,11 @@ __device__ __forceinline__ int claim_tile(int* counter, int lane) {
 // kWide: see the LDS map.  kClaim: the waves of a workgroup take the segment's tiles first come,
 // first served instead of every 8th tile each; this evens out the waves' finishing times, at the
 // price of results that depend on the order the tiles happened to be taken in (rounding only).
-template <bool kWide, bool kClaim, bool kBigPool = false>
+template <bool kClaim, bool kBigPool = false>
 __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    typedef Lds<kWide> L;
-    const int q0 = kWide ? a.q0 : 0, n_qc = kWide ? a.n_qc : a.n_q;
+    typedef Lds L;
+    const int q0 = 0, n_qc = a.n_q;
     const int item = blockIdx.x, g = blockIdx.y;
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -576,9 +575,7 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
         WaveState st;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
-            // wide build: an in-flight tile may be wholly invisible to a row whose state is still
-            // empty; a finite floor keeps 2^(s - m) at zero there instead of 2^(inf - inf)
-            st.m[rb] = kWide ? -1e30f : -INFINITY;
+            st.m[rb] = -INFINITY;
             st.l[rb] = 0.f;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
@@ -593,7 +590,7 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
             int ln = lane;
             asm volatile("" : "+v"(ln));
             const int l16 = ln & 15, l32 = ln & 31, hf = ln >> 5;
-            const int new_tiles = kWide ? (a.n_q + kTile - 1) / kTile : 1;
+            const int new_tiles = 1;
             for (int it = 0; it < new_tiles; ++it) {
 #pragma unroll
                 for (int rr = 0; rr < 8; ++rr) {
@@ -789,6 +786,428 @@ __global__ __launch_bounds__(kThreads) void pv_attn_mfma_stream(MfmaArgs a) {
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Wide steps: more than 16 queries or more than 64 rows per KV head (the memory-token pass of a
+// closed step with its l + 1 causal queries, prompt chunks, per-position foresight).
+//
+// The queries are cut into chunks of 64 / group queries (at most 64 rows) and wave w of a workgroup
+// owns chunk w: its rotated Q rows are its Q^T operand (rows 0 .. 31 in registers, rows 32 .. 63 in
+// a wave-private LDS tile: both in registers do not fit beside the accumulators), its O^T
+// accumulators are its own.  All eight waves walk over the SAME tiles of the share, so a tile leaves HBM once per
+// call however many queries there are: the 512 threads load a tile's K and V rows together (16
+// bytes of each per thread, one tile ahead, through registers) into a double-buffered pair of LDS
+// tiles, one workgroup barrier per tile.  With eight times the arithmetic per byte the stream is
+// bound by the matrix cores and LDS, not by HBM.  No wave shares rows with another, so there is no
+// merge at the end: every wave leaves (or folds) the partial of its own chunk.  The work plan, the
+// tickets and the page handling are the decode kernel's.  Results do not depend on timing.
+// ---------------------------------------------------------------------------------------------
+struct WideLds {
+    static constexpr int kCs = 0;                                   // cos/sin of every query's position id: 32768
+    static constexpr int kKn = kCs + MS_MAX_QUERIES * 64 * 8;       // rotated in-flight keys, two tiles: 17408
+    static constexpr int kQ1 = kKn + 2 * kTile * kQRowBytes;        // every wave's rotated Q rows 32 .. 63: 69632
+    static constexpr int kK = kQ1 + kWaves * kTile * kQRowBytes;    // K tiles, two buffers: 17408
+    static constexpr int kV = kK + 2 * kTile * kQRowBytes;          // V tiles, two buffers: 20480
+    static constexpr int kFlag = kV + 2 * kVTileBytes;
+    static constexpr int kBytes = kFlag + 16;
+    static_assert(kBytes <= 160 * 1024, "LDS budget of one compute unit");
+};
+constexpr int kWideChunks = kWaves;   // chunks per launch: one per wave
+
+// S^T block = K . Q^T with K read from an LDS tile and the Q^T operand held in registers.
+// The K operands are asked for two ahead of their use: one LDS round trip per multiplication would
+// otherwise be all a wave does.
+__device__ __forceinline__ void qk_block_qreg(f32x16_t& s, const char* kbase, const bf16x8_t (&q)[8]) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
+    uint4 ka[8];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) ka[kk] = *reinterpret_cast<const uint4*>(kbase + 32 * kk);
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        if (kk + 2 < 8) ka[kk + 2] = *reinterpret_cast<const uint4*>(kbase + 32 * (kk + 2));
+        __builtin_amdgcn_sched_barrier(0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ka[kk]), q[kk], s, 0, 0, 0);
+    }
+}
+
+// Both operands from LDS (K tile rows, a wave's Q rows), one pair ahead of their use.
+__device__ __forceinline__ void qk_block_lds2(f32x16_t& s, const char* kbase, const char* qbase) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
+    uint4 ka[8], qa[8];
+    ka[0] = *reinterpret_cast<const uint4*>(kbase);
+    qa[0] = *reinterpret_cast<const uint4*>(qbase);
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        if (kk + 1 < 8) {
+            ka[kk + 1] = *reinterpret_cast<const uint4*>(kbase + 32 * (kk + 1));
+            qa[kk + 1] = *reinterpret_cast<const uint4*>(qbase + 32 * (kk + 1));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ka[kk]), __builtin_bit_cast(bf16x8_t, qa[kk]), s, 0, 0, 0);
+    }
+}
+
+// 16 bytes of K and of V of one token of a tile, as one thread loads them.
+struct WideStage {
+    uint4 k, v;
+};
+
+__global__ __launch_bounds__(kThreads) void pv_attn_mfma_wide(MfmaArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    typedef WideLds L;
+    const int item = blockIdx.x, g = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, hf = lane >> 5, l32 = lane & 31, l16 = lane & 15;
+    // this wave's chunk of queries
+    const int per = kRows / a.group;
+    const int cq0 = a.q0 + w * per;
+    const int cq_left = a.q0 + a.n_qc - cq0;
+    const int cn = cq_left < 0 ? 0 : (cq_left < per ? cq_left : per);
+    const int n_rows = cn * a.group;
+    float2* cs_tab = reinterpret_cast<float2*>(smem + L::kCs);
+    const char* pool = reinterpret_cast<const char*>(a.pool_layer);
+    const size_t page_bytes = (size_t)a.page_elems * 2;
+    // a thread's part of a tile: token tid / 16, 16 bytes at d = 8 (tid % 16)
+    const int my_tok = tid >> 4, my_col = tid & 15;
+    const uint32_t off_k = ((uint32_t)g * 2 * MS_PAGE_SIZE * kD + (my_tok & 15) * kD + 8 * my_col) * 2;
+    const uint32_t off_v = off_k + MS_PAGE_SIZE * kD * 2;
+    char* k_store = smem + L::kK + my_tok * kQRowBytes + my_col * 16;
+    char* v_store = smem + L::kV + my_tok * kVRowBytes + my_col * 16;
+    // operand addressing as in the decode kernel
+    const char* k_read = smem + L::kK + l32 * kQRowBytes + 16 * hf;
+    const char* v_read = smem + L::kV + (4 * hf + (l16 >> 2)) * kVRowBytes + (16 * ((lane >> 4) & 1) + 4 * (l16 & 3)) * 2;
+    const float inv_f = a.inv_freq[lane];
+    const int seg_begin = uniform_load(&a.item_first[item].seg_begin), seg_end = uniform_load(&a.item_first[item].seg_end);
+    for (int si = seg_begin; si < seg_end; ++si) {
+        const Seg* sp = si == seg_begin ? a.item_first + item : a.segs + si;
+        const int sg_b = uniform_load(&sp->b), sg_t0 = uniform_load(&sp->t0), sg_part = uniform_load(&sp->part);
+        const int sg_seq = uniform_load(&sp->seq);
+        const int* pt = a.d_pt + (size_t)sg_seq * a.max_pages;
+        const int len_plan = uniform_load(&sp->len), t1_plan = uniform_load(&sp->t1);
+        const int len_dev = uniform_load(a.d_len + sg_seq);     // see the decode kernel: the device's length counts
+        const int last_page = (len_dev - 1) >> 4;
+        const int n_tok = (t1_plan == len_plan ? len_dev : t1_plan) - sg_t0;
+        const int n_tiles = (n_tok + kTile - 1) / kTile;
+        const bool first_seg = sg_t0 == 0;
+
+        // page id of this thread's token of tile T (clamped: loads are unconditional and stay inside the sequence)
+        auto page_of = [&](int T) {
+            const int tc = T < n_tiles ? T : n_tiles - 1;
+            const int pg = (sg_t0 >> 4) + 2 * tc + (my_tok >> 4);
+            return pt[pg < last_page ? pg : last_page];
+        };
+        auto load_stage = [&](int page) {
+            WideStage st_;
+            const char* base = pool + (size_t)(uint32_t)page * page_bytes;
+            st_.k = *reinterpret_cast<const uint4*>(base + off_k);
+            st_.v = load_stream(base + off_v);
+            return st_;
+        };
+
+        // ---- set-up: cos/sin of every query's position id (wave w: queries w, w + 8, ...), this
+        // wave's raw Q rows, and for a sequence's first segment its in-flight keys ----
+        WideStage sa;
+        int pid_c = 0;
+        if (n_tiles > 0) {
+            const int p0 = page_of(0);
+            pid_c = page_of(1);
+            sa = load_stage(p0);
+        }
+        uint4 xq[2][8];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const int row = 32 * rb + l32;
+            const bool live = row < n_rows;
+            const int qi = cq0 + (live ? row / a.group : 0), qh = live ? row % a.group : 0;
+            const uint16_t* qp = a.q + (((size_t)sg_b * a.n_q + (cn > 0 ? qi : 0)) * a.n_q_heads + g * a.group + qh) * kD + 8 * hf;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) xq[rb][kk] = *reinterpret_cast<const uint4*>(qp + 16 * kk);
+        }
+        const int kr = tid >> 3, kc = tid & 7;     // in-flight key kr, rotation pairs 8 kc .. + 8
+        const uint16_t* kp = a.k_new + (((size_t)sg_b * a.n_q + (kr < a.n_q ? kr : 0)) * a.n_kv_heads + g) * kD + 8 * kc;
+        const uint4 k0v = *reinterpret_cast<const uint4*>(kp);
+        const uint4 k1v = *reinterpret_cast<const uint4*>(kp + 64);
+#pragma unroll
+        for (int k = 0; k < MS_MAX_QUERIES / kWaves; ++k)
+            if (w + 8 * k < a.n_q) {
+                float sn, cs;
+                sincos_reduced((float)uniform_load(a.pos + sg_b * a.n_q + w + 8 * k) * inv_f, &sn, &cs);
+                cs_tab[(w + 8 * k) * 64 + lane] = make_float2(cs, sn);
+            }
+        lds_barrier();
+        // rotate: the lane holds elements 16 kk + 8 hf .. + 8 of its row; element i pairs with i + 64
+        bf16x8_t qreg[8];
+        char* q1_row = smem + L::kQ1 + (w * kTile + l32) * kQRowBytes + 16 * hf;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const int row = 32 * rb + l32;
+            const bool live = row < n_rows;
+            const int qi = cq0 + (live ? row / a.group : 0);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const uint32_t w0[4] = {xq[rb][kk].x, xq[rb][kk].y, xq[rb][kk].z, xq[rb][kk].w};
+                const uint32_t w1[4] = {xq[rb][kk + 4].x, xq[rb][kk + 4].y, xq[rb][kk + 4].z, xq[rb][kk + 4].w};
+                uint32_t y0[4], y1[4];
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    float r0[2], r1[2];
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+                        const float x0 = hh ? __uint_as_float(w0[e2] & 0xffff0000u) : __uint_as_float(w0[e2] << 16);
+                        const float x1 = hh ? __uint_as_float(w1[e2] & 0xffff0000u) : __uint_as_float(w1[e2] << 16);
+                        const float2 c = live ? cs_tab[qi * 64 + 16 * kk + 8 * hf + 2 * e2 + hh] : make_float2(0.f, 0.f);
+                        r0[hh] = (x0 * c.x - x1 * c.y) * a.scale_log2;
+                        r1[hh] = (x1 * c.x + x0 * c.y) * a.scale_log2;
+                    }
+                    y0[e2] = pack_bf16x2(r0[0], r0[1]);
+                    y1[e2] = pack_bf16x2(r1[0], r1[1]);
+                }
+                if (rb == 0) {
+                    qreg[kk] = __builtin_bit_cast(bf16x8_t, make_uint4(y0[0], y0[1], y0[2], y0[3]));
+                    qreg[kk + 4] = __builtin_bit_cast(bf16x8_t, make_uint4(y1[0], y1[1], y1[2], y1[3]));
+                } else {
+                    *reinterpret_cast<uint4*>(q1_row + 32 * kk) = make_uint4(y0[0], y0[1], y0[2], y0[3]);
+                    *reinterpret_cast<uint4*>(q1_row + 32 * (kk + 4)) = make_uint4(y1[0], y1[1], y1[2], y1[3]);
+                }
+            }
+        }
+        if (first_seg) {   // the in-flight keys, rotated, as up to two K tiles (rows at and past n_q are zeros)
+            const uint32_t u0[4] = {k0v.x, k0v.y, k0v.z, k0v.w}, u1[4] = {k1v.x, k1v.y, k1v.z, k1v.w};
+            uint32_t z0[4], z1[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                float s0[2], s1[2];
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    const float x0 = hh ? __uint_as_float(u0[e2] & 0xffff0000u) : __uint_as_float(u0[e2] << 16);
+                    const float x1 = hh ? __uint_as_float(u1[e2] & 0xffff0000u) : __uint_as_float(u1[e2] << 16);
+                    const float2 ck = kr < a.n_q ? cs_tab[kr * 64 + 8 * kc + 2 * e2 + hh] : make_float2(0.f, 0.f);
+                    s0[hh] = x0 * ck.x - x1 * ck.y;
+                    s1[hh] = x1 * ck.x + x0 * ck.y;
+                }
+                z0[e2] = pack_bf16x2(s0[0], s0[1]);
+                z1[e2] = pack_bf16x2(s1[0], s1[1]);
+            }
+            char* krow = smem + L::kKn + kr * kQRowBytes + 16 * kc;
+            *reinterpret_cast<uint4*>(krow) = make_uint4(z0[0], z0[1], z0[2], z0[3]);
+            *reinterpret_cast<uint4*>(krow + 128) = make_uint4(z1[0], z1[1], z1[2], z1[3]);
+        }
+        WaveState st;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            // an in-flight tile may be wholly invisible to a row whose state is still empty: a finite
+            // floor keeps 2^(s - m) at zero there instead of 2^(inf - inf)
+            st.m[rb] = -1e30f;
+            st.l[rb] = 0.f;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) st.o[rb][db][i] = 0.f;
+        }
+
+        // ---- the stream: every wave takes every tile.  Tile t is computed from LDS buffer t % 2
+        // while tile t + 1 is on its way into registers ----
+        if (n_tiles > 0) {
+            *reinterpret_cast<uint4*>(k_store) = sa.k;
+            *reinterpret_cast<uint4*>(v_store) = my_tok < n_tok ? sa.v : make_uint4(0, 0, 0, 0);
+        }
+        lds_barrier();
+        for (int t = 0; t < n_tiles; ++t) {
+            const int buf = t & 1;
+            // the next tile's loads go out before this tile is computed and are stored behind it; the
+            // page id after that is asked for first, so that waiting for it leaves the tile's loads in flight
+            const int pid_n = page_of(t + 2);
+            sa = load_stage(pid_c);          // tile t + 1
+            pid_c = pid_n;
+            const int valid = n_tok - t * kTile;
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+                if (32 * rb < n_rows) {
+                    f32x16_t s;
+                    if (rb == 0) qk_block_qreg(s, k_read + buf * (kTile * kQRowBytes), qreg);
+                    else qk_block_lds2(s, k_read + buf * (kTile * kQRowBytes), q1_row);
+                    if (valid < kTile) mask_tail(s, valid, hf);
+                    softmax_pv(st, s, rb, v_read + buf * kVTileBytes);
+                }
+            // into the other buffer: every wave has finished with tile t - 1 (barrier of the last trip)
+            *reinterpret_cast<uint4*>(k_store + (buf ^ 1) * (kTile * kQRowBytes)) = sa.k;
+            *reinterpret_cast<uint4*>(v_store + (buf ^ 1) * kVTileBytes) =
+                (t + 1) * kTile + my_tok < n_tok ? sa.v : make_uint4(0, 0, 0, 0);     // rows past the end: zeros (stale pool bytes may be NaN)
+            lds_barrier();
+        }
+        // ---- the in-flight tiles (first segment only): keys from the rotated tiles, values from v_new,
+        // the visibility rule on the scores ----
+        if (first_seg) {
+            const int new_tiles = (a.n_q + kTile - 1) / kTile;
+            for (int it = 0; it < new_tiles; ++it) {
+                const int tok = kTile * it + my_tok;
+                const int tc = tok < a.n_q ? tok : a.n_q - 1;
+                const uint4 val = *reinterpret_cast<const uint4*>(a.v_new + (((size_t)sg_b * a.n_q + tc) * a.n_kv_heads + g) * kD + 8 * my_col);
+                *reinterpret_cast<uint4*>(v_store) = tok < a.n_q ? val : make_uint4(0, 0, 0, 0);
+                lds_barrier();
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+                    if (32 * rb < n_rows) {
+                        const int row = 32 * rb + l32;
+                        const bool pad_row = row >= n_rows;
+                        const int i = cq0 + (pad_row ? 0 : row / a.group);
+                        int ctx = a.ctx_new ? a.ctx_new[sg_b * a.n_q + i] : (i < a.n_verify ? i : a.n_verify);
+                        ctx = pad_row ? 0 : (ctx < a.n_q ? ctx : a.n_q);
+                        f32x16_t s;
+                        if (rb == 0) qk_block_qreg(s, smem + L::kKn + (kTile * it + l32) * kQRowBytes + 16 * hf, qreg);
+                        else qk_block_lds2(s, smem + L::kKn + (kTile * it + l32) * kQRowBytes + 16 * hf, q1_row);
+                        mask_inflight(s, ctx - kTile * it, i - kTile * it, hf);
+                        softmax_pv(st, s, rb, v_read);
+                    }
+                lds_barrier();
+            }
+        }
+
+        // ---- the pair's finishing order; this wave's chunk goes to, or is folded with, the partials
+        // [partial][kv head][chunk]: m[64], l[64], then O as [row block][d block][4 registers][lane] ----
+        const int p_begin = uniform_load(a.part_begin + sg_b), p_end = uniform_load(a.part_begin + sg_b + 1);
+        int* ctr = a.arrive + 2 * (sg_b * a.n_kv_heads + g);
+        int lane_t = lane;     // (an opaque copy: what the tail derives from the lane is not kept across the stream)
+        asm volatile("" : "+v"(lane_t));
+        const int lane = lane_t, hf = lane >> 5, l32 = lane & 31;
+        if (tid == 0) *reinterpret_cast<volatile int*>(smem + L::kFlag) = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        float lsum[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) lsum[rb] = st.l[rb] + __shfl_xor(st.l[rb], 32, 64);   // the half-waves hold halves of a row's sum
+        lds_barrier();
+        const bool closing = *reinterpret_cast<volatile int*>(smem + L::kFlag) == p_end - p_begin - 1;
+        const __amdgpu_buffer_rsrc_t rs = partials_descriptor(a.ws);
+        auto part_floats = [&](int p) { return (((size_t)p * a.n_kv_heads + g) * kWideChunks + w) * kPartFloats; };
+        if (!closing) {
+            if (n_rows > 0) {
+                float* part = a.ws + part_floats(sg_part);
+                const uint32_t base = (uint32_t)(part_floats(sg_part) * sizeof(float));
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) {
+                    if (hf == 0) {
+                        store_coherent(part + 32 * rb + l32, st.m[rb]);
+                        store_coherent(part + kRows + 32 * rb + l32, lsum[rb]);
+                    }
+#pragma unroll
+                    for (int db = 0; db < 4; ++db)
+#pragma unroll
+                        for (int i4 = 0; i4 < 4; ++i4)
+                            store_coherent4(rs, base + (2 * kRows + (((rb * 4 + db) * 4 + i4) * 64 + lane) * 4) * 4,
+                                            make_float4(st.o[rb][db][4 * i4], st.o[rb][db][4 * i4 + 1], st.o[rb][db][4 * i4 + 2], st.o[rb][db][4 * i4 + 3]));
+                }
+            }
+            __syncthreads();   // waits for every thread's partial stores
+            if (tid == 0) __hip_atomic_fetch_add(ctr + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            if (tid == 0) {
+                const int others = p_end - p_begin - 1;
+                int seen = __hip_atomic_load(ctr + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int spin = 0; spin < a.poll_limit && seen != others; ++spin) {
+                    __builtin_amdgcn_s_sleep(2);
+                    seen = __hip_atomic_load(ctr + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (seen == others) {
+                    __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(ctr + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    __hip_atomic_store(a.error_word, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);   // see the decode kernel
+                }
+                *reinterpret_cast<volatile int*>(smem + L::kFlag + 8) = seen == others ? 1 : 0;
+            }
+            lds_barrier();
+            asm volatile("" ::: "memory");
+            if (*reinterpret_cast<volatile int*>(smem + L::kFlag + 8) && n_rows > 0) {
+                // fold in partial-index order (this share's own state at its index), so that the
+                // result does not depend on which share closes; the partials' loads go out four at a time
+                constexpr int kFold = 4;
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) {
+                    const int row = 32 * rb + l32;
+                    float m_all = -INFINITY;
+                    for (int p0 = p_begin; p0 < p_end; p0 += kFold) {
+                        float mp[kFold];
+#pragma unroll
+                        for (int k = 0; k < kFold; ++k) {
+                            const int p = p0 + k;
+                            mp[k] = p >= p_end ? -INFINITY : (p == sg_part ? st.m[rb] : load_coherent(a.ws + part_floats(p) + row));
+                        }
+#pragma unroll
+                        for (int k = 0; k < kFold; ++k) m_all = fmaxf(m_all, mp[k]);
+                    }
+                    float l_all = 0.f;
+                    for (int p0 = p_begin; p0 < p_end; p0 += kFold) {
+                        float mp[kFold], lp[kFold];
+#pragma unroll
+                        for (int k = 0; k < kFold; ++k) {
+                            const int p = p0 + k;
+                            const bool mine = p == sg_part, none = p >= p_end;
+                            mp[k] = none ? -INFINITY : (mine ? st.m[rb] : load_coherent(a.ws + part_floats(p) + row));
+                            lp[k] = none ? 0.f : (mine ? lsum[rb] : load_coherent(a.ws + part_floats(p) + kRows + row));
+                        }
+#pragma unroll
+                        for (int k = 0; k < kFold; ++k) l_all += lp[k] * __builtin_amdgcn_exp2f(mp[k] - m_all);   // past the end: 0 * 2^-inf
+                    }
+                    const float inv = 1.f / l_all;
+                    const bool live = row < n_rows;
+                    const int qi = cq0 + (live ? row / a.group : 0), qh = live ? row % a.group : 0;
+                    uint16_t* op = a.out + (((size_t)sg_b * a.n_q + qi) * a.n_q_heads + g * a.group + qh) * kD;
+#pragma unroll
+                    for (int db = 0; db < 4; ++db) {
+                        float4 acc[4];
+#pragma unroll
+                        for (int i4 = 0; i4 < 4; ++i4) acc[i4] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        for (int p0 = p_begin; p0 < p_end; p0 += kFold) {
+                            float f[kFold];
+                            float4 x[kFold][4];
+#pragma unroll
+                            for (int k = 0; k < kFold; ++k) {
+                                const int p = p0 + k;
+                                if (p < p_end && p != sg_part) {
+                                    const uint32_t base = (uint32_t)(part_floats(p) * sizeof(float));
+                                    f[k] = load_coherent(a.ws + part_floats(p) + row);
+#pragma unroll
+                                    for (int i4 = 0; i4 < 4; ++i4)
+                                        x[k][i4] = load_coherent4(rs, base + (2 * kRows + (((rb * 4 + db) * 4 + i4) * 64 + lane) * 4) * 4);
+                                } else {
+                                    const bool mine = p == sg_part;
+                                    f[k] = mine ? st.m[rb] : -INFINITY;
+#pragma unroll
+                                    for (int i4 = 0; i4 < 4; ++i4)
+                                        x[k][i4] = mine ? make_float4(st.o[rb][db][4 * i4], st.o[rb][db][4 * i4 + 1], st.o[rb][db][4 * i4 + 2], st.o[rb][db][4 * i4 + 3])
+                                                        : make_float4(0.f, 0.f, 0.f, 0.f);
+                                }
+                            }
+#pragma unroll
+                            for (int k = 0; k < kFold; ++k) {
+                                const float fk = __builtin_amdgcn_exp2f(f[k] - m_all);
+#pragma unroll
+                                for (int i4 = 0; i4 < 4; ++i4) {
+                                    acc[i4].x += fk * x[k][i4].x;
+                                    acc[i4].y += fk * x[k][i4].y;
+                                    acc[i4].z += fk * x[k][i4].z;
+                                    acc[i4].w += fk * x[k][i4].w;
+                                }
+                            }
+                        }
+                        if (live)
+#pragma unroll
+                            for (int i4 = 0; i4 < 4; ++i4) {   // registers 4 i4 .. + 4 hold d = 32 db + 8 i4 + 4 (lane / 32) .. + 4
+                                uint2 pk;
+                                pk.x = pack_bf16x2(acc[i4].x * inv, acc[i4].y * inv);
+                                pk.y = pack_bf16x2(acc[i4].z * inv, acc[i4].w * inv);
+                                *reinterpret_cast<uint2*>(op + 32 * db + 8 * i4 + 4 * hf) = pk;
+                            }
+                    }
+                }
+            }
+        }
+        lds_barrier();  // the next segment reuses the LDS
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
@@ -809,10 +1228,13 @@ static int mfma_items(const ms_cache* c) {
     return target > kMaxMfmaItems ? kMaxMfmaItems : target;
 }
 
-// every share contributes one partial plus one per sequence boundary inside it
-size_t mfma_workspace_bytes(const ms_cache* c, int B) {
-    size_t n = (size_t)(mfma_items(c) + B) * c->d.n_kv_heads * kPartFloats * sizeof(float);
-    return n;
+// steps the decode kernel does not take: more than 16 queries or more than 64 rows per KV head
+static bool mfma_wide_step(const ms_cache* c, int n_q) { return n_q > kDecodeQueries || n_q * c->group > kRows; }
+
+// every share contributes one partial plus one per sequence boundary inside it; in a wide step one
+// per chunk of queries
+size_t mfma_workspace_bytes(const ms_cache* c, int B, int n_q) {
+    return (size_t)(mfma_items(c) + B) * c->d.n_kv_heads * kPartFloats * sizeof(float) * (mfma_wide_step(c, n_q) ? kWideChunks : 1);
 }
 
 constexpr int kMaxAttrDevices = 64;
@@ -844,13 +1266,12 @@ int mfma_plan_ints(int B) { return kMaxMfmaItems * kSegInts + (kMaxMfmaItems + B
 // Splits the batch's 32-token tiles into equal contiguous shares (work items) and lists each share's
 // segments.  Every sequence gets at least one segment (an empty one if it has no cached tokens): the
 // first segment's workgroup also runs the sequence's in-flight tile.
-static void build_plan(const ms_cache* c, const BatchMeta& bm, int B, int n_items_target, std::vector<int>& blob,
+static void build_plan(const ms_cache* c, const BatchMeta& bm, int B, int n_items_target, long min_tiles, std::vector<int>& blob,
                        int* n_items_out, int* n_parts_out) {
     std::vector<long> tile_prefix(B + 1, 0);
     for (int b = 0; b < B; ++b) tile_prefix[b + 1] = tile_prefix[b] + (bm.len[b] + kTile - 1) / kTile;
     const long nt = tile_prefix[B];
     int n_items = n_items_target;
-    const long min_tiles = 2 * kWaves;  // at least two tiles per wave in a share
     if ((long)n_items * min_tiles > nt) n_items = (int)(nt / min_tiles);
     if (n_items < 1) n_items = 1;
     std::vector<std::vector<Seg>> per_item(n_items);
@@ -944,13 +1365,11 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     if (c->device < 0 || c->device >= kMaxAttrDevices) MS_FAIL(MS_ERR_UNSUPPORTED, "device index %d outside [0, %d)", c->device, kMaxAttrDevices);
     std::call_once(attr_once[c->device], [&] {
         hipError_t e = hipSuccess;
-        const void* decode_builds[] = {(const void*)pv_attn_mfma_stream<false, false, false>, (const void*)pv_attn_mfma_stream<false, true, false>,
-                                       (const void*)pv_attn_mfma_stream<false, false, true>, (const void*)pv_attn_mfma_stream<false, true, true>};
+        const void* decode_builds[] = {(const void*)pv_attn_mfma_stream<false, false>, (const void*)pv_attn_mfma_stream<true, false>,
+                                       (const void*)pv_attn_mfma_stream<false, true>, (const void*)pv_attn_mfma_stream<true, true>};
         for (const void* f : decode_builds)
-            if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Lds<false>::kBytes);
-        const void* wide_builds[] = {(const void*)pv_attn_mfma_stream<true, false, false>, (const void*)pv_attn_mfma_stream<true, false, true>};
-        for (const void* f : wide_builds)
-            if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Lds<true>::kBytes);
+            if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Lds::kBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)pv_attn_mfma_wide, hipFuncAttributeMaxDynamicSharedMemorySize, WideLds::kBytes);
         attr_result[c->device] = e;
     });
     if (attr_result[c->device] != hipSuccess)
@@ -967,13 +1386,20 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     }
     // plan: rebuilt only when the batch (ids, lengths) changed since the last call on this cache
     std::vector<int> key;
-    key.reserve(B + 2);
+    // Smallest share.  Decode steps: two tiles per wave.  Wide steps: a share that does not close its
+    // pair writes one partial per chunk of queries (33 KB each, read back once), so its tiles (16 KB
+    // each) must outweigh them: 24 tiles per chunk keep the partials below a tenth of the traffic.
+    const int n_q = ga.n_q;
+    const int wide_chunks = !mfma_wide_step(c, n_q) ? 0 : std::min(kWideChunks, (n_q + kRows / ga.group - 1) / (kRows / ga.group));
+    const long min_tiles = wide_chunks ? 24L * wide_chunks : 2L * kWaves;
+    key.reserve(B + 3);
     key.push_back(B);
+    key.push_back((int)min_tiles);
     key.push_back((int)c->version);   // any change of lengths or page tables bumps the version
     for (int b = 0; b < B; ++b) key.push_back(bm.seq[b]);
     if (key != c->plan_key) {
         std::vector<int> blob;
-        build_plan(c, bm, B, mfma_items(c), blob, &c->plan_items, &c->plan_parts);
+        build_plan(c, bm, B, mfma_items(c), min_tiles, blob, &c->plan_items, &c->plan_parts);
         const size_t bytes = blob.size() * sizeof(int);
         if (bytes > StageRing::kSlotBytes) MS_FAIL(MS_ERR_UNSUPPORTED, "attention plan of %zu bytes too large", bytes);
         int rc = c->stage.upload_to(c->d_plan, blob.data(), bytes, stream);
@@ -1015,23 +1441,23 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
         }
         c->prof_seen++;
         const dim3 grid(c->plan_items, a.n_kv_heads);
-        if (a.n_q <= kDecodeQueries && a.n_q * a.group <= kRows) {
+        if (!mfma_wide_step(c, a.n_q)) {
             a.q0 = 0;
             a.n_qc = a.n_q;
             const bool big = big_pool(c);
-            auto kern = c->deterministic ? (big ? pv_attn_mfma_stream<false, false, true> : pv_attn_mfma_stream<false, false, false>)
-                                         : (big ? pv_attn_mfma_stream<false, true, true> : pv_attn_mfma_stream<false, true, false>);
+            auto kern = c->deterministic ? (big ? pv_attn_mfma_stream<false, true> : pv_attn_mfma_stream<false, false>)
+                                         : (big ? pv_attn_mfma_stream<true, true> : pv_attn_mfma_stream<true, false>);
             c->launches++;
-            hipLaunchKernelGGL(kern, grid, dim3(kThreads), Lds<false>::kBytes, stream, a);
+            hipLaunchKernelGGL(kern, grid, dim3(kThreads), Lds::kBytes, stream, a);
         } else {
-            // wide steps: one launch per chunk of queries; launches on one stream run in order, so
-            // they can share the partial workspace and the arrival counters
-            const int per_launch = kRows / a.group;
+            // wide steps: a launch takes eight chunks of 64 / group queries, one per wave (with more than
+            // eight query heads per KV head a step of 64 queries has more chunks than that: further
+            // launches, which run in order on the stream and share the workspace and the counters)
+            const int per_launch = kWideChunks * (kRows / a.group);
             for (a.q0 = 0; a.q0 < a.n_q; a.q0 += per_launch) {
                 a.n_qc = a.n_q - a.q0 < per_launch ? a.n_q - a.q0 : per_launch;
-                auto kern = big_pool(c) ? pv_attn_mfma_stream<true, false, true> : pv_attn_mfma_stream<true, false, false>;
                 c->launches++;
-                hipLaunchKernelGGL(kern, grid, dim3(kThreads), Lds<true>::kBytes, stream, a);
+                hipLaunchKernelGGL(pv_attn_mfma_wide, grid, dim3(kThreads), WideLds::kBytes, stream, a);
             }
         }
         MS_HIP_TRY(hipGetLastError());

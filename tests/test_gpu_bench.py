@@ -49,6 +49,12 @@ def test_compaction_bench_small():
     assert cp["kv_row_bytes_written_per_call"] == 4 * 8 * 3 * 4 * 128 * 2 * 2
 
 
+def test_wide_step_bench_small():
+    r = run_bench("--workload", "wide_step", "--layers", "2", "--batch", "2", "--kv", "1000", "--queries", "41", "--steps", "2", "--warmup", "1")
+    check_contract(r)
+    assert r["kernel_launches_per_call"] == 1.0 and r["roofline"]["kernel"] == "pv_attn_mfma_wide"
+
+
 def test_decode_step_bench_small():
     r = run_bench("--workload", "decode_step", "--layers", "1", "--batch", "2", "--kv", "128", "--steps", "2", "--warmup", "1",
                   "--no-gemm-tuning")

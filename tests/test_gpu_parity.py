@@ -131,6 +131,10 @@ SMALL = [
     ("bf16", 4, 4, 128, 33, 7, [90]),                   # one head per KV head, 40 queries in one chunk
     ("f32", 8, 2, 64, 30, 10, [70, 5]),                 # general kernel, 40 queries
     ("bf16", 8, 2, 64, 17, 0, [129]),
+    ("bf16", 28, 4, 128, 41, 0, [5000, 64, 3000, 0]),   # wide steps over caches cut into many shares: several partials per chunk
+    ("bf16", 28, 4, 128, 64, 0, [9000]),
+    ("bf16", 64, 4, 128, 40, 0, [700, 33]),             # 16 query heads per KV head: 4 queries per chunk, two launches
+    ("bf16", 28, 4, 128, 17, 8, [2048, 2047, 31]),      # foresight rows in a wide step
     # the largest batch: 256 short sequences (many segments per workgroup, some sequences empty)
     ("bf16", 28, 4, 128, 2, 1, [(37 * i) % 97 for i in range(256)]),
     ("f32", 4, 2, 64, 1, 1, [(11 * i) % 40 for i in range(256)]),

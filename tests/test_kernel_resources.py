@@ -51,7 +51,7 @@ def test_projection_kernels_do_not_spill():
 
 def test_decode_builds_of_the_stream_kernel_do_not_spill_in_the_stream_loop():
     text, kernels = compiled_kernels("attention_mfma.hip")
-    decode = {n: r for n, r in kernels.items() if "pv_attn_mfma_streamILb0E" in n}
+    decode = {n: r for n, r in kernels.items() if "pv_attn_mfma_stream" in n}
     assert len(decode) == 4, sorted(kernels)           # fixed / first-come tile assignment x small / large layer pool
     lines = text.split("\n")
     for name, r in decode.items():
@@ -67,3 +67,22 @@ def test_decode_builds_of_the_stream_kernel_do_not_spill_in_the_stream_loop():
             assert r["vgpr_spill_count"] == 0 and r["private_segment_fixed_size"] == 0, (name, r)
         else:
             assert r["vgpr_spill_count"] <= 4, (name, r)
+    # the wide-step kernel: spills are tolerated in its set-up and closing, not between the barriers of its tile loop
+    wide = [n for n in kernels if "pv_attn_mfma_wide" in n]
+    assert len(wide) == 1
+    start = next(i for i, ln in enumerate(lines) if ln.startswith(wide[0] + ":"))
+    end = next(i for i in range(start, len(lines)) if "s_endpgm" in lines[i])
+    assert kernels[wide[0]]["vgpr_count"] <= 256
+    # its tile loop is the innermost loop that holds matrix instructions, a workgroup barrier and the
+    # streaming (non-temporal) loads of V: the block between a label and the backward branch to it
+    labels = {lines[i].split(":")[0]: i for i in range(start, end) if lines[i].startswith(".LBB")}
+    loops = []
+    for i in range(start, end):
+        m = re.match(r"\s+s_c?branch\w* (\.LBB\d+_\d+)", lines[i])
+        if m and m.group(1) in labels and labels[m.group(1)] < i:
+            body = lines[labels[m.group(1)]:i]
+            if any("v_mfma" in b for b in body) and any("s_barrier" in b for b in body) and any("global_load" in b and " nt" in b for b in body):
+                loops.append(body)
+    assert loops, "tile loop of the wide kernel not found"
+    inner = min(loops, key=len)
+    assert not [b for b in inner if "scratch_" in b], [b.strip() for b in inner if "scratch_" in b]
