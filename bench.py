@@ -62,9 +62,9 @@ def parse():
     ap.add_argument("--queries", type=int, default=41, help="wide_step: causal queries per sequence (the memory tokens and <o>, or a prompt chunk)")
     ap.add_argument("--workload", choices=["attention", "decode_step", "compaction", "wide_step"], default="attention",
                     help="attention: the metric's workload (default); compaction: configuration 4 (batch 16, 28 layers, "
-                         "256 -> 8 tokens per sequence, then attention over the result); decode_step: the whole model step "
-                         "(Qwen2.5-7B shapes, batch 64, 8k cached tokens, 4 verify + 3 foresight) with torch GEMMs around "
-                         "the hand-written kernels")
+                         "256 -> 8 tokens per sequence, then attention over the result); wide_step: a pass of --queries causal "
+                         "queries; decode_step: the whole model step (Qwen2.5-7B shapes, batch 64, 8k cached tokens, 4 verify + "
+                         "3 foresight)")
     ap.add_argument("--deterministic", action="store_true",
                     help="fixed tile-to-wave assignment in the attention kernel (bit-reproducible results, about 1.5 %% slower)")
     ap.add_argument("--host-commit", action="store_true",
@@ -72,8 +72,6 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fused-lm-head", action="store_true",
                     help="decode_step: LM head and greedy token in one kernel of the library (fp32 sums, no logits)")
-    ap.add_argument("--no-gemm-tuning", action="store_true",
-                    help="decode_step: take torch's default pick for the library GEMMs instead of timing the candidates once")
     ap.add_argument("--cpu-seqs", type=int, default=32, help="sequences the CPU oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 1 GiB device copies, for scaling rocprofv3 byte counters")
@@ -590,7 +588,7 @@ def decode_step_bench(args):
     weights: embedding, 28 x (RMSNorm, Q/K/V GEMMs, fused attention, output GEMM, RMSNorm, MLP GEMMs
     with SwiGLU), final norm, LM head GEMM, greedy tokens, acceptance against them, commit of the
     accepted rows; the next verify block is built on the device from the step's own predictions.
-    GEMMs run through torch (hipBLASLt); everything else is this library's kernels."""
+    Every kernel of the step is this library's."""
     import numpy as np
     import torch
 
@@ -620,7 +618,7 @@ def decode_step_bench(args):
         ses.pool[layer].normal_(0.0, 0.5, generator=gen)
     ids = [M.ms_seq_import(ses.cache, n, pt) for n, pt in zip(lengths, page_tables)]
     weights = D.DecoderTensors.random(cfg, W.BASE_SEED + 6, dev)
-    dec = D.Decoder(cfg, weights, ses, B * nq, tune_library_gemms=not args.no_gemm_tuning, fused_lm_head=args.fused_lm_head)
+    dec = D.Decoder(cfg, weights, ses, B * nq, fused_lm_head=args.fused_lm_head)
     ses.ensure_workspace(B, nq)
 
     foresight_id = cfg.vocab - 1                           # stands for the <f> token
@@ -680,9 +678,7 @@ def decode_step_bench(args):
     kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else float("nan")
     achieved = per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9
     attn_ms = kern_avg_ms * NL      # from the sampled launches (an event pair around every launch would stall the stream)
-    n_params = (sum(t.numel() for lw in weights.layers for name, t in vars(lw).items()
-                     if name not in ("wqkv", "bqkv", "w_gate_up_blocked")) +
-                weights.lm_head.numel() + weights.norm.numel())
+    n_params = sum(t.numel() for lw in weights.layers for t in vars(lw).values()) + weights.lm_head.numel() + weights.norm.numel()
     result = {
         "metric": f"full_decode_step_tokens_per_s_b{B}_kv{L0 // 1024}k",
         "value": round(state["committed"] / (t1 - t0), 1),
@@ -692,13 +688,10 @@ def decode_step_bench(args):
         "config": {
             "workload": f"decode_step_qwen2.5-7b_shapes_batch{B}_kv{L0}_layers{NL}_verify{nv}_foresight{nf}",
             "batch": B, "mean_kv_len": round(float(cur_len.mean()), 1), "layers": NL,
-            "step": "embedding, 28 blocks (hand-written norm / attention / SwiGLU kernels, " +
-                    ("every projection on this library's few-row matrix-core kernel, gate/up with SwiGLU in its epilogue"
-                     if dec._few(B * nq) else
-                     "hand-written GEMM for the fused Q/K/V and the down projection, torch GEMMs for the output, gate/up "
-                     "and LM-head projections") +
-                    "), greedy tokens, accept, commit; random weights, so about one token per sequence is accepted per step",
-            "library_gemms": "default pick" if args.no_gemm_tuning else "candidates timed once per shape (torch.cuda.tunable), in the warm-up",
+            "step": f"embedding, {NL} blocks (norm, fused Q/K/V projection, attention, output projection, norm, gate/up projection with "
+                    "SwiGLU, down projection with the residual add and the next norm), LM head, greedy tokens, accept, commit: every kernel is "
+                    "this library's; random weights, so about one token per sequence is accepted per step",
+            "projections": "few-row matrix-core kernel" if B * nq <= 16 else "tiled matrix-core GEMM",
         },
         "query_tokens_per_s": round(B * nq * args.steps / (t1 - t0), 1),
         "committed_per_step_per_seq": round(state["committed"] / args.steps / B, 3),

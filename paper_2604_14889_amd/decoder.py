@@ -1,15 +1,14 @@
 """One full decode step (Algorithm 1, SpeculativeStep, of the MemoSight paper) on the GPU.
 
-The attention, the residual/RMSNorm, SwiGLU and greedy-token kernels, acceptance and the cache
-update are this library's HIP kernels.  Of the dense projections, the fused Q/K/V projection and
-the MLP down projection run on this library's MFMA GEMM (ms_gemm_bf16: one launch fills the three
-Q/K/V tensors; the down projection's deep K is split over workgroups), where it is faster than the
-library GEMM at a few hundred rows; the output, gate/up and LM-head projections go through torch
-(hipBLASLt underneath), which is still ahead on those shapes.  fused_mlp=True moves the gate/up
-projection onto this library's GEMM as well, with SwiGLU applied in its epilogue
-(ms_gemm_swiglu_bf16): no hipBLASLt in the MLP, about a tenth slower on that projection.
+Everything in the step is this library's HIP kernels: the attention, the residual/RMSNorm and
+greedy-token kernels, acceptance, the cache update, and the dense projections (ms_gemm_bf16 and its
+fused forms: one launch fills the three Q/K/V tensors, the gate/up projection applies SwiGLU in its
+epilogue, the down projection's partial sums are added up by the kernel that also adds the
+residual and applies the next norm, the LM head can leave the greedy token instead of the logits).
+Up to 16 rows (one or two sequences) the projections run on the library's few-row kernel.
 
-Nothing here computes on the CPU; every call fails if the HIP library is missing.
+Nothing here computes on the CPU or in a library GEMM; every call fails if the HIP library is
+missing, and shapes the kernels do not take are refused when the Decoder is built.
 """
 from __future__ import annotations
 
@@ -44,18 +43,14 @@ class LayerTensors:
     """bf16 device tensors of one block; projection weights are [out_features, in_features]."""
 
     def __init__(self, ln1, wq, bq, wk, bk, wv, bv, wo, ln2, w_gate_up, w_down):
-        self.ln1, self.wq, self.bq, self.wk, self.bk, self.wv, self.bv = ln1, wq, bq, wk, bk, wv, bv
-        self.wo, self.ln2, self.w_gate_up, self.w_down = wo, ln2, w_gate_up, w_down
+        self.ln1, self.wo, self.ln2, self.w_down = ln1, wo, ln2, w_down
         # one weight for the fused Q/K/V projection (rows: Q heads, then K heads, then V heads)
         self.wqkv = torch.cat([wq, wk, wv], dim=0).contiguous()
         self.bqkv = torch.cat([bq, bk, bv], dim=0).contiguous()
-        self.w_gate_up_blocked = None   # rows re-ordered for the fused gate/up + SwiGLU GEMM, made on demand
-
-    def gate_up_blocked(self):
-        if self.w_gate_up_blocked is None:
-            inter = self.w_gate_up.shape[0] // 2
-            self.w_gate_up_blocked = M.interleave_gate_up(self.w_gate_up[:inter], self.w_gate_up[inter:])
-        return self.w_gate_up_blocked
+        # gate and up rows interleaved in blocks of 32: the layout the gate/up projection with SwiGLU
+        # in its epilogue reads (a one-off re-ordering of rows at load time)
+        inter = w_gate_up.shape[0] // 2
+        self.w_gate_up_blocked = M.interleave_gate_up(w_gate_up[:inter], w_gate_up[inter:])
 
 
 class DecoderTensors:
@@ -89,25 +84,25 @@ class DecoderTensors:
 class Decoder:
     """Buffers and the step driver for up to max_rows = B * n_q tokens per step."""
 
-    def __init__(self, cfg: DecoderConfig, weights: DecoderTensors, session: Session, max_rows: int,
-                 hand_gemm: bool = True, fused_mlp: bool = False, tune_library_gemms: bool = False,
-                 fused_lm_head: bool = False):
-        """hand_gemm: run the Q/K/V and down projections on this library's GEMM (needs widths that
-        are multiples of 128 and depths that are multiples of 128); otherwise everything dense goes
-        through torch."""
+    def __init__(self, cfg: DecoderConfig, weights: DecoderTensors, session: Session, max_rows: int, fused_lm_head: bool = False):
+        """fused_lm_head: LM head and greedy token in one kernel (the token is taken on the fp32 sums,
+        the logits are never written); step() then returns None for the logits."""
         self.cfg, self.w, self.ses = cfg, weights, session
         dev = weights.embed.device
-        if tune_library_gemms:
-            # the projections left to torch: let it time the library's solutions for each new shape
-            # once (a few seconds at the first call) instead of taking the default pick.  Process-wide.
-            import torch.cuda.tunable as tunable
-            tunable.enable(True)
-            tunable.tuning_enable(True)
-            tunable.set_max_tuning_duration(200)
-            import os
-            import tempfile
-            tunable.set_filename(os.path.join(tempfile.gettempdir(), "memosight_library_gemms.csv"))   # its results file
         qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+        if qd % 128 or kd % 128 or cfg.hidden % 128 or cfg.inter % 256:
+            raise M.MsError(M.MS_ERR_UNSUPPORTED, "the projection kernels need head widths and the hidden size in multiples of 128 "
+                                                  "and an MLP width in multiples of 256")
+        # the LM head's width in multiples of 128: rows of zeros are appended once, here; the greedy
+        # token is taken over the real vocabulary only
+        self.vocab_pad = -(-cfg.vocab // 128) * 128
+        self.lm_head = weights.lm_head
+        if self.vocab_pad != cfg.vocab:
+            self.lm_head = torch.zeros(self.vocab_pad, cfg.hidden, dtype=torch.bfloat16, device=dev)
+            self.lm_head[:cfg.vocab].copy_(weights.lm_head)
+        if fused_lm_head and self.vocab_pad != cfg.vocab:
+            raise M.MsError(M.MS_ERR_UNSUPPORTED, "fused_lm_head needs a vocabulary size in multiples of 128")
+        self.fused_lm_head = fused_lm_head
 
         def buf(*shape, dtype=torch.bfloat16):
             return torch.empty(*shape, dtype=dtype, device=dev)
@@ -120,102 +115,38 @@ class Decoder:
         self._prepared = {}       # rows -> prepared argument tuples of the library calls
         self.attn = buf(max_rows, qd)
         self.proj = buf(max_rows, cfg.hidden)
-        self.gate_up = buf(max_rows, 2 * cfg.inter)
         self.act = buf(max_rows, cfg.inter)
-        self.logits = buf(max_rows, cfg.vocab)
+        self.logits = None if fused_lm_head else buf(max_rows, self.vocab_pad)
         self.targets = buf(max_rows, dtype=torch.int32)
-        self.attn_events = None   # optional list of (start, stop) events around every attention call
         # K is split further when a step has few rows (one row tile: half as many workgroups);
-        # measured at Qwen2.5-7B widths: Q/K/V 4 ways up to 256 rows, 2 above; down 8 and 4
-        self.splits_few, self.splits_many = (4, 8), (2, 4)
-        self.hand_gemm = (hand_gemm and qd % 128 == 0 and kd % 128 == 0 and cfg.hidden % 128 == 0 and
-                          cfg.hidden % (32 * 4) == 0 and cfg.inter % (32 * 8) == 0)
-        # gate/up + SwiGLU in one GEMM: keeps a second, row-interleaved copy of the gate/up weights
-        self.fused_mlp = fused_mlp and self.hand_gemm and cfg.inter % 64 == 0
-        # LM head and greedy token in one kernel of the library (fp32 sums, no logits): step() then
-        # returns None for the logits
-        self.fused_lm_head = fused_lm_head and cfg.vocab % 128 == 0 and cfg.hidden % 32 == 0
+        # measured at Qwen2.5-7B widths: Q/K/V 4 ways up to 256 rows, 2 above; output 4; down 8 and 4
+        self.splits_few, self.splits_many = (4, 4, 8), (2, 4, 4)
+        rows_few = range(1, min(max_rows, 16) + 1)
+        need = max([M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, cfg.hidden, self.splits_few[0]),
+                    M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, qd, self.splits_few[1]),
+                    M.ms_gemm_workspace_bytes(max_rows, 2 * cfg.inter, cfg.hidden, 1),
+                    M.ms_gemm_workspace_bytes(max_rows, self.vocab_pad, cfg.hidden, 1),
+                    M.ms_gemm_add_rmsnorm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[2])] +
+                   [M.ms_gemm_workspace_bytes(r, n, k, 1) for r in rows_few
+                    for n, k in ((qd + 2 * kd, cfg.hidden), (cfg.hidden, qd), (2 * cfg.inter, cfg.hidden), (self.vocab_pad, cfg.hidden))] +
+                   [M.ms_gemm_add_rmsnorm_workspace_bytes(r, cfg.hidden, cfg.inter, self.splits_few[2]) for r in rows_few])
+        self.gemm_ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
         self.lm_ws = None
-        if self.fused_lm_head:
+        if fused_lm_head:
             self.lm_ws = torch.empty(M.ms_lm_head_argmax_workspace_bytes(max_rows, cfg.vocab, cfg.hidden), dtype=torch.uint8, device=dev)
-        self.gemm_ws = None
-        if self.hand_gemm:
-            need = max(M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, cfg.hidden, self.splits_few[0]),
-                       M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[1]),
-                       max(M.ms_gemm_workspace_bytes(r, qd + 2 * kd, cfg.hidden, 1) for r in range(1, min(max_rows, 16) + 1)),
-                       max(M.ms_gemm_workspace_bytes(r, 2 * cfg.inter, cfg.hidden, 1) for r in range(1, min(max_rows, 16) + 1)),
-                       max(M.ms_gemm_workspace_bytes(r, cfg.vocab, cfg.hidden, 1) for r in range(1, min(max_rows, 16) + 1))
-                       if cfg.vocab % 128 == 0 else 0,
-                       max(M.ms_gemm_workspace_bytes(r, cfg.hidden, qd, 1) for r in range(1, min(max_rows, 16) + 1)),
-                       M.ms_gemm_add_rmsnorm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[1]),
-                       max(M.ms_gemm_add_rmsnorm_workspace_bytes(r, cfg.hidden, cfg.inter, self.splits_few[1])
-                           for r in range(1, min(max_rows, 16) + 1)),
-                       M.ms_gemm_workspace_bytes(max_rows, 2 * cfg.inter, cfg.hidden, 1) if self.fused_mlp else 0)
-            self.gemm_ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
-    def step(self, seq_ids: Sequence[int], tokens: torch.Tensor, pos: torch.Tensor, n_verify: int, n_foresight: int,
-             ctx_new: Optional[torch.Tensor] = None):
-        """tokens, pos: int32 device [B, n_q].  Returns (logits [B*n_q, vocab] bf16, greedy tokens
-        [B*n_q] int32), both views of this object's buffers (logits is None with fused_lm_head);
-        step_kv() gives the step's keys and values for ms_commit_accepted."""
-        cfg, w = self.cfg, self.w
-        B = len(seq_ids)
-        n_q = n_verify + n_foresight
-        rows = B * n_q
-        if rows > self.max_rows:
-            raise M.MsError(M.MS_ERR_INVALID, f"step of {rows} rows exceeds the buffers ({self.max_rows})")
-        hq, hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
-        h, x, q, attn, proj = self.h[:rows], self.x[:rows], self.q[:rows], self.attn[:rows], self.proj[:rows]
-        gate_up, act = self.gate_up[:rows], self.act[:rows]
-        if rows not in self._kv:
-            kd = hkv * d
-            self._kv[rows] = (torch.empty(cfg.n_layers, rows, kd, dtype=torch.bfloat16, device=h.device),
-                              torch.empty(cfg.n_layers, rows, kd, dtype=torch.bfloat16, device=h.device))
-        self.k_new, self.v_new = self._kv[rows]
-        if self.hand_gemm and not self.fused_mlp:
-            return self._step_prepared(seq_ids, tokens, pos, n_verify, n_foresight, ctx_new, rows)
-        qkv_split, down_split = self.splits_few if rows <= 256 else self.splits_many
-        M.ms_embed_rows(w.embed, tokens, h)
-        delta = None
-        for li, lw in enumerate(w.layers):
-            M.ms_add_rmsnorm(h, delta, lw.ln1, cfg.eps, x)
-            k, v = self.k_new[li], self.v_new[li]
-            if self.hand_gemm:
-                M.ms_gemm_bf16(x, lw.wqkv, lw.bqkv, [q, k, v], qkv_split, self.gemm_ws)
-            else:
-                torch.addmm(lw.bq, x, lw.wq.t(), out=q)
-                torch.addmm(lw.bk, x, lw.wk.t(), out=k)
-                torch.addmm(lw.bv, x, lw.wv.t(), out=v)
-            self.ses.attention(li, seq_ids, n_verify, n_foresight, q.view(B, n_q, hq, d), k.view(B, n_q, hkv, d),
-                               v.view(B, n_q, hkv, d), pos, ctx_new, 0.0, attn.view(B, n_q, hq, d))
-            torch.mm(attn, lw.wo.t(), out=proj)
-            M.ms_add_rmsnorm(h, proj, lw.ln2, cfg.eps, x)
-            if self.fused_mlp:
-                M.ms_gemm_swiglu_bf16(x, lw.gate_up_blocked(), act, self.gemm_ws)
-            else:
-                torch.mm(x, lw.w_gate_up.t(), out=gate_up)
-                M.ms_swiglu(gate_up, act)
-            if self.hand_gemm:
-                M.ms_gemm_bf16(act, lw.w_down, None, [proj], down_split, self.gemm_ws)
-            else:
-                torch.mm(act, lw.w_down.t(), out=proj)
-            delta = proj
-        M.ms_add_rmsnorm(h, delta, w.norm, cfg.eps, x)
-        return self._greedy_tokens(x, rows)
-
-    # ---- the same step with the library calls' arguments prepared once -------------------------------
+    # ---- argument tuples of the library calls, prepared once per row count ---------------------------
     def _prepare(self, rows: int):
-        """Argument tuples of every per-layer library call of a step of `rows` rows.  All buffers are
-        this object's and all weights are fixed, so the addresses never change; a step with a single
-        sequence is otherwise bound by re-deriving them in Python for its ~200 calls.  Whoever swaps
-        a weight tensor for another one afterwards calls forget_prepared()."""
+        """All buffers are this object's and all weights are fixed, so the addresses never change; a
+        step with a single sequence is otherwise bound by re-deriving them in Python for its ~200
+        calls.  Whoever swaps a weight tensor for another one afterwards calls forget_prepared()."""
         cfg, w = self.cfg, self.w
         ptr = lambda t: t.data_ptr()
         qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
-        h, x, q, attn, proj, gate_up, act = (ptr(t) for t in (self.h, self.x, self.q, self.attn, self.proj, self.gate_up, self.act))
+        h, x, q, attn, proj, act = (ptr(t) for t in (self.h, self.x, self.q, self.attn, self.proj, self.act))
         k_all, v_all = self._kv[rows]
         ws, ws_bytes = ptr(self.gemm_ws), self.gemm_ws.numel()
-        qkv_split, down_split = self.splits_few if rows <= 256 else self.splits_many
+        qkv_split, o_split, down_split = self.splits_few if rows <= 256 else self.splits_many
         cols_qkv = M.int_array([0, qd, qd + kd, qd + 2 * kd])
         cols_h = M.int_array([0, cfg.hidden])
         outs_proj = (C.c_void_p * 1)(proj)
@@ -228,68 +159,57 @@ class Decoder:
                 qkv=(x, ptr(lw.wqkv), ptr(lw.bqkv), rows, qd + 2 * kd, cfg.hidden, 3, (C.c_void_p * 3)(q, k, v), cols_qkv,
                      qkv_split, ws, ws_bytes),
                 k=k, v=v,
-                o=(attn, ptr(lw.wo), None, rows, cfg.hidden, qd, 1, outs_proj, cols_h, 1, ws, ws_bytes),
-                wo_t=lw.wo.t(), w_gate_up_t=lw.w_gate_up.t(),
+                o=(attn, ptr(lw.wo), None, rows, cfg.hidden, qd, 1, outs_proj, cols_h, o_split, ws, ws_bytes),
                 norm2=(h, proj, ptr(lw.ln2), cfg.eps, x, rows, cfg.hidden),
-                swiglu=(gate_up, act, rows, cfg.inter),
-                # few rows: gate/up with SwiGLU in the product's epilogue, from the row-interleaved copy of the weight
-                mlp_few=(x, ptr(lw.gate_up_blocked()), rows, cfg.inter, cfg.hidden, act, ws, ws_bytes) if self._few(rows) else None,
+                # gate/up with SwiGLU in the product's epilogue, from the row-interleaved weight
+                mlp=(x, ptr(lw.w_gate_up_blocked), rows, cfg.inter, cfg.hidden, act, ws, ws_bytes),
                 # the down projection with the residual add and the norm that follow it (the next block's, or the final one)
                 down_norm=(act, ptr(lw.w_down), rows, cfg.hidden, cfg.inter, down_split, h,
                            ptr(w.layers[li + 1].ln1 if li + 1 < len(w.layers) else w.norm), cfg.eps, x, ws, ws_bytes)))
         return dict(layers=layers, q=q, attn=attn)
 
-    def _few(self, rows: int) -> bool:
-        """Steps of at most 16 rows (one or two sequences) run every projection on this library's
-        few-row kernel, gate/up fused with SwiGLU (which keeps a row-interleaved second copy
-        of that weight, made at the first such step)."""
-        return rows <= 16 and self.cfg.inter % 128 == 0
-
     def forget_prepared(self) -> None:
         """Drops the prepared argument tuples (they hold device addresses of the weights)."""
         self._prepared.clear()
 
-    def _step_prepared(self, seq_ids, tokens, pos, n_verify, n_foresight, ctx_new, rows):
+    def step(self, seq_ids: Sequence[int], tokens: torch.Tensor, pos: torch.Tensor, n_verify: int, n_foresight: int,
+             ctx_new: Optional[torch.Tensor] = None):
+        """tokens, pos: int32 device [B, n_q].  Returns (logits [B*n_q, vocab] bf16, greedy tokens
+        [B*n_q] int32), both views of this object's buffers (logits is None with fused_lm_head);
+        step_kv() gives the step's keys and values for ms_commit_accepted."""
         cfg, w, lib, check = self.cfg, self.w, M.lib, M._check
+        B, n_q = len(seq_ids), n_verify + n_foresight
+        rows = B * n_q
+        if rows > self.max_rows:
+            raise M.MsError(M.MS_ERR_INVALID, f"step of {rows} rows exceeds the buffers ({self.max_rows})")
+        if tokens.numel() != rows or pos.numel() != rows or (ctx_new is not None and ctx_new.numel() != rows):
+            raise M.MsError(M.MS_ERR_INVALID, "tokens / pos / ctx_new do not have one entry per row")
+        if rows not in self._kv:
+            kd = cfg.n_kv_heads * cfg.head_dim
+            self._kv[rows] = (torch.empty(cfg.n_layers, rows, kd, dtype=torch.bfloat16, device=self.h.device),
+                              torch.empty(cfg.n_layers, rows, kd, dtype=torch.bfloat16, device=self.h.device))
+        self.k_new, self.v_new = self._kv[rows]
         if rows not in self._prepared:
             self._prepared[rows] = self._prepare(rows)
         prep = self._prepared[rows]
-        B, n_q = len(seq_ids), n_verify + n_foresight
-        if tokens.numel() != rows or pos.numel() != rows or (ctx_new is not None and ctx_new.numel() != rows):
-            raise M.MsError(M.MS_ERR_INVALID, "tokens / pos / ctx_new do not have one entry per row")
         st = M._stream(None)
-        ids = M.int_array(seq_ids)
+        ids = seq_ids if isinstance(seq_ids, C.Array) else M.int_array(seq_ids)
         att_ws = self.ses.ensure_workspace(B, n_q)
         att_ws_ptr, att_ws_bytes = att_ws.data_ptr(), att_ws.numel() * att_ws.element_size()
         pos_ptr, ctx_ptr = M._dev(pos), M._dev(ctx_new)
         cache, q, attn = self.ses.cache, prep["q"], prep["attn"]
-        x_t, attn_t, proj_t, gate_up_t = self.x[:rows], self.attn[:rows], self.proj[:rows], self.gate_up[:rows]
-        few = self._few(rows)
         M.ms_embed_rows(w.embed, tokens, self.h[:rows])
         for li, c in enumerate(prep["layers"]):
             if li == 0:     # the later blocks' input norm is applied by the block before, with its down projection
                 check(lib.ms_add_rmsnorm(*c["norm1"], st))
             check(lib.ms_gemm_bf16(*c["qkv"], st))
-            if self.attn_events is not None:
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
             check(lib.ms_predict_verify_attention(cache, li, B, ids, n_verify, n_foresight, q, c["k"], c["v"], pos_ptr, ctx_ptr, 0.0,
                                                   attn, att_ws_ptr, att_ws_bytes, st))
-            if self.attn_events is not None:
-                e1.record()
-                self.attn_events.append((e0, e1))
-            if few:
-                check(lib.ms_gemm_bf16(*c["o"], st))
-            else:
-                torch.mm(attn_t, c["wo_t"], out=proj_t)
+            check(lib.ms_gemm_bf16(*c["o"], st))
             check(lib.ms_add_rmsnorm(*c["norm2"], st))
-            if few:
-                check(lib.ms_gemm_swiglu_bf16(*c["mlp_few"], st))
-            else:
-                torch.mm(x_t, c["w_gate_up_t"], out=gate_up_t)
-                check(lib.ms_swiglu(*c["swiglu"], st))
+            check(lib.ms_gemm_swiglu_bf16(*c["mlp"], st))
             check(lib.ms_gemm_add_rmsnorm_bf16(*c["down_norm"], st))
-        return self._greedy_tokens(x_t, rows)
+        return self._greedy_tokens(self.x[:rows], rows)
 
     def _greedy_tokens(self, x, rows):
         targets = self.targets[:rows]
@@ -298,15 +218,12 @@ class Decoder:
             need = M.ms_lm_head_argmax_workspace_bytes(rows, self.cfg.vocab, self.cfg.hidden)
             if need > self.lm_ws.numel():
                 self.lm_ws = torch.empty(need, dtype=torch.uint8, device=self.lm_ws.device)
-            M.ms_lm_head_argmax_bf16(x, self.w.lm_head, targets, self.lm_ws)
+            M.ms_lm_head_argmax_bf16(x, self.lm_head, targets, self.lm_ws)
             return None, targets
         logits = self.logits[:rows]
-        if self.hand_gemm and self._few(rows) and self.cfg.vocab % 128 == 0:
-            M.ms_gemm_bf16(x, self.w.lm_head, None, [logits], 1, self.gemm_ws)
-        else:
-            torch.mm(x, self.w.lm_head.t(), out=logits)
+        M.ms_gemm_bf16(x, self.lm_head, None, [logits], 1, self.gemm_ws)
         M.ms_argmax_rows(logits, self.cfg.vocab, targets)
-        return logits, targets
+        return logits[:, :self.cfg.vocab], targets
 
     def step_kv(self):
         """The last step's K / V as contiguous [L, rows, Hkv, D] tensors (input of ms_commit_accepted)."""

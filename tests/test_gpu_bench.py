@@ -56,12 +56,11 @@ def test_wide_step_bench_small():
 
 
 def test_decode_step_bench_small():
-    r = run_bench("--workload", "decode_step", "--layers", "1", "--batch", "2", "--kv", "128", "--steps", "2", "--warmup", "1",
-                  "--no-gemm-tuning")
+    r = run_bench("--workload", "decode_step", "--layers", "1", "--batch", "3", "--kv", "128", "--steps", "2", "--warmup", "1")
     check_contract(r)
     assert r["attention_share_of_step"] > 0
     r = run_bench("--workload", "decode_step", "--layers", "1", "--batch", "1", "--kv", "128", "--steps", "2", "--warmup", "1",
-                  "--no-gemm-tuning", "--fused-lm-head")
+                  "--fused-lm-head")
     check_contract(r)
 
 

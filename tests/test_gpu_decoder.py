@@ -1,4 +1,4 @@
-"""Full decode step on the GPU against the fp64 decoder oracle (reduced model, bf16).
+"""Full decode step on the GPU against the fp64 decoder oracle (bf16; a reduced model, and one block at the real widths).
 
 Tolerances: the GPU rounds every GEMM output and activation to bf16 (relative
 2^-9 each) through 2 layers and the LM head, so logits carry an error of a few 1e-3 of their scale;
@@ -117,14 +117,6 @@ def test_decode_step_matches_oracle_and_commits_accepted_rows():
         max_abs, mean_rel = err.max(), err.mean() / np.abs(ref.logits).mean()
         print(f"logits: max-abs {max_abs:.3e} (scale {scale:.2f}), mean-rel {mean_rel:.3e}")
         assert max_abs <= 4e-2 * scale and mean_rel <= 2e-2
-        # the same step with the gate/up projection and SwiGLU in one GEMM of the library
-        dec_f = D.Decoder(cfg, gw, ses, B * nq, fused_mlp=True)
-        assert dec_f.fused_mlp
-        logits_f, _ = dec_f.step(ids, S.ints_dev(tokens).view(B, nq), S.ints_dev(pos).view(B, nq), nv, nf)
-        torch.cuda.synchronize()
-        err_f = np.abs(logits_f.float().cpu().numpy().reshape(B, nq, cfg.vocab).astype(np.float64) - ref.logits)
-        print(f"logits (fused MLP): max-abs {err_f.max():.3e}, mean-rel {err_f.mean() / np.abs(ref.logits).mean():.3e}")
-        assert err_f.max() <= 4e-2 * scale and err_f.mean() / np.abs(ref.logits).mean() <= 2e-2
         # LM head and greedy token in one kernel (fp32 sums, no logits): same tokens wherever the decision is clear
         dec_g = D.Decoder(cfg, gw, ses, B * nq, fused_lm_head=True)
         assert dec_g.fused_lm_head
@@ -139,7 +131,6 @@ def test_decode_step_matches_oracle_and_commits_accepted_rows():
         # on the other sequences, so the batch's reference serves
         for b in (0, 2):
             dec_1 = D.Decoder(cfg, gw, ses, nq, fused_lm_head=(b == 2))
-            assert dec_1._few(nq)
             logits_1, targets_1 = dec_1.step(ids[b:b + 1], S.ints_dev(tokens[b:b + 1]).view(1, nq), S.ints_dev(pos[b:b + 1]).view(1, nq), nv, nf)
             torch.cuda.synchronize()
             if b == 0:
