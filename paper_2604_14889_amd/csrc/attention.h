@@ -4,11 +4,11 @@
 #include <hip/hip_runtime.h>
 
 #include "memosight.h"
+#include "plan.h"
 
 namespace ms {
 
 constexpr int kMaxRowwaveSplits = 16;
-constexpr int kMaxMfmaItems = 256;   // stream-kernel workgroups per KV head
 
 // Per-call sequence ids and the cache lengths the host knows (lower bounds while device-side commits
 // are outstanding), passed by value in the kernel argument block.
@@ -47,7 +47,6 @@ int static_scratch(int device, void** ptr);
 // attention_mfma.hip
 bool mfma_eligible(const ms_cache* c, int n_q);
 size_t mfma_workspace_bytes(const ms_cache* c, int B, int n_q);
-int mfma_plan_ints(int B);
 int reset_arrival_counters(ms_cache* c, int published, hipStream_t stream);
 int launch_mfma(ms_cache* c, const AttnArgs& a, const BatchMeta& bm, int B, hipStream_t stream);
 

@@ -394,22 +394,12 @@ int reconcile(ms_cache* c) {
     std::vector<int> who(used), lens(c->d.max_seqs);
     if (used > 0) MS_HIP_TRY(hipMemcpy(who.data(), c->d_commit_state + 2, used * sizeof(int), hipMemcpyDeviceToHost));
     MS_HIP_TRY(hipMemcpy(lens.data(), c->d_len, lens.size() * sizeof(int), hipMemcpyDeviceToHost));
-    for (int k = 0; k < used; ++k) {
-        const int seq = who[k], page = c->free_list[k];
-        if (seq < 0 || seq >= c->d.max_seqs || !c->live[seq] || !c->free_pages.count(page))
-            MS_FAIL(MS_ERR_HIP, "device-side commit state is corrupt (page %d to sequence %d)", page, seq);
-        c->free_pages.erase(page);
-        c->pt[seq].push_back(page);
-    }
-    for (int s = 0; s < c->d.max_seqs; ++s)
-        if (c->live[s]) c->len[s] = lens[s];
-    const int in_use = c->d.n_pages - (int)c->free_pages.size();
-    if (in_use > c->peak_pages) c->peak_pages = in_use;
+    if (!c->apply_device_commits(who.data(), used, c->free_list, lens.data()))
+        MS_FAIL(MS_ERR_HIP, "device-side commit state is corrupt (a page of the log is not free, or its sequence is not live)");
     c->pending_growth.assign(c->d.max_seqs, 0);
     c->reserved_pages = 0;
     c->free_list_valid = false;
     c->deferred = false;
-    c->version++;
     return MS_OK;
 }
 
@@ -420,43 +410,7 @@ int reconcile(ms_cache* c) {
         (c)->free_list_valid = false;        \
     } while (0)
 
-static int take_page(ms_cache* c, int seq) {
-    c->version++;
-    int page = *c->free_pages.begin();
-    c->free_pages.erase(c->free_pages.begin());
-    c->pending_pt.push_back(seq);
-    c->pending_pt.push_back((int)c->pt[seq].size());
-    c->pending_pt.push_back(page);
-    c->pt[seq].push_back(page);
-    int in_use = c->d.n_pages - (int)c->free_pages.size();
-    if (in_use > c->peak_pages) c->peak_pages = in_use;
-    return page;
-}
-
-// Queues the sequence's current length for the device copy of the lengths.
-static void note_len(ms_cache* c, int seq) {
-    // one entry per sequence: the patch kernel writes the entries of a batch in no particular order
-    for (size_t i = 0; i + 2 < c->pending_pt.size(); i += 3)
-        if (c->pending_pt[i] == seq && c->pending_pt[i + 1] == -1) {
-            c->pending_pt[i + 2] = c->len[seq];
-            return;
-        }
-    c->pending_pt.push_back(seq);
-    c->pending_pt.push_back(-1);
-    c->pending_pt.push_back(c->len[seq]);
-}
-
-// Grows `seq` by n rows (pages first-fit lowest); the caller has verified capacity.
-static void grow(ms_cache* c, int seq, int n) {
-    c->version++;
-    for (int j = 0; j < n; ++j) {
-        if (c->len[seq] % MS_PAGE_SIZE == 0) take_page(c, seq);
-        c->len[seq]++;
-    }
-    if (n > 0) note_len(c, seq);
-}
-
-static inline int pages_for(long n) { return (int)((n + MS_PAGE_SIZE - 1) / MS_PAGE_SIZE); }
+static inline int pages_for(long n) { return HostTables::pages_for(n); }
 
 template <typename F>
 static int dispatch(const ms_cache* c, F&& f) {
@@ -592,10 +546,7 @@ int ms_cache_create(const ms_cache_desc* desc, ms_cache** out) {
     c->esize = desc->dtype == MS_F32 ? 4 : 2;
     c->page_elems = (size_t)desc->n_kv_heads * 2 * MS_PAGE_SIZE * desc->head_dim;
     c->layer_elems = c->page_elems * desc->n_pages;
-    for (int p = 0; p < desc->n_pages; ++p) c->free_pages.insert(c->free_pages.end(), p);
-    c->pt.assign(desc->max_seqs, {});
-    c->len.assign(desc->max_seqs, 0);
-    c->live.assign(desc->max_seqs, 0);
+    c->init_tables(desc->n_pages, desc->max_seqs, desc->max_pages_per_seq);
     auto fail = [&](int code) {
         ms_cache_destroy(c);
         return code;
@@ -673,16 +624,11 @@ int ms_cache_destroy(ms_cache* c) {
 int ms_seq_create(ms_cache* c, int* seq_id) {
     if (!c || !seq_id) MS_FAIL(MS_ERR_INVALID, "ms_seq_create: null argument");
     MS_RECONCILE(c);
-    for (int s = 0; s < c->d.max_seqs; ++s)
-        if (!c->live[s]) {
-            c->version++;
-            c->live[s] = 1;
-            c->len[s] = 0;
-            c->pt[s].clear();
-            note_len(c, s);
-            *seq_id = s;
-            return MS_OK;
-        }
+    const int s = c->create_seq();
+    if (s >= 0) {
+        *seq_id = s;
+        return MS_OK;
+    }
     MS_FAIL(MS_ERR_INVALID, "ms_seq_create: all %d sequence ids are in use", c->d.max_seqs);
 }
 
@@ -693,26 +639,11 @@ int ms_seq_import(ms_cache* c, int length, const int* pages, int n_pages, int* s
     MS_RECONCILE(c);
     if (n_pages > c->d.max_pages_per_seq)
         MS_FAIL(MS_ERR_OOM_PAGES, "ms_seq_import: %d pages exceed max_pages_per_seq %d", n_pages, c->d.max_pages_per_seq);
-    std::set<int> seen;
-    for (int i = 0; i < n_pages; ++i) {
-        if (pages[i] < 0 || pages[i] >= c->d.n_pages || !c->free_pages.count(pages[i]) || !seen.insert(pages[i]).second)
-            MS_FAIL(MS_ERR_INVALID, "ms_seq_import: page %d is not free or is listed twice", pages[i]);
-    }
+    if (!c->pages_importable(pages, n_pages)) MS_FAIL(MS_ERR_INVALID, "ms_seq_import: a listed page is not free, out of range or listed twice");
     int s = -1;
     int rc = ms_seq_create(c, &s);
     if (rc != MS_OK) return rc;
-    for (int i = 0; i < n_pages; ++i) {
-        c->free_pages.erase(pages[i]);
-        c->pending_pt.push_back(s);
-        c->pending_pt.push_back(i);
-        c->pending_pt.push_back(pages[i]);
-        c->pt[s].push_back(pages[i]);
-    }
-    c->len[s] = length;
-    note_len(c, s);
-    c->version++;
-    int in_use = c->d.n_pages - (int)c->free_pages.size();
-    if (in_use > c->peak_pages) c->peak_pages = in_use;
+    c->import_seq(s, pages, n_pages, length);
     *seq_id = s;
     return flush_page_table_patches(c, (hipStream_t)stream);
 }
@@ -722,12 +653,7 @@ int ms_seq_free(ms_cache* c, int seq_id) {
     int rc = check_seq(c, seq_id, "ms_seq_free");
     if (rc != MS_OK) return rc;
     MS_RECONCILE(c);
-    c->version++;
-    for (int p : c->pt[seq_id]) c->free_pages.insert(p);
-    c->pt[seq_id].clear();
-    c->len[seq_id] = 0;
-    note_len(c, seq_id);
-    c->live[seq_id] = 0;
+    c->free_seq(seq_id);
     return MS_OK;
 }
 
@@ -745,14 +671,9 @@ static int append_rows(ms_cache* c, const char* what, int B, const int* seq_ids,
         if (counts[b] < 0) MS_FAIL(MS_ERR_INVALID, "%s: negative row count", what);
         extra[seq_ids[b]] += counts[b];
     }
-    for (int s = 0; s < c->d.max_seqs; ++s) {
-        if (!extra[s]) continue;
-        int np = pages_for((long)c->len[s] + extra[s]);
-        if (np > c->d.max_pages_per_seq)
-            MS_FAIL(MS_ERR_OOM_PAGES, "%s: sequence %d would need %d pages (max_pages_per_seq %d)", what, s, np,
-                    c->d.max_pages_per_seq);
-        need += np - (int)c->pt[s].size();
-    }
+    need = c->pages_needed(extra);
+    if (need < 0)
+        MS_FAIL(MS_ERR_OOM_PAGES, "%s: sequence %ld would need more than max_pages_per_seq %d pages", what, -1 - need, c->d.max_pages_per_seq);
     if (need > (long)c->free_pages.size())
         MS_FAIL(MS_ERR_OOM_PAGES, "%s: needs %ld pages, %zu free", what, need, c->free_pages.size());
     std::vector<RowDesc> desc;
@@ -761,7 +682,7 @@ static int append_rows(ms_cache* c, const char* what, int B, const int* seq_ids,
         if (counts[b] == 0) continue;
         RowDesc de{seq_ids[b], c->len[seq_ids[b]], src_first[b], total};
         desc.push_back(de);
-        grow(c, seq_ids[b], counts[b]);
+        c->grow(seq_ids[b], counts[b]);
         total += counts[b];
     }
     return patch_and_scatter(c, desc, total, k, v, pos, buf_layer_rows, rope, stream);
@@ -1000,23 +921,19 @@ int ms_compact_segment(ms_cache* c, int B, const int* seq_ids, const int* seg_be
         const int s = seq_ids[b];
         const int L = c->len[s];
         const int t = L - seg_begin[b] - seg_len[b];
-        const int keep = pages_for(seg_begin[b]);
-        c->version++;
-        for (size_t i = keep; i < c->pt[s].size(); ++i) c->free_pages.insert(c->pt[s][i]);
-        c->pt[s].resize(keep);
-        c->len[s] = seg_begin[b];
+        c->cut_to(s, seg_begin[b]);
         if (n_mem[b] > 0) {
             mems.push_back(RowDesc{s, c->len[s], moff, mprefix});
             mprefix += n_mem[b];
         }
-        grow(c, s, n_mem[b]);
+        c->grow(s, n_mem[b]);
         moff += n_mem[b];
         if (t > 0) {
             tails_dst.push_back(RowDesc{s, c->len[s], tp2, tp2});
             tp2 += t;
         }
-        grow(c, s, t);
-        note_len(c, s);
+        c->grow(s, t);
+        c->note_len(s);
     }
     // ---- 3. scatter memory rows (rotated at their UPL position ids), then the saved tails ----
     if (total_tail == 0 && total_mem > 0)
@@ -1073,23 +990,8 @@ int ms_check_integrity(ms_cache* c, void* stream) {
     if (!c) MS_FAIL(MS_ERR_INVALID, "ms_check_integrity: null cache");
     if (int rc = reconcile(c)) return rc;
     if (int rc = flush_page_table_patches(c, (hipStream_t)stream)) return rc;   // lengths of sequences created or freed since
-    std::vector<char> owner(c->d.n_pages, 0);
-    for (int s = 0; s < c->d.max_seqs; ++s) {
-        if (!c->live[s]) {
-            if (!c->pt[s].empty()) MS_FAIL(MS_ERR_INVALID, "integrity: dead sequence %d owns pages", s);
-            continue;
-        }
-        if ((int)c->pt[s].size() != pages_for(c->len[s]))
-            MS_FAIL(MS_ERR_INVALID, "integrity: sequence %d has %zu pages for %d rows", s, c->pt[s].size(), c->len[s]);
-        for (int p : c->pt[s]) {
-            if (p < 0 || p >= c->d.n_pages) MS_FAIL(MS_ERR_INVALID, "integrity: page id %d out of range", p);
-            if (owner[p]++) MS_FAIL(MS_ERR_INVALID, "integrity: page %d owned twice", p);
-        }
-    }
-    for (int p : c->free_pages)
-        if (owner[p]++) MS_FAIL(MS_ERR_INVALID, "integrity: page %d both free and owned", p);
-    for (int p = 0; p < c->d.n_pages; ++p)
-        if (!owner[p]) MS_FAIL(MS_ERR_INVALID, "integrity: page %d leaked", p);
+    const std::string fault = c->check_tables();
+    if (!fault.empty()) MS_FAIL(MS_ERR_INVALID, "integrity: %s", fault.c_str());
     if (!c->pending_pt.empty()) MS_FAIL(MS_ERR_INVALID, "integrity: page-table patches not flushed");
     MS_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
     if (__atomic_load_n(c->h_error, __ATOMIC_RELAXED) != 0)   // left set: the next attention call reports and clears it too

@@ -7,6 +7,7 @@
 #include <set>
 #include <vector>
 
+#include "host_tables.h"
 #include "memosight.h"
 
 namespace ms {
@@ -58,18 +59,15 @@ struct RowDesc {
 
 }  // namespace ms
 
-struct ms_cache {
+// The host tables (page tables, free pages, lengths, queued mirror updates, version) are the base
+// class: plain C++ that also builds for the CPU alone.
+struct ms_cache : ms::HostTables {
     ms_cache_desc d;
     int device = 0;
     int group = 1;               // query heads per KV head
     size_t esize = 2;            // bytes per element
     size_t page_elems = 0;       // elements per page (all heads, K and V)
     size_t layer_elems = 0;      // elements per layer
-    std::set<int> free_pages;    // ordered: *begin() is the lowest free page
-    std::vector<std::vector<int>> pt;
-    std::vector<int> len;
-    std::vector<char> live;
-    int peak_pages = 0;
     int* d_pt = nullptr;         // device mirror [max_seqs][max_pages_per_seq]
     int* d_len = nullptr;        // device [max_seqs]: the sequences' lengths as the kernels see them
     // ---- device-side commits (ms_commit_accepted_device): the kernels take pages from an ordered
@@ -85,8 +83,6 @@ struct ms_cache {
     hipStream_t deferred_stream = nullptr;
     float* d_inv_freq = nullptr; // device [head_dim / 2]
     ms::StageRing stage;
-    std::vector<int> pending_pt; // (seq, index, page) triples not yet sent to the mirror
-    unsigned version = 0;        // bumped by every call that changes lengths or page tables
     int n_cus = 256;             // compute units of the device
     int* d_plan = nullptr;       // device copy of the streaming kernel's work plan
     int* d_arrive = nullptr;     // [MS_MAX_BATCH][n_kv_heads][2] counters of the streaming kernel: shares finished, partials published
