@@ -3,13 +3,22 @@
 // runs the model's projections over the few hundred tokens of a step; Section 3.1 names the models).
 //
 // Shape of the problem: M is small (batch x queries, a few hundred rows), N and K are the model's
-// widths, both operands are K-contiguous.  One workgroup of 8 waves computes a 256 (M) x 128 (N)
-// tile over a K range; grid = (column tiles x row tiles, 1, split_k).  K is walked in steps of 32:
-// both tiles go global -> registers -> LDS (row stride 80 bytes: conflict-free for the 16-byte
-// operand reads); the global loads run three steps ahead of the multiplication, one LDS-only
-// barrier per step.  A wave owns 64 (M) x 64 (N): 2 x 2 accumulator tiles of
-// v_mfma_f32_32x32x16_bf16 with W as the A operand (rows = n) and the activations as the B operand
-// (columns = m), so a lane ends up with four consecutive n of one row m per register quad.
+// widths, both operands are K-contiguous.  One workgroup of 8 waves computes a 256 (M) x 256 (N)
+// tile over a K range; grid = (column tiles x row tiles, 1, split_k); one workgroup per compute
+// unit (two waves per SIMD, up to 256 registers each).  K is walked in steps of 32: both tiles go
+// global -> registers -> LDS (two stages; row stride 80 bytes: conflict-free for the 16-byte
+// operand reads), the global loads requested two steps before they are stored.  A wave owns
+// 128 (M) x 64 (N): 2 x 4 accumulator tiles of v_mfma_f32_32x32x16_bf16 with W as the A operand
+// (rows = n) and the activations as the B operand (columns = m), so a lane ends up with four
+// consecutive n of one row m per register quad; 12 operand reads of 16 bytes feed 16
+// multiplications.
+// The two waves of a SIMD take turns: a wave's step is a data phase (its operands out of LDS into
+// registers, the staged tiles of the next step into the other LDS stage, new global loads) and a
+// multiply phase (16 matrix instructions and nothing else), with a workgroup barrier after each;
+// waves 4 .. 7 start half a step after waves 0 .. 3, so that on every SIMD one wave multiplies
+// while the other moves data.  (With all waves in the same phase at the same time, as in a plain
+// double-buffered loop, the memory instructions' time added to the matrix cores' instead of hiding
+// under it.)  Row blocks past M and column groups past N are not multiplied.
 // split_k > 1 (deep K, few output tiles: the MLP down projection) writes fp32 partials that a
 // second kernel sums, adds the bias to and rounds.  With split_k = 1 and more tiles than the chip
 // holds at once, the tiles of the last, partly filled round are split over K inside the same launch
@@ -23,6 +32,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "ms_device.h"
 #include "ms_internal.h"
 
@@ -31,11 +42,14 @@ namespace ms {
 typedef __attribute__((ext_vector_type(8))) __bf16 g_bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float g_f32x16_t;
 
-constexpr int kGemmBM = 256, kGemmBN = 128, kGemmBK = 32;
+constexpr int kGemmBM = 256, kGemmBN = 256, kGemmBK = 32;
 constexpr int kGemmThreads = 512;
 constexpr int kGemmRowBytes = kGemmBK * 2 + 16;                      // 80
-constexpr int kGemmStageBytes = (kGemmBM + kGemmBN) * kGemmRowBytes;  // 30720
+constexpr int kGemmStageBytes = (kGemmBM + kGemmBN) * kGemmRowBytes;  // 40960
+constexpr int kGemmLdsBytes = 2 * kGemmStageBytes;                   // above the 64 KB a kernel gets without asking
+constexpr int kGemmColGroup = 64;                                    // columns of a wave: granularity of N and of the destinations
 constexpr int kGemmMaxOut = 4;
+constexpr int kGemmNUnit = 128;   // N and the destinations' boundaries are multiples of this
 
 struct GemmArgs {
     const uint16_t* a;      // [M][K]
@@ -97,17 +111,103 @@ __device__ __forceinline__ void gemm_lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// The K loop of one wave for kMi row blocks of 32 that hold rows of the product (0: the wave only
+// moves data and keeps the barriers' count).
+template <int kMi>
+__device__ __forceinline__ void gemm_k_loop(char* smem, const uint16_t* const (&a_src)[2], const uint16_t* const (&w_src)[2], char* a_dst,
+                                            char* w_dst, int a_op, int w_op, int steps, int late, g_f32x16_t (&acc)[2][4]) {
+    // Two register sets of staged tiles: while step s is multiplied, the tiles of step s + 1 are
+    // stored to LDS and those of steps s + 2 and s + 3 are on their way.  Only LDS traffic is ordered
+    // by the barriers, so a data phase waits for the oldest loads alone.
+    // (plain named registers: aggregates handed around by name ended up in scratch memory)
+    uint4 r0a0, r0a1, r0w0, r0w1;
+    uint4 r1a0, r1a1, r1w0, r1w1;
+#define MS_GEMM_FETCH(R, step_)                                                 \
+    do {                                                                        \
+        const int ko_ = (step_) * kGemmBK;                                      \
+        R##a0 = *reinterpret_cast<const uint4*>(a_src[0] + ko_);                \
+        R##a1 = *reinterpret_cast<const uint4*>(a_src[1] + ko_);                \
+        R##w0 = *reinterpret_cast<const uint4*>(w_src[0] + ko_);                \
+        R##w1 = *reinterpret_cast<const uint4*>(w_src[1] + ko_);                \
+    } while (0)
+#define MS_GEMM_STASH(R, buf_)                                                  \
+    do {                                                                        \
+        char* ad_ = a_dst + (buf_) * kGemmStageBytes;                           \
+        char* wd_ = w_dst + (buf_) * kGemmStageBytes;                           \
+        *reinterpret_cast<uint4*>(ad_) = R##a0;                                 \
+        *reinterpret_cast<uint4*>(ad_ + 128 * kGemmRowBytes) = R##a1;           \
+        *reinterpret_cast<uint4*>(wd_) = R##w0;                                 \
+        *reinterpret_cast<uint4*>(wd_ + 128 * kGemmRowBytes) = R##w1;           \
+    } while (0)
+    // steps past the end re-read the last one (clamped): loads stay unconditional, nothing is used
+    const int last = steps - 1;
+#define MS_GEMM_CLAMP(s_) ((s_) < last ? (s_) : last)
+    MS_GEMM_FETCH(r0, 0);
+    MS_GEMM_FETCH(r1, MS_GEMM_CLAMP(1));
+    MS_GEMM_STASH(r0, 0);
+    MS_GEMM_FETCH(r0, MS_GEMM_CLAMP(2));
+    gemm_lds_barrier();
+    if (late) gemm_lds_barrier();   // waves 4 .. 7 run half a step behind waves 0 .. 3
+    // One turn of a wave.  Data phase: the operands of step s out of LDS stage s & 1, the staged
+    // tiles of step s + 1 (set NEXT) into the other stage - last read, as stage s - 1, by the late
+    // waves one barrier ago -, the loads of step s + 3 requested into the freed set.  Barrier.
+    // Multiply phase.  Barrier.  Every wave passes the same number of barriers (the early waves one
+    // more at the end), and between two barriers one half of the waves is in its data phase, the
+    // other in its multiply phase.  Stage s + 1 is complete one barrier after the late waves'
+    // data phase of step s, which is when the early waves first read it.
+    g_bf16x8_t wf[2][2], af[2][kMi > 0 ? kMi : 1];
+#define MS_GEMM_TURN(step_, NEXT)                                                                                           \
+    do {                                                                                                                    \
+        const char* base_ = smem + ((step_) & 1) * kGemmStageBytes;                                                         \
+        if (kMi > 0) {                                                                                                      \
+            _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                                              \
+                _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) wf[kk][ni] = __builtin_bit_cast(                           \
+                    g_bf16x8_t, *reinterpret_cast<const uint4*>(base_ + w_op + ni * 32 * kGemmRowBytes + 32 * kk));         \
+                _Pragma("unroll") for (int mi = 0; mi < kMi; ++mi) af[kk][mi] = __builtin_bit_cast(                         \
+                    g_bf16x8_t, *reinterpret_cast<const uint4*>(base_ + a_op + mi * 32 * kGemmRowBytes + 32 * kk));         \
+            }                                                                                                               \
+        }                                                                                                                   \
+        MS_GEMM_STASH(NEXT, ((step_) + 1) & 1);                                                                             \
+        MS_GEMM_FETCH(NEXT, MS_GEMM_CLAMP((step_) + 3));                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                                                                  \
+        gemm_lds_barrier();                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                                  \
+        __builtin_amdgcn_s_setprio(1);                                                                                      \
+        _Pragma("unroll") for (int kk = 0; kk < 2; ++kk)                                                                    \
+            _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) _Pragma("unroll") for (int mi = 0; mi < kMi; ++mi)             \
+                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk][ni], af[kk][mi], acc[ni][mi], 0, 0, 0);        \
+        __builtin_amdgcn_s_setprio(0);                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                                                  \
+        gemm_lds_barrier();                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                                  \
+    } while (0)
+    int step = 0;
+    for (; step + 2 <= steps; step += 2) {
+        MS_GEMM_TURN(step, r1);
+        MS_GEMM_TURN(step + 1, r0);
+    }
+    if (step < steps) MS_GEMM_TURN(step, r1);
+    if (!late) gemm_lds_barrier();
+#undef MS_GEMM_TURN
+#undef MS_GEMM_CLAMP
+#undef MS_GEMM_FETCH
+#undef MS_GEMM_STASH
+}
+
 template <int kMode>
-__global__ __launch_bounds__(kGemmThreads, 4) void gemm_tn_bf16(GemmArgs g) {
+__global__ __launch_bounds__(kGemmThreads) void gemm_tn_bf16(GemmArgs g) {
     constexpr bool kSplit = kMode == kGemmAllPartial;
-    __shared__ __attribute__((aligned(16))) char smem[2 * kGemmStageBytes];
+    extern __shared__ __attribute__((aligned(16))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = w >> 1, wn = w & 1;                  // wave tile: rows 64 wm .. + 64, columns 64 wn .. + 64
+    const int wm = w >> 2, wn = w & 3;                  // wave tile: rows 128 wm .. + 128, columns 64 wn .. + 64
+    // Waves w and w + 4 of a workgroup share a SIMD (the hardware deals a workgroup's waves out to the
+    // four SIMDs in turn): the two halves take turns at the matrix cores.
+    const int late = wm;
     // Tile mapping.  Workgroups are handed to the 8 XCDs (each with its own L2) round robin, so
     // workgroups 8 apart share an L2: the row tiles of one column tile are placed 8 apart, and the
     // weight tile they share comes from HBM once.
-    const int m_tiles = (g.M + kGemmBM - 1) / kGemmBM, n_tiles = g.N / kGemmBN;
+    const int m_tiles = (g.M + kGemmBM - 1) / kGemmBM, n_tiles = (g.N + kGemmBN - 1) / kGemmBN;
     int block = blockIdx.x, k_part = blockIdx.z, k_len = g.k_per_split;
     bool to_partial = kSplit;
     if (!kSplit && block >= g.tail_first) {   // a K part of a tile of the last round
@@ -123,108 +223,59 @@ __global__ __launch_bounds__(kGemmThreads, 4) void gemm_tn_bf16(GemmArgs g) {
     const int n0 = n_tile * kGemmBN, m0 = m_tile * kGemmBM;
     const int k_begin = k_part * k_len;
     const int steps = k_len / kGemmBK;
+    // 32-row blocks of this wave that hold rows of the product (0 if its columns lie past N)
+    int mi_n = (g.M - m0 - 128 * wm + 31) / 32;
+    mi_n = mi_n < 0 ? 0 : (mi_n > 4 ? 4 : mi_n);
+    if (n0 + kGemmColGroup * wn >= g.N) mi_n = 0;
 
     // global -> LDS staging.  Four consecutive threads bring the 64 bytes one row contributes to a
     // step, so a load instruction of a wave covers 16 rows x 64 contiguous bytes; thread t handles
-    // chunk t % 4 of activation rows r and r + 128 and of weight row r, r = t / 4 up to the order below.
-    // Rows past M are clamped (read again, never stored).
+    // chunk t % 4 of activation rows r and r + 128 and of weight rows r and r + 128, r = t / 4 up to the
+    // order below.  Rows past M or N are clamped (read again, never stored to the product).
     // Within each block of 16 rows the 4 x 4 (lane group, row) order is transposed: the 16 lanes that
     // store together then hold rows r, r + 4, r + 8, r + 12, whose 80-byte strides put their four
     // 16-byte chunks on 16 different groups of 4 banks (rows r .. r + 3 would collide two ways).
     const int sr_lin = tid >> 2, sc = tid & 3;
     const int sr = (sr_lin & ~15) | ((sr_lin & 3) << 2) | ((sr_lin >> 2) & 3);
     const uint16_t* a_src[2];
+    const uint16_t* w_src[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int row = m0 + sr + 128 * i < g.M ? m0 + sr + 128 * i : g.M - 1;
         a_src[i] = g.a + (size_t)row * g.K + k_begin + 8 * sc;
+        const int col = n0 + sr + 128 * i < g.N ? n0 + sr + 128 * i : g.N - 1;
+        w_src[i] = g.w + (size_t)col * g.K + k_begin + 8 * sc;
     }
-    const uint16_t* w_src = g.w + (size_t)(n0 + sr) * g.K + k_begin + 8 * sc;
     char* a_dst = smem + sr * kGemmRowBytes + 16 * sc;
     char* w_dst = smem + kGemmBM * kGemmRowBytes + sr * kGemmRowBytes + 16 * sc;
 
-    // Three register sets of staged tiles: while step s is multiplied out of LDS, the tiles of
-    // steps s + 1 and s + 2 are in registers or on their way and those of s + 3 are requested.  Only
-    // LDS traffic is ordered by the barriers, so a step waits for the oldest loads alone.
-    // (plain named registers: aggregates handed around by name ended up in scratch memory)
-    uint4 r0a0, r0a1, r0w0;
-    uint4 r1a0, r1a1, r1w0;
-    uint4 r2a0, r2a1, r2w0;
-#define MS_GEMM_FETCH(R, step_)                                                 \
-    do {                                                                        \
-        const int ko_ = (step_) * kGemmBK;                                      \
-        R##a0 = *reinterpret_cast<const uint4*>(a_src[0] + ko_);                \
-        R##a1 = *reinterpret_cast<const uint4*>(a_src[1] + ko_);                \
-        R##w0 = *reinterpret_cast<const uint4*>(w_src + ko_);                   \
-    } while (0)
-#define MS_GEMM_STASH(R, buf_)                                                  \
-    do {                                                                        \
-        char* ad_ = a_dst + (buf_) * kGemmStageBytes;                           \
-        char* wd_ = w_dst + (buf_) * kGemmStageBytes;                           \
-        *reinterpret_cast<uint4*>(ad_) = R##a0;                                 \
-        *reinterpret_cast<uint4*>(ad_ + 128 * kGemmRowBytes) = R##a1;           \
-        *reinterpret_cast<uint4*>(wd_) = R##w0;                                 \
-    } while (0)
-
-    g_f32x16_t acc[2][2];
+    g_f32x16_t acc[2][4];
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
+        for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[ni][mi][i] = 0.f;
 
     // operand addresses inside a stage: 16 bytes at k = 16 kk + 8 (lane / 32) of row (lane % 32)
-    const int a_op = (64 * wm + l32) * kGemmRowBytes + 16 * hf;
-    const int w_op = kGemmBM * kGemmRowBytes + (64 * wn + l32) * kGemmRowBytes + 16 * hf;
+    const int a_op = (128 * wm + l32) * kGemmRowBytes + 16 * hf;
+    const int w_op = kGemmBM * kGemmRowBytes + (kGemmColGroup * wn + l32) * kGemmRowBytes + 16 * hf;
 
-    // steps past the end re-read the last one (clamped): loads stay unconditional, nothing is used
-    const int last = steps - 1;
-#define MS_GEMM_CLAMP(s_) ((s_) < last ? (s_) : last)
-    MS_GEMM_FETCH(r0, 0);
-    MS_GEMM_FETCH(r1, MS_GEMM_CLAMP(1));
-    MS_GEMM_FETCH(r2, MS_GEMM_CLAMP(2));
-    MS_GEMM_STASH(r0, 0);
-    gemm_lds_barrier();
-    // one pipeline turn: multiply step s out of LDS[s & 1], request step s + 3 into the set that
-    // step s came from (FREE), move step s + 1 (NEXT) into the other LDS stage
-#define MS_GEMM_TURN(step_, FREE, NEXT)                                                                                     \
-    do {                                                                                                                    \
-        MS_GEMM_FETCH(FREE, MS_GEMM_CLAMP((step_) + 3));                                                                    \
-        const char* base_ = smem + ((step_) & 1) * kGemmStageBytes;                                                         \
-        _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                                                  \
-            g_bf16x8_t wf[2], af[2];                                                                                        \
-            _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) wf[ni] = __builtin_bit_cast(                                   \
-                g_bf16x8_t, *reinterpret_cast<const uint4*>(base_ + w_op + ni * 32 * kGemmRowBytes + 32 * kk));             \
-            _Pragma("unroll") for (int mi = 0; mi < 2; ++mi) af[mi] = __builtin_bit_cast(                                   \
-                g_bf16x8_t, *reinterpret_cast<const uint4*>(base_ + a_op + mi * 32 * kGemmRowBytes + 32 * kk));             \
-            _Pragma("unroll") for (int ni = 0; ni < 2; ++ni) _Pragma("unroll") for (int mi = 0; mi < 2; ++mi)               \
-                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], af[mi], acc[ni][mi], 0, 0, 0);                \
-        }                                                                                                                   \
-        MS_GEMM_STASH(NEXT, ((step_) + 1) & 1); /* that stage was last read before the previous barrier */                  \
-        gemm_lds_barrier();                                                                                                 \
-    } while (0)
-    int step = 0;
-    for (; step + 3 <= steps; step += 3) {
-        MS_GEMM_TURN(step, r0, r1);
-        MS_GEMM_TURN(step + 1, r1, r2);
-        MS_GEMM_TURN(step + 2, r2, r0);
+    switch (mi_n) {   // uniform in the wave
+        case 4: gemm_k_loop<4>(smem, a_src, w_src, a_dst, w_dst, a_op, w_op, steps, late, acc); break;
+        case 3: gemm_k_loop<3>(smem, a_src, w_src, a_dst, w_dst, a_op, w_op, steps, late, acc); break;
+        case 2: gemm_k_loop<2>(smem, a_src, w_src, a_dst, w_dst, a_op, w_op, steps, late, acc); break;
+        case 1: gemm_k_loop<1>(smem, a_src, w_src, a_dst, w_dst, a_op, w_op, steps, late, acc); break;
+        default: gemm_k_loop<0>(smem, a_src, w_src, a_dst, w_dst, a_op, w_op, steps, late, acc); break;
     }
-    if (step < steps) {
-        MS_GEMM_TURN(step, r0, r1);
-        if (step + 1 < steps) MS_GEMM_TURN(step + 1, r1, r2);
-    }
-#undef MS_GEMM_TURN
-#undef MS_GEMM_CLAMP
-#undef MS_GEMM_FETCH
-#undef MS_GEMM_STASH
+    if (mi_n == 0) return;   // nothing of the product in this wave's tile (no barrier follows)
 
     // accumulator i of a lane: n = 8 (i / 4) + 4 (lane / 32) + i % 4, m = lane % 32 (within the 32 x 32 tile)
     if (to_partial) {
         const int p_col0 = kSplit ? 0 : g.tail_col0, p_ld = g.N - p_col0;
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-            const int m = m0 + 64 * wm + 32 * mi + l32;
+        for (int mi = 0; mi < 4; ++mi) {
+            const int m = m0 + 128 * wm + 32 * mi + l32;
             if (m >= g.M) continue;
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)
@@ -241,7 +292,7 @@ __global__ __launch_bounds__(kGemmThreads, 4) void gemm_tn_bf16(GemmArgs g) {
         // group = (column tile, wave column): 64 columns; a lane first folds its 32 of them, then the
         // two half-waves (same row m, the other 4-column pieces) are folded through a lane exchange
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
+        for (int mi = 0; mi < 4; ++mi) {
             unsigned long long best = 0ull;
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)
@@ -250,8 +301,8 @@ __global__ __launch_bounds__(kGemmThreads, 4) void gemm_tn_bf16(GemmArgs g) {
                     best = key_max(best, argmax_key(acc[ni][mi][i], n0 + 64 * wn + 32 * ni + 8 * (i >> 2) + 4 * hf + (i & 3)));
             const uint32_t lo = __shfl_xor((int)(uint32_t)best, 32, 64), hi = __shfl_xor((int)(uint32_t)(best >> 32), 32, 64);
             best = key_max(best, ((unsigned long long)hi << 32) | lo);
-            const int m = m0 + 64 * wm + 32 * mi + l32;
-            if (m < g.M && hf == 0) g.keys[(size_t)(n_tile * 2 + wn) * g.M + m] = best;
+            const int m = m0 + 128 * wm + 32 * mi + l32;
+            if (m < g.M && hf == 0) g.keys[(size_t)(n_tile * 4 + wn) * g.M + m] = best;
         }
         return;
     }
@@ -259,8 +310,8 @@ __global__ __launch_bounds__(kGemmThreads, 4) void gemm_tn_bf16(GemmArgs g) {
         // weight rows 64 wn .. + 32 of the tile are gate rows, the next 32 the matching up rows:
         // accumulators [0][mi] and [1][mi] hold gate and up of output column n0 / 2 + 32 wn + ...
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-            const int m = m0 + 64 * wm + 32 * mi + l32;
+        for (int mi = 0; mi < 4; ++mi) {
+            const int m = m0 + 128 * wm + 32 * mi + l32;
             if (m >= g.M) continue;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -275,12 +326,12 @@ __global__ __launch_bounds__(kGemmThreads, 4) void gemm_tn_bf16(GemmArgs g) {
         }
         return;
     }
-    uint16_t* dst = nullptr;   // the whole tile goes to one destination: boundaries are multiples of 128
+    uint16_t* dst = nullptr;   // a wave's columns go to one destination: boundaries are multiples of 64
     int col0 = 0, ld = 0;
-    pick_destination(g, n0, dst, col0, ld);
+    pick_destination(g, n0 + kGemmColGroup * wn, dst, col0, ld);
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-        const int m = m0 + 64 * wm + 32 * mi + l32;
+    for (int mi = 0; mi < 4; ++mi) {
+        const int m = m0 + 128 * wm + 32 * mi + l32;
         if (m >= g.M) continue;
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
@@ -625,7 +676,8 @@ __global__ __launch_bounds__(kSkinnyThreads) void skinny_mfma_bf16(GemmArgs g, i
 
 static bool g_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Workgroups the chip holds at once (two per compute unit), for the current device.
+// Twice the compute units of the current device (the few-row kernel's workgroups per round; the
+// tiled kernel runs one workgroup per compute unit).
 static int gemm_slots() {
     static int cached[64] = {};
     int dev = 0;
@@ -650,14 +702,14 @@ struct GemmPlan {
 static GemmPlan gemm_plan(int M, int N, int K, int split_k) {
     GemmPlan p;
     p.m_tiles = (M + kGemmBM - 1) / kGemmBM;
-    p.n_groups = (N / kGemmBN + 7) / 8;
+    p.n_groups = ((N + kGemmBN - 1) / kGemmBN + 7) / 8;
     p.group_blocks = 8 * p.m_tiles;
     p.main_groups = p.n_groups;
     p.tail_groups = 0;
     p.tail_split = 1;
     p.workspace_bytes = split_k > 1 ? (size_t)split_k * M * N * sizeof(float) : 0;
     if (split_k != 1) return p;
-    const int per_round = gemm_slots() / p.group_blocks;
+    const int per_round = gemm_slots() / 2 / p.group_blocks;
     if (per_round < 1 || p.n_groups <= per_round) return p;
     const int rem = p.n_groups % per_round;
     if (rem == 0 || 10 * rem > 6 * per_round) return p;
@@ -748,10 +800,10 @@ static int skinny_dispatch(const GemmArgs& g, const SkinnyPlan& v, hipStream_t s
 
 static int gemm_check_shape(const char* what, int M, int N, int K, int split_k) {
     if (M < 0 || N < 1 || K < 1 || split_k < 1) MS_FAIL(MS_ERR_INVALID, "%s: bad size", what);
-    if (N % kGemmBN || K % (kGemmBK * split_k))
-        MS_FAIL(MS_ERR_UNSUPPORTED, "%s: N must be a multiple of %d and K of %d x split_k", what, kGemmBN, kGemmBK);
+    if (N % kGemmNUnit || K % (kGemmBK * split_k))
+        MS_FAIL(MS_ERR_UNSUPPORTED, "%s: N must be a multiple of %d and K of %d x split_k", what, kGemmNUnit, kGemmBK);
     if ((long long)M * N >= (1ll << 40) || split_k > 64 ||
-        (long long)((N / kGemmBN + 7) / 8) * 8 * ((M + kGemmBM - 1) / kGemmBM) * 9 > 2000000000ll)
+        (long long)((N / kGemmNUnit + 7) / 8) * 8 * ((M + kGemmBM - 1) / kGemmBM) * 9 > 2000000000ll)
         MS_FAIL(MS_ERR_UNSUPPORTED, "%s: shape too large", what);
     return MS_OK;
 }
@@ -764,6 +816,25 @@ struct NormTail {
     float eps;
     uint16_t* out;
 };
+
+// The tiled kernel's two LDS stages (80 KB) are above the default limit: allowed once per device.
+static int gemm_allow_lds() {
+    static std::once_flag once[64];
+    static hipError_t result[64];
+    int dev = 0;
+    MS_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) MS_FAIL(MS_ERR_UNSUPPORTED, "device index %d outside [0, 64)", dev);
+    std::call_once(once[dev], [&] {
+        hipError_t e = hipSuccess;
+        const void* builds[] = {(const void*)gemm_tn_bf16<kGemmPlain>, (const void*)gemm_tn_bf16<kGemmAllPartial>,
+                                (const void*)gemm_tn_bf16<kGemmSwiglu>, (const void*)gemm_tn_bf16<kGemmArgmax>};
+        for (const void* f : builds)
+            if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+        result[dev] = e;
+    });
+    if (result[dev] != hipSuccess) MS_FAIL(MS_ERR_HIP, "hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed: %s", hipGetErrorString(result[dev]));
+    return MS_OK;
+}
 
 // Launches the tiles (and the reduction of the parts, if any).  g holds operands and destinations.
 static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, size_t ws_bytes, hipStream_t stream,
@@ -798,6 +869,7 @@ static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, s
             return MS_OK;
         }
     }
+    if (int rc = gemm_allow_lds()) return rc;
     GemmPlan p = gemm_plan(g.M, g.N, g.K, split_k);
     if (split_k == 1 && p.tail_groups && (!workspace || ws_bytes < p.workspace_bytes || !g_aligned16(workspace))) {
         p.main_groups = p.n_groups;   // no room for the parts: whole tiles throughout
@@ -817,7 +889,7 @@ static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, s
             MS_FAIL(MS_ERR_WORKSPACE, "ms_gemm_bf16: split-K workspace of %zu bytes needed", p.workspace_bytes);
         g.partial = (float*)workspace;
         g.tail_first = (int)grid.x;   // unused by this build of the kernel
-        hipLaunchKernelGGL((gemm_tn_bf16<kGemmAllPartial>), grid, dim3(kGemmThreads), 0, stream, g);
+        hipLaunchKernelGGL((gemm_tn_bf16<kGemmAllPartial>), grid, dim3(kGemmThreads), kGemmLdsBytes, stream, g);
         if (norm) {
             hipLaunchKernelGGL(reduce_add_rmsnorm, dim3((unsigned)g.M), dim3(kNormThreads), 0, stream, (const float*)g.partial, split_k,
                                g.M, g.N, norm->h, norm->weight, norm->eps, norm->out);
@@ -829,9 +901,9 @@ static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, s
         if (norm) MS_FAIL(MS_ERR_INVALID, "ms_gemm_add_rmsnorm_bf16: split_k >= 2 needed above %d rows", kSkinnyMaxRows);
         if (p.tail_groups) g.partial = (float*)workspace;
         if (swiglu)
-            hipLaunchKernelGGL((gemm_tn_bf16<kGemmSwiglu>), grid, dim3(kGemmThreads), 0, stream, g);
+            hipLaunchKernelGGL((gemm_tn_bf16<kGemmSwiglu>), grid, dim3(kGemmThreads), kGemmLdsBytes, stream, g);
         else
-            hipLaunchKernelGGL((gemm_tn_bf16<kGemmPlain>), grid, dim3(kGemmThreads), 0, stream, g);
+            hipLaunchKernelGGL((gemm_tn_bf16<kGemmPlain>), grid, dim3(kGemmThreads), kGemmLdsBytes, stream, g);
         if (p.tail_groups) {
             const size_t quads = (size_t)g.M * (g.N - g.tail_col0) / (swiglu ? 8 : 4);
             const dim3 rgrid((unsigned)((quads + 255) / 256));
@@ -848,7 +920,7 @@ static int gemm_launch(GemmArgs& g, int split_k, bool swiglu, void* workspace, s
 }  // namespace ms
 
 extern "C" size_t ms_gemm_workspace_bytes(int M, int N, int K, int split_k) {
-    if (M < 1 || N < 1 || K < 1 || split_k < 1 || N % ms::kGemmBN || K % (ms::kGemmBK * split_k)) return 0;
+    if (M < 1 || N < 1 || K < 1 || split_k < 1 || N % ms::kGemmNUnit || K % (ms::kGemmBK * split_k)) return 0;
     const size_t tiled = ms::gemm_plan(M, N, K, split_k).workspace_bytes;
     const size_t few = ms::skinny_plan(M, N, K).workspace_bytes;   // enough for either kernel
     return tiled > few ? tiled : few;
@@ -874,9 +946,9 @@ extern "C" int ms_gemm_bf16(const void* a, const void* w, const void* bias, int 
     g.keys = nullptr;
     if (out_col[0] != 0 || out_col[n_out] != N) MS_FAIL(MS_ERR_INVALID, "ms_gemm_bf16: destinations must cover columns 0 .. N");
     for (int i = 0; i < n_out; ++i) {
-        if (out_col[i + 1] <= out_col[i] || out_col[i] % kGemmBN || !out[i] || (reinterpret_cast<uintptr_t>(out[i]) & 7u) ||
+        if (out_col[i + 1] <= out_col[i] || out_col[i] % kGemmNUnit || !out[i] || (reinterpret_cast<uintptr_t>(out[i]) & 7u) ||
             (out_col[i + 1] - out_col[i]) % 4)
-            MS_FAIL(MS_ERR_INVALID, "ms_gemm_bf16: destination %d: boundaries must rise in multiples of %d, pointers be 8-byte aligned", i, kGemmBN);
+            MS_FAIL(MS_ERR_INVALID, "ms_gemm_bf16: destination %d: boundaries must rise in multiples of %d, pointers be 8-byte aligned", i, kGemmNUnit);
         g.out[i] = (uint16_t*)out[i];
         g.out_col[i] = out_col[i];
     }
@@ -889,7 +961,7 @@ extern "C" int ms_gemm_bf16(const void* a, const void* w, const void* bias, int 
 }
 
 extern "C" size_t ms_gemm_add_rmsnorm_workspace_bytes(int M, int N, int K, int split_k) {
-    if (M < 1 || N < 1 || K < 1 || split_k < 1 || N % ms::kGemmBN || K % (ms::kGemmBK * split_k)) return 0;
+    if (M < 1 || N < 1 || K < 1 || split_k < 1 || N % ms::kGemmNUnit || K % (ms::kGemmBK * split_k)) return 0;
     const size_t tiled = split_k > 1 ? ms::gemm_plan(M, N, K, split_k).workspace_bytes : 0;
     const size_t few = ms::skinny_plan(M, N, K, 2).workspace_bytes;
     return tiled > few ? tiled : few;
@@ -958,11 +1030,11 @@ extern "C" int ms_gemm_swiglu_bf16(const void* a, const void* w_gate_up, int M, 
 // Column groups that leave a key per row in greedy-token mode, for the kernel the shape runs on.
 static int argmax_groups(int M, int N, int K) {
     const ms::SkinnyPlan sk = ms::skinny_plan(M, N, K);
-    return sk.parts == 1 ? N / (16 * sk.nt) : N / ms::kGemmBN * 2;
+    return sk.parts == 1 ? N / (16 * sk.nt) : N / ms::kGemmColGroup;
 }
 
 extern "C" size_t ms_lm_head_argmax_workspace_bytes(int M, int vocab, int K) {
-    if (M < 1 || vocab < 1 || K < 1 || vocab % ms::kGemmBN || K % ms::kGemmBK) return 0;
+    if (M < 1 || vocab < 1 || K < 1 || vocab % ms::kGemmNUnit || K % ms::kGemmBK) return 0;
     return (size_t)argmax_groups(M, vocab, K) * M * sizeof(unsigned long long);
 }
 
@@ -998,13 +1070,15 @@ extern "C" int ms_lm_head_argmax_bf16(const void* a, const void* w, int M, int v
         rc = skinny_dispatch(g, sk, stream);
         if (rc != MS_OK) return rc;
     } else {
+        rc = gemm_allow_lds();
+        if (rc != MS_OK) return rc;
         const GemmPlan p = gemm_plan(M, vocab, K, 1);
         const int blocks = p.n_groups * p.group_blocks;   // whole tiles throughout
         g.tail_first = blocks;
         g.tail_blocks = 0;
         g.tail_k = K;
         g.tail_col0 = vocab;
-        hipLaunchKernelGGL((gemm_tn_bf16<kGemmArgmax>), dim3((unsigned)blocks), dim3(kGemmThreads), 0, stream, g);
+        hipLaunchKernelGGL((gemm_tn_bf16<kGemmArgmax>), dim3((unsigned)blocks), dim3(kGemmThreads), kGemmLdsBytes, stream, g);
     }
     hipLaunchKernelGGL(argmax_finish, dim3((unsigned)M), dim3(256), 0, stream, (const unsigned long long*)workspace, groups, M, out);
     MS_HIP_TRY(hipGetLastError());
