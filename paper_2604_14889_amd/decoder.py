@@ -114,22 +114,28 @@ class Decoder:
         self._kv = {}             # rows -> (k_new, v_new), each [L, rows, Hkv*D] contiguous for the commit
         self._prepared = {}       # rows -> prepared argument tuples of the library calls
         self.attn = buf(max_rows, qd)
-        self.proj = buf(max_rows, cfg.hidden)
         self.act = buf(max_rows, cfg.inter)
         self.logits = None if fused_lm_head else buf(max_rows, self.vocab_pad)
         self.targets = buf(max_rows, dtype=torch.int32)
-        # K is split further when a step has few rows (one row tile: half as many workgroups);
-        # measured at Qwen2.5-7B widths: Q/K/V 4 ways up to 256 rows, 2 above; output 4; down 8 and 4
-        self.splits_few, self.splits_many = (4, 4, 8), (2, 4, 4)
+        # K is divided over workgroups where a projection has few output tiles (one 256 x 256 tile per
+        # workgroup, one workgroup per compute unit); measured at Qwen2.5-7B widths: Q/K/V 7 ways up to
+        # 256 rows (one row tile) and 4 above, output 8 and 4, down 16 and 8.  Other widths take the
+        # largest divisor of their K steps below those.
+        def split(k, want):
+            steps = k // 32
+            return max(s for s in range(1, want + 1) if steps % s == 0 and (s == 1 or steps // s >= 4))
+        self.splits_few = (split(cfg.hidden, 7), max(2, split(qd, 8)), max(2, split(cfg.inter, 16)))
+        self.splits_many = (split(cfg.hidden, 4), max(2, split(qd, 4)), max(2, split(cfg.inter, 8)))
         rows_few = range(1, min(max_rows, 16) + 1)
         need = max([M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, cfg.hidden, self.splits_few[0]),
-                    M.ms_gemm_workspace_bytes(max_rows, cfg.hidden, qd, self.splits_few[1]),
+                    M.ms_gemm_add_rmsnorm_workspace_bytes(max_rows, cfg.hidden, qd, self.splits_few[1]),
                     M.ms_gemm_workspace_bytes(max_rows, 2 * cfg.inter, cfg.hidden, 1),
                     M.ms_gemm_workspace_bytes(max_rows, self.vocab_pad, cfg.hidden, 1),
                     M.ms_gemm_add_rmsnorm_workspace_bytes(max_rows, cfg.hidden, cfg.inter, self.splits_few[2])] +
                    [M.ms_gemm_workspace_bytes(r, n, k, 1) for r in rows_few
-                    for n, k in ((qd + 2 * kd, cfg.hidden), (cfg.hidden, qd), (2 * cfg.inter, cfg.hidden), (self.vocab_pad, cfg.hidden))] +
-                   [M.ms_gemm_add_rmsnorm_workspace_bytes(r, cfg.hidden, cfg.inter, self.splits_few[2]) for r in rows_few])
+                    for n, k in ((qd + 2 * kd, cfg.hidden), (2 * cfg.inter, cfg.hidden), (self.vocab_pad, cfg.hidden))] +
+                   [M.ms_gemm_add_rmsnorm_workspace_bytes(r, cfg.hidden, k, s) for r in rows_few
+                    for k, s in ((qd, self.splits_few[1]), (cfg.inter, self.splits_few[2]))])
         self.gemm_ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
         self.lm_ws = None
         if fused_lm_head:
@@ -143,24 +149,22 @@ class Decoder:
         cfg, w = self.cfg, self.w
         ptr = lambda t: t.data_ptr()
         qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
-        h, x, q, attn, proj, act = (ptr(t) for t in (self.h, self.x, self.q, self.attn, self.proj, self.act))
+        h, x, q, attn, act = (ptr(t) for t in (self.h, self.x, self.q, self.attn, self.act))
         k_all, v_all = self._kv[rows]
         ws, ws_bytes = ptr(self.gemm_ws), self.gemm_ws.numel()
         qkv_split, o_split, down_split = self.splits_few if rows <= 256 else self.splits_many
         cols_qkv = M.int_array([0, qd, qd + kd, qd + 2 * kd])
-        cols_h = M.int_array([0, cfg.hidden])
-        outs_proj = (C.c_void_p * 1)(proj)
         layers = []
         for li, lw in enumerate(w.layers):
             k, v = ptr(k_all[li]), ptr(v_all[li])
             layers.append(dict(
-                keep=(outs_proj, cols_qkv, cols_h),
-                norm1=(h, proj if li else None, ptr(lw.ln1), cfg.eps, x, rows, cfg.hidden),
+                keep=(cols_qkv,),
+                norm1=(h, None, ptr(lw.ln1), cfg.eps, x, rows, cfg.hidden),   # used by the first block only
                 qkv=(x, ptr(lw.wqkv), ptr(lw.bqkv), rows, qd + 2 * kd, cfg.hidden, 3, (C.c_void_p * 3)(q, k, v), cols_qkv,
                      qkv_split, ws, ws_bytes),
                 k=k, v=v,
-                o=(attn, ptr(lw.wo), None, rows, cfg.hidden, qd, 1, outs_proj, cols_h, o_split, ws, ws_bytes),
-                norm2=(h, proj, ptr(lw.ln2), cfg.eps, x, rows, cfg.hidden),
+                # the output projection with the residual add and the post-attention norm that follow it
+                o_norm=(attn, ptr(lw.wo), rows, cfg.hidden, qd, o_split, h, ptr(lw.ln2), cfg.eps, x, ws, ws_bytes),
                 # gate/up with SwiGLU in the product's epilogue, from the row-interleaved weight
                 mlp=(x, ptr(lw.w_gate_up_blocked), rows, cfg.inter, cfg.hidden, act, ws, ws_bytes),
                 # the down projection with the residual add and the norm that follow it (the next block's, or the final one)
@@ -205,8 +209,7 @@ class Decoder:
             check(lib.ms_gemm_bf16(*c["qkv"], st))
             check(lib.ms_predict_verify_attention(cache, li, B, ids, n_verify, n_foresight, q, c["k"], c["v"], pos_ptr, ctx_ptr, 0.0,
                                                   attn, att_ws_ptr, att_ws_bytes, st))
-            check(lib.ms_gemm_bf16(*c["o"], st))
-            check(lib.ms_add_rmsnorm(*c["norm2"], st))
+            check(lib.ms_gemm_add_rmsnorm_bf16(*c["o_norm"], st))
             check(lib.ms_gemm_swiglu_bf16(*c["mlp"], st))
             check(lib.ms_gemm_add_rmsnorm_bf16(*c["down_norm"], st))
         return self._greedy_tokens(self.x[:rows], rows)
