@@ -60,7 +60,10 @@ def parse():
                          "layers launch back to back; 1 for decode_step, where other kernels run between them)")
     ap.add_argument("--no-also", action="store_true", help="skip the two extra points (batch 32 x 4096 tokens, ragged batch)")
     ap.add_argument("--queries", type=int, default=41, help="wide_step: causal queries per sequence (the memory tokens and <o>, or a prompt chunk)")
-    ap.add_argument("--workload", choices=["attention", "decode_step", "compaction", "wide_step"], default="attention",
+    ap.add_argument("--rows", type=int, default=448, help="projections: rows of the step (batch x queries)")
+    ap.add_argument("--library-reference", action="store_true",
+                    help="projections: also time torch.mm (hipBLASLt) on the same products, as a reference only")
+    ap.add_argument("--workload", choices=["attention", "decode_step", "compaction", "wide_step", "projections"], default="attention",
                     help="attention: the metric's workload (default); compaction: configuration 4 (batch 16, 28 layers, "
                          "256 -> 8 tokens per sequence, then attention over the result); wide_step: a pass of --queries causal "
                          "queries; decode_step: the whole model step (Qwen2.5-7B shapes, batch 64, 8k cached tokens, 4 verify + "
@@ -99,6 +102,8 @@ def main():
         return compaction_bench(args)
     if args.workload == "wide_step":
         return wide_step_bench(args)
+    if args.workload == "projections":
+        return projections_bench(args)
     args.batch = args.batch or 32
     import torch
 
@@ -631,33 +636,43 @@ def decode_step_bench(args):
     pos_d = torch.empty(B, nq, dtype=torch.int32, device=dev)
     pos_np, acc_np = pos_h.numpy(), acc_h.numpy()
     next_pid = np.asarray([3 * n + 1 for n in lengths], dtype=np.int32)
+    first_pid_d = torch.from_numpy(next_pid.copy()).to(dev)
+    total_steps = args.warmup + args.steps
+    commit_log = torch.zeros(total_steps, B, dtype=torch.int32, device=dev)   # rows kept per step and sequence
+    host_commit = args.host_commit
     cur_len = np.asarray(lengths, dtype=np.int64)
     stream = torch.cuda.current_stream()
-    state = {"committed": 0, "kv_bytes": 0.0}
+    state = {"committed": 0, "kv_bytes": 0.0, "step": 0}
 
     def step():
-        M.ms_step_positions(next_pid, nv, nf, pos_np)
-        pos_d.copy_(pos_h, non_blocking=True)
+        if host_commit:
+            M.ms_step_positions(next_pid, nv, nf, pos_np)
+            pos_d.copy_(pos_h, non_blocking=True)
+        else:
+            M.ms_step_positions_device(first_pid_d, nv, nf, pos_d)
         _, targets = dec.step(ids, tokens, pos_d, nv, nf)
-        state["kv_bytes"] += NL * float(np.sum(2 * cur_len * Hkv * Dh * 2))
         tg = targets.view(B, nq)
         M.ms_accept(B, nv - 1, tokens[:, 1:nv].contiguous(), tg[:, :nv - 1].contiguous(), None, acc_d, nxt_d)
-        acc_h.copy_(acc_d, non_blocking=True)
         # next verify block: the token after the accepted ones, then the foresight rows' predictions
         tokens[:, 0] = torch.gather(tg, 1, acc_d.long().unsqueeze(1)).squeeze(1)
         tokens[:, 1:nv] = tg[:, nv:]
-        stream.synchronize()
-        n_commit = acc_np + 1                               # the block's first token is always kept
         k_new, v_new = dec.step_kv()
-        M.ms_commit_accepted(ses.cache, ids, n_commit, nq, k_new, v_new, pos_d)
-        next_pid[:] += n_commit
-        cur_len[:] += n_commit
-        state["committed"] += int(n_commit.sum())
+        n_commit_d = commit_log[state["step"]]
+        torch.add(acc_d, 1, out=n_commit_d)                 # the block's first token is always kept
+        state["step"] += 1
+        if not host_commit:
+            # the commit reads the counts on the device, takes pages in the host's order and advances the
+            # lengths and the next position ids: no synchronisation in the step
+            M.ms_commit_accepted_device(ses.cache, ids, n_commit_d, nq, nv, k_new, v_new, pos_d, first_pid_d)
+            return
+        acc_h.copy_(n_commit_d, non_blocking=True)
+        stream.synchronize()
+        M.ms_commit_accepted(ses.cache, ids, acc_np, nq, k_new, v_new, pos_d)
+        next_pid[:] += acc_np
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    state.update(committed=0, kv_bytes=0.0)
     # other kernels run between the layers' attention launches here: one launch per event pair
     M.ms_profile_attention(ses.cache, args.steps * NL, args.event_stride or 29, 1)
     torch.cuda.synchronize()
@@ -672,9 +687,15 @@ def decode_step_bench(args):
     kern_ms = M.ms_profile_read(ses.cache, args.steps * NL)
     M.ms_profile_attention(ses.cache, 0, 1, 1)
     M.ms_check_integrity(ses.cache)
-    assert np.array_equal(np.asarray(ses.lengths(ids)), cur_len)
+    log = commit_log.cpu().numpy().astype(np.int64)
+    cur_len = cur_len + log.sum(0)
+    assert np.array_equal(np.asarray(ses.lengths(ids)), cur_len), "the cache's lengths differ from the logged commits"
+    state["committed"] = int(log[args.warmup:].sum())
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    per_launch_bytes = int(np.sum(2 * cur_len * Hkv * Dh * 2 + 4 * (-(-cur_len // 16)))) + B * nq * (2 * Hq + 2 * Hkv) * Dh * 2
+    # bytes of the timed launches: mean over the timed steps of the lengths they started from
+    start_len = np.asarray(lengths, dtype=np.int64)[None, :] + np.cumsum(log, 0) - log
+    mean_len = start_len[args.warmup:].mean(0)
+    per_launch_bytes = int(np.sum(2 * mean_len * Hkv * Dh * 2 + 4 * np.ceil(mean_len / 16))) + B * nq * (2 * Hq + 2 * Hkv) * Dh * 2
     kern_avg_ms = float(np.mean(kern_ms)) if kern_ms else float("nan")
     achieved = per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9
     attn_ms = kern_avg_ms * NL      # from the sampled launches (an event pair around every launch would stall the stream)
@@ -690,7 +711,8 @@ def decode_step_bench(args):
             "batch": B, "mean_kv_len": round(float(cur_len.mean()), 1), "layers": NL,
             "step": f"embedding, {NL} blocks (norm, fused Q/K/V projection, attention, output projection, norm, gate/up projection with "
                     "SwiGLU, down projection with the residual add and the next norm), LM head, greedy tokens, accept, commit: every kernel is "
-                    "this library's; random weights, so about one token per sequence is accepted per step",
+                    "this library's; random weights, so about one token per sequence is accepted per step; "
+                    + ("accept lengths read back by the host before the commit" if host_commit else "commit on the device, no synchronisation in the step"),
             "projections": "few-row matrix-core kernel" if B * nq <= 16 else "tiled matrix-core GEMM",
         },
         "query_tokens_per_s": round(B * nq * args.steps / (t1 - t0), 1),
@@ -707,6 +729,101 @@ def decode_step_bench(args):
         "cpu_baseline": None,
     }
     ses.close()
+    print(json.dumps(result))
+
+
+def projections_bench(args):
+    """The five dense projections of a decoder block and the LM head at Qwen2.5-7B widths (Algorithm 1,
+    SpeculativeStep; Section 3.1), each as the decoder calls it (bias, K split, SwiGLU or residual add +
+    RMSNorm in the same call), stand-alone with cold weights: every call takes the next of several
+    weight copies that together exceed the chip's caches.  One HIP-event pair around `--steps` calls."""
+    import torch
+
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import decoder as D
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = D.DecoderConfig.qwen2_5_7b()
+    rows = args.rows
+    qd, kd, hid, inter = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim, cfg.hidden, cfg.inter
+    vocab = -(-cfg.vocab // 128) * 128
+    # the decoder's K splits (decoder.py): one row tile up to 256 rows
+    few = rows <= 256
+    splits = {"qkv": 7 if few else 4, "out": 8 if few else 4, "down": 16 if few else 8}
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20260414)
+
+    def rand(*shape, scale=1.0):
+        return (torch.randn(*shape, device=dev, dtype=torch.float32, generator=gen) * scale).to(torch.bfloat16)
+
+    def copies(n, k):   # enough copies of an [n, k] weight to exceed 640 MB (L2 + the 256 MB memory-side cache twice over)
+        return [rand(n, k, scale=k ** -0.5) for _ in range(max(2, min(24, -(-640_000_000 // (n * k * 2)))))]
+
+    ws = torch.empty(max(M.ms_gemm_workspace_bytes(rows, qd + 2 * kd, hid, splits["qkv"]),
+                         M.ms_gemm_add_rmsnorm_workspace_bytes(rows, hid, qd, splits["out"]),
+                         M.ms_gemm_add_rmsnorm_workspace_bytes(rows, hid, inter, splits["down"]),
+                         M.ms_gemm_workspace_bytes(rows, 2 * inter, hid, 1), M.ms_gemm_workspace_bytes(rows, vocab, hid, 1), 16),
+                     dtype=torch.uint8, device=dev)
+    x_h, x_q, x_i = rand(rows, hid), rand(rows, qd), rand(rows, inter, scale=0.1)
+    h = torch.zeros(rows, hid, dtype=torch.float32, device=dev)
+    norm_w = rand(hid)
+    bias = rand(qd + 2 * kd, scale=0.1)
+    q, k, v = (torch.empty(rows, n, dtype=torch.bfloat16, device=dev) for n in (qd, kd, kd))
+    x_out = torch.empty(rows, hid, dtype=torch.bfloat16, device=dev)
+    act = torch.empty(rows, inter, dtype=torch.bfloat16, device=dev)
+    logits = torch.empty(rows, vocab, dtype=torch.bfloat16, device=dev)
+    cases = [
+        ("qkv", qd + 2 * kd, hid, f"bias, three outputs, K split {splits['qkv']}", lambda w: M.ms_gemm_bf16(x_h, w, bias, [q, k, v], splits["qkv"], ws), x_h),
+        ("out+add+norm", hid, qd, f"K split {splits['out']}, residual add and RMSNorm in the reduction", lambda w: M.ms_gemm_add_rmsnorm_bf16(x_q, w, h, norm_w, 1e-6, x_out, splits["out"], ws), x_q),
+        ("gate/up+SwiGLU", 2 * inter, hid, "SwiGLU in the epilogue", lambda w: M.ms_gemm_swiglu_bf16(x_h, w, act, ws), x_h),
+        ("down+add+norm", hid, inter, f"K split {splits['down']}, residual add and RMSNorm in the reduction", lambda w: M.ms_gemm_add_rmsnorm_bf16(x_i, w, h, norm_w, 1e-6, x_out, splits["down"], ws), x_i),
+        ("lm_head", vocab, hid, "logits", lambda w: M.ms_gemm_bf16(x_h, w, None, [logits], 1, ws), x_h),
+    ]
+
+    def timed(fn, weights):
+        state = [0]
+
+        def call():
+            fn(weights[state[0] % len(weights)])
+            state[0] += 1
+        for _ in range(max(1, args.warmup)):
+            call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps * 1e3
+
+    table, flops_total, us_total = [], 0.0, 0.0
+    for name, n, kk, what, fn, xin in cases:
+        weights = copies(n, kk)
+        us = timed(fn, weights)
+        flops = 2.0 * rows * n * kk
+        row = {"projection": name, "rows": rows, "N": n, "K": kk, "call": what, "us": round(us, 1), "pflops": round(flops / us / 1e9, 3),
+               "frac_of_2.5_pflops": round(flops / us / 1e9 / 2.5, 3), "weight_gbps": round(n * kk * 2 / us / 1e3, 1)}
+        if args.library_reference:   # a reference, not on any path of the library: the bare product through torch.mm
+            ref = torch.empty(rows, n, dtype=torch.bfloat16, device=dev)
+            row["library_us_bare_product"] = round(timed(lambda w: torch.mm(xin, w.t(), out=ref), weights), 1)
+            del ref
+        table.append(row)
+        flops_total += flops
+        us_total += us
+        del weights
+    step_us = 28 * sum(r["us"] for r in table[:4]) + table[4]["us"]
+    result = {
+        "metric": f"decoder_projections_pflops_rows{rows}", "value": round(flops_total / us_total / 1e9, 3), "unit": "PFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(step_us / 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"qwen2.5-7b_projections_rows{rows}", "note": "ms_per_step = 28 blocks' four projections + the LM head, stand-alone times added up"},
+        "projections": table,
+        "roofline": {"kernel": "gemm_tn_bf16 (+ its reduction kernels)", "bound": "mfma", "achieved": round(flops_total / us_total / 1e6, 1),
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops_total / us_total / 1e6 / 2500.0, 4), "traffic": None},
+        "cpu_baseline": None,
+    }
     print(json.dumps(result))
 
 

@@ -64,6 +64,12 @@ def test_decode_step_bench_small():
     check_contract(r)
 
 
+def test_projections_bench_small():
+    r = run_bench("--workload", "projections", "--rows", "63", "--steps", "2", "--warmup", "1")
+    assert r["roofline"]["bound"] == "mfma" and r["roofline"]["peak"] == 2500.0 and len(r["projections"]) == 5
+    assert all(p["us"] > 0 for p in r["projections"]) and r["config"]["workload"] == "qwen2.5-7b_projections_rows63"
+
+
 def test_more_than_one_gpu_is_refused():
     res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120, cwd=ROOT)
     assert res.returncode != 0
