@@ -32,19 +32,42 @@ def compiled_kernels(source: str):
     return text, kernels
 
 
+def loops_with_priority_changes(lines, start, end):
+    """(first, last) line of every loop (a backward branch to a label) between start and end whose body raises the wave priority."""
+    label_at = {ln.split(":")[0]: i for i, ln in enumerate(lines[start:end], start) if ln.startswith(".LBB") and ":" in ln}
+    loops = []
+    for i in range(start, end):
+        m = re.match(r"\s+s_c?branch\w*\s+(\.LBB\w+)", lines[i])
+        if m and m.group(1) in label_at and label_at[m.group(1)] < i:
+            first = label_at[m.group(1)]
+            if any("s_setprio" in lines[j] for j in range(first, i)):
+                loops.append((first, i))
+    return loops
+
+
 def test_projection_kernels_do_not_spill():
-    """The few-row kernel keeps 16 loads in flight per wave and the tiled one sits at its 128-register
-    budget (two workgroups per CU): a spilled value would put a wait for all loads into their loops."""
-    _, kernels = compiled_kernels("gemm.hip")
+    """The few-row kernel keeps 16 loads in flight per wave and the tiled one runs two waves per SIMD
+    (256 registers each): a spilled value inside their loops would put a wait for all loads there.  The
+    tiled kernel may park a few registers around its K loops (stored before, reloaded after)."""
+    text, kernels = compiled_kernels("gemm.hip")
     few = {n: r for n, r in kernels.items() if "skinny_mfma_bf16" in n}
     assert len(few) == 6, sorted(kernels)
     for name, r in few.items():
         assert r["vgpr_spill_count"] == 0 and r["private_segment_fixed_size"] == 0 and r["vgpr_count"] <= 128, (name, r)
     tiled = {n: r for n, r in kernels.items() if "gemm_tn_bf16" in n}
     assert len(tiled) == 4, sorted(kernels)
+    lines = text.split("\n")
     for name, r in tiled.items():
-        greedy = "ILi3E" in name      # the greedy-token build parks two registers across its loop (stored before, reloaded after)
-        assert r["vgpr_spill_count"] <= (2 if greedy else 0) and r["vgpr_count"] <= 128, (name, r)
+        assert r["vgpr_spill_count"] <= 8 and r["vgpr_count"] <= 256, (name, r)
+        start = next(i for i, ln in enumerate(lines) if ln.startswith(name + ":"))
+        end = next(i for i in range(start, len(lines)) if "s_endpgm" in lines[i])
+        loops = loops_with_priority_changes(lines, start, end)
+        multiplying = 0
+        for first, last in loops:
+            body = lines[first:last]
+            multiplying += sum("v_mfma" in ln for ln in body) >= 8
+            assert not [ln.strip() for ln in body if "scratch_" in ln], (name, first)
+        assert multiplying >= 4, (name, loops)          # one K loop per number of valid row blocks (1 to 4; 0 only moves data)
     norm = [r for n, r in kernels.items() if "reduce_add_rmsnorm" in n]
     assert len(norm) == 1 and norm[0]["vgpr_spill_count"] == 0 and norm[0]["vgpr_count"] <= 128, norm
 
