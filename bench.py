@@ -750,7 +750,7 @@ def projections_bench(args):
     vocab = -(-cfg.vocab // 128) * 128
     # the decoder's K splits (decoder.py): one row tile up to 256 rows
     few = rows <= 256
-    splits = {"qkv": 7 if few else 4, "out": 8 if few else 4, "down": 16 if few else 8}
+    splits = {"qkv": 7 if few else 4, "out": 8 if few else 7, "down": 16 if few else 8}
     gen = torch.Generator(device=dev)
     gen.manual_seed(20260414)
 

@@ -367,12 +367,27 @@ __global__ __launch_bounds__(256) void gemm_reduce(GemmArgs g, int parts, int co
     // SwiGLU: output column c of this range <- gate column 64 (c / 32) + c % 32 and the up column 32 further
     const int n_rel = kSwiglu ? 64 * (c / 32) + c % 32 : c;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f), u = s;
-    for (int z = 0; z < parts; ++z) {
-        const float* p = g.partial + ((size_t)z * g.M + m) * width + n_rel;
-        const float4 a = *reinterpret_cast<const float4*>(p);
+    const float* p0 = g.partial + (size_t)m * width + n_rel;
+    const size_t part_stride = (size_t)g.M * width;
+    int z = 0;
+    for (; z + 4 <= parts; z += 4) {   // four parts per memory round trip, added in their order
+        float4 a[4], b[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            a[t] = *reinterpret_cast<const float4*>(p0 + (z + t) * part_stride);
+            if (kSwiglu) b[t] = *reinterpret_cast<const float4*>(p0 + (z + t) * part_stride + 32);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            s.x += a[t].x; s.y += a[t].y; s.z += a[t].z; s.w += a[t].w;
+            if (kSwiglu) { u.x += b[t].x; u.y += b[t].y; u.z += b[t].z; u.w += b[t].w; }
+        }
+    }
+    for (; z < parts; ++z) {
+        const float4 a = *reinterpret_cast<const float4*>(p0 + z * part_stride);
         s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
         if (kSwiglu) {
-            const float4 b = *reinterpret_cast<const float4*>(p + 32);
+            const float4 b = *reinterpret_cast<const float4*>(p0 + z * part_stride + 32);
             u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
         }
     }

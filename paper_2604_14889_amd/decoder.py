@@ -119,13 +119,13 @@ class Decoder:
         self.targets = buf(max_rows, dtype=torch.int32)
         # K is divided over workgroups where a projection has few output tiles (one 256 x 256 tile per
         # workgroup, one workgroup per compute unit); measured at Qwen2.5-7B widths: Q/K/V 7 ways up to
-        # 256 rows (one row tile) and 4 above, output 8 and 4, down 16 and 8.  Other widths take the
+        # 256 rows (one row tile) and 4 above, output 8 and 7, down 16 and 8.  Other widths take the
         # largest divisor of their K steps below those.
         def split(k, want):
             steps = k // 32
             return max(s for s in range(1, want + 1) if steps % s == 0 and (s == 1 or steps // s >= 4))
         self.splits_few = (split(cfg.hidden, 7), max(2, split(qd, 8)), max(2, split(cfg.inter, 16)))
-        self.splits_many = (split(cfg.hidden, 4), max(2, split(qd, 4)), max(2, split(cfg.inter, 8)))
+        self.splits_many = (split(cfg.hidden, 4), max(2, split(qd, 7)), max(2, split(cfg.inter, 8)))
         rows_few = range(1, min(max_rows, 16) + 1)
         need = max([M.ms_gemm_workspace_bytes(max_rows, qd + 2 * kd, cfg.hidden, self.splits_few[0]),
                     M.ms_gemm_add_rmsnorm_workspace_bytes(max_rows, cfg.hidden, qd, self.splits_few[1]),
