@@ -1271,12 +1271,15 @@ int launch_mfma(ms_cache* c, const AttnArgs& ga, const BatchMeta& bm, int B, hip
     }
     // plan: rebuilt only when the batch (ids, lengths) changed since the last call on this cache
     std::vector<int> key;
-    // Smallest share.  Decode steps: two tiles per wave.  Wide steps: a share that does not close its
-    // pair writes one partial per chunk of queries (33 KB each, read back once), so its tiles (16 KB
-    // each) must outweigh them: 24 tiles per chunk keep the partials below a tenth of the traffic.
+    // Smallest share.  Decode steps: two tiles per wave.  Wide steps: 32 tiles.  A share that does not
+    // close its pair writes one partial per chunk of queries (33 KB each, read back once), which
+    // argues for long shares; but a wide pass is bound by the work inside a workgroup, not by HBM,
+    // so what counts is that every compute unit has a share: shares of 24 tiles per chunk (partials
+    // below a tenth of the traffic) left three quarters of the chip idle on a batch of 8 sequences of
+    // 4096 tokens and took 250 us where shares of 32 tiles take 95 us.
     const int n_q = ga.n_q;
     const int wide_chunks = !mfma_wide_step(c, n_q) ? 0 : std::min(kWideChunks, (n_q + kRows / ga.group - 1) / (kRows / ga.group));
-    const long min_tiles = wide_chunks ? 24L * wide_chunks : 2L * kWaves;
+    const long min_tiles = wide_chunks ? 32L : 2L * kWaves;
     key.reserve(B + 3);
     key.push_back(B);
     key.push_back((int)min_tiles);
