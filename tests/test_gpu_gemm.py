@@ -22,6 +22,8 @@ CASES = [
     (300, 1024, 2048, [128, 512, 256, 128], 8, True),
     (448, 37888, 512, [37888], 1, True),          # gate/up width: 296 tiles on 256 compute units, the last round split over K
     (100, 67584, 512, [67584], 1, False),         # one row tile: 264 tiles, the last 8 split over K
+    (1024, 640, 256, [640], 1, True),             # four row tiles, a last column tile that is half past N
+    (700, 384, 512, [256, 128], 2, False),        # a ragged third row tile (188 rows: 4 and 2 row blocks of its waves), K in two parts
     # at most 16 rows and K a multiple of 128: the few-row kernel that streams the weight once (split_k is not used there)
     (1, 128, 512, [128], 1, False),
     (7, 4608, 3584, [3584, 512, 512], 1, True),   # a single sequence's fused Q / K / V projection
