@@ -642,6 +642,52 @@ def test_device_side_commit_keeps_pace_with_host_commit_and_oracle():
         M.ms_check_integrity(dev.cache)
 
 
+def test_wide_step_after_device_side_commits():
+    """A pass of 41 causal queries (the memory-token pass) right after device-side commits: the wide kernel goes by
+    the device's lengths and looks up the pages the commits added, while the host still holds the old tables."""
+    M, S = _mods()
+    rng = W.make_rng(418)
+    L, Hq, Hkv, D, NP, nv, nf = 1, 28, 4, 128, 240, 4, 3
+    nq = nv + nf
+    start = [1000, 15, 2040, 0, 333]
+    B = len(start)
+    bf = O.bf16_bits_to_f32
+    ses = S.Session(L, Hq, Hkv, D, NP, M.MS_BF16, 1000000.0, max_seqs=8, max_pages_per_seq=140)
+    ora = O.PagedCache(L, Hkv, D, NP, dtype=O.BF16, rope_base=1000000.0, max_seqs=8)
+    with ses:
+        ids = [M.ms_seq_create(ses.cache) for _ in range(B)]
+        assert ids == [ora.seq_create() for _ in range(B)]
+        n = sum(start)
+        k, v = W.normal_bf16_bits(rng, (L, n, Hkv, D)), W.normal_bf16_bits(rng, (L, n, Hkv, D))
+        pos = np.concatenate([np.arange(1, c + 1) for c in start]).astype(np.int32)
+        M.ms_append_kv(ses.cache, ids, start, S.to_device(k, M.MS_BF16), S.to_device(v, M.MS_BF16), S.ints_dev(pos))
+        ora.append(ids, start, bf(k), bf(v), pos)
+        first = np.asarray([c + 1 for c in start], np.int32)
+        first_d = S.ints_dev(first)
+        pos_d = torch.empty(B, nq, dtype=torch.int32, device="cuda")
+        wide_q = 41
+        for step, acc in enumerate([[4, 4, 4, 4, 4], [4, 1, 4, 0, 3], [4, 4, 4, 4, 4], [2, 4, 4, 4, 4]]):
+            # a wide pass first: it sees what the commits so far have left (the plan is the one cut before them)
+            qw = W.normal_bf16_bits(rng, (B, wide_q, Hq, D))
+            kw, vw = W.normal_bf16_bits(rng, (B, wide_q, Hkv, D)), W.normal_bf16_bits(rng, (B, wide_q, Hkv, D))
+            pw = np.stack([np.arange(f, f + wide_q) for f in first]).astype(np.int32)
+            got = ses.attention(0, ids, wide_q, 0, S.to_device(qw, M.MS_BF16), S.to_device(kw, M.MS_BF16), S.to_device(vw, M.MS_BF16),
+                                S.ints_dev(pw).view(B, wide_q))
+            want = O.attention(ora, 0, ids, wide_q, 0, bf(qw), bf(kw), bf(vw), pw)
+            check_out(S.to_host_f32(got), want, "bf16", f"wide pass before commit {step}")
+            kn, vn = W.normal_bf16_bits(rng, (L, B, nq, Hkv, D)), W.normal_bf16_bits(rng, (L, B, nq, Hkv, D))
+            M.ms_step_positions_device(first_d, nv, nf, pos_d)
+            pq = M.ms_step_positions(first, nv, nf)
+            M.ms_commit_accepted_device(ses.cache, ids, S.ints_dev(acc), nq, nv, S.to_device(kn, M.MS_BF16), S.to_device(vn, M.MS_BF16), pos_d, first_d)
+            for b in range(B):
+                ora.append([ids[b]], [acc[b]], bf(kn)[:, b, :acc[b]], bf(vn)[:, b, :acc[b]], pq[b, :acc[b]])
+            first = first + np.asarray(acc, np.int32)
+        M.ms_cache_sync(ses.cache)
+        for s_ in ids:
+            assert M.ms_seq_page_table(ses.cache, s_) == ora.page_table[s_] and M.ms_seq_len(ses.cache, s_) == ora.seq_len[s_]
+        M.ms_check_integrity(ses.cache)
+
+
 def test_device_side_commit_general_kernel_and_errors():
     M, S = _mods()
     rng = W.make_rng(416)
