@@ -186,6 +186,24 @@ def test_gemm_last_round_split_is_optional():
     assert float(d.max()) <= 2.0 ** -7 * float(o2.float().abs().max())   # other order of fp32 additions: one bf16 step at most
 
 
+def test_gemm_results_do_not_depend_on_timing():
+    """The K parts are summed in a fixed order and no tile depends on which workgroup ran first: repeated calls
+    give the same bits, with K divided over workgroups, with the last round divided, and with whole tiles."""
+    from paper_2604_14889_amd import binding as M
+    from paper_2604_14889_amd import session as S
+    rng = W.make_rng(906)
+    for m, n, k, split in ((448, 4608, 3584, 4), (448, 37888, 512, 1), (300, 1280, 2048, 8), (448, 3584, 3584, 7)):
+        ad = S.to_device(W.normal_bf16_bits(rng, (m, k), 1.0), M.MS_BF16)
+        wd = S.to_device(W.normal_bf16_bits(rng, (n, k), k ** -0.5), M.MS_BF16)
+        ws = torch.empty(max(16, M.ms_gemm_workspace_bytes(m, n, k, split)), dtype=torch.uint8, device="cuda")
+        first = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+        M.ms_gemm_bf16(ad, wd, None, [first], split, ws)
+        for _ in range(4):
+            again = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device="cuda")
+            M.ms_gemm_bf16(ad, wd, None, [again], split, ws)
+            assert torch.equal(again.view(torch.int16), first.view(torch.int16)), (m, n, k, split)
+
+
 SWIGLU_CASES = [(7, 64, 32), (300, 1088, 256), (448, 18944, 512),
                 (7, 18944, 512), (16, 128, 128), (5, 1152, 384), (1, 2048, 3584),   # few rows: the few-row kernel
                 (14, 18944, 3584), (16, 16384, 3584)]                               # ... with a whole compute unit's LDS for A
