@@ -41,6 +41,17 @@ def test_attention_bench_small():
     assert r["metric"] == "predict_verify_attn_hbm_gbps_b32_kv8k" and r["roofline"]["traffic"] is not None
 
 
+def test_attention_bench_other_paths_small():
+    """The host-side commit (accept lengths read back every step) and the fixed tile assignment stay runnable; 16 steps
+    take the small caches through a compaction of the 56-token segment."""
+    for flag in ("--host-commit", "--deterministic"):
+        r = run_bench("--layers", "2", "--batch", "3", "--kv", "512", "--steps", "16", "--warmup", "1", "--event-stride", "1",
+                      "--no-cpu-baseline", flag)
+        check_contract(r)
+    r = run_bench("--workload", "decode_step", "--layers", "1", "--batch", "3", "--kv", "128", "--steps", "2", "--warmup", "1", "--host-commit")
+    check_contract(r)
+
+
 def test_compaction_bench_small():
     r = run_bench("--workload", "compaction", "--layers", "3", "--batch", "4", "--steps", "3", "--warmup", "1")
     check_contract(r)
