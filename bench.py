@@ -44,8 +44,10 @@ SEG_TOKENS, RATIO = 56, 7
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20,
+                    help="untimed steps before the timed ones; after an idle spell the part's power management needs "
+                         "about ten steps (25 ms) of this workload to settle, during which launches run up to 10 %% slower")
     ap.add_argument("--layers", type=int, default=28)
     ap.add_argument("--batch", type=int, default=None, help="sequences (default: 32 for the attention workload, 64 for decode_step)")
     ap.add_argument("--kv", type=int, default=8192)
@@ -119,7 +121,7 @@ def main():
         also = []
         for name, shape, ragged in (("batch32_kv4096", W.metric_point(32, 4096, n_layers=args.layers), False),
                                     ("config3_ragged_1k_16k", W.config3(n_layers=args.layers, batch=32), True)):
-            r = attention_workload(args, shape, max(4, args.steps // 2), 2, False, ragged)
+            r = attention_workload(args, shape, max(4, args.steps // 2), max(2, args.warmup // 2), False, ragged)
             also.append({"workload": r["config"]["workload"], "value": r["value"], "unit": "GB/s", "ms_per_step": r["ms_per_step"],
                          "steps": r["steps"], "pct_of_hbm_peak": r["pct_of_hbm_peak"], "roofline_frac": r["roofline"]["frac"],
                          "avg_kernel_ms": r["roofline"]["avg_kernel_ms"],
@@ -276,17 +278,19 @@ def attention_workload(args, sh, steps, warmup, want_cpu, ragged):
             catch_up()
             compact_if_due()
 
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    # one event pair per step around its NL back-to-back attention launches: nothing else runs on the
-    # stream between them, so span time / NL is the kernel's duration plus the gap to the next launch
-    ev_stride = args.event_stride or NL
-    ev_span = min(args.event_span or NL, ev_stride)
-    M.ms_profile_attention(ses.cache, steps * NL, ev_stride, ev_span)
-    torch.cuda.synchronize()
     gc.collect()
     gc.disable()    # a full collection in the middle of a step stalls the launch thread for tens of milliseconds
+    for _ in range(warmup):
+        step()
+    # one event pair per step around its NL back-to-back attention launches: nothing else runs on the
+    # stream between them, so span time / NL is the kernel's duration plus the gap to the next launch.
+    # Nothing slow may sit between the warm-up and the timed steps (a pause of some tens of milliseconds
+    # lets the part drop its clocks, and the first ten steps after it run up to 10 % slower), so the
+    # collector ran before the warm-up and only as many events are created as there are spans.
+    ev_stride = args.event_stride or NL
+    ev_span = min(args.event_span or NL, ev_stride)
+    torch.cuda.synchronize()
+    M.ms_profile_attention(ses.cache, -(-steps * NL // ev_stride), ev_stride, ev_span)
     t0 = time.perf_counter()
     for _ in range(steps):
         step()
@@ -613,10 +617,11 @@ def decode_step_bench(args):
     NL, Hq, Hkv, Dh = cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     lengths = [L0] * B
     pages_per_seq = -(-L0 // 16)
-    n_pages = B * (pages_per_seq + 16)
+    room = max(16, -(-(args.warmup + args.steps) * nv // 16) + 1)    # pages a sequence can grow by while the bench runs
+    n_pages = B * (pages_per_seq + room)
     rng = W.make_rng(1005, B, NL)
     page_tables = W.shuffled_page_tables(rng, n_pages, lengths)
-    ses = S.Session(NL, Hq, Hkv, Dh, n_pages, M.MS_BF16, cfg.rope_base, max_seqs=B, max_pages_per_seq=pages_per_seq + 64)
+    ses = S.Session(NL, Hq, Hkv, Dh, n_pages, M.MS_BF16, cfg.rope_base, max_seqs=B, max_pages_per_seq=pages_per_seq + max(64, room + 1))
     gen = torch.Generator(device=dev)
     gen.manual_seed(W.BASE_SEED + 5)
     for layer in range(NL):
@@ -670,14 +675,15 @@ def decode_step_bench(args):
         M.ms_commit_accepted(ses.cache, ids, acc_np, nq, k_new, v_new, pos_d)
         next_pid[:] += acc_np
 
+    gc.collect()
+    gc.disable()    # a full collection in the middle of a step stalls the launch thread for tens of milliseconds
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     # other kernels run between the layers' attention launches here: one launch per event pair
-    M.ms_profile_attention(ses.cache, args.steps * NL, args.event_stride or 29, 1)
-    torch.cuda.synchronize()
-    gc.collect()
-    gc.disable()    # a full collection in the middle of a step stalls the launch thread for tens of milliseconds
+    # (as many events as spans: creating thousands of them would idle the GPU between warm-up and timing)
+    ev_stride = args.event_stride or 29
+    M.ms_profile_attention(ses.cache, -(-args.steps * NL // ev_stride), ev_stride, 1)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
