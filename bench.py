@@ -75,12 +75,37 @@ def parse():
     ap.add_argument("--host-commit", action="store_true",
                     help="attention workload: read the accept lengths back and commit from the host (synchronises the stream every step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--read-probe", action="store_true",
+                    help="time the library's plain read kernel over the layer pools even without the CPU baseline (with it, always)")
     ap.add_argument("--fused-lm-head", action="store_true",
                     help="decode_step: LM head and greedy token in one kernel of the library (fp32 sums, no logits)")
     ap.add_argument("--cpu-seqs", type=int, default=32, help="sequences the CPU oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 1 GiB device copies, for scaling rocprofv3 byte counters")
     return ap.parse_args()
+
+
+def read_probe(torch, M, ses, NL, achieved_gbps):
+    """Plain read kernel of the library over the layer pools, ordinary and non-temporal loads; GB/s of the better one."""
+    sink = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    best = {}
+    pool_bytes = ses.pool[0].numel() * ses.pool[0].element_size()
+    warm = max(NL, int(40e-3 * 6e12 / pool_bytes))       # about 40 ms of reading first: the clocks settle (see --warmup)
+    timed = max(NL, int(20e-3 * 6e12 / pool_bytes))
+    for name, nt in (("ordinary", False), ("non_temporal", True)):
+        for i in range(warm):
+            M.ms_hbm_read_probe(ses.pool[i % NL], nt, sink)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        nbytes = 0
+        for i in range(timed):
+            nbytes += M.ms_hbm_read_probe(ses.pool[i % NL], nt, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        best[name] = nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    top = max(best.values())
+    return {"plain_read_gbps": {k: round(v, 1) for k, v in best.items()},
+            "frac_of_plain_read": round(achieved_gbps / top, 4)}
 
 
 def calibrate_copy(torch, dev, gen):
@@ -373,12 +398,18 @@ def attention_workload(args, sh, steps, warmup, want_cpu, ragged):
             "traffic": traffic,
             "traffic_source": traffic_source,
             "avg_kernel_ms": round(kern_avg_ms, 5),
+            "median_kernel_ms": round(float(np.median(kern_ms)), 5) if kern_ms else None,
+            "min_kernel_ms": round(float(np.min(kern_ms)), 5) if kern_ms else None,
             "launches": len(kern_ms) * ev_span,
             "launches_per_event_pair": ev_span,
             "algorithmic_bytes_per_launch": per_launch_bytes,
         },
     }
 
+    if want_cpu or args.read_probe:
+        # what a plain streaming read of the same layer pools reaches on this machine (the layers in turn, so
+        # every pass comes from HBM): the other denominator beside the published peak
+        result["roofline"].update(read_probe(torch, M, ses, NL, per_launch_bytes / (kern_avg_ms * 1e-3) / 1e9))
     if args.calibrate_copy:
         calibrate_copy(torch, dev, gen)
     if want_cpu:
@@ -883,6 +914,20 @@ def cpu_baseline(args, ses, sh, ids, lengths, q, k_new, v_new, pos_d, out, M, S,
             list(ex.map(one, tasks))
         dt = time.perf_counter() - t0
     nbytes = sum(2 * lengths[b] * sh.n_kv_heads * sh.head_dim * 2 for b in range(n))
+    # the same oracle on one thread: one sequence of 4096 cached tokens, 4 verify + 3 foresight queries, all heads
+    c2 = W.config2()
+    inp = W.attention_inputs(c2, 2)
+    ora2 = O.PagedCache(1, c2.n_kv_heads, c2.head_dim, c2.n_pages, dtype=O.BF16, rope_base=c2.rope_base, max_seqs=1,
+                        pool=np.ascontiguousarray(W.bits_as_f32(inp.pool)))
+    oid2 = ora2.seq_import(c2.lengths[0], inp.page_tables[0])
+    p0 = inp.first_pid[0]       # verify block at consecutive positions, the foresight tokens right after it (Section 2.1.1)
+    pos2 = np.asarray(list(range(p0, p0 + c2.n_verify)) + O.foresight_pids(p0 + c2.n_verify - 1, c2.n_foresight), dtype=np.int64)
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        O.attention_rows(ora2, 0, oid2, W.bits_as_f32(inp.q[0]), W.bits_as_f32(inp.k_new[0]), W.bits_as_f32(inp.v_new[0]),
+                         pos2, O.default_ctx_new(c2.n_verify, c2.n_foresight))
+        dt2 = time.perf_counter() - t0
+    bytes2 = 2 * c2.lengths[0] * c2.n_kv_heads * c2.head_dim * 2
     err = float(np.abs(got - want).max())
     rel = float(np.abs(got - want).mean() / np.abs(want).mean())
     return {
@@ -894,6 +939,8 @@ def cpu_baseline(args, ses, sh, ids, lengths, q, k_new, v_new, pos_d, out, M, S,
         "kind": "oracle",
         "sample": f"{n} of {sh.batch} sequences, layer 0, all {nv + nf} x {sh.n_q_heads} query rows, one task per (sequence, KV head) "
                   f"on {threads} threads, {nbytes / 1e6:.1f} MB of KV in {dt:.2f} s (1 of {sh.n_layers} layers of one step)",
+        "single_thread": {"workload": "one sequence, 4096 cached tokens, 4 verify + 3 foresight, 28 / 4 heads", "seconds": round(dt2, 3),
+                          "value": round(bytes2 / dt2 / 1e9, 4), "unit": "GB/s", "cores": 1},
         "gpu_vs_oracle_max_abs": round(err, 6),
         "gpu_vs_oracle_mean_rel": round(rel, 6),
         "tolerance": {"max_abs": 2e-2, "mean_rel": 1e-2},

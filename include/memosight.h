@@ -365,6 +365,19 @@ int ms_profile_attention(ms_cache* cache, int capacity, int stride, int span);
  * recorded (complete ones only: a span still open is dropped).  Resets the count. */
 int ms_profile_read(ms_cache* cache, float* ms_out, int cap, int* n);
 
+/* A plain streaming read of device memory at `src` (16-byte aligned) on `stream`: the first
+ * `bytes` bytes rounded down to a multiple of 32 KiB (*bytes_read, if not NULL, receives that
+ * count; less than 32 KiB launches nothing), MS_READ_PROBE_BLOCKS_PER_CU workgroups of 256 threads
+ * per compute unit taking 32 KiB groups in turn with eight 16-byte loads per thread in flight,
+ * non-temporal loads if `non_temporal` is not 0.  Nothing is written (`sink`, device memory of at
+ * least 4 bytes per workgroup, takes a word only for data that folds to one particular value; it
+ * keeps the loads alive).  What this reaches is the bandwidth a kernel that makes one pass over
+ * the cache (Section 2.3: every cached token is visible to every query) can be compared with
+ * besides the part's published peak.  Asynchronous; the caller times it.  MS_ERR_INVALID on a null
+ * or misaligned pointer. */
+#define MS_READ_PROBE_BLOCKS_PER_CU 2
+int ms_hbm_read_probe(const void* src, size_t bytes, int non_temporal, void* sink, void* stream, size_t* bytes_read);
+
 /* ---- position layout helpers (pure host integer functions) --------------------------------- */
 
 /* Adaptive Memory Allocation: ceil(n_tokens / c).  Negative on bad input. */

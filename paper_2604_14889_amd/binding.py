@@ -90,6 +90,7 @@ _SIGS = {
     "ms_gemm_bf16": (_I, [_P, _P, _P, _I, _I, _I, _I, C.POINTER(_P), _IP, _I, _P, _SZ, _P]),
     "ms_profile_attention": (_I, [_P, _I, _I, _I]),
     "ms_profile_read": (_I, [_P, C.POINTER(C.c_float), _I, _IP]),
+    "ms_hbm_read_probe": (_I, [_P, C.c_size_t, _I, _P, _P, C.POINTER(C.c_size_t)]),
     "ms_ama_count": (_I, [_I, _I]),
     "ms_upl_positions": (_I, [_I, _I, _I, _IP, _I]),
     "ms_output_token_pid": (_I, [_I]),
@@ -455,6 +456,14 @@ def ms_profile_read(cache, cap: int):
     n = C.c_int(0)
     _check(lib.ms_profile_read(cache, buf, cap, C.byref(n)))
     return list(buf[:min(n.value, cap)])
+
+
+def ms_hbm_read_probe(src, non_temporal: bool, sink, stream=None):
+    """Plain streaming read of the tensor `src` (device, contiguous); `sink`: device tensor of >= 8192 bytes.
+    Returns the bytes read (the tensor's size rounded down to a multiple of 32 KiB)."""
+    n = C.c_size_t(0)
+    _check(lib.ms_hbm_read_probe(_dev(src), src.numel() * src.element_size(), 1 if non_temporal else 0, _dev(sink), _stream(stream), C.byref(n)))
+    return n.value
 
 
 def ms_ama_count(n_tokens: int, c: int) -> int:

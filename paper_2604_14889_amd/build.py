@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libmemosight.so")
 
-SOURCES = ["cache.hip", "attention.hip", "attention_mfma.hip", "accept.hip", "decoder.hip", "gemm.hip", "layout.cpp"]
+SOURCES = ["cache.hip", "attention.hip", "attention_mfma.hip", "accept.hip", "decoder.hip", "gemm.hip", "probe.hip", "layout.cpp"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -84,6 +84,7 @@ def test_bad_arguments_return_errors_not_crashes():
     assert e.value.code == M.MS_ERR_INVALID and "pool" in str(e.value)
     with pytest.raises(M.MsError):
         M.ms_accept(-1, 4, None, None, None, None, None)
+    assert M.lib.ms_hbm_read_probe(None, 1 << 20, 0, None, None, None) == M.MS_ERR_INVALID     # null pointers: refused on the host
 
 
 def test_projection_workspace_sizes_follow_the_launch_shapes():

@@ -36,9 +36,32 @@ def test_attention_bench_small():
     assert r["config"]["workload"].startswith("batch3_kv512_layers2") and "also" not in r
     cb = r["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["value"] > 0 and 1 <= cb["cores"] <= cb["cores_usable"] <= cb["nproc"]
+    assert cb["single_thread"]["cores"] == 1 and cb["single_thread"]["value"] > 0
+    rf = r["roofline"]
+    assert rf["min_kernel_ms"] <= rf["median_kernel_ms"] and rf["min_kernel_ms"] <= rf["avg_kernel_ms"]
+    assert set(rf["plain_read_gbps"]) == {"ordinary", "non_temporal"} and min(rf["plain_read_gbps"].values()) > 0 and rf["frac_of_plain_read"] > 0
     assert cb["gpu_vs_oracle_max_abs"] <= 2e-2 and cb["gpu_vs_oracle_mean_rel"] <= 1e-2 and cb["within_tolerance"] is True
     r = run_bench("--layers", "2", "--batch", "32", "--kv", "8192", "--steps", "2", "--warmup", "1", "--no-cpu-baseline", "--no-also")
     assert r["metric"] == "predict_verify_attn_hbm_gbps_b32_kv8k" and r["roofline"]["traffic"] is not None
+
+
+def test_read_probe_reads_and_leaves_the_sink_alone():
+    """The plain read kernel behind `plain_read_gbps`: any size and both load kinds run, nothing is written."""
+    import torch
+
+    from paper_2604_14889_amd import binding as M
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    sink = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    for nbytes in (16, 4096 + 16, 3 * 256 * 16 * 2048 + 48, 64 << 20):
+        src = torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device="cuda", generator=gen)
+        for nt in (False, True):
+            assert M.ms_hbm_read_probe(src, nt, sink) == nbytes // 32768 * 32768
+    torch.cuda.synchronize()
+    assert int(sink.count_nonzero()) == 0
+    with pytest.raises(M.MsError):
+        M.ms_hbm_read_probe(src[1:17], False, sink)      # not 16-byte aligned
 
 
 def test_attention_bench_other_paths_small():
