@@ -3,19 +3,22 @@
 
 One step = one pass of the whole hot path over the batch, shaped like a decode step of a
 Qwen2.5-7B-sized model (28 attention layers, 28 query / 4 KV heads x 128, bf16):
-  position ids from the layout helpers (host)            -> uploaded
+  position ids of the block, built on the device from the next position ids
   28 x fused Predict+Verify attention, one per layer pool -> the HBM-bound part
-  greedy longest-prefix acceptance on the device, accept lengths read back
-  commit of the accepted verify rows into every layer's cache
+  greedy longest-prefix acceptance on the device
+  commit of the accepted verify rows into every layer's cache, the accept lengths read on the device
   every 14th step: the 56-token segment closed so far is compacted to 8 memory tokens
-    (ratio 7, as in the paper's long-context analysis), in every layer.
+    (ratio 7, as in the paper's long-context analysis), in every layer (the host catches up here).
 The workload is the metric point: batch 32, 8192 cached tokens per sequence, 5 verify + 4 foresight
 queries, page tables shuffled over a shared pool.  All inputs are seeded and synthetic.
 
 Prints ONE JSON line.  `value` is whole-step algorithmic KV throughput in GB/s with everything
 resident in HBM; `roofline` prices the streaming attention kernel alone against 8 TB/s; the
 `cpu_baseline` leg times the CPU oracle on a bounded sample of the same workload and the run fails
-(exit status 3) if the GPU's result for that sample is outside the bf16 tolerance.  The default run
+(exit status 3) if the GPU's result for that sample is outside the bf16 tolerance.  `roofline.traffic`
+(HBM bytes per launch by the memory-side counters) comes from two short child runs of this script
+under `rocprofv3 --pmc`, started before this process touches the GPU; if they cannot run, the
+committed summary of the same two runs is reported instead and `traffic_source` says so.  The default run
 also times two more points of the target's range -- batch 32 with 4096 cached tokens and the ragged
 1k-16k batch -- for a few steps each and reports them under `also`.
 
@@ -27,10 +30,15 @@ step (configuration 5).
 from __future__ import annotations
 
 import argparse
+import csv
 import gc
+import glob
 import json
 import os
+import shutil
+import subprocess
 import sys
+import tempfile
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -74,6 +82,9 @@ def parse():
                     help="fixed tile-to-wave assignment in the attention kernel (bit-reproducible results, about 1.5 %% slower)")
     ap.add_argument("--host-commit", action="store_true",
                     help="attention workload: read the accept lengths back and commit from the host (synchronises the stream every step)")
+    ap.add_argument("--no-live-traffic", action="store_true",
+                    help="do not start the two rocprofv3 --pmc child runs that measure the attention kernel's HBM bytes per launch "
+                         "(default workload only); the committed summary's figure is reported instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--read-probe", action="store_true",
                     help="time the library's plain read kernel over the layer pools even without the CPU baseline (with it, always)")
@@ -83,6 +94,58 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 1 GiB device copies, for scaling rocprofv3 byte counters")
     return ap.parse_args()
+
+
+def live_traffic():
+    """HBM bytes per launch of the attention kernel by the memory-side counters: two short runs of this
+    script (the same workload, 3 steps, plus plain 1 GiB device copies that scale the counters) as
+    children under `rocprofv3 --pmc`, one counter each -- rocprofv3 does not split passes, and a
+    process whose counters are being read cannot also time itself.  Must be called before this
+    process initialises the GPU.  Returns (bytes, note) or (None, reason)."""
+    exe = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
+    if not os.path.exists(exe):
+        return None, "rocprofv3 not found"
+    out = tempfile.mkdtemp(prefix="ms_pmc_", dir="/tmp")
+    per_launch, scale, alg = {}, {}, None
+    try:
+        for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+            cmd = [exe, "--pmc", counter, "--output-format", "csv", "-d", os.path.join(out, counter), "-o", "pmc", "--",
+                   sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "2", "--warmup", "1", "--no-cpu-baseline", "--no-also",
+                   "--calibrate-copy", "--no-live-traffic"]
+            try:
+                res = subprocess.run(cmd, cwd="/tmp", env=dict(os.environ, TMPDIR="/tmp"), capture_output=True, text=True, timeout=150)
+            except subprocess.TimeoutExpired:
+                return None, f"the {counter} run under rocprofv3 did not finish in 150 s"
+            if res.returncode != 0:
+                return None, f"the {counter} run under rocprofv3 ended with status {res.returncode}"
+            for line in res.stdout.splitlines():
+                if line.startswith('{"metric"'):
+                    alg = json.loads(line)["roofline"]["algorithmic_bytes_per_launch"]     # of the child's (shorter) run
+            files = glob.glob(os.path.join(out, counter, "**", "*counter_collection.csv"), recursive=True)
+            if not files:
+                return None, f"the {counter} run left no counter file"
+            kern, copy = [], []
+            for r in csv.DictReader(open(files[0])):
+                if r.get("Counter_Name") != counter:
+                    continue
+                if "pv_attn_mfma_stream" in r["Kernel_Name"]:
+                    kern.append(float(r["Counter_Value"]))
+                elif "copyBuffer" in r["Kernel_Name"]:
+                    copy.append(float(r["Counter_Value"]))
+            if not kern or not copy or max(copy) <= 0:
+                return None, f"the {counter} file has no rows for the kernel or the copy"
+            scale[counter] = 1048576.0 / max(copy)        # a 1 GiB copy reads and writes 1 GiB = 1048576 KiB
+            per_launch[counter] = sum(kern) / len(kern)
+        total = (per_launch["FETCH_SIZE"] * scale["FETCH_SIZE"] + per_launch["WRITE_SIZE"] * scale["WRITE_SIZE"]) * 1024.0
+        note = ("two child runs of this script under rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; KiB per dispatch scaled by what a 1 GiB "
+                f"copy reads: factors {scale['FETCH_SIZE']:.3f} and {scale['WRITE_SIZE']:.3f}): fetched "
+                f"{per_launch['FETCH_SIZE'] * scale['FETCH_SIZE'] * 1024 / 1e6:.1f} MB, written "
+                f"{per_launch['WRITE_SIZE'] * scale['WRITE_SIZE'] * 1024 / 1e6:.1f} MB per launch")
+        if alg:
+            note += f", against {alg / 1e6:.1f} MB algorithmic in those runs = {total / alg:.3f} x"
+        return int(round(total)), note
+    finally:
+        shutil.rmtree(out, ignore_errors=True)
 
 
 def read_probe(torch, M, ses, NL, achieved_gbps):
@@ -132,6 +195,10 @@ def main():
     if args.workload == "projections":
         return projections_bench(args)
     args.batch = args.batch or 32
+    default_point = not args.ragged and args.batch == 32 and args.kv == 8192 and args.layers == 28 and (args.q_heads, args.kv_heads) == (28, 4)
+    live = None
+    if default_point and not args.no_live_traffic:
+        live = live_traffic()       # children first: this process has not touched the GPU yet
     import torch
 
     import workloads as W
@@ -140,7 +207,12 @@ def main():
     sh = W.config3(n_layers=args.layers, batch=args.batch) if args.ragged else \
         W.metric_point(args.batch, args.kv, n_layers=args.layers)
     result = attention_workload(args, sh, args.steps, args.warmup, not args.no_cpu_baseline, args.ragged)
-    default_point = not args.ragged and args.batch == 32 and args.kv == 8192 and args.layers == 28
+    if live is not None:
+        nbytes, note = live
+        if nbytes is not None:
+            result["roofline"]["traffic"], result["roofline"]["traffic_source"] = nbytes, note
+        else:
+            result["roofline"]["traffic_source"] = (result["roofline"]["traffic_source"] or "none") + f"; no live measurement: {note}"
     if default_point and not args.no_also:
         # two more points of the target's range (batch 32, 4k to 16k tokens), a few steps each
         also = []
