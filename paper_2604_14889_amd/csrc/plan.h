@@ -28,7 +28,7 @@ struct Seg {
 };
 
 constexpr int kSegInts = (int)(sizeof(Seg) / sizeof(int));
-constexpr int kSegOverheadTiles = 24;   // set-up + merge of a segment, in units of one tile of streaming
+constexpr int kSegOverheadTiles = 16;   // set-up + merge of a segment, in units of one tile of streaming (12 to 20 measured alike, 8 and 24 slower)
 
 // plan blob: [first segment of every item][all segments][partial range of every sequence]
 inline int mfma_plan_ints(int B) { return kMaxMfmaItems * kSegInts + (kMaxMfmaItems + B) * kSegInts + (B + 1); }
